@@ -1,0 +1,273 @@
+/*
+ * FreeCache cached denoising layer-step: CPU oracle.
+ *
+ * TEST INFRASTRUCTURE ONLY.  This file is the slow, plain definition the GPU
+ * library is checked against.  It shares no code with the HIP path, is never
+ * called by it, and must not be used as a fallback for it.
+ *
+ * What it computes (paper, section 3.2.1 "FreeCache", paragraphs
+ * "Initialization and Partitioning", "Windowed Re-computation" and
+ * "Progressive Caching"; cost rows of Table 1):
+ *   1. the fused Q/K/V projection of the rows of the active window only
+ *      (Table 1, row "W_Q, W_K, W_V projections", with the row count L
+ *      replaced by the window size A),
+ *   2. rotary position embedding of q and k (the paper is silent on the
+ *      position encoding; Dream/LLaDA-style half-split RoPE is this build's
+ *      reading),
+ *   3. the overwrite of exactly those rows of a persistent K/V cache
+ *      ("KV projections are recomputed only for tokens within this window";
+ *      everything outside is frozen),
+ *   4. bidirectional softmax attention of the window's queries over the first
+ *      kv_len cached rows (Table 1, rows "QK^T" and "Attention Score x Value",
+ *      L x L replaced by A x L), grouped-query aware, with no mask.
+ *
+ * All sums run in double, in ascending index order, with no blocking, fusion
+ * or reordering.  Values are rounded only where the storage format demands it:
+ * q, k, v when they are stored, and the attention output.
+ *
+ * Array layouts (row-major, all "storage" arrays hold floats whose values are
+ * exactly representable in the storage dtype):
+ *   X      [B][A][d]             W  [N][d], N = (Hq + 2 Hkv) Dh, rows ordered
+ *   bias   [N] or NULL               q heads | k heads | v heads
+ *   pos    [B][A] absolute position, or -1 for a padded (skipped) row
+ *   Q      [B][Hq][A][Dh]
+ *   Knew, Vnew [B][A][Hkv][Dh]
+ *   Kc, Vc [B][Hkv][Smax][Dh]
+ *   O      [B][A][Hq*Dh]
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+enum { FCO_F32 = 0, FCO_BF16 = 1 };
+
+typedef struct {
+    int32_t batch;       /* B */
+    int32_t hidden;      /* d */
+    int32_t n_q_heads;   /* Hq */
+    int32_t n_kv_heads;  /* Hkv, divides Hq */
+    int32_t head_dim;    /* Dh, even */
+    int32_t max_seq;     /* Smax: rows per (batch, kv head) in the cache */
+    int32_t dtype;       /* FCO_F32 or FCO_BF16: the storage format */
+    double rope_base;
+    double softmax_scale; /* <= 0 means 1/sqrt(Dh) */
+} fco_config;
+
+/* Round a double to the storage format, round-to-nearest-even, directly from
+ * double (no intermediate float rounding for bf16).  bf16 = 1 sign, 8 exponent,
+ * 7 stored significand bits: 8 significant bits, minimum normal 2^-126. */
+double fco_round_to_storage(double x, int32_t dtype)
+{
+    if (dtype == FCO_F32) return (double)(float)x;
+    if (x == 0.0 || isnan(x) || isinf(x)) return x;
+    int e;
+    (void)frexp(x, &e);          /* |x| = m * 2^e, m in [0.5, 1) */
+    int q = e - 8;               /* exponent of the last kept bit */
+    if (q < -133) q = -133;      /* bf16 subnormal spacing 2^-133 */
+    double r = ldexp(rint(ldexp(x, -q)), q); /* rint: ties to even */
+    const double bf16_max = (2.0 - ldexp(1.0, -7)) * ldexp(1.0, 127);
+    if (fabs(r) > bf16_max) return x > 0 ? INFINITY : -INFINITY;
+    return r;
+}
+
+/* Element-wise fco_round_to_storage over an array. */
+void fco_round_array(const double *in, double *out, int64_t n, int32_t dtype)
+{
+    for (int64_t i = 0; i < n; ++i) out[i] = fco_round_to_storage(in[i], dtype);
+}
+
+static int cfg_ok(const fco_config *c)
+{
+    return c && c->batch > 0 && c->hidden > 0 && c->n_q_heads > 0 && c->n_kv_heads > 0 &&
+           c->n_q_heads % c->n_kv_heads == 0 && c->head_dim > 0 && c->head_dim % 2 == 0 &&
+           c->max_seq > 0 && (c->dtype == FCO_F32 || c->dtype == FCO_BF16);
+}
+
+/* Steps 1-2: project the window rows, rotate q and k, round to storage.
+ * pre (optional, [B][A][N] doubles) receives the rotated, not yet rounded
+ * values in the order q heads | k heads | v heads. */
+int fco_project_rope(const fco_config *c, int32_t A, const float *X, const float *W,
+                     const float *bias, const int32_t *pos, float *Q, float *Knew,
+                     float *Vnew, double *pre)
+{
+    if (!cfg_ok(c) || A < 1 || !X || !W || !pos || !Q || !Knew || !Vnew) return 1;
+    const int B = c->batch, d = c->hidden, Hq = c->n_q_heads, Hkv = c->n_kv_heads;
+    const int Dh = c->head_dim, half = Dh / 2;
+    const int N = (Hq + 2 * Hkv) * Dh;
+#pragma omp parallel for collapse(2) schedule(static)
+    for (int b = 0; b < B; ++b) {
+        for (int a = 0; a < A; ++a) {
+            double *y = (double *)malloc(sizeof(double) * (size_t)N);
+            const float *x = X + ((size_t)b * A + a) * d;
+            const int32_t p = pos[(size_t)b * A + a];
+            for (int n = 0; n < N; ++n) {
+                const float *w = W + (size_t)n * d;
+                double acc = 0.0;
+                for (int k = 0; k < d; ++k) acc += (double)x[k] * (double)w[k];
+                if (bias) acc += (double)bias[n];
+                y[n] = acc;
+            }
+            /* rotary embedding on the Hq + Hkv heads that hold q and k */
+            if (p >= 0) {
+                for (int h = 0; h < Hq + Hkv; ++h) {
+                    double *v = y + (size_t)h * Dh;
+                    for (int i = 0; i < half; ++i) {
+                        const double theta = pow(c->rope_base, -2.0 * (double)i / (double)Dh);
+                        const double ang = (double)p * theta;
+                        const double cs = cos(ang), sn = sin(ang);
+                        const double x0 = v[i], x1 = v[i + half];
+                        v[i] = x0 * cs - x1 * sn;
+                        v[i + half] = x1 * cs + x0 * sn;
+                    }
+                }
+            }
+            for (int n = 0; n < N; ++n) {
+                double val = (p >= 0) ? y[n] : 0.0;
+                if (pre) pre[((size_t)b * A + a) * N + n] = val;
+                float r = (float)fco_round_to_storage(val, c->dtype);
+                int h = n / Dh, i = n % Dh;
+                if (h < Hq)
+                    Q[(((size_t)b * Hq + h) * A + a) * Dh + i] = r;
+                else if (h < Hq + Hkv)
+                    Knew[(((size_t)b * A + a) * Hkv + (h - Hq)) * Dh + i] = r;
+                else
+                    Vnew[(((size_t)b * A + a) * Hkv + (h - Hq - Hkv)) * Dh + i] = r;
+            }
+            free(y);
+        }
+    }
+    return 0;
+}
+
+/* Step 3: overwrite the cache rows of the window; nothing else is touched.
+ * Returns 2 if a position falls outside [0, Smax). */
+int fco_scatter(const fco_config *c, int32_t A, const float *Knew, const float *Vnew,
+                const int32_t *pos, float *Kc, float *Vc)
+{
+    if (!cfg_ok(c) || A < 1 || !Knew || !Vnew || !pos || !Kc || !Vc) return 1;
+    const int B = c->batch, Hkv = c->n_kv_heads, Dh = c->head_dim, Smax = c->max_seq;
+    for (int b = 0; b < B; ++b)
+        for (int a = 0; a < A; ++a)
+            if (pos[(size_t)b * A + a] >= Smax) return 2;
+    for (int b = 0; b < B; ++b) {
+        for (int a = 0; a < A; ++a) {
+            const int32_t p = pos[(size_t)b * A + a];
+            if (p < 0) continue;
+            for (int j = 0; j < Hkv; ++j) {
+                const size_t src = (((size_t)b * A + a) * Hkv + j) * Dh;
+                const size_t dst = (((size_t)b * Hkv + j) * Smax + p) * Dh;
+                memcpy(Kc + dst, Knew + src, sizeof(float) * (size_t)Dh);
+                memcpy(Vc + dst, Vnew + src, sizeof(float) * (size_t)Dh);
+            }
+        }
+    }
+    return 0;
+}
+
+/* Step 4: O[b,a,h] = softmax(scale * q . Kc^T) Vc over rows [0, kv_len) of kv
+ * head floor(h / g).  No mask.  probs (optional, [B][Hq][A][kv_len] doubles)
+ * receives the normalised attention weights.  Rows with pos = -1 give zeros. */
+int fco_attend(const fco_config *c, int32_t A, const float *Q, const float *Kc,
+               const float *Vc, const int32_t *pos, int32_t kv_len, float *O, double *probs)
+{
+    if (!cfg_ok(c) || A < 1 || !Q || !Kc || !Vc || !O) return 1;
+    if (kv_len < 1 || kv_len > c->max_seq) return 2;
+    const int B = c->batch, Hq = c->n_q_heads, Hkv = c->n_kv_heads, Dh = c->head_dim;
+    const int Smax = c->max_seq, g = Hq / Hkv;
+    const double scale = c->softmax_scale > 0 ? c->softmax_scale : 1.0 / sqrt((double)Dh);
+#pragma omp parallel for collapse(3) schedule(static)
+    for (int b = 0; b < B; ++b) {
+        for (int h = 0; h < Hq; ++h) {
+            for (int a = 0; a < A; ++a) {
+                float *o = O + ((size_t)b * A + a) * ((size_t)Hq * Dh) + (size_t)h * Dh;
+                double *pr = probs ? probs + (((size_t)b * Hq + h) * A + a) * (size_t)kv_len : NULL;
+                if (pos && pos[(size_t)b * A + a] < 0) {
+                    for (int i = 0; i < Dh; ++i) o[i] = 0.0f;
+                    if (pr) for (int t = 0; t < kv_len; ++t) pr[t] = 0.0;
+                    continue;
+                }
+                const int j = h / g;
+                const float *q = Q + (((size_t)b * Hq + h) * A + a) * Dh;
+                const float *K = Kc + ((size_t)b * Hkv + j) * (size_t)Smax * Dh;
+                const float *V = Vc + ((size_t)b * Hkv + j) * (size_t)Smax * Dh;
+                double *s = (double *)malloc(sizeof(double) * (size_t)kv_len);
+                double *acc = (double *)calloc((size_t)Dh, sizeof(double));
+                double m = -INFINITY;
+                for (int t = 0; t < kv_len; ++t) {
+                    double dot = 0.0;
+                    for (int i = 0; i < Dh; ++i) dot += (double)q[i] * (double)K[(size_t)t * Dh + i];
+                    s[t] = scale * dot;
+                    if (s[t] > m) m = s[t];
+                }
+                double l = 0.0;
+                for (int t = 0; t < kv_len; ++t) {
+                    s[t] = exp(s[t] - m);
+                    l += s[t];
+                }
+                for (int t = 0; t < kv_len; ++t)
+                    for (int i = 0; i < Dh; ++i) acc[i] += s[t] * (double)V[(size_t)t * Dh + i];
+                for (int i = 0; i < Dh; ++i) o[i] = (float)fco_round_to_storage(acc[i] / l, c->dtype);
+                if (pr) for (int t = 0; t < kv_len; ++t) pr[t] = s[t] / l;
+                free(s);
+                free(acc);
+            }
+        }
+    }
+    return 0;
+}
+
+/* One cached layer-step: every row of the window is projected and stored
+ * before any attention is computed, because attention is bidirectional and
+ * each window query reads each fresh key. */
+int fco_layer_step(const fco_config *c, int32_t A, const float *X, const float *W,
+                   const float *bias, const int32_t *pos, int32_t kv_len, float *Kc,
+                   float *Vc, float *Q, float *O)
+{
+    if (!cfg_ok(c) || A < 1) return 1;
+    const size_t nkv = (size_t)c->batch * A * c->n_kv_heads * c->head_dim;
+    float *Knew = (float *)malloc(sizeof(float) * nkv);
+    float *Vnew = (float *)malloc(sizeof(float) * nkv);
+    int rc = fco_project_rope(c, A, X, W, bias, pos, Q, Knew, Vnew, NULL);
+    if (!rc) {
+        for (int i = 0; i < c->batch * A && !rc; ++i)
+            if (pos[i] >= kv_len) rc = 2;
+    }
+    if (!rc) rc = fco_scatter(c, A, Knew, Vnew, pos, Kc, Vc);
+    if (!rc) rc = fco_attend(c, A, Q, Kc, Vc, pos, kv_len, O, NULL);
+    free(Knew);
+    free(Vnew);
+    return rc;
+}
+
+/*
+ * Window schedule (section 3.2.1).  The generation region [P, P+G) is cut into
+ * N = ceil(G / Bk) blocks; cached step s works on block i = floor(s /
+ * steps_per_block).
+ *   mode 0 (block window): the window is block i alone.
+ *   mode 1 (reducing window, the paper's literal statement): the window is
+ *          block i and every later block, so it shrinks as blocks complete.
+ * refresh_after is 1 when refresh_every > 0 and (s + 1) is a multiple of it:
+ * the caller then re-projects the generation region before the next step.
+ * Returns 1 for invalid arguments, 2 when s is past the last block.
+ */
+int fco_window(int32_t step, int32_t P, int32_t G, int32_t Bk, int32_t steps_per_block,
+               int32_t refresh_every, int32_t mode, int32_t *win_start, int32_t *rows,
+               int32_t *refresh_after)
+{
+    if (step < 0 || P < 0 || G < 1 || Bk < 1 || steps_per_block < 1 || refresh_every < 0 ||
+        (mode != 0 && mode != 1) || !win_start || !rows || !refresh_after)
+        return 1;
+    const int32_t N = (G + Bk - 1) / Bk;
+    const int32_t i = step / steps_per_block;
+    if (i >= N) return 2;
+    *win_start = P + i * Bk;
+    if (mode == 1) {
+        *rows = G - i * Bk;
+    } else {
+        int32_t left = G - i * Bk;
+        *rows = left < Bk ? left : Bk;
+    }
+    *refresh_after = (refresh_every > 0 && (step + 1) % refresh_every == 0) ? 1 : 0;
+    return 0;
+}

@@ -1,0 +1,216 @@
+"""ctypes front end of the CPU oracle (oracle/fc_oracle.c).
+
+TEST INFRASTRUCTURE ONLY: imported by tests/, by __graft_entry__.smoke() and by
+bench.py's cpu_baseline leg.  It never touches the GPU library and the GPU
+library never touches it.
+
+All storage arrays are numpy float32 whose values are exactly representable in
+the configured storage dtype ("f32" or "bf16"); see fc_oracle.c for layouts and
+for the passages of the paper each function follows.
+"""
+import ctypes
+import os
+from dataclasses import dataclass
+
+import numpy as np
+
+from . import build as _build
+
+F32, BF16 = 0, 1
+_DTYPES = {"f32": F32, "bf16": BF16}
+
+
+class _Cfg(ctypes.Structure):
+    _fields_ = [
+        ("batch", ctypes.c_int32),
+        ("hidden", ctypes.c_int32),
+        ("n_q_heads", ctypes.c_int32),
+        ("n_kv_heads", ctypes.c_int32),
+        ("head_dim", ctypes.c_int32),
+        ("max_seq", ctypes.c_int32),
+        ("dtype", ctypes.c_int32),
+        ("rope_base", ctypes.c_double),
+        ("softmax_scale", ctypes.c_double),
+    ]
+
+
+@dataclass
+class OracleConfig:
+    batch: int
+    hidden: int
+    n_q_heads: int
+    n_kv_heads: int
+    head_dim: int
+    max_seq: int
+    dtype: str = "bf16"
+    rope_base: float = 10000.0
+    softmax_scale: float = 0.0  # 0 => 1/sqrt(head_dim)
+
+    @property
+    def qkv_width(self) -> int:
+        return (self.n_q_heads + 2 * self.n_kv_heads) * self.head_dim
+
+    def c(self) -> _Cfg:
+        return _Cfg(self.batch, self.hidden, self.n_q_heads, self.n_kv_heads, self.head_dim,
+                    self.max_seq, _DTYPES[self.dtype], self.rope_base, self.softmax_scale)
+
+
+_lib = None
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        path = _build.build()
+        L = ctypes.CDLL(path)
+        L.fco_round_to_storage.restype = ctypes.c_double
+        L.fco_round_to_storage.argtypes = [ctypes.c_double, ctypes.c_int32]
+        L.fco_round_array.restype = None
+        for name in ("fco_project_rope", "fco_scatter", "fco_attend", "fco_layer_step", "fco_window"):
+            getattr(L, name).restype = ctypes.c_int
+        _lib = L
+    return _lib
+
+
+def set_threads(n: int) -> None:
+    """Set the OpenMP thread count used by the oracle's outer loops."""
+    os.environ["OMP_NUM_THREADS"] = str(n)
+    try:
+        omp = ctypes.CDLL("libgomp.so.1")
+        omp.omp_set_num_threads(int(n))
+    except OSError:
+        pass
+
+
+def get_threads() -> int:
+    try:
+        omp = ctypes.CDLL("libgomp.so.1")
+        return int(omp.omp_get_max_threads())
+    except OSError:
+        return 1
+
+
+def _f32(a, shape=None):
+    a = np.ascontiguousarray(a, dtype=np.float32)
+    if shape is not None:
+        assert a.shape == tuple(shape), (a.shape, shape)
+    return a
+
+
+def _p(a, ctype):
+    if a is None:
+        return None
+    return a.ctypes.data_as(ctypes.POINTER(ctype))
+
+
+def _check(rc, what):
+    if rc != 0:
+        raise ValueError("%s failed with oracle status %d" % (what, rc))
+
+
+def round_to_storage(x, dtype: str):
+    """Round doubles to the storage dtype (RNE); returns float64 array."""
+    x = np.ascontiguousarray(x, dtype=np.float64)
+    out = np.empty_like(x)
+    lib().fco_round_array(_p(x, ctypes.c_double), _p(out, ctypes.c_double),
+                          ctypes.c_int64(x.size), ctypes.c_int32(_DTYPES[dtype]))
+    return out
+
+
+def project_rope(cfg: OracleConfig, X, W, bias, pos, want_pre=False):
+    """Steps 1-2. Returns Q [B,Hq,A,Dh], Knew, Vnew [B,A,Hkv,Dh] (+ pre [B,A,N])."""
+    B, A = pos.shape
+    X = _f32(X, (B, A, cfg.hidden))
+    W = _f32(W, (cfg.qkv_width, cfg.hidden))
+    bias = None if bias is None else _f32(bias, (cfg.qkv_width,))
+    pos = np.ascontiguousarray(pos, dtype=np.int32)
+    Q = np.empty((B, cfg.n_q_heads, A, cfg.head_dim), np.float32)
+    Kn = np.empty((B, A, cfg.n_kv_heads, cfg.head_dim), np.float32)
+    Vn = np.empty_like(Kn)
+    pre = np.empty((B, A, cfg.qkv_width), np.float64) if want_pre else None
+    c = cfg.c()
+    rc = lib().fco_project_rope(ctypes.byref(c), ctypes.c_int32(A), _p(X, ctypes.c_float),
+                                _p(W, ctypes.c_float), _p(bias, ctypes.c_float),
+                                _p(pos, ctypes.c_int32), _p(Q, ctypes.c_float),
+                                _p(Kn, ctypes.c_float), _p(Vn, ctypes.c_float),
+                                _p(pre, ctypes.c_double))
+    _check(rc, "fco_project_rope")
+    return (Q, Kn, Vn, pre) if want_pre else (Q, Kn, Vn)
+
+
+def scatter(cfg: OracleConfig, Knew, Vnew, pos, Kc, Vc):
+    """Step 3, in place on Kc, Vc [B,Hkv,Smax,Dh]."""
+    B, A = pos.shape
+    assert Kc.dtype == np.float32 and Vc.dtype == np.float32
+    assert Kc.flags.c_contiguous and Vc.flags.c_contiguous
+    assert Kc.shape == (B, cfg.n_kv_heads, cfg.max_seq, cfg.head_dim) == Vc.shape
+    Knew = _f32(Knew, (B, A, cfg.n_kv_heads, cfg.head_dim))
+    Vnew = _f32(Vnew, (B, A, cfg.n_kv_heads, cfg.head_dim))
+    pos = np.ascontiguousarray(pos, dtype=np.int32)
+    c = cfg.c()
+    rc = lib().fco_scatter(ctypes.byref(c), ctypes.c_int32(A), _p(Knew, ctypes.c_float),
+                           _p(Vnew, ctypes.c_float), _p(pos, ctypes.c_int32),
+                           _p(Kc, ctypes.c_float), _p(Vc, ctypes.c_float))
+    _check(rc, "fco_scatter")
+
+
+def attend(cfg: OracleConfig, Q, Kc, Vc, kv_len, pos=None, want_probs=False):
+    """Step 4. Returns O [B,A,Hq*Dh] (+ probs [B,Hq,A,kv_len])."""
+    B, Hq, A, Dh = Q.shape
+    Q = _f32(Q, (cfg.batch, cfg.n_q_heads, A, cfg.head_dim))
+    Kc = _f32(Kc, (B, cfg.n_kv_heads, cfg.max_seq, Dh))
+    Vc = _f32(Vc, (B, cfg.n_kv_heads, cfg.max_seq, Dh))
+    if pos is not None:
+        pos = np.ascontiguousarray(pos, dtype=np.int32)
+        assert pos.shape == (B, A)
+    O = np.empty((B, A, Hq * Dh), np.float32)
+    probs = np.empty((B, Hq, A, kv_len), np.float64) if want_probs else None
+    c = cfg.c()
+    rc = lib().fco_attend(ctypes.byref(c), ctypes.c_int32(A), _p(Q, ctypes.c_float),
+                          _p(Kc, ctypes.c_float), _p(Vc, ctypes.c_float),
+                          _p(pos, ctypes.c_int32), ctypes.c_int32(kv_len),
+                          _p(O, ctypes.c_float), _p(probs, ctypes.c_double))
+    _check(rc, "fco_attend")
+    return (O, probs) if want_probs else O
+
+
+def layer_step(cfg: OracleConfig, X, W, bias, pos, kv_len, Kc, Vc):
+    """One cached layer-step; Kc, Vc updated in place. Returns Q, O."""
+    B, A = pos.shape
+    X = _f32(X, (B, A, cfg.hidden))
+    W = _f32(W, (cfg.qkv_width, cfg.hidden))
+    bias = None if bias is None else _f32(bias, (cfg.qkv_width,))
+    pos = np.ascontiguousarray(pos, dtype=np.int32)
+    assert Kc.dtype == np.float32 and Vc.dtype == np.float32
+    assert Kc.flags.c_contiguous and Vc.flags.c_contiguous
+    assert Kc.shape == (B, cfg.n_kv_heads, cfg.max_seq, cfg.head_dim) == Vc.shape
+    Q = np.empty((B, cfg.n_q_heads, A, cfg.head_dim), np.float32)
+    O = np.empty((B, A, cfg.n_q_heads * cfg.head_dim), np.float32)
+    c = cfg.c()
+    rc = lib().fco_layer_step(ctypes.byref(c), ctypes.c_int32(A), _p(X, ctypes.c_float),
+                              _p(W, ctypes.c_float), _p(bias, ctypes.c_float),
+                              _p(pos, ctypes.c_int32), ctypes.c_int32(kv_len),
+                              _p(Kc, ctypes.c_float), _p(Vc, ctypes.c_float),
+                              _p(Q, ctypes.c_float), _p(O, ctypes.c_float))
+    _check(rc, "fco_layer_step")
+    return Q, O
+
+
+def refresh(cfg: OracleConfig, X, W, bias, start, kv_len, Kc, Vc):
+    """Full refresh of rows [start, start+R): the same step with a wide window."""
+    B, R = X.shape[0], X.shape[1]
+    pos = np.tile(np.arange(start, start + R, dtype=np.int32), (B, 1))
+    return layer_step(cfg, X, W, bias, pos, kv_len, Kc, Vc)
+
+
+def window(step, P, G, Bk, steps_per_block, refresh_every=0, mode=0):
+    """Window schedule. Returns (win_start, rows, refresh_after)."""
+    ws, rows, ra = ctypes.c_int32(), ctypes.c_int32(), ctypes.c_int32()
+    rc = lib().fco_window(ctypes.c_int32(step), ctypes.c_int32(P), ctypes.c_int32(G),
+                          ctypes.c_int32(Bk), ctypes.c_int32(steps_per_block),
+                          ctypes.c_int32(refresh_every), ctypes.c_int32(mode),
+                          ctypes.byref(ws), ctypes.byref(rows), ctypes.byref(ra))
+    if rc == 2:
+        raise IndexError("step past the last block")
+    _check(rc, "fco_window")
+    return ws.value, rows.value, ra.value

@@ -1,0 +1,442 @@
+"""Pins of the CPU oracle against things that are not the oracle.
+
+Each test ties one part of oracle/fc_oracle.c to a brute-force recompute, a
+closed form, a library routine or an invariant, so that a dropped term, a wrong
+sign or index, or a transposed operand in the oracle fails at least one of them.
+The definition being pinned is the cached layer-step of the paper's section
+3.2.1 (window re-projection, frozen rows, attention over the whole cache) and
+the cost rows of Table 1.
+"""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import fc_oracle as orc
+from paper_2505_21467_amd import inputs
+from tests.dense_reference import dense_layer, rope_complex
+
+
+def _cfg(B=1, d=32, Hq=4, Hkv=2, Dh=8, Smax=24, dtype="f32", base=10000.0, scale=0.0):
+    return orc.OracleConfig(B, d, Hq, Hkv, Dh, Smax, dtype, base, scale)
+
+
+def _rand(seed, shape, std=1.0):
+    return np.random.default_rng(seed).normal(0.0, std, size=shape).astype(np.float32)
+
+
+def _pos(B, start, rows):
+    return np.tile(np.arange(start, start + rows, dtype=np.int32), (B, 1))
+
+
+# --------------------------------------------------------------------------- rounding
+
+def test_bf16_rounding_matches_torch_cast():
+    rng = np.random.default_rng(1)
+    x = np.concatenate([
+        rng.normal(0, 1, 20000), rng.normal(0, 1e-3, 2000), rng.normal(0, 1e4, 2000),
+        rng.normal(0, 1, 500) * 1e-39,  # bf16 subnormals
+    ]).astype(np.float32)
+    got = orc.round_to_storage(x.astype(np.float64), "bf16")
+    want = torch.from_numpy(x).to(torch.bfloat16).to(torch.float64).numpy()
+    assert np.array_equal(got, want)
+
+
+def test_bf16_rounding_ties_and_limits():
+    r = lambda v: float(orc.round_to_storage(np.array([v]), "bf16")[0])
+    assert r(1.0 + 2.0 ** -8) == 1.0                      # tie -> even (down)
+    assert r(1.0 + 3 * 2.0 ** -8) == 1.0 + 2.0 ** -6      # tie -> even (up)
+    assert r(1.0 + 2.0 ** -8 + 2.0 ** -40) == 1.0 + 2.0 ** -7  # just above a tie: a float32
+    # intermediate would have rounded this down to the tie and then to 1.0
+    assert r(-2.5) == -2.5 and r(0.0) == 0.0
+    big = (2.0 - 2.0 ** -7) * 2.0 ** 127
+    assert r(big) == big and math.isinf(r(big * (1 + 2.0 ** -8)))
+    assert r(2.0 ** -133) == 2.0 ** -133 and r(2.0 ** -135) == 0.0
+    assert float(orc.round_to_storage(np.array([0.1]), "f32")[0]) == float(np.float32(0.1))
+
+
+# --------------------------------------------------------------------------- projection
+
+def test_projection_identity_weights_return_x():
+    # Hq=1, Hkv=1, Dh=d: W = [I; I; I], positions 0 => q = k = v = x exactly
+    d = 16
+    cfg = _cfg(B=2, d=d, Hq=1, Hkv=1, Dh=d, Smax=8)
+    X = _rand(2, (2, 3, d))
+    W = np.concatenate([np.eye(d, dtype=np.float32)] * 3, axis=0)
+    pos = np.zeros((2, 3), np.int32)
+    Q, Kn, Vn = orc.project_rope(cfg, X, W, None, pos)
+    assert np.array_equal(Q[:, 0], X) and np.array_equal(Kn[:, :, 0], X) and np.array_equal(Vn[:, :, 0], X)
+
+
+def test_projection_matches_blas_and_is_linear():
+    cfg = _cfg(B=2, d=48, Hq=4, Hkv=2, Dh=8, Smax=16)
+    N = cfg.qkv_width
+    X1, X2 = _rand(3, (2, 5, 48)), _rand(4, (2, 5, 48))
+    W, b = _rand(5, (N, 48), 0.1), _rand(6, (N,), 0.1)
+    pos = np.zeros((2, 5), np.int32)  # position 0: rotation is the identity
+    _, _, _, pre1 = orc.project_rope(cfg, X1, W, b, pos, want_pre=True)
+    want = X1.astype(np.float64) @ W.astype(np.float64).T + b.astype(np.float64)
+    assert np.allclose(pre1, want, rtol=0, atol=1e-12)
+    # a non-square W with distinct rows catches a transposed operand
+    _, _, _, pre2 = orc.project_rope(cfg, X2, W, None, pos, want_pre=True)
+    _, _, _, pre12 = orc.project_rope(cfg, (2 * X1 + X2), W, None, pos, want_pre=True)
+    _, _, _, pre1nb = orc.project_rope(cfg, X1, W, None, pos, want_pre=True)
+    assert np.allclose(pre12, 2 * pre1nb + pre2, atol=1e-5)  # 2*X1+X2 is rounded to float32
+
+
+def test_projection_output_split_and_layout():
+    # one-hot rows of W route a chosen input feature to a chosen (head, lane)
+    cfg = _cfg(B=1, d=12, Hq=2, Hkv=1, Dh=4, Smax=8)
+    N = cfg.qkv_width  # 16: q0 q1 | k0 | v0
+    W = np.zeros((N, 12), np.float32)
+    for n in range(N):
+        W[n, n % 12] = float(n + 1)
+    X = _rand(7, (1, 2, 12))
+    pos = np.zeros((1, 2), np.int32)
+    Q, Kn, Vn = orc.project_rope(cfg, X, W, None, pos)
+    for a in range(2):
+        for h in range(2):
+            for i in range(4):
+                n = h * 4 + i
+                assert Q[0, h, a, i] == np.float32(np.float64(X[0, a, n % 12]) * (n + 1))
+        for i in range(4):
+            assert Kn[0, a, 0, i] == np.float32(np.float64(X[0, a, (8 + i) % 12]) * (9 + i))
+            assert Vn[0, a, 0, i] == np.float32(np.float64(X[0, a, (12 + i) % 12]) * (13 + i))
+
+
+# --------------------------------------------------------------------------- RoPE
+
+def _rope_only(x, p, Dh, base):
+    """Push one vector through the oracle's rotation: d = Dh, W = [I; I; I]."""
+    cfg = _cfg(B=1, d=Dh, Hq=1, Hkv=1, Dh=Dh, Smax=max(p + 1, 1), base=base)
+    W = np.concatenate([np.eye(Dh, dtype=np.float32)] * 3, axis=0)
+    _, _, _, pre = orc.project_rope(cfg, x.reshape(1, 1, Dh), W, None,
+                                    np.array([[p]], np.int32), want_pre=True)
+    pre = pre.reshape(3, Dh)
+    return pre[0], pre[1], pre[2]
+
+
+def test_rope_two_dim_is_plane_rotation_by_p_radians():
+    q, k, v = _rope_only(np.array([1.0, 0.0], np.float32), 1, 2, 10000.0)
+    assert np.allclose(q, [math.cos(1.0), math.sin(1.0)], atol=1e-15)
+    assert np.allclose(k, q) and np.array_equal(v, [1.0, 0.0])  # v is never rotated
+    q, _, _ = _rope_only(np.array([0.0, 1.0], np.float32), 3, 2, 10000.0)
+    assert np.allclose(q, [-math.sin(3.0), math.cos(3.0)], atol=1e-15)
+
+
+def test_rope_frequency_and_pairing():
+    # Dh=4, base=100: pair (0,2) turns by p, pair (1,3) by p * 100^(-1/2) = p/10
+    x = np.array([1.0, 1.0, 0.0, 0.0], np.float32)
+    q, _, _ = _rope_only(x, 5, 4, 100.0)
+    assert np.allclose(q, [math.cos(5.0), math.cos(0.5), math.sin(5.0), math.sin(0.5)], atol=1e-15)
+
+
+def test_rope_norm_position0_and_complex_form():
+    Dh = 16
+    x = _rand(8, (Dh,))
+    q0, _, _ = _rope_only(x, 0, Dh, 10000.0)
+    assert np.array_equal(q0, x.astype(np.float64))
+    for p in (1, 7, 300):
+        q, k, _ = _rope_only(x, p, Dh, 10000.0)
+        assert abs(np.linalg.norm(q) - np.linalg.norm(x.astype(np.float64))) < 1e-12
+        want = rope_complex(x.astype(np.float64).reshape(1, 1, Dh), np.array([p]), 10000.0).reshape(Dh)
+        assert np.allclose(q, want, atol=1e-12) and np.allclose(k, want, atol=1e-12)
+
+
+def test_rope_scores_depend_on_relative_position_only():
+    Dh = 8
+    xq, xk = _rand(9, (Dh,)), _rand(10, (Dh,))
+    dots = []
+    for shift in (0, 5, 111):
+        q, _, _ = _rope_only(xq, 3 + shift, Dh, 10000.0)
+        _, k, _ = _rope_only(xk, 9 + shift, Dh, 10000.0)
+        dots.append(float(q @ k))
+    assert abs(dots[0] - dots[1]) < 1e-12 and abs(dots[0] - dots[2]) < 1e-12
+    q, _, _ = _rope_only(xq, 3, Dh, 10000.0)
+    _, k, _ = _rope_only(xk, 10, Dh, 10000.0)
+    assert abs(float(q @ k) - dots[0]) > 1e-6  # a different offset does change it
+
+
+# --------------------------------------------------------------------------- attention
+
+def _attn_inputs(seed, cfg, A, kv_len):
+    Q = _rand(seed, (cfg.batch, cfg.n_q_heads, A, cfg.head_dim))
+    Kc = _rand(seed + 1, (cfg.batch, cfg.n_kv_heads, cfg.max_seq, cfg.head_dim))
+    Vc = _rand(seed + 2, (cfg.batch, cfg.n_kv_heads, cfg.max_seq, cfg.head_dim))
+    return Q, Kc, Vc
+
+
+def test_attention_matches_library_sdpa_noncausal_fp64():
+    cfg = _cfg(B=2, Hq=4, Hkv=2, Dh=8, Smax=40)
+    A, S = 5, 33
+    Q, Kc, Vc = _attn_inputs(11, cfg, A, S)
+    O, probs = orc.attend(cfg, Q, Kc, Vc, S, want_probs=True)
+    g = cfg.n_q_heads // cfg.n_kv_heads
+    q = torch.from_numpy(Q).double()
+    k = torch.from_numpy(Kc[:, :, :S]).double().repeat_interleave(g, dim=1)
+    v = torch.from_numpy(Vc[:, :, :S]).double().repeat_interleave(g, dim=1)
+    ref = torch.nn.functional.scaled_dot_product_attention(q, k, v, is_causal=False)  # [B,Hq,A,Dh]
+    ref = ref.permute(0, 2, 1, 3).reshape(cfg.batch, A, -1).numpy()
+    unrounded = np.einsum("bhat,bhtd->bahd", probs, v.numpy()).reshape(cfg.batch, A, -1)
+    assert np.allclose(unrounded, ref, rtol=0, atol=1e-12)
+    assert np.array_equal(O, ref.astype(np.float32)) or np.max(np.abs(O - ref)) < 1e-7
+    # rows beyond kv_len must not matter
+    Kc2, Vc2 = Kc.copy(), Vc.copy()
+    Kc2[:, :, S:] = 1e3
+    Vc2[:, :, S:] = -1e3
+    assert np.array_equal(orc.attend(cfg, Q, Kc2, Vc2, S), O)
+
+
+def test_attention_is_not_causal():
+    cfg = _cfg(B=1, Hq=2, Hkv=2, Dh=8, Smax=12)
+    A = S = 12
+    Q, Kc, Vc = _attn_inputs(14, cfg, A, S)
+    O, probs = orc.attend(cfg, Q, Kc, Vc, S, want_probs=True)
+    assert probs[0, 0, 0, S - 1] > 0 and np.all(probs[:, :, 0, 1:] > 0)  # row 0 sees later keys
+    q, k, v = (torch.from_numpy(t).double() for t in (Q, Kc, Vc))
+    causal = torch.nn.functional.scaled_dot_product_attention(q, k, v, is_causal=True)
+    causal = causal.permute(0, 2, 1, 3).reshape(1, A, -1).numpy()
+    assert np.max(np.abs(O[:, :-1] - causal[:, :-1])) > 1e-3
+    assert np.allclose(O[:, -1], causal[:, -1], atol=1e-6)  # only the last row sees everything either way
+
+
+def test_softmax_rows_sum_to_one_and_are_positive():
+    cfg = _cfg(B=2, Hq=4, Hkv=1, Dh=8, Smax=50)
+    Q, Kc, Vc = _attn_inputs(17, cfg, 3, 50)
+    _, probs = orc.attend(cfg, 4.0 * Q, Kc, Vc, 50, want_probs=True)
+    assert np.all(probs >= 0) and np.allclose(probs.sum(-1), 1.0, rtol=0, atol=1e-12)
+
+
+def test_single_key_returns_its_value():
+    cfg = _cfg(B=1, Hq=2, Hkv=1, Dh=8, Smax=4)
+    Q, Kc, Vc = _attn_inputs(20, cfg, 3, 1)
+    O = orc.attend(cfg, Q, Kc, Vc, 1).reshape(1, 3, 2, 8)
+    assert np.array_equal(O, np.broadcast_to(Vc[0, 0, 0], O.shape))
+
+
+def test_identical_keys_or_zero_query_give_mean_of_values():
+    cfg = _cfg(B=1, Hq=2, Hkv=1, Dh=8, Smax=21)
+    Q, Kc, Vc = _attn_inputs(23, cfg, 2, 21)
+    mean_v = Vc[0, 0, :21].astype(np.float64).mean(0)
+    Ksame = np.broadcast_to(Kc[:, :, :1], Kc.shape).copy()
+    O = orc.attend(cfg, Q, Ksame, Vc, 21).reshape(2, 2, 8)
+    assert np.allclose(O, mean_v, atol=1e-6)
+    O = orc.attend(cfg, np.zeros_like(Q), Kc, Vc, 21).reshape(2, 2, 8)
+    assert np.allclose(O, mean_v, atol=1e-6)
+
+
+def test_constant_score_shift_changes_nothing():
+    cfg = _cfg(B=1, Hq=1, Hkv=1, Dh=8, Smax=16)
+    Q, Kc, Vc = _attn_inputs(26, cfg, 1, 16)
+    _, p0 = orc.attend(cfg, Q, Kc, Vc, 16, want_probs=True)
+    q = Q[0, 0, 0].astype(np.float64)
+    u = (q / (q @ q)).astype(np.float32)  # q . u = 1 (up to float32 rounding of u)
+    _, p1 = orc.attend(cfg, Q, Kc + 3.0 * u, Vc, 16, want_probs=True)
+    assert np.allclose(p0, p1, atol=1e-6)
+
+
+def test_scale_is_inverse_sqrt_head_dim_unless_given():
+    cfg = _cfg(B=1, Hq=1, Hkv=1, Dh=16, Smax=2)
+    Q = np.zeros((1, 1, 1, 16), np.float32)
+    Q[..., 0] = 1.0
+    Kc = np.zeros((1, 1, 2, 16), np.float32)
+    Kc[0, 0, 1, 0] = 8.0  # scores (0, 8 * scale)
+    Vc = np.zeros_like(Kc)
+    _, p = orc.attend(cfg, Q, Kc, Vc, 2, want_probs=True)
+    assert abs(p[0, 0, 0, 1] / p[0, 0, 0, 0] - math.exp(8.0 / 4.0)) < 1e-12
+    cfg2 = _cfg(B=1, Hq=1, Hkv=1, Dh=16, Smax=2, scale=0.5)
+    _, p = orc.attend(cfg2, Q, Kc, Vc, 2, want_probs=True)
+    assert abs(p[0, 0, 0, 1] / p[0, 0, 0, 0] - math.exp(4.0)) < 1e-11
+
+
+def test_joint_permutation_of_cached_rows_leaves_output_unchanged():
+    cfg = _cfg(B=1, Hq=2, Hkv=2, Dh=8, Smax=30)
+    Q, Kc, Vc = _attn_inputs(29, cfg, 4, 30)
+    _, p0 = orc.attend(cfg, Q, Kc, Vc, 30, want_probs=True)
+    perm = np.random.default_rng(0).permutation(30)
+    O1, p1 = orc.attend(cfg, Q, Kc[:, :, perm].copy(), Vc[:, :, perm].copy(), 30, want_probs=True)
+    assert np.allclose(p0[..., perm], p1, atol=1e-14)
+    assert np.allclose(orc.attend(cfg, Q, Kc, Vc, 30), O1, atol=1e-6)
+
+
+def test_gqa_equals_mha_with_consecutively_repeated_kv_heads():
+    g = 3
+    cfg = _cfg(B=2, Hq=6, Hkv=2, Dh=8, Smax=20)
+    Q, Kc, Vc = _attn_inputs(32, cfg, 4, 20)
+    O = orc.attend(cfg, Q, Kc, Vc, 20)
+    mha = _cfg(B=2, Hq=6, Hkv=6, Dh=8, Smax=20)
+    O2 = orc.attend(mha, Q, np.repeat(Kc, g, axis=1), np.repeat(Vc, g, axis=1), 20)
+    assert np.array_equal(O, O2)
+    # and head h does use kv head h // g, not h % Hkv
+    Vc3 = Vc.copy()
+    Vc3[:, 1] += 1.0
+    O3 = orc.attend(cfg, Q, Kc, Vc3, 20).reshape(2, 4, 6, 8)
+    O = O.reshape(2, 4, 6, 8)
+    assert np.array_equal(O3[:, :, :3], O[:, :, :3]) and np.allclose(O3[:, :, 3:], O[:, :, 3:] + 1.0, atol=1e-6)
+
+
+def test_output_layout_is_row_major_heads_then_lanes():
+    cfg = _cfg(B=1, Hq=3, Hkv=3, Dh=4, Smax=1)
+    Q = np.zeros((1, 3, 2, 4), np.float32)
+    Vc = np.arange(12, dtype=np.float32).reshape(1, 3, 1, 4)
+    O = orc.attend(cfg, Q, np.zeros_like(Vc), Vc, 1)
+    assert O.shape == (1, 2, 12) and np.array_equal(O[0, 0], np.arange(12)) and np.array_equal(O[0, 1], np.arange(12))
+
+
+# --------------------------------------------------------------------------- scatter / freeze
+
+def test_scatter_touches_exactly_the_window_rows():
+    cfg = _cfg(B=2, d=16, Hq=4, Hkv=2, Dh=8, Smax=20)
+    sentinel = np.float32(-7.25)
+    Kc = np.full((2, 2, 20, 8), sentinel, np.float32)
+    Vc = np.full((2, 2, 20, 8), sentinel, np.float32)
+    pos = np.array([[3, 9, 4, -1], [0, 19, 7, 8]], np.int32)
+    Kn, Vn = _rand(35, (2, 4, 2, 8)), _rand(36, (2, 4, 2, 8))
+    orc.scatter(cfg, Kn, Vn, pos, Kc, Vc)
+    touched = np.zeros((2, 20), bool)
+    for b in range(2):
+        for a in range(4):
+            p = pos[b, a]
+            if p < 0:
+                continue
+            touched[b, p] = True
+            for j in range(2):
+                assert np.array_equal(Kc[b, j, p], Kn[b, a, j]) and np.array_equal(Vc[b, j, p], Vn[b, a, j])
+    for b in range(2):
+        for p in range(20):
+            if not touched[b, p]:
+                assert np.all(Kc[b, :, p].view(np.uint32) == sentinel.view(np.uint32))
+                assert np.all(Vc[b, :, p].view(np.uint32) == sentinel.view(np.uint32))
+    assert touched.sum() == 7
+    with pytest.raises(ValueError):
+        orc.scatter(cfg, Kn, Vn, np.full((2, 4), 20, np.int32), Kc, Vc)
+
+
+def test_layer_step_freezes_rows_outside_window_bitwise():
+    w = inputs.C1.scaled(hidden=64, cached_len=40, active=8)
+    S = w.kv_len
+    cfg = orc.OracleConfig(w.batch, w.hidden, w.n_q_heads, w.n_kv_heads, w.head_dim, S + 5, "f32")
+    W = inputs.as_oracle(inputs.weights(w, 0))
+    X = inputs.as_oracle(inputs.hidden_states(w, 0, S))
+    Kc = np.zeros((1, w.n_kv_heads, S + 5, w.head_dim), np.float32)
+    Vc = np.zeros_like(Kc)
+    orc.refresh(cfg, X, W, None, 0, S, Kc, Vc)
+    K0, V0 = Kc.copy(), Vc.copy()
+    X2 = inputs.as_oracle(inputs.hidden_states(w, 1, w.active, tag="x2"))
+    orc.layer_step(cfg, X2, W, None, _pos(1, 40, 8), S, Kc, Vc)
+    outside = np.r_[0:40, 48:S + 5]
+    assert np.array_equal(Kc[:, :, outside].view(np.uint32), K0[:, :, outside].view(np.uint32))
+    assert np.array_equal(Vc[:, :, outside].view(np.uint32), V0[:, :, outside].view(np.uint32))
+    assert not np.array_equal(Kc[:, :, 40:48], K0[:, :, 40:48])
+    with pytest.raises(ValueError):  # a window row beyond the attended length
+        orc.layer_step(cfg, X2, W, None, _pos(1, S - 4, 8), S, Kc, Vc)
+
+
+# --------------------------------------------------------------------------- whole step vs brute force
+
+@pytest.mark.parametrize("dtype,Hq,Hkv", [("f32", 4, 4), ("f32", 6, 2), ("bf16", 4, 2)])
+def test_full_refresh_equals_uncached_dense_layer(dtype, Hq, Hkv):
+    B, d, Dh, S = 2, 40, 8, 19
+    cfg = orc.OracleConfig(B, d, Hq, Hkv, Dh, S, dtype, 10000.0)
+    N = cfg.qkv_width
+    X = inputs.as_oracle(inputs.normal(3, "x", (B, S, d), 1.0, dtype))
+    W = inputs.as_oracle(inputs.normal(3, "w", (N, d), 0.2, dtype))
+    b = inputs.as_oracle(inputs.normal(3, "b", (N,), 0.2, dtype))
+    Kc = np.full((B, Hkv, S, Dh), np.nan, np.float32)
+    Vc = np.full((B, Hkv, S, Dh), np.nan, np.float32)
+    Q, O = orc.refresh(cfg, X, W, b, 0, S, Kc, Vc)
+    q, k, v, o = dense_layer(X, W, b, Hq, Hkv, Dh, 10000.0, dtype)
+    if dtype == "f32":
+        assert np.allclose(Q, q, atol=1e-6) and np.allclose(Kc, k, atol=1e-6)
+        assert np.allclose(Vc, v, atol=1e-6) and np.allclose(O, o, atol=1e-6)
+    else:
+        # identical up to the rare tie decided differently by a double rounding
+        for got, want in ((Q, q), (Kc, k), (Vc, v)):
+            assert np.mean(got == want) > 0.999 and np.max(np.abs(got - want)) < 0.04
+        assert np.max(np.abs(O - o)) < 0.02
+
+
+def test_cached_step_on_unchanged_inputs_equals_window_rows_of_full_recompute():
+    # configuration 1 in miniature: refresh rows [0, L), then a cached step on [L, L+A)
+    w = inputs.C1.scaled(hidden=64, cached_len=48, active=16)
+    L, A, S = w.cached_len, w.active, w.kv_len
+    cfg = orc.OracleConfig(1, w.hidden, w.n_q_heads, w.n_kv_heads, w.head_dim, S, "f32")
+    W = inputs.as_oracle(inputs.weights(w, 0))
+    X = inputs.as_oracle(inputs.hidden_states(w, 0, S))
+    Kf = np.zeros((1, w.n_kv_heads, S, w.head_dim), np.float32)
+    Vf = np.zeros_like(Kf)
+    Qf, Of = orc.refresh(cfg, X, W, None, 0, S, Kf, Vf)
+    Kc, Vc = np.zeros_like(Kf), np.zeros_like(Kf)
+    orc.refresh(cfg, X[:, :L], W, None, 0, L, Kc, Vc)
+    Qc, Oc = orc.layer_step(cfg, X[:, L:], W, None, _pos(1, L, A), S, Kc, Vc)
+    assert np.array_equal(Kc, Kf) and np.array_equal(Vc, Vf)
+    assert np.array_equal(Qc, Qf[:, :, L:]) and np.array_equal(Oc, Of[:, L:])
+    # and the brute-force layer agrees on those rows
+    _, _, _, o = dense_layer(X, W, None, w.n_q_heads, w.n_kv_heads, w.head_dim, 10000.0, "f32")
+    assert np.allclose(Oc, o[:, L:], atol=1e-6)
+    # a stale cache is an approximation: changing the window input changes only window rows
+    X2 = X.copy()
+    X2[:, L:] += 0.5
+    K1, V1 = Kc.copy(), Vc.copy()
+    orc.layer_step(cfg, X2[:, L:], W, None, _pos(1, L, A), S, K1, V1)
+    assert np.array_equal(K1[:, :, :L], Kc[:, :, :L]) and not np.array_equal(K1[:, :, L:], Kc[:, :, L:])
+
+
+def test_padded_rows_are_skipped():
+    cfg = _cfg(B=1, d=16, Hq=2, Hkv=1, Dh=8, Smax=10)
+    X, W = _rand(40, (1, 3, 16)), _rand(41, (cfg.qkv_width, 16), 0.3)
+    Kc = _rand(42, (1, 1, 10, 8))
+    Vc = _rand(43, (1, 1, 10, 8))
+    K0 = Kc.copy()
+    pos = np.array([[4, -1, 5]], np.int32)
+    Q, O = orc.layer_step(cfg, X, W, None, pos, 10, Kc, Vc)
+    assert np.all(O[0, 1] == 0) and np.all(Q[0, :, 1] == 0)
+    changed = np.any(Kc != K0, axis=-1)[0, 0]
+    assert list(np.nonzero(changed)[0]) == [4, 5]
+    # the valid rows equal a step without the padded row
+    Kc2, Vc2 = K0.copy(), Vc.copy()
+    Vc2[:] = Vc  # Vc was updated in place; rows 4, 5 are rewritten identically below
+    Q2, O2 = orc.layer_step(cfg, X[:, [0, 2]], W, None, np.array([[4, 5]], np.int32), 10, Kc2, Vc2)
+    assert np.array_equal(O2, O[:, [0, 2]]) and np.array_equal(Kc2, Kc)
+
+
+# --------------------------------------------------------------------------- window schedule
+
+def test_window_schedule_long_context_closed_form():
+    # window slides by one 32-token block every 8 steps from 16384; 100 steps end inside block 12
+    for s in range(100):
+        ws, rows, ra = orc.window(s, 16384, 416, 32, 8)
+        assert ws == 16384 + 32 * (s // 8) and rows == 32 and ra == 0
+    assert orc.window(99, 16384, 416, 32, 8)[0] + 32 == 16800
+    assert orc.window(103, 16384, 416, 32, 8)[0] == 16768
+    with pytest.raises(IndexError):
+        orc.window(104, 16384, 416, 32, 8)
+
+
+def test_window_schedule_refresh_flag_and_monotonic():
+    last = -1
+    flags = []
+    for s in range(64):
+        ws, rows, ra = orc.window(s, 2048, 256, 32, 8, refresh_every=8)
+        assert ws >= last and rows == 32 and ws + rows <= 2048 + 256
+        last = ws
+        flags.append(ra)
+    assert [s for s, f in enumerate(flags) if f] == list(range(7, 64, 8))
+
+
+def test_window_schedule_reducing_mode_total_rows():
+    # the paper's literal reducing window: block i and all later blocks are re-projected
+    P, Bk, N, spb = 100, 32, 5, 3
+    total = 0
+    for s in range(N * spb):
+        ws, rows, _ = orc.window(s, P, N * Bk, Bk, spb, mode=1)
+        i = s // spb
+        assert ws == P + i * Bk and ws + rows == P + N * Bk
+        total += rows
+    assert total == spb * Bk * N * (N + 1) // 2
+    # a ragged last block
+    assert orc.window(2, 0, 70, 32, 1) == (64, 6, 0)
+    assert orc.window(2, 0, 70, 32, 1, mode=1) == (64, 6, 0)
+    with pytest.raises(ValueError):
+        orc.window(0, 0, 0, 32, 1)
