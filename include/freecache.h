@@ -1,0 +1,171 @@
+/*
+ * freecache.h - C ABI of the FreeCache cached denoising layer-step for MI355X (gfx950).
+ *
+ * FreeCache (paper section 3.2.1) keeps, per transformer layer, the K/V projections of the
+ * prompt and of the already committed blocks, re-projects only the rows of the active window at
+ * each denoising step, overwrites exactly those rows of the cache, and lets the window's queries
+ * attend bidirectionally over the whole cached sequence.  One such step per layer is what this
+ * library computes; Table 1 of the paper gives its cost rows (projection O(A d^2), QK^T and
+ * score x V O(A L d/h), with A the window size instead of the full length L).
+ *
+ * Conventions
+ *  - "device" pointers are HIP device memory of the current device; "host" pointers are ordinary
+ *    host memory.  Unless a function says otherwise, every pointer argument is borrowed: the
+ *    library keeps no reference after the enqueued work has run.
+ *  - Element type of all tensors is fc_config.dtype (float or bfloat16, the latter as raw 16-bit
+ *    words), except pos (int32) and the workspace (opaque bytes).
+ *  - Compute entry points only enqueue work on `stream` (a hipStream_t passed as void*; NULL is the
+ *    default stream).  They never synchronise and never allocate.  Two calls on one stream execute
+ *    in order; the attention of a step relies on this to see the step's fresh K/V rows.
+ *  - All argument checks happen on the host before any HIP call.  On failure a nonzero fc_status is
+ *    returned, nothing has been enqueued, and fc_last_error() describes the problem.  No entry
+ *    point aborts or throws across the ABI.
+ *  - Calls on distinct caches are independent.  One cache must not be used from two streams at
+ *    the same time.
+ */
+#ifndef FREECACHE_H
+#define FREECACHE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    FC_OK = 0,
+    FC_ERR_INVALID_ARG = 1, /* NULL where a pointer is required, non-positive size, bad enum */
+    FC_ERR_BOUNDS = 2,      /* layer, window or kv_len outside the cache */
+    FC_ERR_UNSUPPORTED = 3, /* shape the kernels do not cover (see fc_config) */
+    FC_ERR_OOM = 4,         /* the library could not allocate cache storage */
+    FC_ERR_WORKSPACE = 5,   /* workspace missing or smaller than fc_workspace_bytes() */
+    FC_ERR_HIP = 6          /* a HIP call or kernel launch failed */
+} fc_status;
+
+typedef enum { FC_F32 = 0, FC_BF16 = 1 } fc_dtype;
+
+/* Geometry of one model's attention layers.
+ * Supported: head_dim 64 or 128; n_q_heads a multiple of n_kv_heads (query head h reads KV head
+ * h / (n_q_heads / n_kv_heads)); hidden a multiple of 8; max_seq up to 2^24 rows. */
+typedef struct {
+    int32_t n_layers;
+    int32_t batch;        /* B: sequences held by the cache */
+    int32_t hidden;       /* d: width of the layer input */
+    int32_t n_q_heads;    /* Hq */
+    int32_t n_kv_heads;   /* Hkv */
+    int32_t head_dim;     /* Dh */
+    int32_t max_seq;      /* Smax: cache capacity in rows per sequence */
+    int32_t dtype;        /* fc_dtype */
+    float rope_base;      /* rotary base, e.g. 10000 */
+    float softmax_scale;  /* 0 selects 1/sqrt(head_dim) */
+} fc_config;
+
+typedef struct fc_cache fc_cache; /* opaque */
+
+/* Thread-local description of the last failure on the calling thread ("" if none). */
+const char *fc_last_error(void);
+
+/* ---------------------------------------------------------------------------------------------
+ * Persistent per-layer KV cache (section 3.2.1, "Initialization and Partitioning": the K/V
+ * projections of prompt + all blocks are saved once and then reused).
+ *
+ * Storage layout (private to the library, documented for snapshotting): with Spad = max_seq
+ * rounded up to a multiple of 64,
+ *   K: [layer][B][Hkv][Spad][Dh]            row-major rows,
+ *   V: [layer][B][Hkv][Spad/64][Dh][64]     64-row tiles stored transposed (key index fastest),
+ * so that both stream as 16-byte coalesced loads in the order the matrix cores consume them.
+ * Use fc_cache_write_rows / fc_cache_read_rows to move rows in the plain [B][Hkv][rows][Dh] layout.
+ */
+
+/* Bytes needed for EACH of the K and the V storage of a cache with this config; 0 on bad config. */
+size_t fc_cache_storage_bytes(const fc_config *cfg);
+
+/* Create a cache handle.  k_storage / v_storage: device buffers of fc_cache_storage_bytes() bytes
+ * each, borrowed for the life of the handle (e.g. torch tensors), or both NULL to let the library
+ * allocate zero-filled storage it then owns.  *out receives the handle (host object).
+ * Errors: INVALID_ARG, UNSUPPORTED (geometry), OOM. */
+fc_status fc_cache_alloc(const fc_config *cfg, void *k_storage, void *v_storage, fc_cache **out);
+
+/* Destroy the handle and free library-owned storage.  The caller must have synchronised every
+ * stream that used the cache.  NULL is accepted. */
+fc_status fc_cache_free(fc_cache *cache);
+
+/* Device base pointers of one layer's K and V storage (layout above). */
+fc_status fc_cache_ptrs(const fc_cache *cache, int32_t layer, void **k, void **v);
+
+/* Copy rows [start, start+rows) of every (sequence, kv head) between the cache and plain device
+ * arrays k_rows, v_rows of shape [B][Hkv][rows][Dh].  Pure bit copies (prefill, snapshot, tests).
+ * Errors: INVALID_ARG, BOUNDS (start < 0 or start + rows > max_seq), HIP. */
+fc_status fc_cache_write_rows(fc_cache *cache, int32_t layer, const void *k_rows, const void *v_rows,
+                              int32_t start, int32_t rows, void *stream);
+fc_status fc_cache_read_rows(const fc_cache *cache, int32_t layer, void *k_rows, void *v_rows,
+                             int32_t start, int32_t rows, void *stream);
+
+/* ---------------------------------------------------------------------------------------------
+ * Window schedule (section 3.2.1: the generation region [P, P+G) is cut into fixed-size blocks
+ * B_1..B_N; block i is decoded over steps_per_block steps; finished blocks are frozen).
+ * Host-only, pure integer function.  Step `step` works on block i = step / steps_per_block.
+ *   mode 0: window = block i alone                      (rows = min(Bk, rest of the region))
+ *   mode 1: window = block i and all later blocks       (the paper's reducing window)
+ * *refresh_after = 1 when refresh_every > 0 and (step + 1) % refresh_every == 0: the caller is
+ * expected to fc_refresh the generation region before the next step.
+ * Errors: INVALID_ARG; BOUNDS when step lies past the last block. */
+fc_status fc_window(int32_t step, int32_t P, int32_t G, int32_t Bk, int32_t steps_per_block,
+                    int32_t refresh_every, int32_t mode, int32_t *win_start, int32_t *rows,
+                    int32_t *refresh_after);
+
+/* ---------------------------------------------------------------------------------------------
+ * The cached layer-step (section 3.2.1, "Windowed Re-computation" and "Progressive Caching").
+ */
+
+/* Project the A window rows of every sequence to q, k, v (Table 1, projection row, with L -> A),
+ * apply rotary embedding to q and k at each row's absolute position (half-split pairing
+ * (i, i + Dh/2), angle pos * rope_base^(-2i/Dh)), write q to q_out and overwrite the cache rows
+ * at those positions with k and v.  No other cache row is modified.
+ *   x      device [B][A][hidden]
+ *   w_qkv  device [N][hidden], N = (Hq + 2 Hkv) Dh, rows ordered q heads | k heads | v heads
+ *   b_qkv  device [N] or NULL
+ *   pos    device int32 [B][A] absolute positions, or NULL meaning win_start + a.  A negative
+ *          entry marks a padded row: nothing is stored for it and its q is zero.  Entries
+ *          >= max_seq are treated the same way (the kernel never writes out of bounds).
+ *          Duplicate positions within one sequence are undefined.
+ *   q_out  device [B][Hq][A][Dh]
+ * Errors: INVALID_ARG (NULL cache/x/w_qkv/q_out, A < 1), BOUNDS (layer; with pos == NULL:
+ * win_start < 0 or win_start + A > max_seq), HIP. */
+fc_status fc_qkv_project_scatter(fc_cache *cache, int32_t layer, const void *x, const void *w_qkv,
+                                 const void *b_qkv, int32_t win_start, int32_t A,
+                                 const int32_t *pos, void *q_out, void *stream);
+
+/* Workspace bytes fc_active_attention / fc_refresh need for windows of up to max_rows rows
+ * (split-KV partial results).  0 on bad arguments. */
+size_t fc_workspace_bytes(const fc_config *cfg, int32_t max_rows);
+
+/* Bidirectional attention of the window's queries over cache rows [0, kv_len) (Table 1, rows
+ * "QK^T" and "score x V", L x L -> A x L): out[b][a][h*Dh + i] = sum_t softmax_t(scale q.k_t) v_t[i]
+ * with the KV head h / (Hq/Hkv); no mask of any kind.
+ *   q      device [B][Hq][A][Dh] (as written by fc_qkv_project_scatter)
+ *   pos    device int32 [B][A] or NULL; rows with a negative entry produce zeros
+ *   out    device [B][A][Hq*Dh]
+ *   workspace  device, >= fc_workspace_bytes(cfg, A) bytes, contents irrelevant; may be NULL only
+ *          if that size is 0.  Two calls that overlap in time must not share a workspace.
+ * Errors: INVALID_ARG, BOUNDS (layer; kv_len < 1 or > max_seq), WORKSPACE, HIP. */
+fc_status fc_active_attention(fc_cache *cache, int32_t layer, const void *q, int32_t A,
+                              int32_t kv_len, const int32_t *pos, void *out, void *workspace,
+                              size_t workspace_bytes, void *stream);
+
+/* Full refresh of rows [start, start+R) (section 3.2.1: the initial pass that fills the cache for
+ * prompt + all blocks, and any later re-projection of a region): fc_qkv_project_scatter with
+ * pos = start + r followed, if out != NULL, by fc_active_attention over [0, kv_len).
+ *   x          device [B][R][hidden]
+ *   q_scratch  device [B][Hq][R][Dh], receives the rotated queries
+ *   out        device [B][R][Hq*Dh], or NULL to refresh K/V only (then workspace may be NULL)
+ * Errors: as the two calls above, plus BOUNDS when start + R > kv_len and out != NULL. */
+fc_status fc_refresh(fc_cache *cache, int32_t layer, const void *x, const void *w_qkv,
+                     const void *b_qkv, int32_t start, int32_t R, int32_t kv_len, void *q_scratch,
+                     void *out, void *workspace, size_t workspace_bytes, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FREECACHE_H */

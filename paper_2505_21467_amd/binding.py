@@ -1,0 +1,172 @@
+"""Thin ctypes binding of libfreecache.so: same names as include/freecache.h.
+
+Argument marshalling only: torch tensors are used for device memory and streams,
+every step of the path runs in the library's HIP kernels.  There is no fallback:
+if the shared library is missing, loading raises.
+"""
+import ctypes
+import os
+
+import torch
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG, "libfreecache.so")
+
+FC_OK, FC_ERR_INVALID_ARG, FC_ERR_BOUNDS, FC_ERR_UNSUPPORTED, FC_ERR_OOM, FC_ERR_WORKSPACE, FC_ERR_HIP = range(7)
+FC_F32, FC_BF16 = 0, 1
+DTYPE_CODE = {"f32": FC_F32, "bf16": FC_BF16, torch.float32: FC_F32, torch.bfloat16: FC_BF16}
+TORCH_DTYPE = {FC_F32: torch.float32, FC_BF16: torch.bfloat16}
+
+EXPORTS = (
+    "fc_last_error", "fc_cache_storage_bytes", "fc_cache_alloc", "fc_cache_free", "fc_cache_ptrs",
+    "fc_cache_write_rows", "fc_cache_read_rows", "fc_window", "fc_qkv_project_scatter",
+    "fc_workspace_bytes", "fc_active_attention", "fc_refresh",
+)
+
+
+class fc_config(ctypes.Structure):
+    _fields_ = [
+        ("n_layers", ctypes.c_int32), ("batch", ctypes.c_int32), ("hidden", ctypes.c_int32),
+        ("n_q_heads", ctypes.c_int32), ("n_kv_heads", ctypes.c_int32), ("head_dim", ctypes.c_int32),
+        ("max_seq", ctypes.c_int32), ("dtype", ctypes.c_int32), ("rope_base", ctypes.c_float),
+        ("softmax_scale", ctypes.c_float),
+    ]
+
+
+class FreeCacheError(RuntimeError):
+    def __init__(self, status, text):
+        super().__init__("fc_status %d: %s" % (status, text))
+        self.status = status
+
+
+_lib = None
+
+
+def lib():
+    """Load libfreecache.so (built by paper_2505_21467_amd.build); raises if it is absent."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise FileNotFoundError(
+                "%s not found: run `python -m paper_2505_21467_amd.build` first" % LIB_PATH)
+        L = ctypes.CDLL(LIB_PATH)
+        vp, i32, sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_size_t
+        cfgp = ctypes.POINTER(fc_config)
+        L.fc_last_error.restype = ctypes.c_char_p
+        L.fc_last_error.argtypes = []
+        L.fc_cache_storage_bytes.restype = sz
+        L.fc_cache_storage_bytes.argtypes = [cfgp]
+        L.fc_cache_alloc.restype = ctypes.c_int
+        L.fc_cache_alloc.argtypes = [cfgp, vp, vp, ctypes.POINTER(vp)]
+        L.fc_cache_free.restype = ctypes.c_int
+        L.fc_cache_free.argtypes = [vp]
+        L.fc_cache_ptrs.restype = ctypes.c_int
+        L.fc_cache_ptrs.argtypes = [vp, i32, ctypes.POINTER(vp), ctypes.POINTER(vp)]
+        for name in ("fc_cache_write_rows", "fc_cache_read_rows"):
+            getattr(L, name).restype = ctypes.c_int
+            getattr(L, name).argtypes = [vp, i32, vp, vp, i32, i32, vp]
+        L.fc_window.restype = ctypes.c_int
+        L.fc_window.argtypes = [i32] * 7 + [ctypes.POINTER(i32)] * 3
+        L.fc_qkv_project_scatter.restype = ctypes.c_int
+        L.fc_qkv_project_scatter.argtypes = [vp, i32, vp, vp, vp, i32, i32, vp, vp, vp]
+        L.fc_workspace_bytes.restype = sz
+        L.fc_workspace_bytes.argtypes = [cfgp, i32]
+        L.fc_active_attention.restype = ctypes.c_int
+        L.fc_active_attention.argtypes = [vp, i32, vp, i32, i32, vp, vp, vp, sz, vp]
+        L.fc_refresh.restype = ctypes.c_int
+        L.fc_refresh.argtypes = [vp, i32, vp, vp, vp, i32, i32, i32, vp, vp, vp, sz, vp]
+        _lib = L
+    return _lib
+
+
+def fc_last_error() -> str:
+    return lib().fc_last_error().decode()
+
+
+def _check(status):
+    if status != FC_OK:
+        raise FreeCacheError(status, fc_last_error())
+
+
+def _ptr(t):
+    """Device (or raw) pointer of a tensor / int / None."""
+    if t is None:
+        return None
+    if isinstance(t, int):
+        return t
+    return t.data_ptr()
+
+
+def _stream(stream):
+    if stream is None:
+        return torch.cuda.current_stream().cuda_stream
+    if isinstance(stream, int):
+        return stream
+    return stream.cuda_stream
+
+
+def make_config(n_layers, batch, hidden, n_q_heads, n_kv_heads, head_dim, max_seq, dtype,
+                rope_base=10000.0, softmax_scale=0.0) -> fc_config:
+    return fc_config(n_layers, batch, hidden, n_q_heads, n_kv_heads, head_dim, max_seq,
+                     DTYPE_CODE[dtype], rope_base, softmax_scale)
+
+
+def fc_cache_storage_bytes(cfg: fc_config) -> int:
+    return int(lib().fc_cache_storage_bytes(ctypes.byref(cfg)))
+
+
+def fc_cache_alloc(cfg: fc_config, k_storage=None, v_storage=None):
+    """Returns an opaque handle (int). Storage tensors, if given, are borrowed: keep them alive."""
+    out = ctypes.c_void_p()
+    _check(lib().fc_cache_alloc(ctypes.byref(cfg), _ptr(k_storage), _ptr(v_storage), ctypes.byref(out)))
+    return out.value
+
+
+def fc_cache_free(cache) -> None:
+    _check(lib().fc_cache_free(cache))
+
+
+def fc_cache_ptrs(cache, layer: int):
+    k, v = ctypes.c_void_p(), ctypes.c_void_p()
+    _check(lib().fc_cache_ptrs(cache, layer, ctypes.byref(k), ctypes.byref(v)))
+    return k.value, v.value
+
+
+def fc_cache_write_rows(cache, layer, k_rows, v_rows, start, rows, stream=None) -> None:
+    _check(lib().fc_cache_write_rows(cache, layer, _ptr(k_rows), _ptr(v_rows), start, rows, _stream(stream)))
+
+
+def fc_cache_read_rows(cache, layer, k_rows, v_rows, start, rows, stream=None) -> None:
+    _check(lib().fc_cache_read_rows(cache, layer, _ptr(k_rows), _ptr(v_rows), start, rows, _stream(stream)))
+
+
+def fc_window(step, P, G, Bk, steps_per_block, refresh_every=0, mode=0):
+    ws, rows, ra = ctypes.c_int32(), ctypes.c_int32(), ctypes.c_int32()
+    _check(lib().fc_window(step, P, G, Bk, steps_per_block, refresh_every, mode,
+                           ctypes.byref(ws), ctypes.byref(rows), ctypes.byref(ra)))
+    return ws.value, rows.value, ra.value
+
+
+def fc_qkv_project_scatter(cache, layer, x, w_qkv, b_qkv, win_start, A, pos, q_out, stream=None) -> None:
+    _check(lib().fc_qkv_project_scatter(cache, layer, _ptr(x), _ptr(w_qkv), _ptr(b_qkv), win_start, A,
+                                        _ptr(pos), _ptr(q_out), _stream(stream)))
+
+
+def fc_workspace_bytes(cfg: fc_config, max_rows: int) -> int:
+    return int(lib().fc_workspace_bytes(ctypes.byref(cfg), max_rows))
+
+
+def fc_active_attention(cache, layer, q, A, kv_len, pos, out, workspace, workspace_bytes=None,
+                        stream=None) -> None:
+    if workspace_bytes is None:
+        workspace_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(lib().fc_active_attention(cache, layer, _ptr(q), A, kv_len, _ptr(pos), _ptr(out),
+                                     _ptr(workspace), workspace_bytes, _stream(stream)))
+
+
+def fc_refresh(cache, layer, x, w_qkv, b_qkv, start, R, kv_len, q_scratch, out, workspace,
+               workspace_bytes=None, stream=None) -> None:
+    if workspace_bytes is None:
+        workspace_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(lib().fc_refresh(cache, layer, _ptr(x), _ptr(w_qkv), _ptr(b_qkv), start, R, kv_len,
+                            _ptr(q_scratch), _ptr(out), _ptr(workspace), workspace_bytes, _stream(stream)))

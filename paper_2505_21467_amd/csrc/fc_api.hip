@@ -1,0 +1,320 @@
+// C-ABI host layer of libfreecache: argument validation, launch planning, kernel enqueue.
+// Every check happens before the first HIP call of an entry point.
+#include <math.h>
+#include <stdarg.h>
+#include <stdio.h>
+#include <string.h>
+
+#include <new>
+
+#include "fc_internal.h"
+
+namespace {
+
+thread_local char g_err[512] = "";
+
+fc_status fail(fc_status st, const char *fmt, ...)
+{
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof g_err, fmt, ap);
+    va_end(ap);
+    return st;
+}
+
+size_t esize_of(int dtype) { return dtype == FC_F32 ? 4 : 2; }
+
+// Validate a configuration; on failure fills the error text and returns the status.
+fc_status check_config(const fc_config *c)
+{
+    if (!c) return fail(FC_ERR_INVALID_ARG, "config is NULL");
+    if (c->dtype != FC_F32 && c->dtype != FC_BF16)
+        return fail(FC_ERR_INVALID_ARG, "dtype %d is neither FC_F32 nor FC_BF16", c->dtype);
+    if (c->n_layers < 1 || c->batch < 1 || c->hidden < 1 || c->n_q_heads < 1 || c->n_kv_heads < 1 ||
+        c->head_dim < 1 || c->max_seq < 1)
+        return fail(FC_ERR_INVALID_ARG, "config sizes must be positive");
+    if (!(c->rope_base > 1.0f) || !isfinite(c->rope_base))
+        return fail(FC_ERR_INVALID_ARG, "rope_base must be finite and > 1");
+    if (c->softmax_scale < 0.0f || !isfinite(c->softmax_scale))
+        return fail(FC_ERR_INVALID_ARG, "softmax_scale must be finite and >= 0");
+    if (c->n_q_heads % c->n_kv_heads != 0)
+        return fail(FC_ERR_UNSUPPORTED, "n_q_heads %d is not a multiple of n_kv_heads %d", c->n_q_heads,
+                    c->n_kv_heads);
+    if (c->head_dim != 64 && c->head_dim != 128)
+        return fail(FC_ERR_UNSUPPORTED, "head_dim %d not supported (64 or 128)", c->head_dim);
+    if (c->hidden % 8 != 0) return fail(FC_ERR_UNSUPPORTED, "hidden %d is not a multiple of 8", c->hidden);
+    if (c->max_seq > (1 << 24)) return fail(FC_ERR_UNSUPPORTED, "max_seq %d exceeds 2^24", c->max_seq);
+    if (c->batch > 65535 || c->n_q_heads > 65535)
+        return fail(FC_ERR_UNSUPPORTED, "batch and n_q_heads are limited to 65535");
+    return FC_OK;
+}
+
+int spad_of(const fc_config &c) { return (c.max_seq + FC_VTILE - 1) / FC_VTILE * FC_VTILE; }
+
+FcGeom geom_of(const fc_cache *cache)
+{
+    const fc_config &c = cache->cfg;
+    FcGeom G;
+    G.B = c.batch;
+    G.d = c.hidden;
+    G.Hq = c.n_q_heads;
+    G.Hkv = c.n_kv_heads;
+    G.Dh = c.head_dim;
+    G.max_seq = c.max_seq;
+    G.spad = cache->spad;
+    G.g = c.n_q_heads / c.n_kv_heads;
+    G.scale = c.softmax_scale > 0.f ? c.softmax_scale : (float)(1.0 / sqrt((double)c.head_dim));
+    G.log_base = log((double)c.rope_base);
+    return G;
+}
+
+void *layer_ptr(const fc_cache *c, void *base, int layer)
+{
+    return (char *)base + (size_t)layer * c->layer_elems * c->esize;
+}
+
+fc_status check_cache_layer(const fc_cache *cache, int32_t layer)
+{
+    if (!cache) return fail(FC_ERR_INVALID_ARG, "cache is NULL");
+    if (layer < 0 || layer >= cache->cfg.n_layers)
+        return fail(FC_ERR_BOUNDS, "layer %d outside [0, %d)", layer, cache->cfg.n_layers);
+    return FC_OK;
+}
+
+fc_status hip_fail(hipError_t e, const char *what)
+{
+    return fail(FC_ERR_HIP, "%s: %s", what, hipGetErrorString(e));
+}
+
+}  // namespace
+
+// ---------------------------------------------------------------------------------------------
+// Launch planning (pure host functions).
+
+FcAttnPlan fc_plan_attention(const fc_config &cfg, int A, int kv_len)
+{
+    (void)A;
+    (void)kv_len;
+    (void)cfg;
+    FcAttnPlan p;
+    p.kind = 0;
+    p.splits = 1;
+    p.keys_per_split = 0;
+    p.row_tiles = 0;
+    p.tiles_per_wg = 0;
+    return p;
+}
+
+size_t fc_plan_workspace(const fc_config &cfg, const FcAttnPlan &p, int A)
+{
+    if (p.kind == 0 || p.splits <= 1) return 0;
+    // per (b, q head, row, split): Dh partial outputs + running max + running sum, fp32
+    return (size_t)cfg.batch * cfg.n_q_heads * A * p.splits * (cfg.head_dim + 2) * sizeof(float);
+}
+
+extern "C" {
+
+const char *fc_last_error(void) { return g_err; }
+
+size_t fc_cache_storage_bytes(const fc_config *cfg)
+{
+    if (check_config(cfg) != FC_OK) return 0;
+    return (size_t)cfg->n_layers * cfg->batch * cfg->n_kv_heads * spad_of(*cfg) * cfg->head_dim *
+           esize_of(cfg->dtype);
+}
+
+fc_status fc_cache_alloc(const fc_config *cfg, void *k_storage, void *v_storage, fc_cache **out)
+{
+    if (!out) return fail(FC_ERR_INVALID_ARG, "out is NULL");
+    *out = nullptr;
+    fc_status st = check_config(cfg);
+    if (st != FC_OK) return st;
+    if ((k_storage == nullptr) != (v_storage == nullptr))
+        return fail(FC_ERR_INVALID_ARG, "k_storage and v_storage must both be given or both be NULL");
+    if (k_storage && (((uintptr_t)k_storage | (uintptr_t)v_storage) & 15))
+        return fail(FC_ERR_INVALID_ARG, "cache storage must be 16-byte aligned");
+    fc_cache *c = new (std::nothrow) fc_cache;
+    if (!c) return fail(FC_ERR_OOM, "host allocation failed");
+    c->cfg = *cfg;
+    c->spad = spad_of(*cfg);
+    c->esize = esize_of(cfg->dtype);
+    c->layer_elems = (size_t)cfg->batch * cfg->n_kv_heads * c->spad * cfg->head_dim;
+    c->k = k_storage;
+    c->v = v_storage;
+    c->owned = false;
+    if (!k_storage) {
+        const size_t bytes = fc_cache_storage_bytes(cfg);
+        void *k = nullptr, *v = nullptr;
+        if (hipMalloc(&k, bytes) != hipSuccess || hipMalloc(&v, bytes) != hipSuccess ||
+            hipMemset(k, 0, bytes) != hipSuccess || hipMemset(v, 0, bytes) != hipSuccess) {
+            (void)hipGetLastError();
+            if (k) (void)hipFree(k);
+            if (v) (void)hipFree(v);
+            delete c;
+            return fail(FC_ERR_OOM, "could not allocate 2 x %zu bytes of cache storage", bytes);
+        }
+        c->k = k;
+        c->v = v;
+        c->owned = true;
+    }
+    *out = c;
+    return FC_OK;
+}
+
+fc_status fc_cache_free(fc_cache *cache)
+{
+    if (!cache) return FC_OK;
+    fc_status st = FC_OK;
+    if (cache->owned) {
+        hipError_t e1 = hipFree(cache->k), e2 = hipFree(cache->v);
+        if (e1 != hipSuccess || e2 != hipSuccess) st = hip_fail(e1 != hipSuccess ? e1 : e2, "hipFree");
+    }
+    delete cache;
+    return st;
+}
+
+fc_status fc_cache_ptrs(const fc_cache *cache, int32_t layer, void **k, void **v)
+{
+    fc_status st = check_cache_layer(cache, layer);
+    if (st != FC_OK) return st;
+    if (!k || !v) return fail(FC_ERR_INVALID_ARG, "k or v is NULL");
+    *k = layer_ptr(cache, cache->k, layer);
+    *v = layer_ptr(cache, cache->v, layer);
+    return FC_OK;
+}
+
+static fc_status copy_rows(const fc_cache *cache, int32_t layer, void *k_rows, void *v_rows,
+                           int32_t start, int32_t rows, void *stream, bool to_cache)
+{
+    fc_status st = check_cache_layer(cache, layer);
+    if (st != FC_OK) return st;
+    if (!k_rows || !v_rows) return fail(FC_ERR_INVALID_ARG, "k_rows or v_rows is NULL");
+    if (rows < 1) return fail(FC_ERR_INVALID_ARG, "rows %d must be >= 1", rows);
+    if (start < 0 || start > cache->cfg.max_seq - rows)
+        return fail(FC_ERR_BOUNDS, "rows [%d, %d+%d) outside the cache of %d rows", start, start, rows,
+                    cache->cfg.max_seq);
+    hipError_t e = fc_launch_copy_rows(geom_of(cache), cache->cfg.dtype, layer_ptr(cache, cache->k, layer),
+                                       layer_ptr(cache, cache->v, layer), k_rows, v_rows, start, rows,
+                                       to_cache, (hipStream_t)stream);
+    return e == hipSuccess ? FC_OK : hip_fail(e, "row copy launch");
+}
+
+fc_status fc_cache_write_rows(fc_cache *cache, int32_t layer, const void *k_rows, const void *v_rows,
+                              int32_t start, int32_t rows, void *stream)
+{
+    return copy_rows(cache, layer, (void *)k_rows, (void *)v_rows, start, rows, stream, true);
+}
+
+fc_status fc_cache_read_rows(const fc_cache *cache, int32_t layer, void *k_rows, void *v_rows,
+                             int32_t start, int32_t rows, void *stream)
+{
+    return copy_rows(cache, layer, k_rows, v_rows, start, rows, stream, false);
+}
+
+fc_status fc_window(int32_t step, int32_t P, int32_t G, int32_t Bk, int32_t steps_per_block,
+                    int32_t refresh_every, int32_t mode, int32_t *win_start, int32_t *rows,
+                    int32_t *refresh_after)
+{
+    if (!win_start || !rows || !refresh_after) return fail(FC_ERR_INVALID_ARG, "output pointer is NULL");
+    if (step < 0 || P < 0 || G < 1 || Bk < 1 || steps_per_block < 1 || refresh_every < 0)
+        return fail(FC_ERR_INVALID_ARG, "step/P >= 0, G/Bk/steps_per_block >= 1, refresh_every >= 0 required");
+    if (mode != 0 && mode != 1) return fail(FC_ERR_INVALID_ARG, "mode %d is neither 0 nor 1", mode);
+    const int64_t n_blocks = ((int64_t)G + Bk - 1) / Bk;
+    const int64_t blk = step / steps_per_block;
+    if (blk >= n_blocks)
+        return fail(FC_ERR_BOUNDS, "step %d lies past the last of %lld blocks", step, (long long)n_blocks);
+    const int64_t first = blk * Bk;  // offset of the block inside the generation region
+    const int64_t rest = (int64_t)G - first;
+    if ((int64_t)P + G > INT32_MAX) return fail(FC_ERR_INVALID_ARG, "P + G overflows int32");
+    *win_start = (int32_t)(P + first);
+    *rows = (int32_t)(mode == 1 ? rest : (rest < Bk ? rest : Bk));
+    *refresh_after = (refresh_every > 0 && ((int64_t)step + 1) % refresh_every == 0) ? 1 : 0;
+    return FC_OK;
+}
+
+fc_status fc_qkv_project_scatter(fc_cache *cache, int32_t layer, const void *x, const void *w_qkv,
+                                 const void *b_qkv, int32_t win_start, int32_t A, const int32_t *pos,
+                                 void *q_out, void *stream)
+{
+    fc_status st = check_cache_layer(cache, layer);
+    if (st != FC_OK) return st;
+    if (!x || !w_qkv || !q_out) return fail(FC_ERR_INVALID_ARG, "x, w_qkv or q_out is NULL");
+    if (A < 1) return fail(FC_ERR_INVALID_ARG, "A %d must be >= 1", A);
+    if ((int64_t)A * cache->cfg.batch > (1 << 24))
+        return fail(FC_ERR_UNSUPPORTED, "batch * A exceeds 2^24 rows");
+    if (!pos && (win_start < 0 || win_start > cache->cfg.max_seq - A))
+        return fail(FC_ERR_BOUNDS, "window [%d, %d+%d) outside the cache of %d rows", win_start, win_start,
+                    A, cache->cfg.max_seq);
+    const FcGeom G = geom_of(cache);
+    void *kl = layer_ptr(cache, cache->k, layer), *vl = layer_ptr(cache, cache->v, layer);
+    hipError_t e = fc_launch_project_generic(G, cache->cfg.dtype, x, w_qkv, b_qkv, pos, win_start, A, q_out,
+                                             kl, vl, (hipStream_t)stream);
+    return e == hipSuccess ? FC_OK : hip_fail(e, "projection launch");
+}
+
+size_t fc_workspace_bytes(const fc_config *cfg, int32_t max_rows)
+{
+    if (check_config(cfg) != FC_OK || max_rows < 1) return 0;
+    size_t best = 0;
+    for (int a = 1; a <= max_rows; ++a) {
+        const FcAttnPlan p = fc_plan_attention(*cfg, a, cfg->max_seq);
+        const size_t b = fc_plan_workspace(*cfg, p, a);
+        if (b > best) best = b;
+    }
+    return best;
+}
+
+fc_status fc_active_attention(fc_cache *cache, int32_t layer, const void *q, int32_t A, int32_t kv_len,
+                              const int32_t *pos, void *out, void *workspace, size_t workspace_bytes,
+                              void *stream)
+{
+    fc_status st = check_cache_layer(cache, layer);
+    if (st != FC_OK) return st;
+    if (!q || !out) return fail(FC_ERR_INVALID_ARG, "q or out is NULL");
+    if (A < 1) return fail(FC_ERR_INVALID_ARG, "A %d must be >= 1", A);
+    if ((int64_t)A * cache->cfg.batch > (1 << 24))
+        return fail(FC_ERR_UNSUPPORTED, "batch * A exceeds 2^24 rows");
+    if (kv_len < 1 || kv_len > cache->cfg.max_seq)
+        return fail(FC_ERR_BOUNDS, "kv_len %d outside [1, %d]", kv_len, cache->cfg.max_seq);
+    const FcAttnPlan plan = fc_plan_attention(cache->cfg, A, kv_len);
+    const size_t need = fc_plan_workspace(cache->cfg, plan, A);
+    if (need > 0 && (!workspace || workspace_bytes < need))
+        return fail(FC_ERR_WORKSPACE, "workspace of %zu bytes needed, %zu given", need,
+                    workspace ? workspace_bytes : (size_t)0);
+    const FcGeom G = geom_of(cache);
+    void *kl = layer_ptr(cache, cache->k, layer), *vl = layer_ptr(cache, cache->v, layer);
+    hipError_t e = fc_launch_attention_generic(G, cache->cfg.dtype, q, kl, vl, pos, A, kv_len, out,
+                                               (hipStream_t)stream);
+    return e == hipSuccess ? FC_OK : hip_fail(e, "attention launch");
+}
+
+fc_status fc_refresh(fc_cache *cache, int32_t layer, const void *x, const void *w_qkv, const void *b_qkv,
+                     int32_t start, int32_t R, int32_t kv_len, void *q_scratch, void *out,
+                     void *workspace, size_t workspace_bytes, void *stream)
+{
+    fc_status st = check_cache_layer(cache, layer);
+    if (st != FC_OK) return st;
+    if (!x || !w_qkv || !q_scratch) return fail(FC_ERR_INVALID_ARG, "x, w_qkv or q_scratch is NULL");
+    if (R < 1) return fail(FC_ERR_INVALID_ARG, "R %d must be >= 1", R);
+    if (start < 0 || start > cache->cfg.max_seq - R)
+        return fail(FC_ERR_BOUNDS, "rows [%d, %d+%d) outside the cache of %d rows", start, start, R,
+                    cache->cfg.max_seq);
+    if (out) {
+        // validate the attention half before anything is enqueued, so a failure has no side effects
+        if (kv_len < 1 || kv_len > cache->cfg.max_seq)
+            return fail(FC_ERR_BOUNDS, "kv_len %d outside [1, %d]", kv_len, cache->cfg.max_seq);
+        if (start + R > kv_len)
+            return fail(FC_ERR_BOUNDS, "refreshed rows end at %d, beyond kv_len %d", start + R, kv_len);
+        const FcAttnPlan plan = fc_plan_attention(cache->cfg, R, kv_len);
+        const size_t need = fc_plan_workspace(cache->cfg, plan, R);
+        if (need > 0 && (!workspace || workspace_bytes < need))
+            return fail(FC_ERR_WORKSPACE, "workspace of %zu bytes needed, %zu given", need,
+                        workspace ? workspace_bytes : (size_t)0);
+    }
+    st = fc_qkv_project_scatter(cache, layer, x, w_qkv, b_qkv, start, R, nullptr, q_scratch, stream);
+    if (st != FC_OK || !out) return st;
+    return fc_active_attention(cache, layer, q_scratch, R, kv_len, nullptr, out, workspace, workspace_bytes,
+                               stream);
+}
+
+}  // extern "C"

