@@ -3,6 +3,7 @@
 #include <math.h>
 #include <stdarg.h>
 #include <stdio.h>
+#include <stdlib.h>
 #include <string.h>
 
 #include <new>
@@ -91,25 +92,59 @@ fc_status hip_fail(hipError_t e, const char *what)
 // ---------------------------------------------------------------------------------------------
 // Launch planning (pure host functions).
 
+// Tuning knobs for experiments: FC_ATTN_TILES=R,W forces the workgroup shape, FC_ATTN_WGS the
+// number of workgroups the split heuristic aims for.  Read once.
+static void attn_env(int *r, int *w, int *target)
+{
+    static int er = 0, ew = 0, et = 0, init = 0;
+    if (!init) {
+        if (const char *e = getenv("FC_ATTN_TILES")) sscanf(e, "%d,%d", &er, &ew);
+        if (const char *e = getenv("FC_ATTN_WGS")) et = atoi(e);
+        init = 1;
+    }
+    if (er > 0 && ew > 0) {
+        *r = er;
+        *w = ew;
+    }
+    if (et > 0) *target = et;
+}
+
 FcAttnPlan fc_plan_attention(const fc_config &cfg, int A, int kv_len)
 {
-    (void)A;
-    (void)kv_len;
-    (void)cfg;
     FcAttnPlan p;
-    p.kind = 0;
-    p.splits = 1;
-    p.keys_per_split = 0;
-    p.row_tiles = 0;
-    p.tiles_per_wg = 0;
+    memset(&p, 0, sizeof p);
+    p.splits = p.splits_bound = 1;
+    if (cfg.dtype != FC_BF16 || cfg.head_dim != 128) return p;  // kind 0: generic kernel
+    p.kind = 1;
+    const int g = cfg.n_q_heads / cfg.n_kv_heads;
+    p.row_tiles = (int)(((int64_t)g * A + 31) / 32);
+    int R = p.row_tiles >= 4 ? 4 : 2, W = 4, target = 512;
+    attn_env(&R, &W, &target);
+    if (!((R == 2 && W == 4) || (R == 4 && W == 4) || (R == 4 && W == 8) || (R == 8 && W == 8))) {
+        R = p.row_tiles >= 4 ? 4 : 2;
+        W = 4;
+    }
+    p.tiles_per_wg = R;
+    p.waves = W;
+    const int64_t n_rg = (p.row_tiles + R - 1) / R;
+    const int64_t base = (int64_t)cfg.batch * cfg.n_kv_heads * n_rg;
+    const int n_stages = (kv_len + 63) / 64;
+    int64_t splits = (target + base - 1) / base;   // enough workgroups to fill the chip
+    const int64_t by_len = n_stages / 4 > 1 ? n_stages / 4 : 1;  // at least 256 keys per split
+    if (splits > by_len) splits = by_len;
+    if (splits < 1) splits = 1;
+    p.splits_bound = (int)splits;
+    const int stages_per_split = (int)((n_stages + splits - 1) / splits);
+    p.keys_per_split = stages_per_split * 64;
+    p.splits = (n_stages + stages_per_split - 1) / stages_per_split;
     return p;
 }
 
 size_t fc_plan_workspace(const fc_config &cfg, const FcAttnPlan &p, int A)
 {
-    if (p.kind == 0 || p.splits <= 1) return 0;
+    if (p.kind == 0 || p.splits_bound <= 1) return 0;
     // per (b, q head, row, split): Dh partial outputs + running max + running sum, fp32
-    return (size_t)cfg.batch * cfg.n_q_heads * A * p.splits * (cfg.head_dim + 2) * sizeof(float);
+    return (size_t)cfg.batch * cfg.n_q_heads * A * p.splits_bound * (cfg.head_dim + 2) * sizeof(float);
 }
 
 extern "C" {
@@ -283,8 +318,11 @@ fc_status fc_active_attention(fc_cache *cache, int32_t layer, const void *q, int
                     workspace ? workspace_bytes : (size_t)0);
     const FcGeom G = geom_of(cache);
     void *kl = layer_ptr(cache, cache->k, layer), *vl = layer_ptr(cache, cache->v, layer);
-    hipError_t e = fc_launch_attention_generic(G, cache->cfg.dtype, q, kl, vl, pos, A, kv_len, out,
-                                               (hipStream_t)stream);
+    hipError_t e = plan.kind == 1
+                       ? fc_launch_attention_mfma(G, plan, q, kl, vl, pos, A, kv_len, out, workspace,
+                                                  (hipStream_t)stream)
+                       : fc_launch_attention_generic(G, cache->cfg.dtype, q, kl, vl, pos, A, kv_len, out,
+                                                     (hipStream_t)stream);
     return e == hipSuccess ? FC_OK : hip_fail(e, "attention launch");
 }
 

@@ -39,11 +39,13 @@ __host__ __device__ inline size_t fc_v_index(const FcGeom &G, int b, int j, int 
 
 // Launch plan of the split-KV attention (host, pure function of the shape).
 struct FcAttnPlan {
-    int kind;         // 0 = generic kernel (no workspace), 1 = MFMA split-KV
-    int splits;       // key-range splits per (sequence, kv head, row group)
+    int kind;            // 0 = generic kernel (no workspace), 1 = MFMA split-KV
+    int splits;          // key ranges per (sequence, kv head); every one is non-empty
+    int splits_bound;    // upper bound of `splits` over all kv_len <= the given one (workspace sizing)
     int keys_per_split;  // multiple of 64
-    int row_tiles;    // 32-row tiles of the flattened (head-in-group, a) rows per (b, kv head)
-    int tiles_per_wg; // row tiles handled by one workgroup
+    int row_tiles;       // 32-row tiles of the flattened (head-in-group, a) rows per (b, kv head)
+    int tiles_per_wg;    // row tiles handled by one workgroup
+    int waves;           // waves per workgroup (tiles_per_wg or twice that)
 };
 FcAttnPlan fc_plan_attention(const fc_config &cfg, int A, int kv_len);
 size_t fc_plan_workspace(const fc_config &cfg, const FcAttnPlan &p, int A);
