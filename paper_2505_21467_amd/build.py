@@ -22,7 +22,7 @@ FLAGS = [
     # keep the compiler from forming packed-fp32 instructions
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
     "-I" + os.path.join(ROOT, "include"), "-I" + CSRC,
-]
+] + os.environ.get("FC_EXTRA_HIPCC_FLAGS", "").split()
 
 
 def _sources():

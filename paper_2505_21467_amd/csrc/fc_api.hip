@@ -118,14 +118,15 @@ FcAttnPlan fc_plan_attention(const fc_config &cfg, int A, int kv_len)
     p.kind = 1;
     const int g = cfg.n_q_heads / cfg.n_kv_heads;
     p.row_tiles = (int)(((int64_t)g * A + 31) / 32);
-    int R = p.row_tiles >= 4 ? 4 : 2, W = 4, target = 512;
+    // Row tiles per workgroup: 2 (four waves share one tile pair), 4 or 8 (each wave its own pair).
+    // One workgroup per compute unit (its LDS ring takes 128 KB), so aim for one wave of them.
+    const int r_default = p.row_tiles <= 2 ? 2 : (p.row_tiles <= 7 ? 4 : 8);
+    int R = r_default, W = 8, target = 256;
     attn_env(&R, &W, &target);
-    if (!((R == 2 && W == 4) || (R == 4 && W == 4) || (R == 4 && W == 8) || (R == 8 && W == 8))) {
-        R = p.row_tiles >= 4 ? 4 : 2;
-        W = 4;
-    }
+    if (R != 2 && R != 4 && R != 8) R = r_default;
+    if (W != 4 && W != 8) W = 8;
     p.tiles_per_wg = R;
-    p.waves = W;
+    p.waves = W;  // 8: one row tile per wave; 4: two
     const int64_t n_rg = (p.row_tiles + R - 1) / R;
     const int64_t base = (int64_t)cfg.batch * cfg.n_kv_heads * n_rg;
     const int n_stages = (kv_len + 63) / 64;
@@ -282,8 +283,11 @@ fc_status fc_qkv_project_scatter(fc_cache *cache, int32_t layer, const void *x, 
                     A, cache->cfg.max_seq);
     const FcGeom G = geom_of(cache);
     void *kl = layer_ptr(cache, cache->k, layer), *vl = layer_ptr(cache, cache->v, layer);
-    hipError_t e = fc_launch_project_generic(G, cache->cfg.dtype, x, w_qkv, b_qkv, pos, win_start, A, q_out,
-                                             kl, vl, (hipStream_t)stream);
+    hipError_t e = fc_project_mfma_supported(cache->cfg, A)
+                       ? fc_launch_project_mfma(G, x, w_qkv, b_qkv, pos, win_start, A, q_out, kl, vl,
+                                                (hipStream_t)stream)
+                       : fc_launch_project_generic(G, cache->cfg.dtype, x, w_qkv, b_qkv, pos, win_start, A,
+                                                   q_out, kl, vl, (hipStream_t)stream);
     return e == hipSuccess ? FC_OK : hip_fail(e, "projection launch");
 }
 

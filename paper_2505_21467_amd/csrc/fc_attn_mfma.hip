@@ -1,10 +1,16 @@
 // Active-query attention on the matrix cores (bf16, head_dim 128), split over the key axis.
 //
 // Work decomposition.  For one (sequence, kv head) the g*A query rows (head-in-group major, then
-// window row) are cut into 32-row tiles.  A workgroup owns R row tiles and one contiguous key range
-// ("split"); its W waves each own one row tile and, when W = 2R, one 32-key half of every 64-key
-// stage.  K rows and transposed V tiles stream HBM -> registers -> LDS as 16-byte coalesced chunks,
-// double buffered; every wave reads its operands from LDS.
+// window row) are cut into 32-row tiles.  A workgroup of W waves owns R row tiles and one contiguous
+// key range ("split").  A wave owns T row tiles; KW waves share the same tiles and divide the keys
+// among themselves (KW = 2: one 32-key half of every 64-key stage each; KW = 4: additionally
+// alternate stages), so R = T * W / KW.
+//
+// Data movement.  K rows and transposed V tiles stream HBM -> LDS with 16-byte direct-to-LDS loads
+// (no registers in between) into a ring of four 32 KB stages, two stages ahead of the compute.  The
+// LDS image is XOR-swizzled at 16-byte granularity (the swizzle is applied to the global address of
+// each lane, since direct loads land in lane order), so the 128-bit operand reads are spread over
+// the banks.
 //
 // Per 32 keys a wave computes S^T = K Q^T with v_mfma_f32_32x32x16_bf16 (K rows are the A operand,
 // so each lane ends up holding 16 scores of ONE query row), does the online-softmax update with a
@@ -16,6 +22,8 @@
 //
 // Each split writes unnormalised partial outputs with their running max and sum; a small second
 // kernel merges the splits.  With one split the first kernel writes the final output itself.
+#include <stdlib.h>
+
 #include "fc_device.h"
 #include "fc_internal.h"
 
@@ -25,12 +33,15 @@ typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 
 constexpr int DH = 128;
-constexpr int KT = 64;                         // keys per LDS stage (= one transposed V tile)
-constexpr int K_STRIDE = 272;                  // bytes per key row in LDS: 256 + 16 of padding
-constexpr int V_STRIDE = 144;                  // bytes per head-dim row of V^T in LDS: 128 + 16
-constexpr int K_BYTES = KT * K_STRIDE;         // 17408
-constexpr int V_BYTES = DH * V_STRIDE;         // 18432
-constexpr int STAGE_BYTES = K_BYTES + V_BYTES; // 35840
+constexpr int KT = 64;                 // keys per stage (= one transposed V tile)
+constexpr int K_BYTES = KT * DH * 2;   // 16384
+constexpr int STAGE_BYTES = 2 * K_BYTES;
+constexpr int SLOTS = 4;
+constexpr int AHEAD = 2;               // stages in flight ahead of the one being consumed
+constexpr int RING_BYTES = SLOTS * STAGE_BYTES;  // 131072
+constexpr int LDS_BYTES = 136 * 1024;            // ring, reused as exchange / output staging (8 x 17152 B)
+constexpr int XCHG_FLOATS = 66 * 64;   // one tile state handed between waves: 64 O regs + m + l per lane
+constexpr int OROW = 132;              // floats per row of the output staging tile (128 + 4 padding)
 
 struct AttnArgs {
     const uint16_t *Q;    // [B][Hq][A][128]
@@ -43,21 +54,34 @@ struct AttnArgs {
     int B, Hq, Hkv, g, A, kv_len, spad, max_seq;
     int row_tiles, n_rg, splits, keys_per_split, n_units;
     float c;              // softmax scale * log2(e)
+#ifdef FC_ATTN_TIMING
+    unsigned long long *dbg;  // tuning builds only: 8 cycle-counter stamps per workgroup
+    int dbg_flags;            // tuning builds only: 1 = skip the compute, 2 = skip the loads
+#endif
 };
+
+#ifdef FC_ATTN_TIMING
+#define FC_STAMP(k) do { if (p.dbg && threadIdx.x == 0) p.dbg[(size_t)blockIdx.x * 8 + (k)] = __builtin_readcyclecounter(); } while (0)
+#else
+#define FC_STAMP(k) do { } while (0)
+#endif
 
 __device__ __forceinline__ int kappa(int x) { return (x & 0x13) | ((x & 4) << 1) | ((x & 8) >> 1); }
 
-__device__ __forceinline__ float swap32(float v)
+// Lanes l and l^32 hold the two halves of a query row.  v_permlane32_swap exchanges the upper 32
+// lanes of its first operand with the lower 32 lanes of its second; fed the same value twice it
+// returns (lower half in all lanes, upper half in all lanes), so one instruction pairs the halves.
+__device__ __forceinline__ float row_max2(float v)
 {
-    // value held by the lane 32 away (the other half of the same query row)
-    return __shfl_xor(v, 32, 64);
+    const unsigned u = __float_as_uint(v);
+    const auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+    return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
 }
-
-__device__ __forceinline__ bf16x8 as_bf16x8(uint4 v)
+__device__ __forceinline__ float row_sum2(float v)
 {
-    union { uint4 u; bf16x8 b; } x;
-    x.u = v;
-    return x.b;
+    const unsigned u = __float_as_uint(v);
+    const auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+    return __uint_as_float(r[0]) + __uint_as_float(r[1]);
 }
 
 __device__ __forceinline__ bool row_is_padded(const int32_t *pos, int idx, int max_seq)
@@ -67,212 +91,345 @@ __device__ __forceinline__ bool row_is_padded(const int32_t *pos, int idx, int m
     return p < 0 || p >= max_seq;
 }
 
-template <int R, int W>
+__device__ __forceinline__ void load_lds16(const void *g, void *l)
+{
+    __builtin_amdgcn_global_load_lds((const void __attribute__((address_space(1))) *)g,
+                                     (void __attribute__((address_space(3))) *)l, 16, 0, 0);
+}
+
+// wait until at most N of this wave's vector-memory operations are outstanding
+template <int N>
+__device__ __forceinline__ void wait_vm()
+{
+    // gfx9 s_waitcnt immediate: vmcnt[3:0] | expcnt[6:4] | lgkmcnt[11:8] | vmcnt[5:4] at [15:14]
+    __builtin_amdgcn_s_waitcnt((N & 15) | (7 << 4) | (15 << 8) | ((N >> 4) << 14));
+}
+
+// State of one 32-row tile inside a wave.
+struct Tile {
+    bf16x8 q[8];
+    f32x16 o[4];
+    float m, l;
+};
+
+// One 32-key group against one row tile: online softmax on the scores s, bf16 probabilities out.
+__device__ __forceinline__ void softmax_tile(Tile &t, f32x16 &s, bf16x8 (&pf)[2], float c, int kbase, int k1,
+                                             int hi)
+{
+    if (kbase + 32 > k1) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int key = kbase + kappa(8 * (r >> 2) + 4 * hi + (r & 3));
+            s[r] = key < k1 ? s[r] : -INFINITY;
+        }
+    }
+    float mx = s[0];
+#pragma unroll
+    for (int r = 1; r < 16; ++r) mx = fmaxf(mx, s[r]);
+    mx = row_max2(mx);
+    // t.m is a reference maximum, not the exact running one: it only moves (and the accumulators are
+    // only rescaled) when some row's scores exceed it by more than 8 in the log2 domain, so the
+    // probabilities stay below 2^8 and the common case costs no rescaling work at all.
+    if (__any((mx - t.m) * c > 8.0f)) {
+        const float m_new = fmaxf(t.m, mx);
+        const float alpha = __builtin_amdgcn_exp2f((t.m - m_new) * c);
+        t.l *= alpha;
+#pragma unroll
+        for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) t.o[dt][r] *= alpha;
+        t.m = m_new;
+    }
+    const float mc = t.m * c;
+    float lsum = 0.f;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+        const float pr = __builtin_amdgcn_exp2f(s[r] * c - mc);
+        lsum += pr;
+        pf[r >> 3][r & 7] = (__bf16)pr;
+    }
+    t.l += lsum;
+}
+
+template <int T, int W, int KW>
 __global__ __launch_bounds__(W * 64) void k_attn_mfma(AttnArgs p)
 {
-    constexpr int KP = W / R;        // waves per row tile, each on its own 32-key half of a stage
-    static_assert(KP == 1 || KP == 2, "W must be R or 2R");
     constexpr int NT = W * 64;
-    constexpr int ROUNDS = 1024 / NT;  // 16-byte chunks per thread for one 16 KB tile
-    extern __shared__ __align__(16) unsigned char smem[];
+    constexpr int G = W / KW;      // wave groups: each owns T row tiles, its KW waves split the keys
+    constexpr int R = G * T;       // row tiles per workgroup
+    constexpr int LB = 32 / W;     // 1 KB load blocks per wave and stage
+    static_assert(W % KW == 0 && (KW == 1 || KW == 2 || KW == 4) && (W == 4 || W == 8), "shape");
+    extern __shared__ __align__(1024) unsigned char smem[];
 
+    FC_STAMP(0);
     // Workgroup -> (unit, row group): the n_rg workgroups that stream the same keys get ids that are
     // equal modulo 8, i.e. land on the same XCD and share its L2.
     const int id = blockIdx.x;
-    const int xcd = id & 7, q = id >> 3;
-    const int rg = q % p.n_rg;
-    const int unit = (q / p.n_rg) * 8 + xcd;
+    const int xcd = id & 7, qd = id >> 3;
+    const int rg = qd % p.n_rg;
+    const int unit = (qd / p.n_rg) * 8 + xcd;
     if (unit >= p.n_units) return;
     const int split = unit % p.splits, bj = unit / p.splits;
     const int b = bj / p.Hkv, j = bj % p.Hkv;
 
-    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // scalar: keeps per-wave branches uniform
     const int col = lane & 31, hi = lane >> 5;
-    const int rt = rg * R + (wave % R);
-    const int kh = wave / R;
-    const bool tile_valid = rt < p.row_tiles;
-    const int rho = rt * 32 + col;
-    const bool row_valid = tile_valid && rho < p.g * p.A;
-    const int hg = row_valid ? rho / p.A : 0;
-    const int a = row_valid ? rho - hg * p.A : 0;
-    const int hq = j * p.g + hg;
-    const size_t grow = ((size_t)b * p.Hq + hq) * p.A + a;  // global row id
+    const int gi = wave % G, kw = wave / G;
+    const int rt0 = rg * R + gi * T;  // first row tile of this wave
+    const int nrows = p.g * p.A;
 
-    bf16x8 qf[8];
-    {
-        const uint4 *qrow = (const uint4 *)(p.Q + grow * DH);
+    bool tile_valid[T], row_valid[T];
+    int hq[T], a[T];
+    size_t grow[T];
+    Tile t[T];
 #pragma unroll
-        for (int s = 0; s < 8; ++s) qf[s] = as_bf16x8(row_valid ? qrow[2 * s + hi] : make_uint4(0, 0, 0, 0));
+    for (int u = 0; u < T; ++u) {
+        tile_valid[u] = rt0 + u < p.row_tiles;
+        const int rho = (rt0 + u) * 32 + col;
+        row_valid[u] = tile_valid[u] && rho < nrows;
+        const int hg = row_valid[u] ? rho / p.A : 0;
+        a[u] = row_valid[u] ? rho - hg * p.A : 0;
+        hq[u] = j * p.g + hg;
+        grow[u] = ((size_t)b * p.Hq + hq[u]) * p.A + a[u];
+        const uint4 *qrow = (const uint4 *)(p.Q + grow[u] * DH);
+#pragma unroll
+        for (int s = 0; s < 8; ++s) {
+            union { uint4 u4; bf16x8 v; } x;
+            x.u4 = row_valid[u] ? qrow[2 * s + hi] : make_uint4(0, 0, 0, 0);
+            t[u].q[s] = x.v;
+        }
+#pragma unroll
+        for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) t[u].o[dt][r] = 0.f;
+        t[u].m = -INFINITY;
+        t[u].l = 0.f;
     }
 
     const int k0 = split * p.keys_per_split;
     const int k1 = min(p.kv_len, k0 + p.keys_per_split);
     const int n_stages = (k1 - k0 + KT - 1) / KT;
-    const uint16_t *Kbase = p.Kc + ((size_t)bj * p.spad) * DH;
-    const uint16_t *Vbase = p.Vc + ((size_t)bj * p.spad) * DH;
 
-    uint4 kreg[ROUNDS], vreg[ROUNDS];
-    auto load_stage = [&](int ks) {
-        const uint4 *kg = (const uint4 *)(Kbase + (size_t)ks * DH);
-        const uint4 *vg = (const uint4 *)(Vbase + (size_t)ks * DH);  // tile ks/64 starts at ks*128
+    // ---- loader: the first half of the waves brings the 16 K blocks of a stage, the second half the
+    // 16 V^T blocks; a block is one wave-wide direct-to-LDS load of 1 KB.  Per-lane source offsets (in
+    // bytes, relative to the stage's first K row / V tile) are fixed for the whole kernel.
+    const unsigned char *gsrc;  // this wave's source for stage k0
+    uint32_t goff[LB];
+    uint32_t lds_dst;           // byte offset inside a stage of this wave's first block
+    if (wave < W / 2) {
+        gsrc = (const unsigned char *)(p.Kc + ((size_t)bj * p.spad + k0) * DH);
 #pragma unroll
-        for (int r = 0; r < ROUNDS; ++r) {
-            kreg[r] = kg[r * NT + tid];
-            vreg[r] = vg[r * NT + tid];
+        for (int i = 0; i < LB; ++i) {
+            const int bi = wave * LB + i;
+            const int rf = 4 * bi + (lane >> 4);  // LDS row 0..63: half * 32 + rho
+            const int rho = rf & 31;
+            const int key = (rf & 32) + kappa(rho);
+            const int c = (lane & 15) ^ (rho & 15);
+            goff[i] = (uint32_t)(key * 256 + c * 16);
         }
-    };
-    auto store_stage = [&](unsigned char *st, int ks) {
-        const bool tail = ks + KT > p.kv_len;  // rows past kv_len may hold anything: zero their V
+        lds_dst = (uint32_t)(wave * LB * 1024);
+    } else {
+        gsrc = (const unsigned char *)(p.Vc + ((size_t)bj * p.spad + k0) * DH);
 #pragma unroll
-        for (int r = 0; r < ROUNDS; ++r) {
-            const int c = r * NT + tid;
-            *(uint4 *)(st + (c >> 4) * K_STRIDE + (c & 15) * 16) = kreg[r];
-            uint4 v = vreg[r];
-            if (tail) {
-                const int key = ks + (c & 7) * 8;  // first of the 8 keys in this chunk
-                uint32_t *w = (uint32_t *)&v;
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    if (key + 2 * e >= p.kv_len) w[e] = 0;
-                    else if (key + 2 * e + 1 >= p.kv_len) w[e] &= 0xffffu;
-                }
-            }
-            *(uint4 *)(st + K_BYTES + (c >> 3) * V_STRIDE + (c & 7) * 16) = v;
+        for (int i = 0; i < LB; ++i) {
+            const int bi = (wave - W / 2) * LB + i;
+            const int dh = 8 * bi + (lane >> 3);
+            const int c = (lane & 7) ^ (dh & 7);
+            goff[i] = (uint32_t)(dh * 128 + c * 16);
         }
+        lds_dst = (uint32_t)(K_BYTES + (wave - W / 2) * LB * 1024);
+    }
+    auto issue_stage = [&](int st) {
+        const unsigned char *src = gsrc + (size_t)st * (STAGE_BYTES / 2);  // 64 keys * 256 B for K and for V
+        unsigned char *dst = smem + (st % SLOTS) * STAGE_BYTES + lds_dst;
+#ifdef FC_ATTN_TIMING
+        if (p.dbg_flags & 2) return;
+#endif
+#pragma unroll
+        for (int i = 0; i < LB; ++i) load_lds16(src + goff[i], dst + i * 1024);
     };
 
-    f32x16 O[4];
+    // ---- operand read offsets inside a stage (bytes)
+    uint32_t koff[8];  // K fragment ss of LDS row `col` (add half * 8192)
 #pragma unroll
-    for (int dt = 0; dt < 4; ++dt)
+    for (int ss = 0; ss < 8; ++ss) koff[ss] = (uint32_t)(col * 256 + (((2 * ss + hi) ^ (col & 15)) << 4));
+    uint32_t voff[2][2];  // V^T fragment (half, jj) of row `col` (add dt * 4096)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) O[dt][r] = 0.f;
-    float m = -INFINITY, l = 0.f;
+    for (int sub = 0; sub < 2; ++sub)
+#pragma unroll
+        for (int jj = 0; jj < 2; ++jj)
+            voff[sub][jj] = (uint32_t)(K_BYTES + col * 128 + (((4 * sub + 2 * jj + hi) ^ (col & 7)) << 4));
 
-    load_stage(k0);
-    store_stage(smem, k0);
-    __syncthreads();
+    if (n_stages > 0) issue_stage(0);
+    if (n_stages > 1) issue_stage(1);
+    FC_STAMP(1);
 
     for (int it = 0; it < n_stages; ++it) {
         const int ks = k0 + it * KT;
-        const bool more = it + 1 < n_stages;
-        if (more) load_stage(ks + KT);
-        const unsigned char *st = smem + (it & 1) * STAGE_BYTES;
+        if (it + AHEAD < n_stages) {
+            issue_stage(it + AHEAD);
+            wait_vm<2 * LB>();
+        } else if (it + 1 < n_stages) {
+            wait_vm<LB>();
+        } else {
+            wait_vm<0>();
+        }
+        __builtin_amdgcn_s_barrier();
+        unsigned char *st = smem + (it % SLOTS) * STAGE_BYTES;
 
-        if (tile_valid) {
+        if (ks + KT > p.kv_len) {
+            // Rows past kv_len may hold anything (also NaN): zero their V so that 0 * V stays 0.
+            for (int e = tid; e < DH * KT; e += NT) {
+                const int dh = e >> 6, kl = e & 63;
+                if (ks + kl >= p.kv_len)
+                    *(uint16_t *)(st + K_BYTES + dh * 128 + (((kl >> 3) ^ (dh & 7)) << 4) + (kl & 7) * 2) = 0;
+            }
+            __syncthreads();
+        }
+#ifdef FC_ATTN_TIMING
+        if (p.dbg_flags & 1) continue;
+#endif
+        if (KW == 4 && (it & 1) != (kw >> 1)) continue;
 #pragma unroll
-            for (int hh = 0; hh < 2 / KP; ++hh) {
-                const int sub = (KP == 2) ? kh : hh;
-                const int kbase = ks + 32 * sub;
-                if (kbase >= k1) continue;  // wave-uniform
-                f32x16 s;
+        for (int hh = 0; hh < (KW == 1 ? 2 : 1); ++hh) {
+            const int sub = (KW == 1) ? hh : (kw & 1);
+            const int kbase = ks + 32 * sub;
+            if (kbase >= k1 || !tile_valid[0]) continue;  // wave-uniform
+            const unsigned char *kb = st + sub * 8192;
+            bf16x8 kf[8];
 #pragma unroll
-                for (int r = 0; r < 16; ++r) s[r] = 0.f;
-                const unsigned char *krow = st + (32 * sub + kappa(col)) * K_STRIDE + hi * 16;
+            for (int ss = 0; ss < 8; ++ss) kf[ss] = *(const bf16x8 *)(kb + koff[ss]);
+            f32x16 s[T];
 #pragma unroll
-                for (int ss = 0; ss < 8; ++ss) {
-                    const bf16x8 kf = *(const bf16x8 *)(krow + ss * 32);
-                    s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ss], s, 0, 0, 0);
+            for (int u = 0; u < T; ++u) {
+#pragma unroll
+                for (int r = 0; r < 16; ++r) s[u][r] = 0.f;
+                if (u == 0 || tile_valid[u]) {
+#pragma unroll
+                    for (int ss = 0; ss < 8; ++ss)
+                        s[u] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[ss], t[u].q[ss], s[u], 0, 0, 0);
                 }
-                float mx = -INFINITY;
-                if (kbase + 32 > k1) {
+            }
+            bf16x8 vf[8];
 #pragma unroll
-                    for (int r = 0; r < 16; ++r) {
-                        const int key = kbase + kappa(8 * (r >> 2) + 4 * hi + (r & 3));
-                        if (key >= k1) s[r] = -INFINITY;
-                    }
-                }
+            for (int dt = 0; dt < 4; ++dt)
 #pragma unroll
-                for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s[r]);
-                mx = fmaxf(mx, swap32(mx));
-                const float m_new = fmaxf(m, mx);
-                const float alpha = __builtin_amdgcn_exp2f((m - m_new) * p.c);
-                if (__any(alpha != 1.0f)) {
-                    l *= alpha;
+                for (int jj = 0; jj < 2; ++jj)
+                    vf[dt * 2 + jj] = *(const bf16x8 *)(st + voff[sub][jj] + dt * 4096);
+#pragma unroll
+            for (int u = 0; u < T; ++u) {
+                if (u == 0 || tile_valid[u]) {
+                    bf16x8 pf[2];
+                    softmax_tile(t[u], s[u], pf, p.c, kbase, k1, hi);
 #pragma unroll
                     for (int dt = 0; dt < 4; ++dt)
 #pragma unroll
-                        for (int r = 0; r < 16; ++r) O[dt][r] *= alpha;
-                }
-                m = m_new;
-                const float mc = m_new * p.c;
-                bf16x8 pf[2];
-#pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    const float pr = __builtin_amdgcn_exp2f(s[r] * p.c - mc);
-                    l += pr;
-                    pf[r >> 3][r & 7] = (__bf16)pr;
-                }
-                const unsigned char *vrow = st + K_BYTES + col * V_STRIDE + (32 * sub + 8 * hi) * 2;
-#pragma unroll
-                for (int dt = 0; dt < 4; ++dt) {
-#pragma unroll
-                    for (int jj = 0; jj < 2; ++jj) {
-                        const bf16x8 vf = *(const bf16x8 *)(vrow + dt * 32 * V_STRIDE + jj * 32);
-                        O[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[jj], O[dt], 0, 0, 0);
-                    }
+                        for (int jj = 0; jj < 2; ++jj)
+                            t[u].o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[dt * 2 + jj], pf[jj], t[u].o[dt], 0, 0, 0);
                 }
             }
         }
-        if (more) store_stage(smem + ((it + 1) & 1) * STAGE_BYTES, ks + KT);
-        __syncthreads();
     }
+    __syncthreads();  // every wave is done with the ring; LDS is reused below
+    FC_STAMP(2);
 
-    l += swap32(l);
+    float *xch = (float *)smem;
+#pragma unroll
+    for (int u = 0; u < T; ++u) t[u].l = row_sum2(t[u].l);
 
-    if (KP == 2) {
-        // merge the two key halves of each row tile: the kh = 1 wave hands over through LDS
-        float *xo = (float *)smem + (size_t)(wave % R) * (66 * 64);
-        if (kh == 1) {
+    if (KW > 1) {
+        // merge the KW partial states of each tile into the kw == 0 wave
+        if (kw > 0) {
 #pragma unroll
-            for (int dt = 0; dt < 4; ++dt)
+            for (int u = 0; u < T; ++u) {
+                float *x = xch + (size_t)(((kw - 1) * G + gi) * T + u) * XCHG_FLOATS;
 #pragma unroll
-                for (int r = 0; r < 16; ++r) xo[(dt * 16 + r) * 64 + lane] = O[dt][r];
-            xo[64 * 64 + lane] = m;
-            xo[65 * 64 + lane] = l;
-        }
-        __syncthreads();
-        if (kh == 0) {
-            const float m1 = xo[64 * 64 + lane], l1 = xo[65 * 64 + lane];
-            const float mf = fmaxf(m, m1);
-            const float a0 = __builtin_amdgcn_exp2f((m - mf) * p.c);
-            const float a1 = __builtin_amdgcn_exp2f((m1 - mf) * p.c);
+                for (int dt = 0; dt < 4; ++dt)
 #pragma unroll
-            for (int dt = 0; dt < 4; ++dt)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) O[dt][r] = a0 * O[dt][r] + a1 * xo[(dt * 16 + r) * 64 + lane];
-            l = a0 * l + a1 * l1;
-            m = mf;
-        }
-    }
-    if (kh != 0 || !row_valid) return;
-
-    // lane holds, for its row, head-dim indices 32 dt + 8 (r / 4) + 4 hi + (r % 4)
-    if (p.splits == 1) {
-        const bool padded = row_is_padded(p.pos, b * p.A + a, p.max_seq);
-        const float inv = padded ? 0.f : 1.0f / l;
-        uint16_t *o = p.out + ((size_t)b * p.A + a) * ((size_t)p.Hq * DH) + (size_t)hq * DH;
-#pragma unroll
-        for (int dt = 0; dt < 4; ++dt)
-#pragma unroll
-            for (int rq = 0; rq < 4; ++rq) {
-                uint2 w;
-                w.x = (uint32_t)fc_bf16_bits(O[dt][4 * rq] * inv) | ((uint32_t)fc_bf16_bits(O[dt][4 * rq + 1] * inv) << 16);
-                w.y = (uint32_t)fc_bf16_bits(O[dt][4 * rq + 2] * inv) | ((uint32_t)fc_bf16_bits(O[dt][4 * rq + 3] * inv) << 16);
-                *(uint2 *)(o + 32 * dt + 8 * rq + 4 * hi) = w;
+                    for (int r = 0; r < 16; ++r) x[(dt * 16 + r) * 64 + lane] = t[u].o[dt][r];
+                x[64 * 64 + lane] = t[u].m;
+                x[65 * 64 + lane] = t[u].l;
             }
-    } else {
-        float *po = p.part_o + (grow * p.splits + split) * DH;
+        }
+        __syncthreads();
+        FC_STAMP(3);
+        if (kw == 0) {
+#pragma unroll
+            for (int u = 0; u < T; ++u) {
+                for (int w2 = 1; w2 < KW; ++w2) {
+                    const float *x = xch + (size_t)(((w2 - 1) * G + gi) * T + u) * XCHG_FLOATS;
+                    const float m1 = x[64 * 64 + lane], l1 = x[65 * 64 + lane];
+                    const float mf = fmaxf(t[u].m, m1);
+                    const float a0 = (t[u].m == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f((t[u].m - mf) * p.c);
+                    const float a1 = (m1 == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f((m1 - mf) * p.c);
+#pragma unroll
+                    for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+                        for (int r = 0; r < 16; ++r)
+                            t[u].o[dt][r] = a0 * t[u].o[dt][r] + a1 * x[(dt * 16 + r) * 64 + lane];
+                    t[u].l = a0 * t[u].l + a1 * l1;
+                    t[u].m = mf;
+                }
+            }
+        }
+        __syncthreads();  // the exchange area is reused as output staging
+        FC_STAMP(4);
+    }
+    if (kw != 0) return;
+
+    // ---- output.  Each owner wave stages its tile as [row][128] floats in its own LDS area, then
+    // writes whole rows: 512 contiguous bytes of partials, or 256 of final bf16 output.
+    float *stg = xch + (size_t)gi * (32 * OROW + 64);
+    size_t *rowid = (size_t *)(stg + 32 * OROW);  // 32 entries
+#pragma unroll
+    for (int u = 0; u < T; ++u) {
+        if (!tile_valid[u]) continue;
+        const float inv = (p.splits == 1) ? 1.0f / t[u].l : 1.0f;
 #pragma unroll
         for (int dt = 0; dt < 4; ++dt)
 #pragma unroll
             for (int rq = 0; rq < 4; ++rq)
-                *(float4 *)(po + 32 * dt + 8 * rq + 4 * hi) =
-                    make_float4(O[dt][4 * rq], O[dt][4 * rq + 1], O[dt][4 * rq + 2], O[dt][4 * rq + 3]);
+                *(float4 *)(stg + col * OROW + 32 * dt + 8 * rq + 4 * hi) =
+                    make_float4(t[u].o[dt][4 * rq] * inv, t[u].o[dt][4 * rq + 1] * inv,
+                                t[u].o[dt][4 * rq + 2] * inv, t[u].o[dt][4 * rq + 3] * inv);
         if (hi == 0) {
-            float *ml = p.part_ml + (grow * p.splits + split) * 2;
-            *(float2 *)ml = make_float2(m * p.c, l);
+            // destination row (or an all-ones marker for rows that do not exist)
+            size_t dst;
+            if (p.splits == 1) {
+                dst = ((size_t)b * p.A + a[u]) * ((size_t)p.Hq * DH) + (size_t)hq[u] * DH;
+                if (row_is_padded(p.pos, b * p.A + a[u], p.max_seq)) dst |= (size_t)1 << 62;
+            } else {
+                dst = (grow[u] * p.splits + split) * DH;
+                if (row_valid[u])
+                    *(float2 *)(p.part_ml + (grow[u] * p.splits + split) * 2) = make_float2(t[u].m * p.c, t[u].l);
+            }
+            rowid[col] = row_valid[u] ? dst : ~(size_t)0;
         }
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_s_waitcnt(0xc07f);  // lgkmcnt(0): the staged tile is visible to the whole wave
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            const int idx = i * 64 + lane;
+            const int row = idx >> 5, c4 = idx & 31;
+            const size_t dst = rowid[row];
+            if (dst == ~(size_t)0) continue;
+            const float4 v = *(const float4 *)(stg + row * OROW + c4 * 4);
+            if (p.splits == 1) {
+                const bool padded = (dst >> 62) & 1;
+                uint16_t *o = p.out + (dst & (((size_t)1 << 62) - 1)) + c4 * 4;
+                uint2 w;
+                w.x = padded ? 0u : ((uint32_t)fc_bf16_bits(v.x) | ((uint32_t)fc_bf16_bits(v.y) << 16));
+                w.y = padded ? 0u : ((uint32_t)fc_bf16_bits(v.z) | ((uint32_t)fc_bf16_bits(v.w) << 16));
+                *(uint2 *)o = w;
+            } else {
+                *(float4 *)(p.part_o + dst + c4 * 4) = v;
+            }
+        }
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_s_waitcnt(0xc07f);  // reads of the staging area are done before the next tile reuses it
     }
+    FC_STAMP(5);
 }
 
 // Merge the per-split partials of one query row: one block per (sequence, head, row), one thread
@@ -294,6 +451,7 @@ __global__ __launch_bounds__(DH) void k_attn_combine(AttnArgs p)
     float mx = -INFINITY;
     for (int s = 0; s < p.splits; ++s) mx = fmaxf(mx, ml[2 * s]);
     float num = 0.f, den = 0.f;
+#pragma unroll 8
     for (int s = 0; s < p.splits; ++s) {
         const float w = __builtin_amdgcn_exp2f(ml[2 * s] - mx);
         num += w * po[s * DH + i];
@@ -302,15 +460,15 @@ __global__ __launch_bounds__(DH) void k_attn_combine(AttnArgs p)
     o[i] = fc_bf16_bits(num / den);
 }
 
-template <int R, int W>
+template <int T, int W, int KW>
 hipError_t launch(const AttnArgs &args, hipStream_t s)
 {
-    static hipError_t attr = hipFuncSetAttribute((const void *)k_attn_mfma<R, W>,
-                                                 hipFuncAttributeMaxDynamicSharedMemorySize, 2 * STAGE_BYTES);
+    static hipError_t attr = hipFuncSetAttribute((const void *)k_attn_mfma<T, W, KW>,
+                                                 hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
     if (attr != hipSuccess) return attr;
     const int groups8 = (args.n_units + 7) / 8;
     const unsigned grid = (unsigned)(groups8 * 8 * args.n_rg);
-    k_attn_mfma<R, W><<<dim3(grid), dim3(W * 64), 2 * STAGE_BYTES, s>>>(args);
+    k_attn_mfma<T, W, KW><<<dim3(grid), dim3(W * 64), LDS_BYTES, s>>>(args);
     return hipGetLastError();
 }
 
@@ -343,12 +501,27 @@ hipError_t fc_launch_attention_mfma(const FcGeom &G, const FcAttnPlan &pl, const
     a.keys_per_split = pl.keys_per_split;
     a.n_units = G.B * G.Hkv * pl.splits;
     a.c = G.scale * 1.4426950408889634f;
+#ifdef FC_ATTN_TIMING
+    {
+        const char *env = getenv("FC_ATTN_DBG_PTR");
+        a.dbg = env ? (unsigned long long *)strtoull(env, nullptr, 0) : nullptr;
+        const char *fl = getenv("FC_ATTN_DBG_FLAGS");
+        a.dbg_flags = fl ? atoi(fl) : 0;
+    }
+#endif
     hipError_t e;
-    if (pl.tiles_per_wg == 2 && pl.waves == 4) e = launch<2, 4>(a, s);
-    else if (pl.tiles_per_wg == 4 && pl.waves == 4) e = launch<4, 4>(a, s);
-    else if (pl.tiles_per_wg == 4 && pl.waves == 8) e = launch<4, 8>(a, s);
-    else if (pl.tiles_per_wg == 8 && pl.waves == 8) e = launch<8, 8>(a, s);
-    else return hipErrorInvalidValue;
+    const int R = pl.tiles_per_wg;
+    if (pl.waves == 8) {  // one tile per wave
+        if (R == 8) e = launch<1, 8, 1>(a, s);
+        else if (R == 4) e = launch<1, 8, 2>(a, s);
+        else if (R == 2) e = launch<1, 8, 4>(a, s);
+        else return hipErrorInvalidValue;
+    } else {              // two tiles per wave
+        if (R == 8) e = launch<2, 4, 1>(a, s);
+        else if (R == 4) e = launch<2, 4, 2>(a, s);
+        else if (R == 2) e = launch<2, 4, 4>(a, s);
+        else return hipErrorInvalidValue;
+    }
     if (e != hipSuccess || pl.splits == 1) return e;
     k_attn_combine<<<dim3((unsigned)rows), dim3(DH), 0, s>>>(a);
     return hipGetLastError();

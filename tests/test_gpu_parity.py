@@ -111,6 +111,8 @@ def test_config1_tiny_fp32_refresh_vs_cached():
     ("bf16", 2, 128, 6, 3, 64, 97, 20),      # Dh 64, A not a multiple of 16
     ("f32", 2, 64, 6, 2, 128, 150, 17),      # fp32 with Dh 128, odd A
     ("bf16", 1, 256, 14, 2, 128, 64, 1),     # a single active row
+    ("bf16", 1, 256, 8, 1, 128, 200, 40),    # 10 row tiles per kv head: two row groups of 8 tiles
+    ("bf16", 2, 256, 16, 2, 128, 1500, 48),  # 12 row tiles, several key splits, ragged last stage
 ])
 def test_cached_step_matches_oracle(dtype, B, d, Hq, Hkv, Dh, L, A):
     _say("cached step %s B%d d%d Hq%d Hkv%d Dh%d L%d A%d" % (dtype, B, d, Hq, Hkv, Dh, L, A))
