@@ -178,6 +178,8 @@ fc_status fc_cache_alloc(const fc_config *cfg, void *k_storage, void *v_storage,
     c->k = k_storage;
     c->v = v_storage;
     c->owned = false;
+    for (int i = 0; i < 64; ++i)
+        c->inv_freq[i] = i < cfg->head_dim / 2 ? pow((double)cfg->rope_base, -2.0 * i / cfg->head_dim) : 0.0;
     if (!k_storage) {
         const size_t bytes = fc_cache_storage_bytes(cfg);
         void *k = nullptr, *v = nullptr;
@@ -284,7 +286,7 @@ fc_status fc_qkv_project_scatter(fc_cache *cache, int32_t layer, const void *x, 
     const FcGeom G = geom_of(cache);
     void *kl = layer_ptr(cache, cache->k, layer), *vl = layer_ptr(cache, cache->v, layer);
     hipError_t e = fc_project_mfma_supported(cache->cfg, A)
-                       ? fc_launch_project_mfma(G, x, w_qkv, b_qkv, pos, win_start, A, q_out, kl, vl,
+                       ? fc_launch_project_mfma(G, cache->inv_freq, x, w_qkv, b_qkv, pos, win_start, A, q_out, kl, vl,
                                                 (hipStream_t)stream)
                        : fc_launch_project_generic(G, cache->cfg.dtype, x, w_qkv, b_qkv, pos, win_start, A,
                                                    q_out, kl, vl, (hipStream_t)stream);

@@ -16,6 +16,7 @@ struct fc_cache {
     void *k;             // device
     void *v;             // device
     bool owned;
+    double inv_freq[64]; // rotary frequencies rope_base^(-2i/Dh), i < Dh/2, computed once on the host
 };
 
 // Geometry handed to kernels by value.
@@ -60,7 +61,7 @@ hipError_t fc_launch_attention_generic(const FcGeom &G, int dtype, const void *q
                                        const void *v_layer, const int32_t *pos, int A, int kv_len,
                                        void *out, hipStream_t s);
 bool fc_project_mfma_supported(const fc_config &cfg, int A);
-hipError_t fc_launch_project_mfma(const FcGeom &G, const void *x, const void *w, const void *bias,
+hipError_t fc_launch_project_mfma(const FcGeom &G, const double *inv_freq, const void *x, const void *w, const void *bias,
                                   const int32_t *pos, int win_start, int A, void *q_out,
                                   void *k_layer, void *v_layer, hipStream_t s);
 hipError_t fc_launch_attention_mfma(const FcGeom &G, const FcAttnPlan &p, const void *q,

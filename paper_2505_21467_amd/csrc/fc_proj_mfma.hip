@@ -7,12 +7,14 @@
 // X fragments are loaded straight from global memory into operand registers: no LDS, no transposes.
 //
 // A workgroup owns 16 rows of W -- 8 rows i0..i0+7 of one head and their rotary partners
-// i0+64..i0+71 -- and up to 64 rows of X.  Its four waves split the hidden dimension; every wave
-// issues all loads of its quarter of the 16 weight rows up front (about 30 KB in flight per wave, which
-// is what keeps HBM busy), multiplies, and the four partial tiles are summed through LDS.  In the
+// i0+64..i0+71 -- and up to 32 rows of X.  Its eight waves split the hidden dimension; every wave
+// issues all loads of its slice (weights from HBM, activations from L2) before the first multiply, so
+// there is no dependent chain of memory latencies, and the partial tiles are summed through LDS.  In the
 // 16x16 accumulator layout a lane holds 4 consecutive head-dim indices of one window row, and the
 // rotary partner of every value sits in the lane 32 away, so the rotation needs one cross-lane swap.
 // The rotated q goes to q_out; k and v go directly to their cache rows (v into the transposed tiles).
+#include <stdlib.h>
+
 #include "fc_device.h"
 #include "fc_internal.h"
 
@@ -31,8 +33,21 @@ struct ProjArgs {
     uint16_t *Vc;          // one layer
     FcGeom G;
     int M, A, K, win_start, n_tiles;
+    double log2_base_64;   // log2(rope_base) / 64
+#ifdef FC_ATTN_TIMING
+    unsigned long long *dbg;  // tuning builds only
+#endif
 };
 
+#ifdef FC_ATTN_TIMING
+#define FC_PSTAMP(k) do { if (p.dbg && threadIdx.x == 0) p.dbg[(size_t)blockIdx.x * 8 + (k)] = __builtin_readcyclecounter(); } while (0)
+#else
+#define FC_PSTAMP(k) do { } while (0)
+#endif
+
+#ifndef FC_PROJ_VARIANT
+#define FC_PROJ_VARIANT 0  // tuning builds: 1 = no activation loads, 2 = no weight loads
+#endif
 __device__ __forceinline__ bf16x8 ld8(const uint16_t *p)
 {
     union { uint4 u; bf16x8 v; } x;
@@ -48,11 +63,14 @@ __device__ __forceinline__ float swap32f(float v)
     return (threadIdx.x & 32) ? __uint_as_float(r[0]) : __uint_as_float(r[1]);
 }
 
-// KS = k-steps (of 32) per wave when known at compile time, 0 = runtime loop.
-template <int MT, int KS>
-__global__ __launch_bounds__(256) void k_proj_skinny(ProjArgs p)
+// NW = waves per workgroup (they split the hidden dimension), KS = k-steps (of 32) per wave when
+// known at compile time (then every load of the wave is issued before the first multiply), 0 = loop.
+template <int MT, int NW, int KS>
+__global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(4, 4))) void k_proj_skinny(ProjArgs p)
 {
-    __shared__ float red[3][MT][4][64];
+    __shared__ float red[NW - 1][MT][4][64];
+    __shared__ float2 cs[16 * MT][8];  // (cos, sin) for (window row of this chunk, rotary index i0 + e)
+    FC_PSTAMP(0);
     const FcGeom &G = p.G;
     // workgroup id -> (m chunk, n tile): chunks of one n tile have ids equal modulo 8 (same XCD)
     const int tiles8 = (p.n_tiles + 7) & ~7;
@@ -63,7 +81,7 @@ __global__ __launch_bounds__(256) void k_proj_skinny(ProjArgs p)
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int rho = lane & 15, q = lane >> 4;
     const int n = hs * 128 + (rho < 8 ? i0 + rho : 64 + i0 + rho - 8);
-    const int kq = p.K >> 2;  // hidden elements per wave
+    const int kq = p.K / NW;  // hidden elements per wave
     const int m0 = mc * (16 * MT);
 
     const uint16_t *wrow = p.W + (size_t)n * p.K + (size_t)wave * kq + 8 * q;
@@ -75,35 +93,64 @@ __global__ __launch_bounds__(256) void k_proj_skinny(ProjArgs p)
         xrow[mt] = p.X + (size_t)m * p.K + (size_t)wave * kq + 8 * q;
     }
 
+    // Rotary factors for this workgroup's rows and its 8 rotary indices, one (or two) per thread.
+    // The angle pos * inv_freq is formed and reduced to a fraction of a turn in double; the
+    // hardware sine/cosine take their argument in turns.  Called once the loads are in flight: the
+    // table does not depend on them and their latency covers it.
+    auto rope_table = [&]() {
+        if (hs >= G.Hq + G.Hkv) return;
+        for (int idx = tid; idx < 16 * MT * 8; idx += NW * 64) {
+            const int lr = idx >> 3, e = idx & 7;
+            const int m = min(m0 + lr, p.M - 1);
+            const int pp = p.pos ? p.pos[m] : p.win_start + (m % p.A);
+            // rope_base^(-2i/128) = 2^(-i * log2(base) / 64), evaluated in double
+            const double inv_freq = exp2(-(double)(i0 + e) * p.log2_base_64);
+            const double turns = (double)pp * inv_freq * 0.15915494309189533576888;
+            const float fr = (float)(turns - rint(turns));
+            cs[lr][e] = make_float2(__builtin_amdgcn_cosf(fr), __builtin_amdgcn_sinf(fr));
+        }
+    };
+
     f32x4 acc[MT];
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) acc[mt] = f32x4{0.f, 0.f, 0.f, 0.f};
 
     if (KS > 0) {
-        bf16x8 wf[KS > 0 ? KS : 1];
+        // All weight loads of the wave and the first half of its activation loads are issued before
+        // the first multiply; the second half follows once the first has been consumed, which keeps
+        // the kernel within 128 registers so that two workgroups share a compute unit.
+        constexpr int H = KS / 2;
+        bf16x8 wf[KS > 0 ? KS : 1], xf[MT][H > 0 ? H : 1];
 #pragma unroll
-        for (int s = 0; s < KS; ++s) wf[s] = ld8(wrow + 32 * s);
-        bf16x8 xf[2][MT][4];
+        for (int s = 0; s < KS; ++s) wf[s] = (FC_PROJ_VARIANT == 2) ? bf16x8{} : ld8(wrow + 32 * s);
 #pragma unroll
-        for (int mt = 0; mt < MT; ++mt)
+        for (int s = 0; s < H; ++s)
 #pragma unroll
-            for (int s = 0; s < 4; ++s) xf[0][mt][s] = ld8(xrow[mt] + 32 * s);
+            for (int mt = 0; mt < MT; ++mt) xf[mt][s] = (FC_PROJ_VARIANT == 1) ? wf[s] : ld8(xrow[mt] + 32 * s);
+        __builtin_amdgcn_sched_barrier(0);
+        FC_PSTAMP(1);
+        rope_table();
+        __builtin_amdgcn_sched_barrier(0);
+        FC_PSTAMP(2);
 #pragma unroll
-        for (int c = 0; c < KS / 4; ++c) {
-            if (c + 1 < KS / 4) {
+        for (int s = 0; s < H; ++s)
 #pragma unroll
-                for (int mt = 0; mt < MT; ++mt)
+            for (int mt = 0; mt < MT; ++mt)
+                acc[mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf[s], xf[mt][s], acc[mt], 0, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-                    for (int s = 0; s < 4; ++s) xf[(c + 1) & 1][mt][s] = ld8(xrow[mt] + 32 * (4 * (c + 1) + s));
-            }
+        for (int s = 0; s < H; ++s)
 #pragma unroll
-            for (int s = 0; s < 4; ++s)
+            for (int mt = 0; mt < MT; ++mt) xf[mt][s] = (FC_PROJ_VARIANT == 1) ? wf[H + s] : ld8(xrow[mt] + 32 * (H + s));
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-                for (int mt = 0; mt < MT; ++mt)
-                    acc[mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf[4 * c + s], xf[c & 1][mt][s], acc[mt], 0, 0, 0);
-        }
+        for (int s = 0; s < H; ++s)
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt)
+                acc[mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf[H + s], xf[mt][s], acc[mt], 0, 0, 0);
     } else {
         const int ks = kq >> 5;
+        rope_table();
         for (int s = 0; s < ks; ++s) {
             const bf16x8 wfrag = ld8(wrow + 32 * s);
 #pragma unroll
@@ -112,19 +159,23 @@ __global__ __launch_bounds__(256) void k_proj_skinny(ProjArgs p)
         }
     }
 
-    // sum the four hidden-dimension quarters in wave 0
+    // sum the partial tiles of the NW waves in wave 0
     if (wave > 0) {
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
             for (int r = 0; r < 4; ++r) red[wave - 1][mt][r][lane] = acc[mt][r];
     }
+    FC_PSTAMP(3);
     __syncthreads();
     if (wave > 0) return;
+    FC_PSTAMP(4);
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
-        for (int r = 0; r < 4; ++r) acc[mt][r] += red[0][mt][r][lane] + red[1][mt][r][lane] + red[2][mt][r][lane];
+        for (int r = 0; r < 4; ++r)
+#pragma unroll
+            for (int w2 = 0; w2 < NW - 1; ++w2) acc[mt][r] += red[w2][mt][r][lane];
 
     // lane (rho, q) holds W rows 4q..4q+3 of the tile for window row rho of each m tile:
     // q = 0,1 -> head-dim i0 + 4q + r; q = 2,3 -> 64 + i0 + 4(q-2) + r (the rotary partners)
@@ -151,9 +202,8 @@ __global__ __launch_bounds__(256) void k_proj_skinny(ProjArgs p)
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
                 const float other = swap32f(y[r]);
-                float c, s;
-                fc_rope_cs(valid ? pp : 0, ib + r, 128, G.log_base, &c, &s);
-                y[r] = second ? y[r] * c + other * s : y[r] * c - other * s;
+                const float2 f = cs[16 * mt + rho][4 * (q & 1) + r];
+                y[r] = second ? y[r] * f.x + other * f.y : y[r] * f.x - other * f.y;
             }
         }
         uint2 w;
@@ -174,16 +224,21 @@ __global__ __launch_bounds__(256) void k_proj_skinny(ProjArgs p)
             }
         }
     }
+    FC_PSTAMP(5);
 }
 
 template <int MT>
 hipError_t launch_mt(const ProjArgs &a, int m_chunks, hipStream_t s)
 {
     const unsigned grid = (unsigned)(((a.n_tiles + 7) & ~7) * m_chunks);
-    const int ks = a.K / 128;
-    if (ks == 28) k_proj_skinny<MT, 28><<<dim3(grid), dim3(256), 0, s>>>(a);
-    else if (ks == 32) k_proj_skinny<MT, 32><<<dim3(grid), dim3(256), 0, s>>>(a);
-    else k_proj_skinny<MT, 0><<<dim3(grid), dim3(256), 0, s>>>(a);
+    if (a.K % 256 == 0) {  // eight waves split the hidden dimension
+        const int ks = a.K / 256;
+        if (ks == 14) k_proj_skinny<MT, 8, 14><<<dim3(grid), dim3(512), 0, s>>>(a);
+        else if (ks == 16) k_proj_skinny<MT, 8, 16><<<dim3(grid), dim3(512), 0, s>>>(a);
+        else k_proj_skinny<MT, 8, 0><<<dim3(grid), dim3(512), 0, s>>>(a);
+    } else {
+        k_proj_skinny<MT, 4, 0><<<dim3(grid), dim3(256), 0, s>>>(a);
+    }
     return hipGetLastError();
 }
 
@@ -195,7 +250,7 @@ bool fc_project_mfma_supported(const fc_config &cfg, int A)
     return cfg.dtype == FC_BF16 && cfg.head_dim == 128 && cfg.hidden % 128 == 0;
 }
 
-hipError_t fc_launch_project_mfma(const FcGeom &G, const void *x, const void *w, const void *bias,
+hipError_t fc_launch_project_mfma(const FcGeom &G, const double *inv_freq, const void *x, const void *w, const void *bias,
                                   const int32_t *pos, int win_start, int A, void *q_out, void *k_layer,
                                   void *v_layer, hipStream_t s)
 {
@@ -213,7 +268,14 @@ hipError_t fc_launch_project_mfma(const FcGeom &G, const void *x, const void *w,
     a.K = G.d;
     a.win_start = win_start;
     a.n_tiles = (G.Hq + 2 * G.Hkv) * 8;
+    (void)inv_freq;
+    a.log2_base_64 = G.log_base * 1.4426950408889634074 / 64.0;
+#ifdef FC_ATTN_TIMING
+    {
+        const char *env = getenv("FC_PROJ_DBG_PTR");
+        a.dbg = env ? (unsigned long long *)strtoull(env, nullptr, 0) : nullptr;
+    }
+#endif
     if (a.M <= 16) return launch_mt<1>(a, 1, s);
-    if (a.M <= 32) return launch_mt<2>(a, 1, s);
-    return launch_mt<4>(a, (a.M + 63) / 64, s);
+    return launch_mt<2>(a, (a.M + 31) / 32, s);
 }
