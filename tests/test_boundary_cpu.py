@@ -132,7 +132,9 @@ def test_workspace_is_demanded_when_the_plan_splits_keys():
     h = fc.fc_cache_alloc(c, FAKE, FAKE)
     try:
         _raises(fc.FC_ERR_WORKSPACE, fc.fc_active_attention, h, 0, FAKE, 32, 16800, None, FAKE, None, 0, 0)
-        _raises(fc.FC_ERR_WORKSPACE, fc.fc_active_attention, h, 0, FAKE, 32, 16800, None, FAKE, FAKE, need - 1, 0)
+        # `need` covers every window of up to 32 rows; any window's own requirement is far above 4 KB
+        _raises(fc.FC_ERR_WORKSPACE, fc.fc_active_attention, h, 0, FAKE, 32, 16800, None, FAKE, FAKE, 4096, 0)
+        _raises(fc.FC_ERR_WORKSPACE, fc.fc_active_attention, h, 0, FAKE, 7, 16800, None, FAKE, FAKE, 4096, 0)
         _raises(fc.FC_ERR_WORKSPACE, fc.fc_refresh, h, 0, FAKE, FAKE, None, 0, 32, 16800, FAKE, FAKE, FAKE, 8, 0)
     finally:
         fc.fc_cache_free(h)

@@ -1,0 +1,158 @@
+"""GPU parity at the full sizes of the measurement configurations, in the launch configuration the
+bench uses.  Where the whole problem is too large for the CPU oracle in seconds, one sampled
+sequence is checked in full (every sequence is independent on this path)."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import fc_oracle as orc
+from paper_2505_21467_amd import binding as fc
+from paper_2505_21467_amd import inputs
+from tests.harness import GpuLayerCache, OracleLayerCache, assert_close
+
+pytestmark = pytest.mark.gpu
+
+
+def _say(msg):
+    print("[case] " + msg, flush=True)
+
+
+def _window_rows(K, V, o, lo, hi, dtype, what):
+    assert_close(K[:, :, lo:hi], o.Kc[:, :, lo:hi], dtype, what + " K window rows")
+    assert_close(V[:, :, lo:hi], o.Vc[:, :, lo:hi], dtype, what + " V window rows")
+
+
+def test_config2_dream_shaped_cached_step():
+    w = inputs.C2
+    L, A, S = w.cached_len, w.active, w.kv_len
+    _say("config2 bf16 B1 d3584 28/4 Dh128 L1024 A32")
+    g = GpuLayerCache(w.dtype, 1, w.hidden, w.n_q_heads, w.n_kv_heads, w.head_dim, S, max_rows=A, fill=0.5)
+    o = OracleLayerCache(w.dtype, 1, w.hidden, w.n_q_heads, w.n_kv_heads, w.head_dim, S, fill=0.5)
+    K, V = inputs.kv_fill(w, 0, L)
+    g.write_rows(0, K, V, 0)
+    o.write_rows(K, V, 0)
+    W, X = inputs.weights(w, 0), inputs.hidden_states(w, 0, A)
+    Qg, Og = g.step(0, X, W, None, L, S)
+    Qo, Oo = o.step(X, W, None, L, S)
+    assert_close(Qg, Qo, w.dtype, "Q")
+    assert_close(Og, Oo, w.dtype, "O")
+    Kg, Vg = g.read_rows(0, 0, S)
+    assert np.array_equal(Kg[:, :, :L], o.Kc[:, :, :L]) and np.array_equal(Vg[:, :, :L], o.Vc[:, :, :L])
+    _window_rows(Kg, Vg, o, L, S, w.dtype, "config2")
+    g.close()
+
+
+def test_config2_prompt_refresh_then_cached_step():
+    """The cache filled by a refresh of prompt activations (reduced prompt of 160 rows, full width)."""
+    w = inputs.C2.scaled(cached_len=160)
+    L, A, S = w.cached_len, w.active, w.kv_len
+    _say("config2-shaped refresh of %d prompt rows (K/V only), then cached step" % L)
+    g = GpuLayerCache(w.dtype, 1, w.hidden, w.n_q_heads, w.n_kv_heads, w.head_dim, S, max_rows=L, fill=0.0)
+    o = OracleLayerCache(w.dtype, 1, w.hidden, w.n_q_heads, w.n_kv_heads, w.head_dim, S, fill=0.0)
+    W = inputs.weights(w, 0)
+    Xp = inputs.hidden_states(w, 0, L, tag="x_prompt")
+    g.refresh(0, Xp, W, None, 0, L, want_out=False)
+    o.project_only(Xp, W, None, 0)
+    Kg, Vg = g.read_rows(0, 0, S)
+    _window_rows(Kg, Vg, o, 0, L, w.dtype, "prompt refresh")
+    X = inputs.hidden_states(w, 0, A)
+    Qg, Og = g.step(0, X, W, None, L, S)
+    Qo, Oo = o.step(X, W, None, L, S)
+    assert_close(Qg, Qo, w.dtype, "Q")
+    assert_close(Og, Oo, w.dtype, "O")
+    g.close()
+
+
+def test_config3_llada_shaped_cached_step():
+    w = inputs.C3
+    B, L, A, S = w.batch, w.cached_len, w.active, w.kv_len
+    _say("config3 bf16 B4 d4096 32/32 Dh128 L4096 A64 (direct K/V fill)")
+    g = GpuLayerCache(w.dtype, B, w.hidden, w.n_q_heads, w.n_kv_heads, w.head_dim, S, max_rows=A)
+    o = OracleLayerCache(w.dtype, B, w.hidden, w.n_q_heads, w.n_kv_heads, w.head_dim, S)
+    K, V = inputs.kv_fill(w, 0, L)
+    g.write_rows(0, K, V, 0)
+    o.write_rows(K, V, 0)
+    W, X = inputs.weights(w, 0), inputs.hidden_states(w, 0, A)
+    Qg, Og = g.step(0, X, W, None, L, S)
+    Qo, Oo = o.step(X, W, None, L, S)
+    assert_close(Qg, Qo, w.dtype, "Q")
+    assert_close(Og, Oo, w.dtype, "O")
+    Kg, Vg = g.read_rows(0, L, A)
+    assert_close(Kg, o.Kc[:, :, L:S], w.dtype, "K window rows")
+    assert_close(Vg, o.Vc[:, :, L:S], w.dtype, "V window rows")
+    g.close()
+
+
+def test_config4_long_context_hundred_steps():
+    """100 consecutive cached steps, window sliding by 32 every 8 steps; parity at steps 0, 7, 8, 99."""
+    w = inputs.C4
+    A, S, P = w.active, w.kv_len, w.cached_len
+    check = (0, 7, 8, 99)
+    _say("config4 bf16 28/4 Dh128 L16384 kv_len %d, 100 steps, parity at %s" % (S, check))
+    g = GpuLayerCache(w.dtype, 1, w.hidden, w.n_q_heads, w.n_kv_heads, w.head_dim, S, max_rows=A)
+    o = OracleLayerCache(w.dtype, 1, w.hidden, w.n_q_heads, w.n_kv_heads, w.head_dim, S)
+    K, V = inputs.kv_fill(w, 0, S)
+    g.write_rows(0, K, V, 0)
+    o.write_rows(K, V, 0)
+    W = inputs.weights(w, 0)
+    for s in range(100):
+        ws, rows, _ = fc.fc_window(s, P, w.gen_len, w.block, w.steps_per_block)
+        assert (ws, rows) == orc.window(s, P, w.gen_len, w.block, w.steps_per_block)[:2]
+        assert ws == P + 32 * (s // 8) and rows == A
+        X = inputs.hidden_states(w, 0, A, tag="x.%d" % s)
+        Qg, Og = g.step(0, X, W, None, ws, S)
+        if s in check:
+            _say("  step %d" % s)
+            Qo, Oo = o.step(X, W, None, ws, S)
+            assert_close(Qg, Qo, w.dtype, "step %d Q" % s)
+            assert_close(Og, Oo, w.dtype, "step %d O" % s)
+        elif s % 8 == 7:
+            # the last write to a finished block is what later steps attend to
+            o.project_only(X, W, None, ws)
+    assert ws + A == S
+    Kg, Vg = g.read_rows(0, 0, S)
+    assert np.array_equal(Kg[:, :, :P], o.Kc[:, :, :P]) and np.array_equal(Vg[:, :, :P], o.Vc[:, :, :P])
+    _window_rows(Kg, Vg, o, P, S, w.dtype, "after 100 steps")
+    g.close()
+
+
+def test_config5_one_layer_of_28_cached_step_and_block_refresh():
+    """Layer 27 of a 28-layer, batch-8 cache: one cached step (all sequences against the oracle on a
+    sampled sequence) and the periodic refresh of the generation region."""
+    w = inputs.C5
+    B, P, G, A = w.batch, w.cached_len, w.gen_len, w.active
+    S = P + G
+    layer, b_s = 27, 5  # sampled sequence
+    _say("config5 bf16 B8 28 layers P2048 G256: layer %d, oracle on sequence %d" % (layer, b_s))
+    g = GpuLayerCache(w.dtype, B, w.hidden, w.n_q_heads, w.n_kv_heads, w.head_dim, S, n_layers=w.n_layers,
+                      max_rows=G)
+    o = OracleLayerCache(w.dtype, 1, w.hidden, w.n_q_heads, w.n_kv_heads, w.head_dim, S)
+    K, V = inputs.kv_fill(w, 0, S)  # stands in for the initial full pass
+    g.write_rows(layer, K, V, 0)
+    o.write_rows(K[b_s:b_s + 1], V[b_s:b_s + 1], 0)
+    W = inputs.weights(w, 0, layer=layer)
+    s = 27  # block 3
+    ws, rows, ra = fc.fc_window(s, P, G, w.block, w.steps_per_block, w.refresh_every)
+    assert (ws, rows, ra) == (P + 96, 32, 0)
+    X = inputs.hidden_states(w, 0, A, tag="x.%d" % s)
+    Qg, Og = g.step(layer, X, W, None, ws, S)
+    Qo, Oo = o.step(X[b_s:b_s + 1], W, None, ws, S)
+    assert_close(Qg[b_s:b_s + 1], Qo, w.dtype, "cached Q")
+    assert_close(Og[b_s:b_s + 1], Oo, w.dtype, "cached O")
+    assert np.all(np.isfinite(Og))
+
+    _say("  refresh of the generation region [2048, 2304) after step 31")
+    assert fc.fc_window(31, P, G, w.block, w.steps_per_block, w.refresh_every)[2] == 1
+    Xr = inputs.hidden_states(w, 0, G, tag="x.refresh")
+    Qg, Og = g.refresh(layer, Xr, W, None, P, S)
+    Qo, Oo = o.step(Xr[b_s:b_s + 1], W, None, P, S)
+    assert_close(Qg[b_s:b_s + 1], Qo, w.dtype, "refresh Q")
+    assert_close(Og[b_s:b_s + 1], Oo, w.dtype, "refresh O")
+    Kg, Vg = g.read_rows(layer, 0, S)
+    Kf, Vf = inputs.as_oracle(K), inputs.as_oracle(V)
+    assert np.array_equal(Kg[:, :, :P], Kf[:, :, :P]) and np.array_equal(Vg[:, :, :P], Vf[:, :, :P])
+    assert_close(Kg[b_s:b_s + 1, :, P:], o.Kc[:, :, P:], w.dtype, "refresh K rows")
+    assert_close(Vg[b_s:b_s + 1, :, P:], o.Vc[:, :, P:], w.dtype, "refresh V rows")
+    K0, V0 = g.read_rows(0, 0, 64)  # other layers untouched
+    assert np.all(K0 == 0) and np.all(V0 == 0)
+    g.close()
