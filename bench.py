@@ -184,6 +184,15 @@ def main():
         "host_wall_us_per_step": round(t_host * 1e6 / args.steps, 2),
     }
 
+    # A plain device-to-device copy of known size, so that a counter run of this same command
+    # (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE) can be scaled: 256 MiB read and 256 MiB written.
+    cal_src = torch.ones(64 * 1024 * 1024, dtype=torch.float32, device=dev)
+    cal_dst = torch.empty_like(cal_src)
+    for _ in range(3):
+        cal_dst.copy_(cal_src)
+    torch.cuda.synchronize()
+    out["calibration_copy_bytes"] = cal_src.numel() * 4
+
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(w, inputs)
 
