@@ -195,6 +195,30 @@ fc_status fc_cache_alloc(const fc_config *cfg, void *k_storage, void *v_storage,
         c->v = v;
         c->owned = true;
     }
+    // Scratch for kernels that hand partial results between workgroups.  On a host without a GPU
+    // (argument-validation tests) the handle is still created; compute calls then fail at launch.
+    c->scratch = nullptr;
+    {
+        void *s = nullptr;
+        hipError_t e = hipMalloc(&s, FC_SCRATCH_BYTES);
+        if (e == hipSuccess) e = hipMemset(s, 0, FC_SCRATCH_COUNTER_BYTES);
+        if (e == hipSuccess) {
+            c->scratch = s;
+        } else {
+            (void)hipGetLastError();
+            if (s) (void)hipFree(s);
+            int ndev = 0;
+            if (hipGetDeviceCount(&ndev) == hipSuccess && ndev > 0) {
+                if (c->owned) {
+                    (void)hipFree(c->k);
+                    (void)hipFree(c->v);
+                }
+                delete c;
+                return fail(FC_ERR_OOM, "could not allocate %u bytes of device scratch", FC_SCRATCH_BYTES);
+            }
+            (void)hipGetLastError();
+        }
+    }
     *out = c;
     return FC_OK;
 }
@@ -206,6 +230,10 @@ fc_status fc_cache_free(fc_cache *cache)
     if (cache->owned) {
         hipError_t e1 = hipFree(cache->k), e2 = hipFree(cache->v);
         if (e1 != hipSuccess || e2 != hipSuccess) st = hip_fail(e1 != hipSuccess ? e1 : e2, "hipFree");
+    }
+    if (cache->scratch) {
+        hipError_t e = hipFree(cache->scratch);
+        if (e != hipSuccess && st == FC_OK) st = hip_fail(e, "hipFree");
     }
     delete cache;
     return st;
@@ -287,7 +315,7 @@ fc_status fc_qkv_project_scatter(fc_cache *cache, int32_t layer, const void *x, 
     void *kl = layer_ptr(cache, cache->k, layer), *vl = layer_ptr(cache, cache->v, layer);
     hipError_t e = fc_project_mfma_supported(cache->cfg, A)
                        ? fc_launch_project_mfma(G, cache->inv_freq, x, w_qkv, b_qkv, pos, win_start, A, q_out, kl, vl,
-                                                (hipStream_t)stream)
+                                                cache->scratch, (hipStream_t)stream)
                        : fc_launch_project_generic(G, cache->cfg.dtype, x, w_qkv, b_qkv, pos, win_start, A,
                                                    q_out, kl, vl, (hipStream_t)stream);
     return e == hipSuccess ? FC_OK : hip_fail(e, "projection launch");

@@ -17,7 +17,14 @@ struct fc_cache {
     void *v;             // device
     bool owned;
     double inv_freq[64]; // rotary frequencies rope_base^(-2i/Dh), i < Dh/2, computed once on the host
+    // Device scratch owned by the handle (nullptr when no GPU was present at creation): arrival
+    // counters, zero between calls, followed by space for cross-workgroup partial sums.
+    void *scratch;
 };
+
+#define FC_SCRATCH_COUNTER_BYTES (64u * 1024u)
+#define FC_SCRATCH_PARTIAL_BYTES (32u * 1024u * 1024u)
+#define FC_SCRATCH_BYTES (FC_SCRATCH_COUNTER_BYTES + FC_SCRATCH_PARTIAL_BYTES)
 
 // Geometry handed to kernels by value.
 struct FcGeom {
@@ -63,7 +70,7 @@ hipError_t fc_launch_attention_generic(const FcGeom &G, int dtype, const void *q
 bool fc_project_mfma_supported(const fc_config &cfg, int A);
 hipError_t fc_launch_project_mfma(const FcGeom &G, const double *inv_freq, const void *x, const void *w, const void *bias,
                                   const int32_t *pos, int win_start, int A, void *q_out,
-                                  void *k_layer, void *v_layer, hipStream_t s);
+                                  void *k_layer, void *v_layer, void *scratch, hipStream_t s);
 hipError_t fc_launch_attention_mfma(const FcGeom &G, const FcAttnPlan &p, const void *q,
                                     const void *k_layer, const void *v_layer, const int32_t *pos,
                                     int A, int kv_len, void *out, void *workspace, hipStream_t s);

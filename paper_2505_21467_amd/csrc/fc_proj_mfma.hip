@@ -34,6 +34,8 @@ struct ProjArgs {
     FcGeom G;
     int M, A, K, win_start, n_tiles;
     double log2_base_64;   // log2(rope_base) / 64
+    unsigned *counters;    // cache scratch: one arrival counter per head slot, zero between launches
+    float *partials;       // cache scratch: partial tiles of the hidden-dimension slices
 #ifdef FC_ATTN_TIMING
     unsigned long long *dbg;  // tuning builds only
 #endif
@@ -227,6 +229,176 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(4, 4)))
     FC_PSTAMP(5);
 }
 
+// -------------------------------------------------------------------------------------------------
+// Head-split kernel for windows of at most 32 rows and hidden sizes that are multiples of 512.
+//
+// A workgroup owns one whole head slot (128 rows of W: 8 waves x 16 rows) and one 512-wide slice of
+// the hidden dimension, so the 32 x 512 slice of X is fetched once per workgroup (direct-to-LDS,
+// swizzled) and shared by the 8 waves instead of being re-read by every 16-row tile.  The partial
+// tiles of the hidden-dimension slices of a head go to the cache's device scratch and are summed
+// by k_proj_finish.
+constexpr int HS_K = 512;  // hidden elements per workgroup
+
+__device__ __forceinline__ void load_lds16p(const void *g, void *l)
+{
+    __builtin_amdgcn_global_load_lds((const void __attribute__((address_space(1))) *)g,
+                                     (void __attribute__((address_space(3))) *)l, 16, 0, 0);
+}
+
+template <int MT>
+__global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(4, 4))) void k_proj_headsplit(ProjArgs p)
+{
+    __shared__ __align__(1024) unsigned char xs[16 * MT * 1024];  // X slice: [row][64 chunks of 16 B]
+    const int S = p.K / HS_K;
+    const int hs = blockIdx.x / S, ks = blockIdx.x % S;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int rho = lane & 15, q = lane >> 4;
+    const int i0 = wave * 8;
+    const int n = hs * 128 + (rho < 8 ? i0 + rho : 64 + i0 + rho - 8);
+
+    // X slice -> LDS: one 1 KB row per wave-wide load; chunk c of row m is stored at c ^ (m & 15)
+#pragma unroll
+    for (int i = 0; i < 2 * MT; ++i) {
+        const int m = wave * 2 * MT + i;
+        const int mg = min(m, p.M - 1);
+        const int c = lane ^ (m & 15);
+        load_lds16p(p.X + (size_t)mg * p.K + (size_t)ks * HS_K + c * 8, xs + m * 1024);
+    }
+    // W fragments of this wave's 16 rows: all 16 k-steps in flight
+    const uint16_t *wrow = p.W + (size_t)n * p.K + (size_t)ks * HS_K + 8 * q;
+    bf16x8 wf[16];
+#pragma unroll
+    for (int s = 0; s < 16; ++s) wf[s] = ld8(wrow + 32 * s);
+    __builtin_amdgcn_sched_barrier(0);
+
+    __syncthreads();  // waits for every load of the workgroup, X slice included
+
+    f32x4 acc[MT];
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) acc[mt] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int s = 0; s < 16; ++s)
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) {
+            const int m = 16 * mt + rho;
+            const bf16x8 xf = *(const bf16x8 *)(xs + m * 1024 + (((4 * s + q) ^ (m & 15)) << 4));
+            acc[mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf[s], xf, acc[mt], 0, 0, 0);
+        }
+
+    // hand the partial tile over: [head][slice][wave][mt][r][lane]
+    float *part = p.partials + ((((size_t)hs * S + ks) * 8 + wave) * MT) * 256;
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) part[mt * 256 + r * 64 + lane] = acc[mt][r];
+}
+
+// Second half of the head-split projection: one wave per (head slot, 16-row tile) sums the partial
+// tiles of the hidden-dimension slices (a kernel boundary is the only cross-workgroup ordering used:
+// device-scope fences inside a kernel cost an L2 write-back per workgroup on this multi-die part),
+// then applies bias and rotary embedding and scatters q, k and v.  Rotary factors are computed per
+// lane: base^(-i/64) by binary powering in double, the angle reduced to a fraction of a turn in
+// double, hardware sine/cosine (argument in turns).
+template <int MT>
+__global__ __launch_bounds__(64) void k_proj_finish(ProjArgs p)
+{
+    const FcGeom &G = p.G;
+    const int S = p.K / HS_K;
+    const int hs = blockIdx.x >> 3, wave = blockIdx.x & 7;  // the wave index of the first kernel = tile
+    const int lane = threadIdx.x;
+    const int rho = lane & 15, q = lane >> 4;
+    const int i0 = wave * 8;
+
+    f32x4 acc[MT];
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) acc[mt] = f32x4{0.f, 0.f, 0.f, 0.f};
+    for (int kb = 0; kb < S; kb += 8) {  // eight slices' worth of loads in flight at a time
+        float v[8][MT][4];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const int k2 = min(kb + u, S - 1);
+            const float *pp2 = p.partials + ((((size_t)hs * S + k2) * 8 + wave) * MT) * 256;
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) v[u][mt][r] = pp2[mt * 256 + r * 64 + lane];
+        }
+#pragma unroll
+        for (int u = 0; u < 8; ++u)
+            if (kb + u < S) {
+#pragma unroll
+                for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) acc[mt][r] += v[u][mt][r];
+            }
+    }
+
+    const bool second = q >= 2;
+    const int ib = i0 + 4 * (q & 1);
+    const int d0 = (second ? 64 : 0) + ib;
+    const bool rotate = hs < G.Hq + G.Hkv;
+    double freq[4];  // base^(-(ib + r)/64) / (2 pi): turns per position
+    if (rotate) {
+        const double r1 = exp2(-p.log2_base_64);
+        double f = 0.15915494309189533576888, b2 = r1;
+#pragma unroll
+        for (int bit = 0; bit < 6; ++bit) {
+            if (ib & (1 << bit)) f *= b2;
+            b2 *= b2;
+        }
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            freq[r] = f;
+            f *= r1;
+        }
+    }
+    float bs[4] = {0.f, 0.f, 0.f, 0.f};
+    if (p.bias) {
+#pragma unroll
+        for (int r = 0; r < 4; ++r) bs[r] = fc_to_float(bf16_t{p.bias[hs * 128 + d0 + r]});
+    }
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) {
+        const int m = 16 * mt + rho;
+        const bool mvalid = m < p.M;
+        const int mm = mvalid ? m : 0;
+        const int b = mm / p.A, a = mm - b * p.A;
+        const int pp = p.pos ? p.pos[mm] : p.win_start + a;
+        const bool valid = mvalid && pp >= 0 && pp < G.max_seq;
+        float y[4];
+#pragma unroll
+        for (int r = 0; r < 4; ++r) y[r] = acc[mt][r] + bs[r];
+        if (rotate) {
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const float other = swap32f(y[r]);
+                const double turns = (double)pp * freq[r];
+                const float fr = (float)(turns - rint(turns));
+                const float c = __builtin_amdgcn_cosf(fr), sn = __builtin_amdgcn_sinf(fr);
+                y[r] = second ? y[r] * c + other * sn : y[r] * c - other * sn;
+            }
+        }
+        uint2 w;
+        w.x = (uint32_t)fc_bf16_bits(y[0]) | ((uint32_t)fc_bf16_bits(y[1]) << 16);
+        w.y = (uint32_t)fc_bf16_bits(y[2]) | ((uint32_t)fc_bf16_bits(y[3]) << 16);
+        if (hs < G.Hq) {
+            if (mvalid) {
+                if (!valid) w = make_uint2(0, 0);
+                *(uint2 *)(p.Q + (((size_t)b * G.Hq + hs) * p.A + a) * 128 + d0) = w;
+            }
+        } else if (valid) {
+            if (hs < G.Hq + G.Hkv) {
+                *(uint2 *)(p.Kc + fc_k_index(G, b, hs - G.Hq, pp, d0)) = w;
+            } else {
+                const int j = hs - G.Hq - G.Hkv;
+#pragma unroll
+                for (int r = 0; r < 4; ++r) p.Vc[fc_v_index(G, b, j, pp, d0 + r)] = fc_bf16_bits(y[r]);
+            }
+        }
+    }
+}
+
 template <int MT>
 hipError_t launch_mt(const ProjArgs &a, int m_chunks, hipStream_t s)
 {
@@ -252,7 +424,7 @@ bool fc_project_mfma_supported(const fc_config &cfg, int A)
 
 hipError_t fc_launch_project_mfma(const FcGeom &G, const double *inv_freq, const void *x, const void *w, const void *bias,
                                   const int32_t *pos, int win_start, int A, void *q_out, void *k_layer,
-                                  void *v_layer, hipStream_t s)
+                                  void *v_layer, void *scratch, hipStream_t s)
 {
     ProjArgs a;
     a.X = (const uint16_t *)x;
@@ -276,6 +448,21 @@ hipError_t fc_launch_project_mfma(const FcGeom &G, const double *inv_freq, const
         a.dbg = env ? (unsigned long long *)strtoull(env, nullptr, 0) : nullptr;
     }
 #endif
+    a.counters = (unsigned *)scratch;
+    a.partials = scratch ? (float *)((char *)scratch + FC_SCRATCH_COUNTER_BYTES) : nullptr;
+    const int slots = G.Hq + 2 * G.Hkv;
+    if (scratch && a.M <= 32 && a.K % HS_K == 0 && (size_t)slots * sizeof(unsigned) <= FC_SCRATCH_COUNTER_BYTES / 2 &&
+        (size_t)slots * (a.K / HS_K) * 8 * 2 * 256 * sizeof(float) <= FC_SCRATCH_PARTIAL_BYTES) {
+        const unsigned grid = (unsigned)(slots * (a.K / HS_K));
+        if (a.M <= 16) {
+            k_proj_headsplit<1><<<dim3(grid), dim3(512), 0, s>>>(a);
+            k_proj_finish<1><<<dim3((unsigned)slots * 8), dim3(64), 0, s>>>(a);
+        } else {
+            k_proj_headsplit<2><<<dim3(grid), dim3(512), 0, s>>>(a);
+            k_proj_finish<2><<<dim3((unsigned)slots * 8), dim3(64), 0, s>>>(a);
+        }
+        return hipGetLastError();
+    }
     if (a.M <= 16) return launch_mt<1>(a, 1, s);
     return launch_mt<2>(a, (a.M + 31) / 32, s);
 }
