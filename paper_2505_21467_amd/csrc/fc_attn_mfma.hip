@@ -347,7 +347,10 @@ __global__ __launch_bounds__(W * 64) void k_attn_mfma(AttnArgs p)
 #pragma unroll
                 for (int dt = 0; dt < 4; ++dt)
 #pragma unroll
-                    for (int r = 0; r < 16; ++r) x[(dt * 16 + r) * 64 + lane] = t[u].o[dt][r];
+                    for (int rq = 0; rq < 4; ++rq)  // 16-byte LDS accesses, lane-contiguous
+                        *(float4 *)(x + ((dt * 4 + rq) * 64 + lane) * 4) =
+                            make_float4(t[u].o[dt][4 * rq], t[u].o[dt][4 * rq + 1], t[u].o[dt][4 * rq + 2],
+                                        t[u].o[dt][4 * rq + 3]);
                 x[64 * 64 + lane] = t[u].m;
                 x[65 * 64 + lane] = t[u].l;
             }
@@ -366,8 +369,13 @@ __global__ __launch_bounds__(W * 64) void k_attn_mfma(AttnArgs p)
 #pragma unroll
                     for (int dt = 0; dt < 4; ++dt)
 #pragma unroll
-                        for (int r = 0; r < 16; ++r)
-                            t[u].o[dt][r] = a0 * t[u].o[dt][r] + a1 * x[(dt * 16 + r) * 64 + lane];
+                        for (int rq = 0; rq < 4; ++rq) {
+                            const float4 v = *(const float4 *)(x + ((dt * 4 + rq) * 64 + lane) * 4);
+                            t[u].o[dt][4 * rq] = a0 * t[u].o[dt][4 * rq] + a1 * v.x;
+                            t[u].o[dt][4 * rq + 1] = a0 * t[u].o[dt][4 * rq + 1] + a1 * v.y;
+                            t[u].o[dt][4 * rq + 2] = a0 * t[u].o[dt][4 * rq + 2] + a1 * v.z;
+                            t[u].o[dt][4 * rq + 3] = a0 * t[u].o[dt][4 * rq + 3] + a1 * v.w;
+                        }
                     t[u].l = a0 * t[u].l + a1 * l1;
                     t[u].m = mf;
                 }
@@ -448,14 +456,31 @@ __global__ __launch_bounds__(DH) void k_attn_combine(AttnArgs p)
     }
     const float *ml = p.part_ml + grow * p.splits * 2;
     const float *po = p.part_o + grow * p.splits * DH;
+    // sixteen splits' worth of loads in flight at a time
     float mx = -INFINITY;
-    for (int s = 0; s < p.splits; ++s) mx = fmaxf(mx, ml[2 * s]);
+    for (int sb = 0; sb < p.splits; sb += 16) {
+        float mv[16];
+#pragma unroll
+        for (int u = 0; u < 16; ++u) mv[u] = ml[2 * min(sb + u, p.splits - 1)];
+#pragma unroll
+        for (int u = 0; u < 16; ++u) mx = fmaxf(mx, mv[u]);
+    }
     float num = 0.f, den = 0.f;
-#pragma unroll 8
-    for (int s = 0; s < p.splits; ++s) {
-        const float w = __builtin_amdgcn_exp2f(ml[2 * s] - mx);
-        num += w * po[s * DH + i];
-        den += w * ml[2 * s + 1];
+    for (int sb = 0; sb < p.splits; sb += 16) {
+        float v[16];
+        float2 mlv[16];
+#pragma unroll
+        for (int u = 0; u < 16; ++u) {
+            const int s = min(sb + u, p.splits - 1);
+            v[u] = po[s * DH + i];
+            mlv[u] = *(const float2 *)(ml + 2 * s);
+        }
+#pragma unroll
+        for (int u = 0; u < 16; ++u) {
+            const float w = (sb + u < p.splits) ? __builtin_amdgcn_exp2f(mlv[u].x - mx) : 0.f;
+            num += w * v[u];
+            den += w * mlv[u].y;
+        }
     }
     o[i] = fc_bf16_bits(num / den);
 }
