@@ -10,13 +10,12 @@ struct bf16_t {
 __device__ __forceinline__ float fc_to_float(float v) { return v; }
 __device__ __forceinline__ float fc_to_float(bf16_t v) { return __uint_as_float((uint32_t)v.bits << 16); }
 
-// float -> bfloat16, round to nearest even; NaN stays NaN.
+// float -> bfloat16, round to nearest even (the hardware conversion of gfx950); NaN stays NaN.
 __device__ __forceinline__ uint16_t fc_bf16_bits(float f)
 {
-    uint32_t u = __float_as_uint(f);
-    if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x0040u);
-    u += 0x7fffu + ((u >> 16) & 1u);
-    return (uint16_t)(u >> 16);
+    union { __bf16 h; uint16_t u; } x;
+    x.h = (__bf16)f;
+    return x.u;
 }
 
 template <typename T>
