@@ -125,8 +125,12 @@ FcAttnPlan fc_plan_attention(const fc_config &cfg, int A, int kv_len)
     attn_env(&R, &W, &target);
     if (R != 2 && R != 4 && R != 8) R = r_default;
     if (W != 4 && W != 8) W = 8;
+    if (W == 4) {  // four-wave workgroups: two or four tiles, two workgroups per compute unit
+        if (R == 8) R = 4;
+        if (target == 256) target = 512;
+    }
     p.tiles_per_wg = R;
-    p.waves = W;  // 8: one row tile per wave; 4: two
+    p.waves = W;  // one row tile per wave group either way
     const int64_t n_rg = (p.row_tiles + R - 1) / R;
     const int64_t base = (int64_t)cfg.batch * cfg.n_kv_heads * n_rg;
     const int n_stages = (kv_len + 63) / 64;
@@ -144,8 +148,10 @@ FcAttnPlan fc_plan_attention(const fc_config &cfg, int A, int kv_len)
 size_t fc_plan_workspace(const fc_config &cfg, const FcAttnPlan &p, int A)
 {
     if (p.kind == 0 || p.splits_bound <= 1) return 0;
-    // per (b, q head, row, split): Dh partial outputs + running max + running sum, fp32
-    return (size_t)cfg.batch * cfg.n_q_heads * A * p.splits_bound * (cfg.head_dim + 2) * sizeof(float);
+    // per (32-row tile, split): 32 x Dh partial outputs + 32 x (running max, running sum), fp32
+    (void)A;
+    return (size_t)cfg.batch * cfg.n_kv_heads * p.row_tiles * p.splits_bound * 32 * (cfg.head_dim + 2) *
+           sizeof(float);
 }
 
 extern "C" {

@@ -36,10 +36,12 @@ constexpr int DH = 128;
 constexpr int KT = 64;                 // keys per stage (= one transposed V tile)
 constexpr int K_BYTES = KT * DH * 2;   // 16384
 constexpr int STAGE_BYTES = 2 * K_BYTES;
-constexpr int SLOTS = 4;
-constexpr int AHEAD = 2;               // stages in flight ahead of the one being consumed
-constexpr int RING_BYTES = SLOTS * STAGE_BYTES;  // 131072
-constexpr int LDS_BYTES = 136 * 1024;            // ring, reused as exchange / output staging (8 x 17152 B)
+// Eight-wave workgroups (one per compute unit) keep a ring of four stages, two in flight ahead of the
+// one being consumed; four-wave workgroups (two per compute unit, drifting independently so that one
+// computes while the other waits) keep two stages, one in flight.  The ring is reused as exchange /
+// output staging area (17152 B per wave group).
+__host__ __device__ constexpr int ring_slots(int W) { return W == 8 ? 4 : 2; }
+__host__ __device__ constexpr int lds_bytes(int W) { return W == 8 ? 136 * 1024 : 68 * 1024; }
 constexpr int XCHG_FLOATS = 66 * 64;   // one tile state handed between waves: 64 O regs + m + l per lane
 constexpr int OROW = 132;              // floats per row of the output staging tile (128 + 4 padding)
 
@@ -49,8 +51,8 @@ struct AttnArgs {
     const uint16_t *Vc;   // one layer, [B][Hkv][spad/64][128][64]
     const int32_t *pos;   // [B][A] or nullptr
     uint16_t *out;        // [B][A][Hq*128]
-    float *part_o;        // [B*Hq*A][splits][128]
-    float *part_ml;       // [B*Hq*A][splits][2]  (max in the log2 domain, sum)
+    float *part_o;        // [B*Hkv*row_tiles][splits][16 slots][64 lanes][4]: accumulators as the lanes hold them
+    float *part_ml;       // [B*Hkv*row_tiles][splits][32 rows][2]  (max in the log2 domain, sum)
     int B, Hq, Hkv, g, A, kv_len, spad, max_seq;
     int row_tiles, n_rg, splits, keys_per_split, n_units;
     float c;              // softmax scale * log2(e)
@@ -61,7 +63,7 @@ struct AttnArgs {
 };
 
 #ifdef FC_ATTN_TIMING
-#define FC_STAMP(k) do { if (p.dbg && threadIdx.x == 0) p.dbg[(size_t)blockIdx.x * 8 + (k)] = __builtin_readcyclecounter(); } while (0)
+#define FC_STAMP(k) do { if (p.dbg && threadIdx.x == 0) p.dbg[(size_t)blockIdx.x * 8 + (k)] = __builtin_amdgcn_s_memrealtime(); } while (0)
 #else
 #define FC_STAMP(k) do { } while (0)
 #endif
@@ -152,9 +154,11 @@ __device__ __forceinline__ void softmax_tile(Tile &t, f32x16 &s, bf16x8 (&pf)[2]
 }
 
 template <int T, int W, int KW>
-__global__ __launch_bounds__(W * 64) void k_attn_mfma(AttnArgs p)
+__global__ __launch_bounds__(W * 64) __attribute__((amdgpu_waves_per_eu(2, 2))) void k_attn_mfma(AttnArgs p)
 {
     constexpr int NT = W * 64;
+    constexpr int SLOTS = ring_slots(W);
+    constexpr int AHEAD = SLOTS / 2;  // stages in flight ahead of the one being consumed
     constexpr int G = W / KW;      // wave groups: each owns T row tiles, its KW waves split the keys
     constexpr int R = G * T;       // row tiles per workgroup
     constexpr int LB = 32 / W;     // 1 KB load blocks per wave and stage
@@ -262,20 +266,30 @@ __global__ __launch_bounds__(W * 64) void k_attn_mfma(AttnArgs p)
             voff[sub][jj] = (uint32_t)(K_BYTES + col * 128 + (((4 * sub + 2 * jj + hi) ^ (col & 7)) << 4));
 
     if (n_stages > 0) issue_stage(0);
-    if (n_stages > 1) issue_stage(1);
+    if (AHEAD > 1 && n_stages > 1) issue_stage(1);
     FC_STAMP(1);
 
     for (int it = 0; it < n_stages; ++it) {
         const int ks = k0 + it * KT;
-        if (it + AHEAD < n_stages) {
-            issue_stage(it + AHEAD);
-            wait_vm<2 * LB>();
-        } else if (it + 1 < n_stages) {
-            wait_vm<LB>();
+        if (SLOTS == 4) {
+            // The slot of stage it+2 last held stage it-2, which every wave left before the barrier of
+            // stage it-1: the load can go out ahead of this stage's barrier.
+            if (it + AHEAD < n_stages) {
+                issue_stage(it + AHEAD);
+                wait_vm<2 * LB>();
+            } else if (it + 1 < n_stages) {
+                wait_vm<LB>();
+            } else {
+                wait_vm<0>();
+            }
+            __builtin_amdgcn_s_barrier();
         } else {
+            // Two slots: the next stage overwrites stage it-1, which other waves may still be reading
+            // until they arrive at this barrier, so its load goes out behind the barrier.
             wait_vm<0>();
+            __builtin_amdgcn_s_barrier();
+            if (it + 1 < n_stages) issue_stage(it + 1);
         }
-        __builtin_amdgcn_s_barrier();
         unsigned char *st = smem + (it % SLOTS) * STAGE_BYTES;
 
         if (ks + KT > p.kv_len) {
@@ -386,14 +400,38 @@ __global__ __launch_bounds__(W * 64) void k_attn_mfma(AttnArgs p)
     }
     if (kw != 0) return;
 
-    // ---- output.  Each owner wave stages its tile as [row][128] floats in its own LDS area, then
-    // writes whole rows: 512 contiguous bytes of partials, or 256 of final bf16 output.
+    if (p.splits > 1) {
+        // ---- partial output, in accumulator order: 16 wave-wide 1 KB stores per tile, no staging.
+        // Lane (col, hi) holds for query row `col` the head-dim elements 32 dt + 8 rq + 4 hi .. + 3 in
+        // registers o[dt][4 rq .. 4 rq + 3]; the merge kernel reads the same order back.
+#pragma unroll
+        for (int u = 0; u < T; ++u) {
+            if (!tile_valid[u]) continue;
+            const size_t ts = ((size_t)bj * p.row_tiles + rt0 + u) * p.splits + split;
+            float4 *po = (float4 *)p.part_o + ts * (16 * 64) + lane;
+#ifdef FC_ATTN_TIMING
+            if (p.dbg_flags & 4) continue;
+#endif
+#pragma unroll
+            for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+                for (int rq = 0; rq < 4; ++rq)
+                    po[(dt * 4 + rq) * 64] = make_float4(t[u].o[dt][4 * rq], t[u].o[dt][4 * rq + 1],
+                                                         t[u].o[dt][4 * rq + 2], t[u].o[dt][4 * rq + 3]);
+            if (hi == 0) ((float2 *)p.part_ml)[ts * 32 + col] = make_float2(t[u].m * p.c, t[u].l);
+        }
+        FC_STAMP(5);
+        return;
+    }
+
+    // ---- final output (single split).  Each owner wave stages its tile as [row][128] floats in its
+    // own LDS area, then writes whole rows of 256 bytes.
     float *stg = xch + (size_t)gi * (32 * OROW + 64);
     size_t *rowid = (size_t *)(stg + 32 * OROW);  // 32 entries
 #pragma unroll
     for (int u = 0; u < T; ++u) {
         if (!tile_valid[u]) continue;
-        const float inv = (p.splits == 1) ? 1.0f / t[u].l : 1.0f;
+        const float inv = 1.0f / t[u].l;
 #pragma unroll
         for (int dt = 0; dt < 4; ++dt)
 #pragma unroll
@@ -403,36 +441,25 @@ __global__ __launch_bounds__(W * 64) void k_attn_mfma(AttnArgs p)
                                 t[u].o[dt][4 * rq + 2] * inv, t[u].o[dt][4 * rq + 3] * inv);
         if (hi == 0) {
             // destination row (or an all-ones marker for rows that do not exist)
-            size_t dst;
-            if (p.splits == 1) {
-                dst = ((size_t)b * p.A + a[u]) * ((size_t)p.Hq * DH) + (size_t)hq[u] * DH;
-                if (row_is_padded(p.pos, b * p.A + a[u], p.max_seq)) dst |= (size_t)1 << 62;
-            } else {
-                dst = (grow[u] * p.splits + split) * DH;
-                if (row_valid[u])
-                    *(float2 *)(p.part_ml + (grow[u] * p.splits + split) * 2) = make_float2(t[u].m * p.c, t[u].l);
-            }
+            size_t dst = ((size_t)b * p.A + a[u]) * ((size_t)p.Hq * DH) + (size_t)hq[u] * DH;
+            if (row_is_padded(p.pos, b * p.A + a[u], p.max_seq)) dst |= (size_t)1 << 62;
             rowid[col] = row_valid[u] ? dst : ~(size_t)0;
         }
         __builtin_amdgcn_wave_barrier();
         __builtin_amdgcn_s_waitcnt(0xc07f);  // lgkmcnt(0): the staged tile is visible to the whole wave
-#pragma unroll
+#pragma unroll 2
         for (int i = 0; i < 16; ++i) {
             const int idx = i * 64 + lane;
             const int row = idx >> 5, c4 = idx & 31;
             const size_t dst = rowid[row];
             if (dst == ~(size_t)0) continue;
             const float4 v = *(const float4 *)(stg + row * OROW + c4 * 4);
-            if (p.splits == 1) {
-                const bool padded = (dst >> 62) & 1;
-                uint16_t *o = p.out + (dst & (((size_t)1 << 62) - 1)) + c4 * 4;
-                uint2 w;
-                w.x = padded ? 0u : ((uint32_t)fc_bf16_bits(v.x) | ((uint32_t)fc_bf16_bits(v.y) << 16));
-                w.y = padded ? 0u : ((uint32_t)fc_bf16_bits(v.z) | ((uint32_t)fc_bf16_bits(v.w) << 16));
-                *(uint2 *)o = w;
-            } else {
-                *(float4 *)(p.part_o + dst + c4 * 4) = v;
-            }
+            const bool padded = (dst >> 62) & 1;
+            uint16_t *o = p.out + (dst & (((size_t)1 << 62) - 1)) + c4 * 4;
+            uint2 w;
+            w.x = padded ? 0u : ((uint32_t)fc_bf16_bits(v.x) | ((uint32_t)fc_bf16_bits(v.y) << 16));
+            w.y = padded ? 0u : ((uint32_t)fc_bf16_bits(v.z) | ((uint32_t)fc_bf16_bits(v.w) << 16));
+            *(uint2 *)o = w;
         }
         __builtin_amdgcn_wave_barrier();
         __builtin_amdgcn_s_waitcnt(0xc07f);  // reads of the staging area are done before the next tile reuses it
@@ -440,54 +467,73 @@ __global__ __launch_bounds__(W * 64) void k_attn_mfma(AttnArgs p)
     FC_STAMP(5);
 }
 
-// Merge the per-split partials of one query row: one block per (sequence, head, row), one thread
-// per head-dim lane.
-__global__ __launch_bounds__(DH) void k_attn_combine(AttnArgs p)
+// Merge the per-split partials: one wave per (row tile, 16-byte accumulator slot).  Lane (col, hi)
+// owns row `col` of the tile and four consecutive head-dim elements, exactly as in the first
+// kernel's accumulators, so every load is a wave-wide contiguous 1 KB and all the loads of a batch
+// of CB splits are in flight together (CB covers all the splits whenever there are at most 32).
+template <int CB>
+__global__ __launch_bounds__(64) void k_attn_combine(AttnArgs p)
 {
-    const size_t grow = blockIdx.x;
-    const int a = (int)(grow % p.A);
-    const int hq = (int)((grow / p.A) % p.Hq);
-    const int b = (int)(grow / ((size_t)p.A * p.Hq));
-    const int i = threadIdx.x;
-    uint16_t *o = p.out + ((size_t)b * p.A + a) * ((size_t)p.Hq * DH) + (size_t)hq * DH;
-    if (row_is_padded(p.pos, b * p.A + a, p.max_seq)) {
-        o[i] = 0;
-        return;
-    }
-    const float *ml = p.part_ml + grow * p.splits * 2;
-    const float *po = p.part_o + grow * p.splits * DH;
-    // sixteen splits' worth of loads in flight at a time
-    float mx = -INFINITY;
-    for (int sb = 0; sb < p.splits; sb += 16) {
-        float mv[16];
+    FC_STAMP(6);
+    const int lane = threadIdx.x, col = lane & 31, hi = lane >> 5;
+    const int slot = blockIdx.x & 15;        // dt * 4 + rq
+    const size_t tg = blockIdx.x >> 4;       // (b * Hkv + j) * row_tiles + rt
+    const int rt = (int)(tg % p.row_tiles);
+    const int bj = (int)(tg / p.row_tiles);
+    const int b = bj / p.Hkv, j = bj % p.Hkv;
+    const float4 *po = (const float4 *)p.part_o + tg * p.splits * (16 * 64) + slot * 64 + lane;
+    const float2 *ml = (const float2 *)p.part_ml + tg * p.splits * 32 + col;
+
+    float m_run = -INFINITY, den = 0.f;
+    float4 num = make_float4(0.f, 0.f, 0.f, 0.f);
+    for (int sb = 0; sb < p.splits; sb += CB) {
+        float4 v[CB];
+        float2 mlv[CB];
 #pragma unroll
-        for (int u = 0; u < 16; ++u) mv[u] = ml[2 * min(sb + u, p.splits - 1)];
-#pragma unroll
-        for (int u = 0; u < 16; ++u) mx = fmaxf(mx, mv[u]);
-    }
-    float num = 0.f, den = 0.f;
-    for (int sb = 0; sb < p.splits; sb += 16) {
-        float v[16];
-        float2 mlv[16];
-#pragma unroll
-        for (int u = 0; u < 16; ++u) {
+        for (int u = 0; u < CB; ++u) {
             const int s = min(sb + u, p.splits - 1);
-            v[u] = po[s * DH + i];
-            mlv[u] = *(const float2 *)(ml + 2 * s);
+            v[u] = po[(size_t)s * (16 * 64)];
+            mlv[u] = ml[(size_t)s * 32];
         }
+        float mb = mlv[0].x;
 #pragma unroll
-        for (int u = 0; u < 16; ++u) {
-            const float w = (sb + u < p.splits) ? __builtin_amdgcn_exp2f(mlv[u].x - mx) : 0.f;
-            num += w * v[u];
+        for (int u = 1; u < CB; ++u) mb = fmaxf(mb, mlv[u].x);
+        const float m_new = fmaxf(m_run, mb);
+        const float keep = __builtin_amdgcn_exp2f(m_run - m_new);  // 0 on the first batch
+        num.x *= keep;
+        num.y *= keep;
+        num.z *= keep;
+        num.w *= keep;
+        den *= keep;
+#pragma unroll
+        for (int u = 0; u < CB; ++u) {
+            const float w = (sb + u < p.splits) ? __builtin_amdgcn_exp2f(mlv[u].x - m_new) : 0.f;
+            num.x += w * v[u].x;
+            num.y += w * v[u].y;
+            num.z += w * v[u].z;
+            num.w += w * v[u].w;
             den += w * mlv[u].y;
         }
+        m_run = m_new;
     }
-    o[i] = fc_bf16_bits(num / den);
+
+    const int rho = rt * 32 + col;
+    if (rho >= p.g * p.A) return;  // row past the end of the last tile
+    const int hg = rho / p.A, a = rho - hg * p.A;
+    const int hq = j * p.g + hg;
+    const bool padded = row_is_padded(p.pos, b * p.A + a, p.max_seq);
+    uint2 w;
+    w.x = padded ? 0u : ((uint32_t)fc_bf16_bits(num.x / den) | ((uint32_t)fc_bf16_bits(num.y / den) << 16));
+    w.y = padded ? 0u : ((uint32_t)fc_bf16_bits(num.z / den) | ((uint32_t)fc_bf16_bits(num.w / den) << 16));
+    const int dh = 32 * (slot >> 2) + 8 * (slot & 3) + 4 * hi;
+    *(uint2 *)(p.out + ((size_t)b * p.A + a) * ((size_t)p.Hq * DH) + (size_t)hq * DH + dh) = w;
+    FC_STAMP(7);
 }
 
 template <int T, int W, int KW>
 hipError_t launch(const AttnArgs &args, hipStream_t s)
 {
+    constexpr int LDS_BYTES = lds_bytes(W);
     static hipError_t attr = hipFuncSetAttribute((const void *)k_attn_mfma<T, W, KW>,
                                                  hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
     if (attr != hipSuccess) return attr;
@@ -509,9 +555,10 @@ hipError_t fc_launch_attention_mfma(const FcGeom &G, const FcAttnPlan &pl, const
     a.Vc = (const uint16_t *)v_layer;
     a.pos = pos;
     a.out = (uint16_t *)out;
-    const size_t rows = (size_t)G.B * G.Hq * A;
+    // workspace: per (row tile, split) 16 x 64 float4 accumulator slots, then 32 x (max, sum)
+    const size_t tiles = (size_t)G.B * G.Hkv * pl.row_tiles;
     a.part_o = (float *)workspace;
-    a.part_ml = workspace ? (float *)workspace + rows * pl.splits * DH : nullptr;
+    a.part_ml = workspace ? (float *)workspace + tiles * pl.splits * (32 * DH) : nullptr;
     a.B = G.B;
     a.Hq = G.Hq;
     a.Hkv = G.Hkv;
@@ -541,13 +588,18 @@ hipError_t fc_launch_attention_mfma(const FcGeom &G, const FcAttnPlan &pl, const
         else if (R == 4) e = launch<1, 8, 2>(a, s);
         else if (R == 2) e = launch<1, 8, 4>(a, s);
         else return hipErrorInvalidValue;
-    } else {              // two tiles per wave
-        if (R == 8) e = launch<2, 4, 1>(a, s);
-        else if (R == 4) e = launch<2, 4, 2>(a, s);
-        else if (R == 2) e = launch<2, 4, 4>(a, s);
+    } else {              // four-wave workgroups, two per compute unit
+        if (R == 4) e = launch<1, 4, 1>(a, s);
+        else if (R == 2) e = launch<1, 4, 2>(a, s);
         else return hipErrorInvalidValue;
     }
     if (e != hipSuccess || pl.splits == 1) return e;
-    k_attn_combine<<<dim3((unsigned)rows), dim3(DH), 0, s>>>(a);
+#ifdef FC_ATTN_TIMING
+    if (a.dbg_flags & 8) return e;
+#endif
+    const dim3 cgrid((unsigned)(tiles * 16)), cblock(64);
+    if (pl.splits <= 8) k_attn_combine<8><<<cgrid, cblock, 0, s>>>(a);
+    else if (pl.splits <= 16) k_attn_combine<16><<<cgrid, cblock, 0, s>>>(a);
+    else k_attn_combine<32><<<cgrid, cblock, 0, s>>>(a);
     return hipGetLastError();
 }
