@@ -319,11 +319,16 @@ fc_status fc_qkv_project_scatter(fc_cache *cache, int32_t layer, const void *x, 
                     A, cache->cfg.max_seq);
     const FcGeom G = geom_of(cache);
     void *kl = layer_ptr(cache, cache->k, layer), *vl = layer_ptr(cache, cache->v, layer);
-    hipError_t e = fc_project_mfma_supported(cache->cfg, A)
-                       ? fc_launch_project_mfma(G, cache->inv_freq, x, w_qkv, b_qkv, pos, win_start, A, q_out, kl, vl,
-                                                cache->scratch, (hipStream_t)stream)
-                       : fc_launch_project_generic(G, cache->cfg.dtype, x, w_qkv, b_qkv, pos, win_start, A,
-                                                   q_out, kl, vl, (hipStream_t)stream);
+    // wide windows: tiled GEMM; short windows: weight-streaming kernels; other shapes: plain ALU kernel
+    hipError_t e;
+    if (fc_project_gemm_supported(cache->cfg, cache->cfg.batch * A))
+        e = fc_launch_project_gemm(G, x, w_qkv, b_qkv, pos, win_start, A, q_out, kl, vl, (hipStream_t)stream);
+    else if (fc_project_mfma_supported(cache->cfg, A))
+        e = fc_launch_project_mfma(G, cache->inv_freq, x, w_qkv, b_qkv, pos, win_start, A, q_out, kl, vl,
+                                   cache->scratch, (hipStream_t)stream);
+    else
+        e = fc_launch_project_generic(G, cache->cfg.dtype, x, w_qkv, b_qkv, pos, win_start, A, q_out, kl, vl,
+                                      (hipStream_t)stream);
     return e == hipSuccess ? FC_OK : hip_fail(e, "projection launch");
 }
 

@@ -9,8 +9,9 @@
 // Data movement.  K rows and transposed V tiles stream HBM -> LDS with 16-byte direct-to-LDS loads
 // (no registers in between) into a ring of four 32 KB stages, two stages ahead of the compute.  The
 // LDS image is XOR-swizzled at 16-byte granularity (the swizzle is applied to the global address of
-// each lane, since direct loads land in lane order), so the 128-bit operand reads are spread over
-// the banks.
+// each lane, since direct loads land in lane order) so that the 16 lanes the LDS serves per clock
+// hit 16 different 16-byte bank groups: K rows (256 B) by the low four bits of the row, V^T rows
+// (128 B, two per 256 B of banks) by bits 1..3 of the row.
 //
 // Per 32 keys a wave computes S^T = K Q^T with v_mfma_f32_32x32x16_bf16 (K rows are the A operand,
 // so each lane ends up holding 16 scores of ONE query row), does the online-softmax update with a
@@ -239,7 +240,7 @@ __global__ __launch_bounds__(W * 64) __attribute__((amdgpu_waves_per_eu(2, 2))) 
         for (int i = 0; i < LB; ++i) {
             const int bi = (wave - W / 2) * LB + i;
             const int dh = 8 * bi + (lane >> 3);
-            const int c = (lane & 7) ^ (dh & 7);
+            const int c = (lane & 7) ^ ((dh >> 1) & 7);
             goff[i] = (uint32_t)(dh * 128 + c * 16);
         }
         lds_dst = (uint32_t)(K_BYTES + (wave - W / 2) * LB * 1024);
@@ -263,7 +264,7 @@ __global__ __launch_bounds__(W * 64) __attribute__((amdgpu_waves_per_eu(2, 2))) 
     for (int sub = 0; sub < 2; ++sub)
 #pragma unroll
         for (int jj = 0; jj < 2; ++jj)
-            voff[sub][jj] = (uint32_t)(K_BYTES + col * 128 + (((4 * sub + 2 * jj + hi) ^ (col & 7)) << 4));
+            voff[sub][jj] = (uint32_t)(K_BYTES + col * 128 + (((4 * sub + 2 * jj + hi) ^ ((col >> 1) & 7)) << 4));
 
     if (n_stages > 0) issue_stage(0);
     if (AHEAD > 1 && n_stages > 1) issue_stage(1);
@@ -297,7 +298,7 @@ __global__ __launch_bounds__(W * 64) __attribute__((amdgpu_waves_per_eu(2, 2))) 
             for (int e = tid; e < DH * KT; e += NT) {
                 const int dh = e >> 6, kl = e & 63;
                 if (ks + kl >= p.kv_len)
-                    *(uint16_t *)(st + K_BYTES + dh * 128 + (((kl >> 3) ^ (dh & 7)) << 4) + (kl & 7) * 2) = 0;
+                    *(uint16_t *)(st + K_BYTES + dh * 128 + (((kl >> 3) ^ ((dh >> 1) & 7)) << 4) + (kl & 7) * 2) = 0;
             }
             __syncthreads();
         }

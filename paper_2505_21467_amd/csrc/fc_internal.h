@@ -71,6 +71,10 @@ bool fc_project_mfma_supported(const fc_config &cfg, int A);
 hipError_t fc_launch_project_mfma(const FcGeom &G, const double *inv_freq, const void *x, const void *w, const void *bias,
                                   const int32_t *pos, int win_start, int A, void *q_out,
                                   void *k_layer, void *v_layer, void *scratch, hipStream_t s);
+bool fc_project_gemm_supported(const fc_config &cfg, int M);
+hipError_t fc_launch_project_gemm(const FcGeom &G, const void *x, const void *w, const void *bias,
+                                  const int32_t *pos, int win_start, int A, void *q_out, void *k_layer,
+                                  void *v_layer, hipStream_t s);
 hipError_t fc_launch_attention_mfma(const FcGeom &G, const FcAttnPlan &p, const void *q,
                                     const void *k_layer, const void *v_layer, const int32_t *pos,
                                     int A, int kv_len, void *out, void *workspace, hipStream_t s);

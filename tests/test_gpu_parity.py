@@ -134,6 +134,34 @@ def test_cached_step_matches_oracle(dtype, B, d, Hq, Hkv, Dh, L, A):
     g.close()
 
 
+@pytest.mark.parametrize("shape", [0, 1, 2])
+@pytest.mark.parametrize("B,d,Hq,Hkv,L,A", [
+    (3, 192, 8, 2, 100, 23),   # 69 window rows: one ragged row tile, three hidden stages
+    (2, 320, 4, 4, 70, 160),   # 320 window rows: several row tiles, the last one ragged
+])
+def test_wide_window_projection_tile_shapes(monkeypatch, shape, B, d, Hq, Hkv, L, A):
+    """The tiled projection (more than 32 window rows) in each of its three tile shapes."""
+    _say("wide-window projection, tile shape %d, B%d d%d Hq%d Hkv%d L%d A%d" % (shape, B, d, Hq, Hkv, L, A))
+    monkeypatch.setenv("FC_PROJ_GEMM_SHAPE", str(shape))
+    dtype, Dh = "bf16", 128
+    w = inputs.Workload("t", dtype, B, d, Hq, Hkv, Dh, L, A)
+    S = L + A
+    g, o = _pair(dtype, B, d, Hq, Hkv, Dh, S + 5, max_rows=A, fill=-0.75)
+    K, V = inputs.kv_fill(w, 11, L)
+    g.write_rows(0, K, V, 0)
+    o.write_rows(K, V, 0)
+    W, b = inputs.weights(w, 11), inputs.bias(w, 11)
+    X = inputs.hidden_states(w, 11, A)
+    Qg, Og = g.step(0, X, W, b, L, S)
+    Qo, Oo = o.step(X, W, b, L, S)
+    assert_close(Qg, Qo, dtype, "Q")
+    assert_close(Og, Oo, dtype, "O")
+    written = np.zeros((B, S + 5), bool)
+    written[:, L:S] = True
+    _compare_cache(g, o, dtype, written=written, what="wide step")
+    g.close()
+
+
 def test_scattered_positions_padding_and_bit_exact_scatter():
     """Arbitrary pos lists, padded rows, and the scatter as a pure bit copy (identity weights)."""
     dtype, B, Dh, Smax, A = "bf16", 2, 128, 210, 24
