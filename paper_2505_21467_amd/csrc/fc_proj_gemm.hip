@@ -27,7 +27,6 @@ typedef __attribute__((ext_vector_type(16))) float f32x16;
 
 constexpr int KS = 64;          // hidden elements per stage
 constexpr int ROWB = KS * 2;    // bytes of one row piece
-constexpr int SLOTS = 3;
 
 struct GemmArgs {
     const uint16_t *X;     // [M][K]
@@ -42,7 +41,17 @@ struct GemmArgs {
     int n_mt;              // row tiles of 32 * NW window rows
     int n_units;           // head slots (NSUB = 4) or half-head slots (NSUB = 2)
     double log2_base_64;   // log2(rope_base) / 64
+#ifdef FC_GEMM_TUNE
+    int flags;             // tuning builds only: 1 skip the multiplies, 2 skip the LDS reads, 4 skip the global loads
+    unsigned long long *dbg;  // tuning builds only: time stamps (100 MHz), 8 per workgroup
+#endif
 };
+
+#ifdef FC_GEMM_TUNE
+#define FC_GSTAMP(k) do { if (p.dbg && threadIdx.x == 0) p.dbg[(size_t)blockIdx.x * 8 + (k)] = __builtin_amdgcn_s_memrealtime(); } while (0)
+#else
+#define FC_GSTAMP(k) do { } while (0)
+#endif
 
 __device__ __forceinline__ void load_lds16g(const void *g, void *l)
 {
@@ -57,18 +66,22 @@ __device__ __forceinline__ void wait_vmg()
     __builtin_amdgcn_s_waitcnt((N & 15) | (7 << 4) | (15 << 8) | ((N >> 4) << 14));
 }
 
-// NW waves (32 window rows each), NSUB feature sub-tiles of 32.
-template <int NW, int NSUB>
+// Workgroup tile: NG head groups x WM row groups of waves (NW = NG * WM waves).  A wave owns MW
+// 32-row sub-tiles of window rows and the NSUB 32-feature sub-tiles of one head (NSUB = 4) or of one
+// rotary-paired half head (NSUB = 2).  SLOTS = stages in the LDS ring.
+template <int NW, int NSUB, int MW, int NG, int SLOTS>
 __global__ __launch_bounds__(NW * 64) void k_proj_gemm(GemmArgs p)
 {
-    constexpr int WROWS = 32 * NSUB, XROWS = 32 * NW;
+    constexpr int WM = NW / NG;
+    constexpr int WROWS = 32 * NSUB * NG, XROWS = 32 * MW * WM;
     constexpr int WBYTES = WROWS * ROWB, STAGE = (WROWS + XROWS) * ROWB;
     constexpr int NBLK = (WROWS + XROWS) / 8;  // 1 KB blocks (8 row pieces) per stage
     constexpr int LBW = NBLK / NW;             // blocks per wave and stage
     constexpr int WBW = (WROWS / 8) / NW;      // of which weight blocks (the first ones)
-    static_assert(NBLK % NW == 0 && (WROWS / 8) % NW == 0, "tile shape");
+    static_assert(NW % NG == 0 && NBLK % NW == 0 && (WROWS / 8) % NW == 0 && (NSUB == 4 || NG == 1), "tile shape");
     extern __shared__ __align__(1024) unsigned char smem[];
     const FcGeom &G = p.G;
+    FC_GSTAMP(0);
 
     // Workgroup -> (unit, row tile): the n_mt workgroups that stream the same weight rows get ids that
     // are equal modulo 8, i.e. land on the same XCD and share its L2.
@@ -77,13 +90,16 @@ __global__ __launch_bounds__(NW * 64) void k_proj_gemm(GemmArgs p)
     const int mt = qd % p.n_mt;
     const int unit = (qd / p.n_mt) * 8 + xcd;
     if (unit >= p.n_units) return;
-    const int hs = NSUB == 4 ? unit : unit >> 1;   // head slot: Hq query heads, Hkv key heads, Hkv value heads
-    const int half = NSUB == 4 ? 0 : unit & 1;     // which rotary-paired half of the head
     const int m0 = mt * XROWS;
+    const int n_slots = G.Hq + 2 * G.Hkv;      // head slots: Hq query heads, Hkv key heads, Hkv value heads
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int col = lane & 31, hi = lane >> 5;
+    const int wn = wave / WM, wm = wave % WM;  // this wave's head group and row group
+    const int hs = NSUB == 4 ? unit * NG + wn : unit >> 1;
+    const int half = NSUB == 4 ? 0 : unit & 1;  // which rotary-paired half of the head
+    const bool head_valid = hs < n_slots;       // an odd number of heads leaves the last pair half empty
 
     // ---- loader: per-lane source offsets (bytes from W / X, hidden offset 0) of this wave's blocks
     uint32_t goff[LBW];
@@ -93,17 +109,26 @@ __global__ __launch_bounds__(NW * 64) void k_proj_gemm(GemmArgs p)
         const int rl = 8 * (i < WBW ? bid : bid - WROWS / 8) + (lane >> 3);  // row of the W / X tile
         const int c = (lane & 7) ^ ((rl >> 1) & 7);  // logical 16-byte chunk that lands at position lane & 7
         if (i < WBW) {
-            const int n = hs * 128 + (NSUB == 4 ? rl : ((rl >> 5) * 64 + 32 * half + (rl & 31)));
+            int n;
+            if (NSUB == 4) n = min(unit * NG + rl / 128, n_slots - 1) * 128 + (rl & 127);
+            else n = hs * 128 + (rl >> 5) * 64 + 32 * half + (rl & 31);
             goff[i] = (uint32_t)n * (uint32_t)(p.K * 2) + c * 16;
         } else {
             const int m = min(m0 + rl, p.M - 1);    // rows past the end re-read the last row; never stored
             goff[i] = (uint32_t)m * (uint32_t)(p.K * 2) + c * 16;
         }
     }
-    auto issue_stage = [&](int st) {
+    // The loads of a stage are issued in four parts spread over the multiplies of the stage before,
+    // because a wave that issues many of them back to back waits for the memory pipeline to take
+    // them before it can issue anything else.  part < 0: all of them.
+    auto issue_stage = [&](int st, int part) {
         unsigned char *dst = smem + (st % SLOTS) * STAGE;
+#ifdef FC_GEMM_TUNE
+        if (FC_GEMM_TUNE & 4) return;
+#endif
 #pragma unroll
         for (int i = 0; i < LBW; ++i) {
+            if (part >= 0 && (i & 3) != part) continue;
             const unsigned char *src = (const unsigned char *)(i < WBW ? p.W : p.X) + (size_t)st * ROWB;
             load_lds16g(src + goff[i], dst + (wave + NW * i) * 1024);
         }
@@ -113,128 +138,186 @@ __global__ __launch_bounds__(NW * 64) void k_proj_gemm(GemmArgs p)
     uint32_t foff[4];
 #pragma unroll
     for (int kk = 0; kk < 4; ++kk) foff[kk] = (uint32_t)(col * ROWB + (((2 * kk + hi) ^ ((col >> 1) & 7)) << 4));
+    const uint32_t w_base = (uint32_t)(wn * NSUB * 32 * ROWB);
+    const uint32_t x_base = (uint32_t)(WBYTES + wm * MW * 32 * ROWB);
 
-    f32x16 acc[NSUB];
+    f32x16 acc[MW][NSUB];
 #pragma unroll
-    for (int t = 0; t < NSUB; ++t)
+    for (int i = 0; i < MW; ++i)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) acc[t][r] = 0.f;
+        for (int t = 0; t < NSUB; ++t)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][t][r] = 0.f;
+
+    // Fragments are double-buffered in registers: the LDS reads of k-step kk+1 are issued before the
+    // multiplies of k-step kk, and the first reads of the next stage go out (behind that stage's
+    // barrier) before the last multiplies of this one, so the matrix core never waits for LDS.
+    bf16x8 xf[2][MW], wf[2][NSUB];
+#ifdef FC_GEMM_TUNE
+    for (int i = 0; i < 2; ++i) { for (int e = 0; e < 8; ++e) wf[i][0][e] = (__bf16)(float)lane; for (int t = 0; t < NSUB; ++t) wf[i][t] = wf[i][0]; for (int t = 0; t < MW; ++t) xf[i][t] = wf[i][0]; }
+#endif
+    auto read_frags = [&](int slot, int kk, int buf) {
+        const unsigned char *st = smem + slot * STAGE;
+#ifdef FC_GEMM_TUNE
+        if (FC_GEMM_TUNE & 2) return;
+#endif
+#pragma unroll
+        for (int i = 0; i < MW; ++i) xf[buf][i] = *(const bf16x8 *)(st + x_base + i * (32 * ROWB) + foff[kk]);
+#pragma unroll
+        for (int t = 0; t < NSUB; ++t) wf[buf][t] = *(const bf16x8 *)(st + w_base + t * (32 * ROWB) + foff[kk]);
+    };
+    auto multiply = [&](int buf) {
+#ifdef FC_GEMM_TUNE
+        if (FC_GEMM_TUNE & 1) { acc[0][0][0] += (float)xf[buf][0][0] + (float)wf[buf][0][0] + (float)wf[buf][NSUB - 1][1]; return; }
+#endif
+#pragma unroll
+        for (int i = 0; i < MW; ++i)
+#pragma unroll
+            for (int t = 0; t < NSUB; ++t)
+                acc[i][t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[buf][t], xf[buf][i], acc[i][t], 0, 0, 0);
+    };
 
     const int n_stages = p.K / KS;
-    issue_stage(0);
-    if (n_stages > 1) issue_stage(1);
+    FC_GSTAMP(1);
+    const int n_pro = min(SLOTS, n_stages);
+    for (int st = 0; st < n_pro; ++st) issue_stage(st, -1);
+    if (n_pro == 3) wait_vmg<2 * LBW>();
+    else if (n_pro == 2) wait_vmg<LBW>();
+    else wait_vmg<0>();
+    __builtin_amdgcn_s_barrier();  // stage 0 is complete for every wave
+    read_frags(0, 0, 0);
+    int slot = 0;
     for (int it = 0; it < n_stages; ++it) {
-        if (it + 1 < n_stages) wait_vmg<LBW>();
-        else wait_vmg<0>();
-        // Behind this barrier stage `it` is complete for every wave and every wave has left stage
-        // it-1, whose slot is the one refilled next.
-        __builtin_amdgcn_s_barrier();
-        if (it + 2 < n_stages) issue_stage(it + 2);
-        const unsigned char *st = smem + (it % SLOTS) * STAGE;
-        const unsigned char *xs = st + WBYTES + wave * (32 * ROWB);
+        // The slot of stage it-1 was released by the barrier in the middle of the previous iteration;
+        // stage it-1+SLOTS goes there: its first quarter was issued behind that barrier, the rest now.
+        const int refill = it - 1 + SLOTS;
+        const bool do_refill = it > 0 && refill < n_stages;
 #pragma unroll
-        for (int kk = 0; kk < 4; ++kk) {
-            const bf16x8 xf = *(const bf16x8 *)(xs + foff[kk]);
-            bf16x8 wf[NSUB];
-#pragma unroll
-            for (int t = 0; t < NSUB; ++t) wf[t] = *(const bf16x8 *)(st + t * (32 * ROWB) + foff[kk]);
-#pragma unroll
-            for (int t = 0; t < NSUB; ++t) acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[t], xf, acc[t], 0, 0, 0);
+        for (int kk = 0; kk < 3; ++kk) {
+            read_frags(slot, kk + 1, (kk + 1) & 1);
+            if (do_refill) issue_stage(refill, kk + 1);
+            __builtin_amdgcn_sched_barrier(0);
+            multiply(kk & 1);
+            __builtin_amdgcn_sched_barrier(0);
         }
+        const int nslot = slot == SLOTS - 1 ? 0 : slot + 1;
+        if (it + 1 < n_stages) {
+            // This wave's reads of stage `it` have all returned (lgkmcnt 0); behind the barrier that
+            // holds for every wave, and stage it+1 is complete (later stages may still be in flight).
+            if (SLOTS == 3 && it + 2 < n_stages) __builtin_amdgcn_s_waitcnt((LBW & 15) | (7 << 4) | (0 << 8) | ((LBW >> 4) << 14));
+            else __builtin_amdgcn_s_waitcnt((0 & 15) | (7 << 4) | (0 << 8));
+            __builtin_amdgcn_s_barrier();
+            if (it + SLOTS < n_stages) issue_stage(it + SLOTS, 0);
+            read_frags(nslot, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        multiply(1);
+        __builtin_amdgcn_sched_barrier(0);
+        slot = nslot;
     }
 
-    // ---- epilogue, in registers.  Lane (col, hi) holds window row m0 + 32 wave + col; register r of
-    // sub-tile t is feature 32 t' + 8 (r >> 2) + 4 hi + (r & 3) of the head, with t' = t for a whole
-    // head and {half, half + 2} for a half head.
-    const int m = m0 + 32 * wave + col;
-    const bool mvalid = m < p.M;
-    const int mm = mvalid ? m : 0;
-    const int b = mm / p.A, a = mm - b * p.A;
-    const int pp = p.pos ? p.pos[mm] : p.win_start + a;
-    const bool valid = mvalid && pp >= 0 && pp < G.max_seq;
+    FC_GSTAMP(2);
+    // ---- epilogue, in registers.  Lane (col, hi) of sub-tile i holds window row m0 + 32 (wm MW + i) + col;
+    // register r of sub-tile t is feature 32 t' + 8 (r >> 2) + 4 hi + (r & 3) of the head, with t' = t
+    // for a whole head and {half, half + 2} for a half head.
+    if (!head_valid) return;
     const bool rotate = hs < G.Hq + G.Hkv;
     constexpr int NP = NSUB / 2;  // rotary pairs of sub-tiles: (t, t + NP)
+    // base^(-1/64) and its powers; base^(-i/64) / (2 pi) = turns per position of pair i
+    const double r1 = exp2(-p.log2_base_64);
+    const double r2 = r1 * r1, r4 = r2 * r2, r8 = r4 * r4, r16 = r8 * r8, r32 = r16 * r16;
 
-    if (p.bias) {
+#pragma unroll
+    for (int i = 0; i < MW; ++i) {
+        const int m = m0 + 32 * (wm * MW + i) + col;
+        const bool mvalid = m < p.M;
+        const int mm = mvalid ? m : 0;
+        const int b = mm / p.A, a = mm - b * p.A;
+        const int pp = p.pos ? p.pos[mm] : p.win_start + a;
+        const bool valid = mvalid && pp >= 0 && pp < G.max_seq;
+
+        if (p.bias) {
+#pragma unroll
+            for (int t = 0; t < NSUB; ++t) {
+                const int tq = NSUB == 4 ? t : half + 2 * t;
+#pragma unroll
+                for (int r = 0; r < 16; ++r)
+                    acc[i][t][r] += fc_to_float(bf16_t{p.bias[hs * 128 + 32 * tq + 8 * (r >> 2) + 4 * hi + (r & 3)]});
+            }
+        }
+        if (rotate) {
+            // the angle is reduced to a fraction of a turn in double, then hardware sine / cosine
+            // (argument in turns)
+#pragma unroll
+            for (int t = 0; t < NP; ++t) {
+                const int tq = NSUB == 4 ? t : half;  // pair index 32 tq + 8 rq + 4 hi + (r & 3) < 64
+                double f = 0.15915494309189533576888;
+                if (tq) f *= r32;
+                if (hi) f *= r4;
+#pragma unroll
+                for (int rq = 0; rq < 4; ++rq) {
+                    double fr = f;
+#pragma unroll
+                    for (int r3 = 0; r3 < 4; ++r3) {
+                        const int r = 4 * rq + r3;
+                        const double turns = (double)pp * fr;
+                        const float ph = (float)(turns - rint(turns));
+                        const float c = __builtin_amdgcn_cosf(ph), sn = __builtin_amdgcn_sinf(ph);
+                        const float lo = acc[i][t][r], hi2 = acc[i][t + NP][r];
+                        acc[i][t][r] = lo * c - hi2 * sn;
+                        acc[i][t + NP][r] = hi2 * c + lo * sn;
+                        fr *= r1;
+                    }
+                    f *= r8;
+                }
+            }
+        }
+        if (!mvalid) continue;
+
 #pragma unroll
         for (int t = 0; t < NSUB; ++t) {
             const int tq = NSUB == 4 ? t : half + 2 * t;
 #pragma unroll
-            for (int r = 0; r < 16; ++r)
-                acc[t][r] += fc_to_float(bf16_t{p.bias[hs * 128 + 32 * tq + 8 * (r >> 2) + 4 * hi + (r & 3)]});
-        }
-    }
-    if (rotate) {
-        // base^(-i/64) / (2 pi) in double by powers of r1 = base^(-1/64); the angle is reduced to a
-        // fraction of a turn in double, then hardware sine / cosine (argument in turns).
-        const double r1 = exp2(-p.log2_base_64);
-        const double r2 = r1 * r1, r4 = r2 * r2, r8 = r4 * r4, r16 = r8 * r8, r32 = r16 * r16;
-#pragma unroll
-        for (int t = 0; t < NP; ++t) {
-            const int tq = NSUB == 4 ? t : half;  // i = 32 tq + 8 rq + 4 hi + (r & 3) < 64
-            double f = 0.15915494309189533576888;
-            if (tq) f *= r32;
-            if (hi) f *= r4;
-#pragma unroll
             for (int rq = 0; rq < 4; ++rq) {
-                double fr = f;
-#pragma unroll
-                for (int r3 = 0; r3 < 4; ++r3) {
-                    const int r = 4 * rq + r3;
-                    const double turns = (double)pp * fr;
-                    const float ph = (float)(turns - rint(turns));
-                    const float c = __builtin_amdgcn_cosf(ph), sn = __builtin_amdgcn_sinf(ph);
-                    const float lo = acc[t][r], hi2 = acc[t + NP][r];
-                    acc[t][r] = lo * c - hi2 * sn;
-                    acc[t + NP][r] = hi2 * c + lo * sn;
-                    fr *= r1;
-                }
-                f *= r8;
-            }
-        }
-    }
-    if (!mvalid) return;
-
-#pragma unroll
-    for (int t = 0; t < NSUB; ++t) {
-        const int tq = NSUB == 4 ? t : half + 2 * t;
-#pragma unroll
-        for (int rq = 0; rq < 4; ++rq) {
-            const int d0 = 32 * tq + 8 * rq + 4 * hi;
-            uint2 w;
-            w.x = (uint32_t)fc_bf16_bits(acc[t][4 * rq]) | ((uint32_t)fc_bf16_bits(acc[t][4 * rq + 1]) << 16);
-            w.y = (uint32_t)fc_bf16_bits(acc[t][4 * rq + 2]) | ((uint32_t)fc_bf16_bits(acc[t][4 * rq + 3]) << 16);
-            if (hs < G.Hq) {
-                if (!valid) w = make_uint2(0, 0);
-                *(uint2 *)(p.Q + (((size_t)b * G.Hq + hs) * p.A + a) * 128 + d0) = w;
-            } else if (valid) {
-                if (hs < G.Hq + G.Hkv) {
-                    *(uint2 *)(p.Kc + fc_k_index(G, b, hs - G.Hq, pp, d0)) = w;
-                } else {
-                    const int j = hs - G.Hq - G.Hkv;
-                    uint16_t *v = p.Vc + fc_v_index(G, b, j, pp, d0);
-                    v[0] = (uint16_t)(w.x & 0xffff);
-                    v[FC_VTILE] = (uint16_t)(w.x >> 16);
-                    v[2 * FC_VTILE] = (uint16_t)(w.y & 0xffff);
-                    v[3 * FC_VTILE] = (uint16_t)(w.y >> 16);
+                const int d0 = 32 * tq + 8 * rq + 4 * hi;
+                uint2 w;
+                w.x = (uint32_t)fc_bf16_bits(acc[i][t][4 * rq]) | ((uint32_t)fc_bf16_bits(acc[i][t][4 * rq + 1]) << 16);
+                w.y = (uint32_t)fc_bf16_bits(acc[i][t][4 * rq + 2]) | ((uint32_t)fc_bf16_bits(acc[i][t][4 * rq + 3]) << 16);
+                if (hs < G.Hq) {
+                    if (!valid) w = make_uint2(0, 0);
+                    *(uint2 *)(p.Q + (((size_t)b * G.Hq + hs) * p.A + a) * 128 + d0) = w;
+                } else if (valid) {
+                    if (hs < G.Hq + G.Hkv) {
+                        *(uint2 *)(p.Kc + fc_k_index(G, b, hs - G.Hq, pp, d0)) = w;
+                    } else {
+                        const int j = hs - G.Hq - G.Hkv;
+                        uint16_t *v = p.Vc + fc_v_index(G, b, j, pp, d0);
+                        v[0] = (uint16_t)(w.x & 0xffff);
+                        v[FC_VTILE] = (uint16_t)(w.x >> 16);
+                        v[2 * FC_VTILE] = (uint16_t)(w.y & 0xffff);
+                        v[3 * FC_VTILE] = (uint16_t)(w.y >> 16);
+                    }
                 }
             }
         }
     }
+    FC_GSTAMP(4);
 }
 
-template <int NW, int NSUB>
+template <int NW, int NSUB, int MW, int NG, int SLOTS>
 hipError_t launch_gemm(GemmArgs a, hipStream_t s)
 {
-    constexpr int LDS = SLOTS * (32 * NSUB + 32 * NW) * ROWB;
-    static hipError_t attr = hipFuncSetAttribute((const void *)k_proj_gemm<NW, NSUB>,
+    constexpr int XROWS = 32 * MW * (NW / NG);
+    constexpr int LDS = SLOTS * (32 * NSUB * NG + XROWS) * ROWB;
+    static_assert(LDS <= 160 * 1024, "LDS ring too large");
+    static hipError_t attr = hipFuncSetAttribute((const void *)k_proj_gemm<NW, NSUB, MW, NG, SLOTS>,
                                                  hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
     if (attr != hipSuccess) return attr;
     const int slots = a.G.Hq + 2 * a.G.Hkv;
-    a.n_units = NSUB == 4 ? slots : 2 * slots;
-    a.n_mt = (a.M + 32 * NW - 1) / (32 * NW);
+    a.n_units = NSUB == 4 ? (slots + NG - 1) / NG : 2 * slots;
+    a.n_mt = (a.M + XROWS - 1) / XROWS;
     const unsigned grid = (unsigned)(((a.n_units + 7) / 8) * 8 * a.n_mt);
-    k_proj_gemm<NW, NSUB><<<dim3(grid), dim3(NW * 64), LDS, s>>>(a);
+    k_proj_gemm<NW, NSUB, MW, NG, SLOTS><<<dim3(grid), dim3(NW * 64), LDS, s>>>(a);
     return hipGetLastError();
 }
 
@@ -267,12 +350,17 @@ hipError_t fc_launch_project_gemm(const FcGeom &G, const void *x, const void *w,
     a.win_start = win_start;
     a.n_mt = a.n_units = 0;
     a.log2_base_64 = G.log_base * 1.4426950408889634074 / 64.0;
+#ifdef FC_GEMM_TUNE
+    a.flags = getenv("FC_GEMM_FLAGS") ? atoi(getenv("FC_GEMM_FLAGS")) : 0;
+    a.dbg = getenv("FC_GEMM_DBG_PTR") ? (unsigned long long *)strtoull(getenv("FC_GEMM_DBG_PTR"), nullptr, 0) : nullptr;
+#endif
     // Tile choice: the largest tile that still gives the chip about one workgroup per compute unit.
     const int slots = G.Hq + 2 * G.Hkv;
     int shape = 0;  // 0: 256 rows x head, 1: 128 rows x head, 2: 128 rows x half head
     if ((int64_t)slots * ((a.M + 255) / 256) < 192) shape = (int64_t)slots * ((a.M + 127) / 128) >= 144 ? 1 : 2;
     if (const char *e = getenv("FC_PROJ_GEMM_SHAPE")) shape = atoi(e);  // tuning knob
-    if (shape == 0) return launch_gemm<8, 4>(a, s);
-    if (shape == 1) return launch_gemm<4, 4>(a, s);
-    return launch_gemm<4, 2>(a, s);
+    if (shape == 3) return launch_gemm<8, 4, 2, 2, 2>(a, s);   // 256 rows x two heads
+    if (shape == 0) return launch_gemm<8, 4, 1, 1, 3>(a, s);   // 256 rows x head
+    if (shape == 1) return launch_gemm<4, 4, 1, 1, 3>(a, s);   // 128 rows x head
+    return launch_gemm<4, 2, 1, 1, 3>(a, s);                   // 128 rows x half head
 }
