@@ -134,7 +134,9 @@ FcAttnPlan fc_plan_attention(const fc_config &cfg, int A, int kv_len)
     const int64_t n_rg = (p.row_tiles + R - 1) / R;
     const int64_t base = (int64_t)cfg.batch * cfg.n_kv_heads * n_rg;
     const int n_stages = (kv_len + 63) / 64;
-    int64_t splits = (target + base - 1) / base;   // enough workgroups to fill the chip
+    // enough workgroups to fill the chip; rounded to nearest, so that a grid that nearly fills it
+    // already is not doubled (the partial results of a split are extra traffic)
+    int64_t splits = (target + base / 2) / base;
     const int64_t by_len = n_stages / 4 > 1 ? n_stages / 4 : 1;  // at least 256 keys per split
     if (splits > by_len) splits = by_len;
     if (splits < 1) splits = 1;
