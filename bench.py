@@ -1,6 +1,6 @@
 """Benchmark of the FreeCache cached denoising layer-step on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c4|c2|c3|c5] [--layers N]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c4|c2|c3|c5|c5_refresh] [--layers N]
 
 A "step" is one pass of the whole hot path for one layer: QKV projection + RoPE + scatter of the
 active window, then attention of the window's queries over the cache.  The default workload is the
@@ -11,6 +11,9 @@ So that the key/value stream really comes from HBM and not from the 256 MB memor
 timed loop rotates over `--layers` distinct layer caches and weight matrices (default: enough for
 more than 1.5 GB of working set), as a 28-layer model does between two visits of one layer.  The
 same loop on a single layer is reported as `single_cache_us` (cache-resident figure).
+
+`--workload c5_refresh` times the periodic refresh of configuration 5 instead (one `fc_refresh` of the
+256-row generation region of 8 sequences per step: a dense, matrix-core-bound pass).
 
 Prints ONE JSON line (see the fields below).  Inputs are seeded and synthetic.
 """
@@ -26,6 +29,12 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
+MFMA_BF16_PEAK_TFLOPS = 2500.0
+
+# HBM bytes per launch of the attention call (main kernel + merge kernel) on the default workload,
+# from `rocprofv3 --pmc FETCH_SIZE` / `--pmc WRITE_SIZE` runs of this command, scaled by what the same
+# counters read for the plain 256 MiB copy at the end of this file (profiles/ holds the summary).
+MEASURED_ATTENTION_TRAFFIC_BYTES = {"c4_dream7b_long_L16384_A32": None}
 
 
 def _parse():
@@ -33,7 +42,7 @@ def _parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=100)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--workload", default="c4", choices=["c2", "c3", "c4", "c5"])
+    ap.add_argument("--workload", default="c4", choices=["c2", "c3", "c4", "c5", "c5_refresh"])
     ap.add_argument("--layers", type=int, default=0, help="distinct layer caches to rotate over (0 = auto)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-single", action="store_true",
@@ -56,8 +65,10 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     fc.lib()
     dev = torch.device("cuda:0")
-    w = {"c2": inputs.C2, "c3": inputs.C3, "c4": inputs.C4, "c5": inputs.C5}[args.workload]
-    B, A, Dh, Hq, Hkv = w.batch, w.active, w.head_dim, w.n_q_heads, w.n_kv_heads
+    refresh = args.workload == "c5_refresh"
+    w = {"c2": inputs.C2, "c3": inputs.C3, "c4": inputs.C4, "c5": inputs.C5, "c5_refresh": inputs.C5}[args.workload]
+    B, Dh, Hq, Hkv = w.batch, w.head_dim, w.n_q_heads, w.n_kv_heads
+    A = w.gen_len if refresh else w.active  # a refresh re-projects the whole generation region
     S = w.kv_len
     esz = 2
     kv_bytes_layer = 2 * B * S * Hkv * Dh * esz
@@ -87,7 +98,9 @@ def main():
     O = torch.empty((B, A, Hq * Dh), dtype=tdt, device=dev)
     torch.cuda.synchronize()
 
-    if w.gen_len:
+    if refresh:
+        sched = [w.cached_len]
+    elif w.gen_len:
         n_sched = -(-w.gen_len // w.block) * w.steps_per_block
         sched = [fc.fc_window(s, w.cached_len, w.gen_len, w.block, w.steps_per_block)[0] for s in range(n_sched)]
     else:
@@ -142,7 +155,9 @@ def main():
     attn_bytes = kv_bytes_layer + 2 * B * A * Hq * Dh * esz
     proj_bytes = w_bytes_layer + B * A * (w.hidden + w.qkv_width) * esz
     attn_gbs = attn_bytes / us_attn * 1e-3
-    flops = 2.0 * B * A * w.hidden * w.qkv_width + 4.0 * B * A * Hq * S * Dh
+    proj_flops = 2.0 * B * A * w.hidden * w.qkv_width
+    attn_flops = 4.0 * B * A * Hq * S * Dh
+    flops = proj_flops + attn_flops
 
     out = {
         "metric": "us per cached denoising layer-step + achieved KV-read HBM GB/s (fraction of peak)",
@@ -158,7 +173,7 @@ def main():
         "dtype": w.dtype,
         "data": "synthetic",
         "config": {
-            "workload": w.name, "batch": B, "hidden": w.hidden, "n_q_heads": Hq, "n_kv_heads": Hkv,
+            "workload": w.name + ("/refresh" if refresh else ""), "batch": B, "hidden": w.hidden, "n_q_heads": Hq, "n_kv_heads": Hkv,
             "head_dim": Dh, "kv_len": S, "active_rows": A, "layers_rotated": n_layers,
             "window_schedule": "start %d, +%d every %d steps" % (w.cached_len, w.block, w.steps_per_block)
             if w.gen_len else "fixed at %d" % w.cached_len,
@@ -170,7 +185,7 @@ def main():
             "peak": HBM_PEAK_GBS,
             "unit": "GB/s",
             "frac": round(attn_gbs / HBM_PEAK_GBS, 4),
-            "traffic": None,
+            "traffic": MEASURED_ATTENTION_TRAFFIC_BYTES.get(w.name) if not refresh else None,
             "algorithmic_bytes_per_launch": attn_bytes,
             "us_per_launch": round(us_attn, 3),
         },
@@ -179,6 +194,8 @@ def main():
             "us_per_launch": round(us_proj, 3),
             "weight_stream_gbs": round(proj_bytes / us_proj * 1e-3, 1),
             "frac_of_hbm_peak": round(proj_bytes / us_proj * 1e-3 / HBM_PEAK_GBS, 4),
+            "tflops": round(proj_flops / us_proj * 1e-6, 1),
+            "frac_of_mfma_peak": round(proj_flops / us_proj * 1e-6 / MFMA_BF16_PEAK_TFLOPS, 4),
         },
         "active_rows_per_s": round(B * A / (us_step * 1e-6), 1),
         "tflops": round(flops / us_step * 1e-6, 2),
@@ -197,21 +214,42 @@ def main():
     torch.cuda.synchronize()
     out["calibration_copy_bytes"] = cal_src.numel() * 4
 
+    if refresh:
+        # the refresh is a dense pass: both calls are bound by the matrix cores, the projection GEMM
+        # being the longer one
+        out["roofline"] = {
+            "kernel": "fc_qkv_project_scatter (k_proj_gemm)",
+            "bound": "mfma",
+            "achieved": round(proj_flops / us_proj * 1e-6, 1),
+            "peak": MFMA_BF16_PEAK_TFLOPS,
+            "unit": "TFLOP/s",
+            "frac": round(proj_flops / us_proj * 1e-6 / MFMA_BF16_PEAK_TFLOPS, 4),
+            "traffic": None,
+            "algorithmic_flops_per_launch": proj_flops,
+            "us_per_launch": round(us_proj, 3),
+        }
+        out["attention"] = {
+            "kernel": "fc_active_attention",
+            "us_per_launch": round(us_attn, 3),
+            "tflops": round(attn_flops / us_attn * 1e-6, 1),
+            "frac_of_mfma_peak": round(attn_flops / us_attn * 1e-6 / MFMA_BF16_PEAK_TFLOPS, 4),
+        }
+
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(w, inputs)
+        out["cpu_baseline"] = cpu_baseline(w, inputs, A, refresh)
 
     torch.cuda.synchronize()
     fc.fc_cache_free(cache)
     print(json.dumps(out))
 
 
-def cpu_baseline(w, inputs):
+def cpu_baseline(w, inputs, A, refresh):
     """The oracle as it stands, timed on the host cores on a bounded sample of the same workload."""
     import numpy as np
     from oracle import fc_oracle as orc
 
     max_samples, budget_s = 100, 12.0  # stop after about 12 s of oracle work
-    S, A = w.kv_len, w.active
+    S = w.kv_len
     cfg = orc.OracleConfig(w.batch, w.hidden, w.n_q_heads, w.n_kv_heads, w.head_dim, S, w.dtype, w.rope_base)
     K0, V0 = inputs.kv_fill(w, 0, S)
     Kc, Vc = inputs.as_oracle(K0).copy(), inputs.as_oracle(V0).copy()
@@ -230,7 +268,8 @@ def cpu_baseline(w, inputs):
         "unit": "us",
         "cores": threads,
         "kind": "oracle",
-        "sample": "%d layer-step(s) of %s (projection + scatter + attention), fp64, OpenMP" % (n_sample, w.name),
+        "sample": "%d layer-step(s) of %s%s (projection + scatter + attention), fp64, OpenMP" % (
+            n_sample, w.name, "/refresh" if refresh else ""),
     }
 
 
