@@ -150,10 +150,10 @@ FcAttnPlan fc_plan_attention(const fc_config &cfg, int A, int kv_len)
 size_t fc_plan_workspace(const fc_config &cfg, const FcAttnPlan &p, int A)
 {
     if (p.kind == 0 || p.splits_bound <= 1) return 0;
-    // per (32-row tile, split): 32 x Dh partial outputs + 32 x (running max, running sum), fp32
+    // per (32-row tile, split): 32 x Dh partial outputs as half floats + 32 x 4 floats of row state
     (void)A;
-    return (size_t)cfg.batch * cfg.n_kv_heads * p.row_tiles * p.splits_bound * 32 * (cfg.head_dim + 2) *
-           sizeof(float);
+    return (size_t)cfg.batch * cfg.n_kv_heads * p.row_tiles * p.splits_bound * 32 *
+           (cfg.head_dim * 2 + 4 * sizeof(float));
 }
 
 extern "C" {

@@ -52,8 +52,8 @@ struct AttnArgs {
     const uint16_t *Vc;   // one layer, [B][Hkv][spad/64][128][64]
     const int32_t *pos;   // [B][A] or nullptr
     uint16_t *out;        // [B][A][Hq*128]
-    float *part_o;        // [B*Hkv*row_tiles][splits][16 slots][64 lanes][4]: accumulators as the lanes hold them
-    float *part_ml;       // [B*Hkv*row_tiles][splits][32 rows][2]  (max in the log2 domain, sum)
+    float *part_o;        // [B*Hkv*row_tiles][splits][8 slot pairs][64 lanes][8 halves]: accumulators as the lanes hold them
+    float *part_ml;       // [B*Hkv*row_tiles][splits][32 rows][4]  (max in the log2 domain, sum, scaling exponent, -)
     int B, Hq, Hkv, g, A, kv_len, spad, max_seq;
     int row_tiles, n_rg, splits, keys_per_split, n_units;
     float c;              // softmax scale * log2(e)
@@ -402,24 +402,38 @@ __global__ __launch_bounds__(W * 64) __attribute__((amdgpu_waves_per_eu(2, 2))) 
     if (kw != 0) return;
 
     if (p.splits > 1) {
-        // ---- partial output, in accumulator order: 16 wave-wide 1 KB stores per tile, no staging.
+        // ---- partial output, in accumulator order, as scaled half floats: the partial of a row is
+        // normalised by its own sum (a convex combination of V rows, so it is no larger than the
+        // largest |V|) and by a power of two that brings the row's largest magnitude into
+        // [2^14, 2^15); eleven significant bits per value, with the row's max, sum and exponent in
+        // fp32.  That halves the one traffic this kernel adds on top of the key/value stream.
         // Lane (col, hi) holds for query row `col` the head-dim elements 32 dt + 8 rq + 4 hi .. + 3 in
-        // registers o[dt][4 rq .. 4 rq + 3]; the merge kernel reads the same order back.
+        // registers o[dt][4 rq .. 4 rq + 3]; a 16-byte store takes the two rq of a pair.
 #pragma unroll
         for (int u = 0; u < T; ++u) {
             if (!tile_valid[u]) continue;
             const size_t ts = ((size_t)bj * p.row_tiles + rt0 + u) * p.splits + split;
-            float4 *po = (float4 *)p.part_o + ts * (16 * 64) + lane;
+            uint4 *po = (uint4 *)p.part_o + ts * (8 * 64) + lane;
 #ifdef FC_ATTN_TIMING
             if (p.dbg_flags & 4) continue;
 #endif
+            float amax = 0.f;
 #pragma unroll
             for (int dt = 0; dt < 4; ++dt)
 #pragma unroll
-                for (int rq = 0; rq < 4; ++rq)
-                    po[(dt * 4 + rq) * 64] = make_float4(t[u].o[dt][4 * rq], t[u].o[dt][4 * rq + 1],
-                                                         t[u].o[dt][4 * rq + 2], t[u].o[dt][4 * rq + 3]);
-            if (hi == 0) ((float2 *)p.part_ml)[ts * 32 + col] = make_float2(t[u].m * p.c, t[u].l);
+                for (int r = 0; r < 16; ++r) amax = fmaxf(amax, fabsf(t[u].o[dt][r]));
+            amax = row_max2(amax);
+            const float inv_l = 1.0f / t[u].l;
+            const int k = 15 - __builtin_amdgcn_frexp_expf(amax * inv_l);  // 15 for an all-zero row
+#pragma unroll
+            for (int q2 = 0; q2 < 8; ++q2) {
+                union { _Float16 h[8]; uint4 u4; } x;
+#pragma unroll
+                for (int e = 0; e < 8; ++e)
+                    x.h[e] = (_Float16)__builtin_amdgcn_ldexpf(t[u].o[q2 >> 1][8 * (q2 & 1) + e] * inv_l, k);
+                po[q2 * 64] = x.u4;
+            }
+            if (hi == 0) ((float4 *)p.part_ml)[ts * 32 + col] = make_float4(t[u].m * p.c, t[u].l, (float)k, 0.f);
         }
         FC_STAMP(5);
         return;
@@ -468,32 +482,35 @@ __global__ __launch_bounds__(W * 64) __attribute__((amdgpu_waves_per_eu(2, 2))) 
     FC_STAMP(5);
 }
 
-// Merge the per-split partials: one wave per (row tile, 16-byte accumulator slot).  Lane (col, hi)
-// owns row `col` of the tile and four consecutive head-dim elements, exactly as in the first
-// kernel's accumulators, so every load is a wave-wide contiguous 1 KB and all the loads of a batch
-// of CB splits are in flight together (CB covers all the splits whenever there are at most 32).
+// Merge the per-split partials: one wave per (row tile, pair of 16-byte accumulator slots).  Lane
+// (col, hi) owns row `col` of the tile and two groups of four consecutive head-dim elements, exactly
+// as in the first kernel's accumulators, so every load is a wave-wide contiguous 1 KB and all the
+// loads of a batch of CB splits are in flight together (CB covers all the splits whenever there are
+// at most 32).
 template <int CB>
 __global__ __launch_bounds__(64) void k_attn_combine(AttnArgs p)
 {
     FC_STAMP(6);
     const int lane = threadIdx.x, col = lane & 31, hi = lane >> 5;
-    const int slot = blockIdx.x & 15;        // dt * 4 + rq
-    const size_t tg = blockIdx.x >> 4;       // (b * Hkv + j) * row_tiles + rt
+    const int q2 = blockIdx.x & 7;           // accumulator slots 2 q2 and 2 q2 + 1: dt = q2 >> 1, rq = 2 (q2 & 1) + {0, 1}
+    const size_t tg = blockIdx.x >> 3;       // (b * Hkv + j) * row_tiles + rt
     const int rt = (int)(tg % p.row_tiles);
     const int bj = (int)(tg / p.row_tiles);
     const int b = bj / p.Hkv, j = bj % p.Hkv;
-    const float4 *po = (const float4 *)p.part_o + tg * p.splits * (16 * 64) + slot * 64 + lane;
-    const float2 *ml = (const float2 *)p.part_ml + tg * p.splits * 32 + col;
+    const uint4 *po = (const uint4 *)p.part_o + tg * p.splits * (8 * 64) + q2 * 64 + lane;
+    const float4 *ml = (const float4 *)p.part_ml + tg * p.splits * 32 + col;
 
     float m_run = -INFINITY, den = 0.f;
-    float4 num = make_float4(0.f, 0.f, 0.f, 0.f);
+    float num[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) num[e] = 0.f;
     for (int sb = 0; sb < p.splits; sb += CB) {
-        float4 v[CB];
-        float2 mlv[CB];
+        uint4 v[CB];
+        float4 mlv[CB];  // (max in the log2 domain, sum, exponent of the half-float scaling, -)
 #pragma unroll
         for (int u = 0; u < CB; ++u) {
             const int s = min(sb + u, p.splits - 1);
-            v[u] = po[(size_t)s * (16 * 64)];
+            v[u] = po[(size_t)s * (8 * 64)];
             mlv[u] = ml[(size_t)s * 32];
         }
         float mb = mlv[0].x;
@@ -501,19 +518,19 @@ __global__ __launch_bounds__(64) void k_attn_combine(AttnArgs p)
         for (int u = 1; u < CB; ++u) mb = fmaxf(mb, mlv[u].x);
         const float m_new = fmaxf(m_run, mb);
         const float keep = __builtin_amdgcn_exp2f(m_run - m_new);  // 0 on the first batch
-        num.x *= keep;
-        num.y *= keep;
-        num.z *= keep;
-        num.w *= keep;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) num[e] *= keep;
         den *= keep;
 #pragma unroll
         for (int u = 0; u < CB; ++u) {
-            const float w = (sb + u < p.splits) ? __builtin_amdgcn_exp2f(mlv[u].x - m_new) : 0.f;
-            num.x += w * v[u].x;
-            num.y += w * v[u].y;
-            num.z += w * v[u].z;
-            num.w += w * v[u].w;
-            den += w * mlv[u].y;
+            // weight of the split's sum; its stored values are (partial / sum) * 2^k
+            const float w = (sb + u < p.splits) ? __builtin_amdgcn_exp2f(mlv[u].x - m_new) * mlv[u].y : 0.f;
+            const float wn = __builtin_amdgcn_ldexpf(w, -(int)mlv[u].z);
+            union { uint4 u4; _Float16 h[8]; } x;
+            x.u4 = v[u];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) num[e] += wn * (float)x.h[e];
+            den += w;
         }
         m_run = m_new;
     }
@@ -523,11 +540,15 @@ __global__ __launch_bounds__(64) void k_attn_combine(AttnArgs p)
     const int hg = rho / p.A, a = rho - hg * p.A;
     const int hq = j * p.g + hg;
     const bool padded = row_is_padded(p.pos, b * p.A + a, p.max_seq);
-    uint2 w;
-    w.x = padded ? 0u : ((uint32_t)fc_bf16_bits(num.x / den) | ((uint32_t)fc_bf16_bits(num.y / den) << 16));
-    w.y = padded ? 0u : ((uint32_t)fc_bf16_bits(num.z / den) | ((uint32_t)fc_bf16_bits(num.w / den) << 16));
-    const int dh = 32 * (slot >> 2) + 8 * (slot & 3) + 4 * hi;
-    *(uint2 *)(p.out + ((size_t)b * p.A + a) * ((size_t)p.Hq * DH) + (size_t)hq * DH + dh) = w;
+    uint16_t *orow = p.out + ((size_t)b * p.A + a) * ((size_t)p.Hq * DH) + (size_t)hq * DH;
+#pragma unroll
+    for (int g2 = 0; g2 < 2; ++g2) {
+        uint2 w;
+        w.x = padded ? 0u : ((uint32_t)fc_bf16_bits(num[4 * g2] / den) | ((uint32_t)fc_bf16_bits(num[4 * g2 + 1] / den) << 16));
+        w.y = padded ? 0u : ((uint32_t)fc_bf16_bits(num[4 * g2 + 2] / den) | ((uint32_t)fc_bf16_bits(num[4 * g2 + 3] / den) << 16));
+        const int dh = 32 * (q2 >> 1) + 8 * (2 * (q2 & 1) + g2) + 4 * hi;
+        *(uint2 *)(orow + dh) = w;
+    }
     FC_STAMP(7);
 }
 
@@ -556,10 +577,10 @@ hipError_t fc_launch_attention_mfma(const FcGeom &G, const FcAttnPlan &pl, const
     a.Vc = (const uint16_t *)v_layer;
     a.pos = pos;
     a.out = (uint16_t *)out;
-    // workspace: per (row tile, split) 16 x 64 float4 accumulator slots, then 32 x (max, sum)
+    // workspace: per (row tile, split) 32 x 128 scaled half floats, then 32 x (max, sum, exponent, -)
     const size_t tiles = (size_t)G.B * G.Hkv * pl.row_tiles;
     a.part_o = (float *)workspace;
-    a.part_ml = workspace ? (float *)workspace + tiles * pl.splits * (32 * DH) : nullptr;
+    a.part_ml = workspace ? (float *)workspace + tiles * pl.splits * (32 * DH / 2) : nullptr;
     a.B = G.B;
     a.Hq = G.Hq;
     a.Hkv = G.Hkv;
@@ -598,7 +619,7 @@ hipError_t fc_launch_attention_mfma(const FcGeom &G, const FcAttnPlan &pl, const
 #ifdef FC_ATTN_TIMING
     if (a.dbg_flags & 8) return e;
 #endif
-    const dim3 cgrid((unsigned)(tiles * 16)), cblock(64);
+    const dim3 cgrid((unsigned)(tiles * 8)), cblock(64);
     if (pl.splits <= 8) k_attn_combine<8><<<cgrid, cblock, 0, s>>>(a);
     else if (pl.splits <= 16) k_attn_combine<16><<<cgrid, cblock, 0, s>>>(a);
     else k_attn_combine<32><<<cgrid, cblock, 0, s>>>(a);
