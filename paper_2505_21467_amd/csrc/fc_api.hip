@@ -137,7 +137,7 @@ FcAttnPlan fc_plan_attention(const fc_config &cfg, int A, int kv_len)
     // enough workgroups to fill the chip; rounded to nearest, so that a grid that nearly fills it
     // already is not doubled (the partial results of a split are extra traffic)
     int64_t splits = (target + base / 2) / base;
-    const int64_t by_len = n_stages / 4 > 1 ? n_stages / 4 : 1;  // at least 256 keys per split
+    const int64_t by_len = n_stages / 2 > 1 ? n_stages / 2 : 1;  // at least 128 keys per split
     if (splits > by_len) splits = by_len;
     if (splits < 1) splits = 1;
     p.splits_bound = (int)splits;
