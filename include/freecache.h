@@ -83,7 +83,10 @@ size_t fc_cache_storage_bytes(const fc_config *cfg);
 
 /* Create a cache handle.  k_storage / v_storage: device buffers of fc_cache_storage_bytes() bytes
  * each, borrowed for the life of the handle (e.g. torch tensors), or both NULL to let the library
- * allocate zero-filled storage it then owns.  *out receives the handle (host object).
+ * allocate zero-filled storage it then owns.  *out receives the handle (host object).  The handle
+ * also owns 32 MB of device scratch (partial sums of the short-window projection), allocated here
+ * and released by fc_cache_free; this is the only allocation the library makes besides the
+ * optional K/V storage, and it is why one cache must not be used from two streams at once.
  * Errors: INVALID_ARG, UNSUPPORTED (geometry), OOM. */
 fc_status fc_cache_alloc(const fc_config *cfg, void *k_storage, void *v_storage, fc_cache **out);
 

@@ -229,6 +229,37 @@ def test_degenerate_attention_cases():
     g.close()
 
 
+def test_split_partials_keep_extreme_value_scales():
+    """Several key splits with value rows of very large, very small and zero magnitude: the partial
+    results exchanged between the splits carry their own scale, so each head keeps its relative
+    accuracy."""
+    dtype, B, Hq, Hkv, Dh, S, A = "bf16", 1, 6, 3, 128, 1500, 8
+    _say("split-KV partials with values scaled by 2^100, 2^-100 and 0")
+    w = inputs.Workload("t", dtype, B, 256, Hq, Hkv, Dh, 0, A)
+    g, o = _pair(dtype, B, 256, Hq, Hkv, Dh, S, max_rows=64)
+    K, V = inputs.kv_fill(w, 13, S)
+    V = V.clone()
+    V[:, 0] = (V[:, 0].float() * 2.0 ** 100).to(V.dtype)
+    V[:, 1] = (V[:, 1].float() * 2.0 ** -100).to(V.dtype)
+    V[:, 2] = 0
+    V[:, 2, 700] = 3.0  # one nonzero row in an otherwise zero head: most splits see only zeros
+    g.write_rows(0, K, V, 0)
+    o.write_rows(K, V, 0)
+    Q = inputs.normal(13, "q", (B, Hq, A, Dh), 1.0, dtype)
+    Og = inputs.as_oracle(g.attend(0, g.dev_t(Q), S)).reshape(B, A, Hq, Dh).astype(np.float64)
+    Oo = orc.attend(o.cfg, inputs.as_oracle(Q), o.Kc, o.Vc, S).reshape(B, A, Hq, Dh).astype(np.float64)
+    assert np.all(np.isfinite(Og))
+    for h in range(Hq):
+        ref, got = Oo[0, :, h], Og[0, :, h]
+        scale = np.abs(ref).mean()
+        assert scale > 0
+        err = np.abs(got - ref)
+        # same bars as the bf16 tolerance, relative to the magnitude of this head's outputs
+        assert err.mean() / scale < 5e-3, "head %d: mean-rel %g" % (h, err.mean() / scale)
+        assert err.max() / np.abs(ref).max() < 2e-2, "head %d: max-rel %g" % (h, err.max() / np.abs(ref).max())
+    g.close()
+
+
 def test_multi_layer_caches_are_independent():
     dtype, B, d, Hq, Hkv, Dh, L, A = "bf16", 1, 256, 8, 2, 128, 96, 32
     _say("3 layers, step on layer 1 only")
