@@ -10,11 +10,17 @@
 // (more, smaller workgroups when the window is too short to fill the chip).  The rotation, the bias and
 // the stores to q_out / the K rows / the transposed V tiles therefore need no exchange between lanes.
 //
-// Both operands are contiguous along the hidden dimension.  64 hidden elements of every row of the
-// tile (128-byte row pieces) stream HBM/L2 -> LDS with direct-to-LDS 16-byte loads into a ring of
-// three stages, two ahead of the multiply; the 16-byte chunks of a row piece are XOR-swizzled with
-// bits 1..3 of the row (applied to the global address of the loading lane), which spreads the 16 lanes
-// the LDS serves per clock over 16 different bank groups.
+// Both operands are contiguous along the hidden dimension.  64 (or 128) hidden elements of every row
+// of the tile (128- or 256-byte row pieces) stream HBM/L2 -> LDS with direct-to-LDS 16-byte loads into
+// a ring of two to four stages; the 16-byte chunks of a row piece are XOR-swizzled with bits 1..3 (or
+// 0..3) of the row (applied to the global address of the loading lane), which spreads the 16 lanes the
+// LDS serves per clock over 16 different bank groups.
+//
+// A wave that issues a direct-to-LDS load waits until the memory pipeline has taken it (about 46
+// cycles per load measured), and that wait is not hidden when the wave is alone on its SIMD.  The
+// 128-row shapes (four multiplying waves) therefore carry four more waves that do nothing but issue
+// the loads; in the 256-row shapes (two multiplying waves per SIMD) every wave issues its share, a
+// quarter at a time between its multiplies.
 #include <stdlib.h>
 
 #include "fc_device.h"
@@ -25,8 +31,7 @@ namespace {
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 
-constexpr int KS = 64;          // hidden elements per stage
-constexpr int ROWB = KS * 2;    // bytes of one row piece
+constexpr int KS_MIN = 64;      // hidden elements per stage: 64 or 128 (template parameter KS)
 
 struct GemmArgs {
     const uint16_t *X;     // [M][K]
@@ -59,26 +64,45 @@ __device__ __forceinline__ void load_lds16g(const void *g, void *l)
                                      (void __attribute__((address_space(3))) *)l, 16, 0, 0);
 }
 
-template <int N>
+// wait until at most N vector-memory operations of this wave are outstanding; LGKM0: and no LDS one
+template <int N, bool LGKM0 = false>
 __device__ __forceinline__ void wait_vmg()
 {
     // gfx9 s_waitcnt immediate: vmcnt[3:0] | expcnt[6:4] | lgkmcnt[11:8] | vmcnt[5:4] at [15:14]
-    __builtin_amdgcn_s_waitcnt((N & 15) | (7 << 4) | (15 << 8) | ((N >> 4) << 14));
+    __builtin_amdgcn_s_waitcnt((N & 15) | (7 << 4) | ((LGKM0 ? 0 : 15) << 8) | ((N >> 4) << 14));
+}
+// the same with N = k * PER for a run-time k in 0..3
+template <int PER, bool LGKM0>
+__device__ __forceinline__ void wait_stages(int k)
+{
+    if (k >= 3) wait_vmg<3 * PER, LGKM0>();
+    else if (k == 2) wait_vmg<2 * PER, LGKM0>();
+    else if (k == 1) wait_vmg<PER, LGKM0>();
+    else wait_vmg<0, LGKM0>();
 }
 
 // Workgroup tile: NG head groups x WM row groups of waves (NW = NG * WM waves).  A wave owns MW
 // 32-row sub-tiles of window rows and the NSUB 32-feature sub-tiles of one head (NSUB = 4) or of one
 // rotary-paired half head (NSUB = 2).  SLOTS = stages in the LDS ring.
-template <int NW, int NSUB, int MW, int NG, int SLOTS>
-__global__ __launch_bounds__(NW * 64) void k_proj_gemm(GemmArgs p)
+// NL = 0: every wave also issues its share of the loads; NL > 0: NL extra waves do nothing but issue
+// the loads, so that the multiplying waves never wait for the memory pipeline to take a load.
+template <int KS, int NW, int NSUB, int MW, int NG, int SLOTS, int NL>
+__global__ __launch_bounds__((NW + NL) * 64) void k_proj_gemm(GemmArgs p)
 {
+    constexpr int ROWB = KS * 2;               // bytes of one row piece: 128 or 256
+    constexpr int CPR = ROWB / 16;             // 16-byte chunks per row piece
+    constexpr int RPB = 1024 / ROWB;           // row pieces per 1 KB block (= one wave-wide load)
+    constexpr int NKK = KS / 16;               // k-steps per stage
     constexpr int WM = NW / NG;
+    constexpr int NLW = NL > 0 ? NL : NW;      // waves that issue loads
     constexpr int WROWS = 32 * NSUB * NG, XROWS = 32 * MW * WM;
     constexpr int WBYTES = WROWS * ROWB, STAGE = (WROWS + XROWS) * ROWB;
-    constexpr int NBLK = (WROWS + XROWS) / 8;  // 1 KB blocks (8 row pieces) per stage
-    constexpr int LBW = NBLK / NW;             // blocks per wave and stage
-    constexpr int WBW = (WROWS / 8) / NW;      // of which weight blocks (the first ones)
-    static_assert(NW % NG == 0 && NBLK % NW == 0 && (WROWS / 8) % NW == 0 && (NSUB == 4 || NG == 1), "tile shape");
+    constexpr int NBLK = (WROWS + XROWS) / RPB;  // 1 KB blocks per stage
+    constexpr int LBW = NBLK / NLW;            // blocks per loading wave and stage
+    constexpr int WBW = (WROWS / RPB) / NLW;   // of which weight blocks (the first ones)
+    static_assert(KS == 64 || KS == 128, "stage depth");
+    static_assert(NW % NG == 0 && NBLK % NLW == 0 && (WROWS / RPB) % NLW == 0 && (NSUB == 4 || NG == 1), "tile shape");
+    static_assert((SLOTS - 1) * LBW < 64 && SLOTS >= 2 && SLOTS <= 4, "vmcnt range");
     extern __shared__ __align__(1024) unsigned char smem[];
     const FcGeom &G = p.G;
     FC_GSTAMP(0);
@@ -96,7 +120,9 @@ __global__ __launch_bounds__(NW * 64) void k_proj_gemm(GemmArgs p)
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int col = lane & 31, hi = lane >> 5;
-    const int wn = wave / WM, wm = wave % WM;  // this wave's head group and row group
+    const bool is_loader = NL > 0 && wave >= NW;  // wave-uniform
+    const int lw = NL > 0 ? wave - NW : wave;     // index among the loading waves
+    const int wn = (wave % NW) / WM, wm = wave % WM;  // this wave's head group and row group
     const int hs = NSUB == 4 ? unit * NG + wn : unit >> 1;
     const int half = NSUB == 4 ? 0 : unit & 1;  // which rotary-paired half of the head
     const bool head_valid = hs < n_slots;       // an odd number of heads leaves the last pair half empty
@@ -105,9 +131,11 @@ __global__ __launch_bounds__(NW * 64) void k_proj_gemm(GemmArgs p)
     uint32_t goff[LBW];
 #pragma unroll
     for (int i = 0; i < LBW; ++i) {
-        const int bid = wave + NW * i;              // block of the stage: weight blocks first
-        const int rl = 8 * (i < WBW ? bid : bid - WROWS / 8) + (lane >> 3);  // row of the W / X tile
-        const int c = (lane & 7) ^ ((rl >> 1) & 7);  // logical 16-byte chunk that lands at position lane & 7
+        const int bid = lw + NLW * i;               // block of the stage: weight blocks first (junk for lw < 0)
+        const int rl = RPB * (i < WBW ? bid : bid - WROWS / RPB) + lane / CPR;  // row of the W / X tile
+        // logical 16-byte chunk that lands at position lane % CPR of the row piece: 128-byte pieces are
+        // swizzled with bits 1..3 of the row, 256-byte pieces with bits 0..3
+        const int c = (lane % CPR) ^ (KS == 64 ? (rl >> 1) & 7 : rl & 15);
         if (i < WBW) {
             int n;
             if (NSUB == 4) n = min(unit * NG + rl / 128, n_slots - 1) * 128 + (rl & 127);
@@ -130,14 +158,15 @@ __global__ __launch_bounds__(NW * 64) void k_proj_gemm(GemmArgs p)
         for (int i = 0; i < LBW; ++i) {
             if (part >= 0 && (i & 3) != part) continue;
             const unsigned char *src = (const unsigned char *)(i < WBW ? p.W : p.X) + (size_t)st * ROWB;
-            load_lds16g(src + goff[i], dst + (wave + NW * i) * 1024);
+            load_lds16g(src + goff[i], dst + (lw + NLW * i) * 1024);
         }
     };
 
     // ---- operand read offsets inside a stage (bytes): row `col` of a 32-row sub-tile, k-step kk
-    uint32_t foff[4];
+    uint32_t foff[NKK];
 #pragma unroll
-    for (int kk = 0; kk < 4; ++kk) foff[kk] = (uint32_t)(col * ROWB + (((2 * kk + hi) ^ ((col >> 1) & 7)) << 4));
+    for (int kk = 0; kk < NKK; ++kk)
+        foff[kk] = (uint32_t)(col * ROWB + (((2 * kk + hi) ^ (KS == 64 ? (col >> 1) & 7 : col & 15)) << 4));
     const uint32_t w_base = (uint32_t)(wn * NSUB * 32 * ROWB);
     const uint32_t x_base = (uint32_t)(WBYTES + wm * MW * 32 * ROWB);
 
@@ -180,10 +209,47 @@ __global__ __launch_bounds__(NW * 64) void k_proj_gemm(GemmArgs p)
     const int n_stages = p.K / KS;
     FC_GSTAMP(1);
     const int n_pro = min(SLOTS, n_stages);
+    if (NL > 0) {
+        // ---- loading waves: one barrier per stage, shared with the multiplying waves.  Barrier `it`
+        // (it = 0 .. n_stages - 2) means: stage it+1 is complete and every multiplying wave has left
+        // stage it, whose slot takes stage it + SLOTS.
+        if (is_loader) {
+            for (int st = 0; st < n_pro; ++st) issue_stage(st, -1);
+            wait_stages<LBW, false>(n_pro - 1);
+            __builtin_amdgcn_s_barrier();  // stage 0 is complete
+            for (int it = 0; it + 1 < n_stages; ++it) {
+                // stages requested so far: min(n_stages, it + SLOTS); those after it+1 may stay in flight
+                wait_stages<LBW, false>(min(n_stages, it + SLOTS) - (it + 2));
+                __builtin_amdgcn_s_barrier();
+                if (it + SLOTS < n_stages) issue_stage(it + SLOTS, -1);
+            }
+            return;
+        }
+        __builtin_amdgcn_s_barrier();  // stage 0 is complete
+        read_frags(0, 0, 0);
+        int slot = 0;
+        for (int it = 0; it < n_stages; ++it) {
+#pragma unroll
+            for (int kk = 0; kk < NKK - 1; ++kk) {
+                read_frags(slot, kk + 1, (kk + 1) & 1);
+                __builtin_amdgcn_sched_barrier(0);
+                multiply(kk & 1);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            const int nslot = slot == SLOTS - 1 ? 0 : slot + 1;
+            if (it + 1 < n_stages) {
+                wait_vmg<63, true>();  // lgkmcnt(0): the reads of stage `it` have returned
+                __builtin_amdgcn_s_barrier();
+                read_frags(nslot, 0, 0);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            multiply(1);
+            __builtin_amdgcn_sched_barrier(0);
+            slot = nslot;
+        }
+    } else {
     for (int st = 0; st < n_pro; ++st) issue_stage(st, -1);
-    if (n_pro == 3) wait_vmg<2 * LBW>();
-    else if (n_pro == 2) wait_vmg<LBW>();
-    else wait_vmg<0>();
+    wait_stages<LBW, false>(n_pro - 1);
     __builtin_amdgcn_s_barrier();  // stage 0 is complete for every wave
     read_frags(0, 0, 0);
     int slot = 0;
@@ -193,9 +259,9 @@ __global__ __launch_bounds__(NW * 64) void k_proj_gemm(GemmArgs p)
         const int refill = it - 1 + SLOTS;
         const bool do_refill = it > 0 && refill < n_stages;
 #pragma unroll
-        for (int kk = 0; kk < 3; ++kk) {
+        for (int kk = 0; kk < NKK - 1; ++kk) {
             read_frags(slot, kk + 1, (kk + 1) & 1);
-            if (do_refill) issue_stage(refill, kk + 1);
+            if (do_refill && kk < 3) issue_stage(refill, kk + 1);
             __builtin_amdgcn_sched_barrier(0);
             multiply(kk & 1);
             __builtin_amdgcn_sched_barrier(0);
@@ -204,8 +270,7 @@ __global__ __launch_bounds__(NW * 64) void k_proj_gemm(GemmArgs p)
         if (it + 1 < n_stages) {
             // This wave's reads of stage `it` have all returned (lgkmcnt 0); behind the barrier that
             // holds for every wave, and stage it+1 is complete (later stages may still be in flight).
-            if (SLOTS == 3 && it + 2 < n_stages) __builtin_amdgcn_s_waitcnt((LBW & 15) | (7 << 4) | (0 << 8) | ((LBW >> 4) << 14));
-            else __builtin_amdgcn_s_waitcnt((0 & 15) | (7 << 4) | (0 << 8));
+            wait_stages<LBW, true>(min(n_stages, it + SLOTS) - (it + 2));
             __builtin_amdgcn_s_barrier();
             if (it + SLOTS < n_stages) issue_stage(it + SLOTS, 0);
             read_frags(nslot, 0, 0);
@@ -214,6 +279,7 @@ __global__ __launch_bounds__(NW * 64) void k_proj_gemm(GemmArgs p)
         multiply(1);
         __builtin_amdgcn_sched_barrier(0);
         slot = nslot;
+    }
     }
 
     FC_GSTAMP(2);
@@ -304,20 +370,20 @@ __global__ __launch_bounds__(NW * 64) void k_proj_gemm(GemmArgs p)
     FC_GSTAMP(4);
 }
 
-template <int NW, int NSUB, int MW, int NG, int SLOTS>
+template <int KS, int NW, int NSUB, int MW, int NG, int SLOTS, int NL>
 hipError_t launch_gemm(GemmArgs a, hipStream_t s)
 {
     constexpr int XROWS = 32 * MW * (NW / NG);
-    constexpr int LDS = SLOTS * (32 * NSUB * NG + XROWS) * ROWB;
+    constexpr int LDS = SLOTS * (32 * NSUB * NG + XROWS) * KS * 2;
     static_assert(LDS <= 160 * 1024, "LDS ring too large");
-    static hipError_t attr = hipFuncSetAttribute((const void *)k_proj_gemm<NW, NSUB, MW, NG, SLOTS>,
+    static hipError_t attr = hipFuncSetAttribute((const void *)k_proj_gemm<KS, NW, NSUB, MW, NG, SLOTS, NL>,
                                                  hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
     if (attr != hipSuccess) return attr;
     const int slots = a.G.Hq + 2 * a.G.Hkv;
     a.n_units = NSUB == 4 ? (slots + NG - 1) / NG : 2 * slots;
     a.n_mt = (a.M + XROWS - 1) / XROWS;
     const unsigned grid = (unsigned)(((a.n_units + 7) / 8) * 8 * a.n_mt);
-    k_proj_gemm<NW, NSUB, MW, NG, SLOTS><<<dim3(grid), dim3(NW * 64), LDS, s>>>(a);
+    k_proj_gemm<KS, NW, NSUB, MW, NG, SLOTS, NL><<<dim3(grid), dim3((NW + NL) * 64), LDS, s>>>(a);
     return hipGetLastError();
 }
 
@@ -327,7 +393,7 @@ bool fc_project_gemm_supported(const fc_config &cfg, int M)
 {
     // 32-bit byte offsets inside X and W; the hidden dimension in whole stages
     const int64_t n = (int64_t)(cfg.n_q_heads + 2 * cfg.n_kv_heads) * cfg.head_dim;
-    return cfg.dtype == FC_BF16 && cfg.head_dim == 128 && cfg.hidden % KS == 0 && M > 32 &&
+    return cfg.dtype == FC_BF16 && cfg.head_dim == 128 && cfg.hidden % KS_MIN == 0 && M > 32 &&
            n * cfg.hidden * 2 < ((int64_t)1 << 32) && (int64_t)M * cfg.hidden * 2 < ((int64_t)1 << 32);
 }
 
@@ -359,8 +425,11 @@ hipError_t fc_launch_project_gemm(const FcGeom &G, const void *x, const void *w,
     int shape = 0;  // 0: 256 rows x head, 1: 128 rows x head, 2: 128 rows x half head
     if ((int64_t)slots * ((a.M + 255) / 256) < 192) shape = (int64_t)slots * ((a.M + 127) / 128) >= 144 ? 1 : 2;
     if (const char *e = getenv("FC_PROJ_GEMM_SHAPE")) shape = atoi(e);  // tuning knob
-    if (shape == 3) return launch_gemm<8, 4, 2, 2, 2>(a, s);   // 256 rows x two heads
-    if (shape == 0) return launch_gemm<8, 4, 1, 1, 3>(a, s);   // 256 rows x head
-    if (shape == 1) return launch_gemm<4, 4, 1, 1, 3>(a, s);   // 128 rows x head
-    return launch_gemm<4, 2, 1, 1, 3>(a, s);                   // 128 rows x half head
+    // The two 128-row shapes get four extra waves that only issue the loads (their four multiplying
+    // waves are alone on their SIMDs); the half-head shape also takes 128 hidden elements per stage.
+    if (shape == 3) return launch_gemm<64, 8, 4, 2, 2, 2, 0>(a, s);   // 256 rows x two heads
+    if (shape == 0) return launch_gemm<64, 8, 4, 1, 1, 3, 0>(a, s);   // 256 rows x head
+    if (shape == 1) return launch_gemm<64, 4, 4, 1, 1, 4, 4>(a, s);   // 128 rows x head
+    if (a.K % 128 == 0) return launch_gemm<128, 4, 2, 1, 1, 3, 4>(a, s);  // 128 rows x half head
+    return launch_gemm<64, 4, 2, 1, 1, 4, 4>(a, s);
 }
