@@ -21,9 +21,18 @@
  *      kv_len cached rows (Table 1, rows "QK^T" and "Attention Score x Value",
  *      L x L replaced by A x L), grouped-query aware, with no mask.
  *
+ * The second half of the file widens the step to the whole transformer layer
+ * on the window rows (Table 1, rows "Output projection (W_out)", "FFN W_1" and
+ * "FFN W_2", again with L replaced by A): RMS normalisation, the attention path
+ * above, the output projection with its residual, and a gated feed-forward
+ * network with its residual.  The paper names the modules but not their inner
+ * form; pre-normalisation with RMSNorm and a SiLU-gated W_1 (the form of the
+ * Dream and LLaDA checkpoints the paper evaluates) is this build's reading.
+ *
  * All sums run in double, in ascending index order, with no blocking, fusion
  * or reordering.  Values are rounded only where the storage format demands it:
- * q, k, v when they are stored, and the attention output.
+ * q, k, v when they are stored, the attention output, and every activation
+ * tensor that the layer hands from one module to the next.
  *
  * Array layouts (row-major, all "storage" arrays hold floats whose values are
  * exactly representable in the storage dtype):
@@ -270,4 +279,118 @@ int fco_window(int32_t step, int32_t P, int32_t G, int32_t Bk, int32_t steps_per
     }
     *refresh_after = (refresh_every > 0 && (step + 1) % refresh_every == 0) ? 1 : 0;
     return 0;
+}
+
+/* -------------------------------------------------------------------------
+ * The rest of the layer on the window rows (Table 1: W_out, FFN W_1, FFN W_2).
+ */
+
+/* RMS normalisation of each row: out[r][k] = x[r][k] / sqrt(mean_k x[r][k]^2 + eps) * w[k],
+ * rounded to the storage format. */
+int fco_rmsnorm(const float *X, const float *w, double eps, int64_t rows, int32_t d,
+                int32_t dtype, float *out)
+{
+    if (!X || !w || !out || rows < 1 || d < 1 || !(eps >= 0.0)) return 1;
+#pragma omp parallel for schedule(static)
+    for (int64_t r = 0; r < rows; ++r) {
+        const float *x = X + (size_t)r * d;
+        double ss = 0.0;
+        for (int k = 0; k < d; ++k) ss += (double)x[k] * (double)x[k];
+        const double inv = 1.0 / sqrt(ss / (double)d + eps);
+        for (int k = 0; k < d; ++k)
+            out[(size_t)r * d + k] = (float)fco_round_to_storage((double)x[k] * inv * (double)w[k], dtype);
+    }
+    return 0;
+}
+
+/* out[m][n] = res[m][n] + sum_k X[m][k] W[n][k], one rounding to storage.  res may be NULL.
+ * This is the output projection W_out and the second FFN matrix W_2, each with the residual
+ * connection of a pre-normalised layer folded in. */
+int fco_linear_residual(const float *X, const float *W, const float *res, int64_t M, int32_t K,
+                        int32_t N, int32_t dtype, float *out)
+{
+    if (!X || !W || !out || M < 1 || K < 1 || N < 1) return 1;
+#pragma omp parallel for schedule(static)
+    for (int64_t m = 0; m < M; ++m) {
+        const float *x = X + (size_t)m * K;
+        for (int n = 0; n < N; ++n) {
+            const float *w = W + (size_t)n * K;
+            double acc = 0.0;
+            for (int k = 0; k < K; ++k) acc += (double)x[k] * (double)w[k];
+            if (res) acc += (double)res[(size_t)m * N + n];
+            out[(size_t)m * N + n] = (float)fco_round_to_storage(acc, dtype);
+        }
+    }
+    return 0;
+}
+
+/* First FFN matrix in its gated form: with g = X Wg^T and u = X Wu^T (both kept in double),
+ * out[m][f] = silu(g[m][f]) * u[m][f], silu(t) = t / (1 + exp(-t)); one rounding to storage. */
+int fco_ffn_gate_up(const float *X, const float *Wg, const float *Wu, int64_t M, int32_t K,
+                    int32_t F, int32_t dtype, float *out)
+{
+    if (!X || !Wg || !Wu || !out || M < 1 || K < 1 || F < 1) return 1;
+#pragma omp parallel for schedule(static)
+    for (int64_t m = 0; m < M; ++m) {
+        const float *x = X + (size_t)m * K;
+        for (int f = 0; f < F; ++f) {
+            const float *wg = Wg + (size_t)f * K, *wu = Wu + (size_t)f * K;
+            double g = 0.0, u = 0.0;
+            for (int k = 0; k < K; ++k) g += (double)x[k] * (double)wg[k];
+            for (int k = 0; k < K; ++k) u += (double)x[k] * (double)wu[k];
+            const double act = g / (1.0 + exp(-g)) * u;
+            out[(size_t)m * F + f] = (float)fco_round_to_storage(act, dtype);
+        }
+    }
+    return 0;
+}
+
+/* Weights of one pre-normalised transformer layer. */
+typedef struct {
+    const float *norm1;  /* [d] */
+    const float *w_qkv;  /* [N][d] */
+    const float *b_qkv;  /* [N] or NULL */
+    const float *w_out;  /* [d][Hq*Dh] */
+    const float *norm2;  /* [d] */
+    const float *w_gate; /* [d_ff][d] */
+    const float *w_up;   /* [d_ff][d] */
+    const float *w_down; /* [d][d_ff] */
+    int32_t d_ff;
+    double eps;
+} fco_layer_weights;
+
+/* One cached step of the whole layer on the window rows X [B][A][d]:
+ *   h1 = rmsnorm(X; norm1)
+ *   (Q, cache rows, O) = the attention path of fco_layer_step on h1
+ *   X2 = X + O W_out^T
+ *   h2 = rmsnorm(X2; norm2)
+ *   Y  = X2 + (silu(h2 Wg^T) * (h2 Wu^T)) W_down^T
+ * Every named tensor is rounded to storage.  X2 (optional, [B][A][d]) receives the
+ * intermediate residual stream.  A padded row (pos < 0) has O = 0 and is otherwise treated like
+ * any other row. */
+int fco_full_layer_step(const fco_config *c, int32_t A, const float *X, const fco_layer_weights *w,
+                        const int32_t *pos, int32_t kv_len, float *Kc, float *Vc, float *Y,
+                        float *X2)
+{
+    if (!cfg_ok(c) || A < 1 || !X || !w || !pos || !Y || w->d_ff < 1) return 1;
+    const int64_t M = (int64_t)c->batch * A;
+    const int d = c->hidden, E = c->n_q_heads * c->head_dim, F = w->d_ff;
+    float *h = (float *)malloc(sizeof(float) * (size_t)M * d);
+    float *q = (float *)malloc(sizeof(float) * (size_t)M * E);
+    float *o = (float *)malloc(sizeof(float) * (size_t)M * E);
+    float *x2 = (float *)malloc(sizeof(float) * (size_t)M * d);
+    float *act = (float *)malloc(sizeof(float) * (size_t)M * F);
+    int rc = fco_rmsnorm(X, w->norm1, w->eps, M, d, c->dtype, h);
+    if (!rc) rc = fco_layer_step(c, A, h, w->w_qkv, w->b_qkv, pos, kv_len, Kc, Vc, q, o);
+    if (!rc) rc = fco_linear_residual(o, w->w_out, X, M, E, d, c->dtype, x2);
+    if (!rc) rc = fco_rmsnorm(x2, w->norm2, w->eps, M, d, c->dtype, h);
+    if (!rc) rc = fco_ffn_gate_up(h, w->w_gate, w->w_up, M, d, F, c->dtype, act);
+    if (!rc) rc = fco_linear_residual(act, w->w_down, x2, M, F, d, c->dtype, Y);
+    if (!rc && X2) memcpy(X2, x2, sizeof(float) * (size_t)M * d);
+    free(h);
+    free(q);
+    free(o);
+    free(x2);
+    free(act);
+    return rc;
 }

@@ -66,7 +66,8 @@ def lib():
         L.fco_round_to_storage.restype = ctypes.c_double
         L.fco_round_to_storage.argtypes = [ctypes.c_double, ctypes.c_int32]
         L.fco_round_array.restype = None
-        for name in ("fco_project_rope", "fco_scatter", "fco_attend", "fco_layer_step", "fco_window"):
+        for name in ("fco_project_rope", "fco_scatter", "fco_attend", "fco_layer_step", "fco_window",
+                     "fco_rmsnorm", "fco_linear_residual", "fco_ffn_gate_up", "fco_full_layer_step"):
             getattr(L, name).restype = ctypes.c_int
         _lib = L
     return _lib
@@ -214,3 +215,88 @@ def window(step, P, G, Bk, steps_per_block, refresh_every=0, mode=0):
         raise IndexError("step past the last block")
     _check(rc, "fco_window")
     return ws.value, rows.value, ra.value
+
+
+# --- the rest of the layer on the window rows (Table 1: W_out, FFN W_1, FFN W_2) ---------------
+
+class _LayerWeights(ctypes.Structure):
+    _fields_ = [(n, ctypes.POINTER(ctypes.c_float)) for n in
+                ("norm1", "w_qkv", "b_qkv", "w_out", "norm2", "w_gate", "w_up", "w_down")] + [
+        ("d_ff", ctypes.c_int32), ("eps", ctypes.c_double)]
+
+
+def rmsnorm(X, w, eps: float, dtype: str):
+    """Row-wise RMS normalisation of X [..., d] with weight w [d]; float32 array of X's shape."""
+    X = _f32(X)
+    d = X.shape[-1]
+    w = _f32(w, (d,))
+    out = np.empty_like(X)
+    rc = lib().fco_rmsnorm(_p(X, ctypes.c_float), _p(w, ctypes.c_float), ctypes.c_double(eps),
+                           ctypes.c_int64(X.size // d), ctypes.c_int32(d),
+                           ctypes.c_int32(_DTYPES[dtype]), _p(out, ctypes.c_float))
+    _check(rc, "fco_rmsnorm")
+    return out
+
+
+def linear_residual(X, W, res, dtype: str):
+    """res + X W^T for X [M, K], W [N, K], res [M, N] or None."""
+    X = _f32(X)
+    M, K = X.shape
+    W = _f32(W)
+    N = W.shape[0]
+    assert W.shape == (N, K)
+    res = None if res is None else _f32(res, (M, N))
+    out = np.empty((M, N), np.float32)
+    rc = lib().fco_linear_residual(_p(X, ctypes.c_float), _p(W, ctypes.c_float), _p(res, ctypes.c_float),
+                                   ctypes.c_int64(M), ctypes.c_int32(K), ctypes.c_int32(N),
+                                   ctypes.c_int32(_DTYPES[dtype]), _p(out, ctypes.c_float))
+    _check(rc, "fco_linear_residual")
+    return out
+
+
+def ffn_gate_up(X, Wg, Wu, dtype: str):
+    """silu(X Wg^T) * (X Wu^T) for X [M, K], Wg, Wu [F, K]."""
+    X = _f32(X)
+    M, K = X.shape
+    Wg, Wu = _f32(Wg), _f32(Wu)
+    F = Wg.shape[0]
+    assert Wg.shape == (F, K) == Wu.shape
+    out = np.empty((M, F), np.float32)
+    rc = lib().fco_ffn_gate_up(_p(X, ctypes.c_float), _p(Wg, ctypes.c_float), _p(Wu, ctypes.c_float),
+                               ctypes.c_int64(M), ctypes.c_int32(K), ctypes.c_int32(F),
+                               ctypes.c_int32(_DTYPES[dtype]), _p(out, ctypes.c_float))
+    _check(rc, "fco_ffn_gate_up")
+    return out
+
+
+def full_layer_step(cfg: OracleConfig, X, weights: dict, pos, kv_len, Kc, Vc, eps: float, want_x2=False):
+    """One cached step of the whole layer; Kc, Vc updated in place.  weights: dict with norm1,
+    w_qkv, b_qkv (or None), w_out, norm2, w_gate, w_up, w_down as float32 arrays.
+    Returns Y [B, A, d] (+ X2, the residual stream after attention)."""
+    B, A = pos.shape
+    d, E = cfg.hidden, cfg.n_q_heads * cfg.head_dim
+    X = _f32(X, (B, A, d))
+    F = weights["w_gate"].shape[0]
+    keep = {
+        "norm1": _f32(weights["norm1"], (d,)), "w_qkv": _f32(weights["w_qkv"], (cfg.qkv_width, d)),
+        "b_qkv": None if weights.get("b_qkv") is None else _f32(weights["b_qkv"], (cfg.qkv_width,)),
+        "w_out": _f32(weights["w_out"], (d, E)), "norm2": _f32(weights["norm2"], (d,)),
+        "w_gate": _f32(weights["w_gate"], (F, d)), "w_up": _f32(weights["w_up"], (F, d)),
+        "w_down": _f32(weights["w_down"], (d, F)),
+    }
+    lw = _LayerWeights(*[_p(keep[n], ctypes.c_float) for n in
+                         ("norm1", "w_qkv", "b_qkv", "w_out", "norm2", "w_gate", "w_up", "w_down")],
+                       F, eps)
+    pos = np.ascontiguousarray(pos, dtype=np.int32)
+    assert Kc.dtype == np.float32 and Vc.dtype == np.float32
+    assert Kc.flags.c_contiguous and Vc.flags.c_contiguous
+    assert Kc.shape == (B, cfg.n_kv_heads, cfg.max_seq, cfg.head_dim) == Vc.shape
+    Y = np.empty((B, A, d), np.float32)
+    X2 = np.empty((B, A, d), np.float32) if want_x2 else None
+    c = cfg.c()
+    rc = lib().fco_full_layer_step(ctypes.byref(c), ctypes.c_int32(A), _p(X, ctypes.c_float),
+                                   ctypes.byref(lw), _p(pos, ctypes.c_int32), ctypes.c_int32(kv_len),
+                                   _p(Kc, ctypes.c_float), _p(Vc, ctypes.c_float),
+                                   _p(Y, ctypes.c_float), _p(X2, ctypes.c_float))
+    _check(rc, "fco_full_layer_step")
+    return (Y, X2) if want_x2 else Y

@@ -36,6 +36,8 @@ class Workload:
     steps_per_block: int = 0
     refresh_every: int = 0
     rope_base: float = 10000.0
+    d_ff: int = 0         # width of the feed-forward network (whole-layer workloads)
+    norm_eps: float = 1e-6
 
     @property
     def qkv_width(self) -> int:
@@ -51,13 +53,15 @@ class Workload:
 
 
 # The five configurations of the measurement plan.
-C1 = Workload("c1_tiny_f32", "f32", 1, 256, 4, 4, 64, 256, 32)
-C2 = Workload("c2_dream7b_L1024_A32", "bf16", 1, 3584, 28, 4, 128, 1024, 32)
-C3 = Workload("c3_llada8b_B4_L4096_A64", "bf16", 4, 4096, 32, 32, 128, 4096, 64)
+# d_ff: 18944 for the Dream-7B geometry (Qwen2.5-7B), 12288 for LLaDA-8B.
+C1 = Workload("c1_tiny_f32", "f32", 1, 256, 4, 4, 64, 256, 32, d_ff=512)
+C2 = Workload("c2_dream7b_L1024_A32", "bf16", 1, 3584, 28, 4, 128, 1024, 32, d_ff=18944)
+C3 = Workload("c3_llada8b_B4_L4096_A64", "bf16", 4, 4096, 32, 32, 128, 4096, 64, d_ff=12288,
+              norm_eps=1e-5)
 C4 = Workload("c4_dream7b_long_L16384_A32", "bf16", 1, 3584, 28, 4, 128, 16384, 32,
-              gen_len=416, block=32, steps_per_block=8)
+              gen_len=416, block=32, steps_per_block=8, d_ff=18944)
 C5 = Workload("c5_dream7b_28layers_B8_P2048_G256", "bf16", 8, 3584, 28, 4, 128, 2048, 32,
-              n_layers=28, gen_len=256, block=32, steps_per_block=8, refresh_every=8)
+              n_layers=28, gen_len=256, block=32, steps_per_block=8, refresh_every=8, d_ff=18944)
 CONFIGS = {w.name: w for w in (C1, C2, C3, C4, C5)}
 
 
@@ -110,3 +114,17 @@ def kv_fill(w: Workload, seed: int, rows: int, tag: str = "kv"):
 def window_positions(batch: int, start: int, rows: int) -> torch.Tensor:
     """pos [B, rows] = start + a."""
     return torch.arange(start, start + rows, dtype=torch.int32).repeat(batch, 1).contiguous()
+
+
+def layer_weights(w: Workload, seed: int, layer: int = 0, with_bias: bool = False) -> dict:
+    """All weights of one pre-normalised layer: matrices ~ N(0, 0.02), norm weights ~ 1 + N(0, 0.1)."""
+    e = w.n_q_heads * w.head_dim
+    t = lambda name, shape: normal(seed, "%s.%d" % (name, layer), shape, 0.02, w.dtype)
+    n = lambda name: (1.0 + 0.1 * torch.randn((w.hidden,), generator=_gen(seed, "%s.%d" % (name, layer)),
+                                              dtype=torch.float32)).to(TORCH_DTYPE[w.dtype]).contiguous()
+    return {
+        "norm1": n("norm1"), "w_qkv": weights(w, seed, layer), "b_qkv": bias(w, seed, layer) if with_bias else None,
+        "w_out": t("w_out", (w.hidden, e)), "norm2": n("norm2"),
+        "w_gate": t("w_gate", (w.d_ff, w.hidden)), "w_up": t("w_up", (w.d_ff, w.hidden)),
+        "w_down": t("w_down", (w.hidden, w.d_ff)),
+    }

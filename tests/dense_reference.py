@@ -8,7 +8,7 @@ vanilla diffusion-LM layer does at each denoising step (paper, section 3.1.1).
 """
 import numpy as np
 import torch
-from scipy.special import softmax
+from scipy.special import expit, softmax
 
 
 def round_storage(x: np.ndarray, dtype: str) -> np.ndarray:
@@ -57,3 +57,27 @@ def dense_layer(X, W, bias, Hq, Hkv, Dh, base, dtype, scale=None, pos=None):
     O = round_storage(o.reshape(B, S, Hq * Dh), dtype)
     return (q.transpose(0, 2, 1, 3).copy(), k.transpose(0, 2, 1, 3).copy(),
             v.transpose(0, 2, 1, 3).copy(), O)
+
+
+def rmsnorm_np(x, w, eps):
+    x = np.asarray(x, np.float64)
+    return x / np.sqrt(np.mean(np.square(x), axis=-1, keepdims=True) + eps) * np.asarray(w, np.float64)
+
+
+def dense_full_layer(X, wts, Hq, Hkv, Dh, base, dtype, eps, pos=None):
+    """Uncached pre-normalised transformer layer over all rows of X [B,S,d]: RMSNorm, bidirectional
+    attention (dense_layer), output projection + residual, RMSNorm, SiLU-gated feed-forward network +
+    residual (Table 1 of the paper lists these modules).  wts: dict of float arrays norm1, w_qkv,
+    b_qkv (or None), w_out, norm2, w_gate, w_up, w_down.  Returns (X2, Y, K, V) as float64; every
+    tensor handed from one module to the next is rounded to the storage dtype."""
+    f = lambda a: np.asarray(a, np.float64)
+    X = f(X)
+    h1 = round_storage(rmsnorm_np(X, wts["norm1"], eps), dtype)
+    _, k, v, O = dense_layer(h1, wts["w_qkv"], wts.get("b_qkv"), Hq, Hkv, Dh, base, dtype, pos=pos)
+    X2 = round_storage(X + O @ f(wts["w_out"]).T, dtype)
+    h2 = round_storage(rmsnorm_np(X2, wts["norm2"], eps), dtype)
+    g = h2 @ f(wts["w_gate"]).T
+    u = h2 @ f(wts["w_up"]).T
+    act = round_storage(g * expit(g) * u, dtype)
+    Y = round_storage(X2 + act @ f(wts["w_down"]).T, dtype)
+    return X2, Y, k, v

@@ -440,3 +440,133 @@ def test_window_schedule_reducing_mode_total_rows():
     assert orc.window(2, 0, 70, 32, 1, mode=1) == (64, 6, 0)
     with pytest.raises(ValueError):
         orc.window(0, 0, 0, 32, 1)
+
+
+# --------------------------------------------------------------------------- rest of the layer
+
+def test_rmsnorm_matches_library_and_closed_forms():
+    x = _rand(60, (5, 24))
+    w = 1.0 + _rand(61, (24,), 0.1)
+    got = orc.rmsnorm(x, w, 1e-6, "f32")
+    want = torch.nn.functional.rms_norm(torch.from_numpy(x).double(), (24,), torch.from_numpy(w).double(), 1e-6)
+    assert np.allclose(got, want.numpy(), atol=1e-6)
+    # unit weight, no eps: every output row has mean square 1; scaling the input changes nothing
+    y = orc.rmsnorm(x, np.ones(24), 0.0, "f32")
+    assert np.allclose(np.mean(y.astype(np.float64) ** 2, axis=-1), 1.0, atol=1e-6)
+    assert np.allclose(orc.rmsnorm(3.0 * x, np.ones(24), 0.0, "f32"), y, atol=1e-6)
+    # constant row c: c / sqrt(c^2 + eps) * w
+    c, eps = -2.0, 0.5
+    got = orc.rmsnorm(np.full((1, 8), c), w[:8], eps, "f32")
+    assert np.allclose(got[0], c / math.sqrt(c * c + eps) * w[:8], atol=1e-6)
+    # the mean runs over the row, not the batch: rows are independent
+    assert np.array_equal(orc.rmsnorm(x[2:3], w, 1e-6, "f32")[0], orc.rmsnorm(x, w, 1e-6, "f32")[2])
+    # bf16 storage: the result is the bf16 rounding of the exact value
+    xb = inputs.as_oracle(inputs.normal(5, "x", (4, 16), 1.0, "bf16"))
+    wb = inputs.as_oracle(inputs.normal(5, "w", (16,), 1.0, "bf16"))
+    exact = xb.astype(np.float64) / np.sqrt(np.mean(xb.astype(np.float64) ** 2, -1, keepdims=True) + 1e-5) * wb
+    assert np.array_equal(orc.rmsnorm(xb, wb, 1e-5, "bf16"), orc.round_to_storage(exact, "bf16").astype(np.float32))
+
+
+def test_linear_residual_matches_blas_and_routes_rows_to_columns():
+    X, W, R = _rand(62, (7, 20)), _rand(63, (11, 20), 0.3), _rand(64, (7, 11))
+    got = orc.linear_residual(X, W, R, "f32")
+    want = R.astype(np.float64) + X.astype(np.float64) @ W.astype(np.float64).T
+    assert np.allclose(got, want, atol=1e-6)
+    assert np.allclose(orc.linear_residual(X, W, None, "f32"), want - R, atol=1e-6)
+    # one-hot weight rows: output column n picks input column sel[n] (transposition / index check)
+    sel = np.array([3, 0, 19, 7, 7], np.int64)
+    W1 = np.zeros((5, 20), np.float32)
+    W1[np.arange(5), sel] = 1.0
+    assert np.array_equal(orc.linear_residual(X, W1, None, "f32"), X[:, sel])
+    # identity weight and a residual: x + r, one rounding
+    Xb = inputs.as_oracle(inputs.normal(6, "x", (3, 8), 1.0, "bf16"))
+    Rb = inputs.as_oracle(inputs.normal(6, "r", (3, 8), 1.0, "bf16"))
+    want = orc.round_to_storage(Xb.astype(np.float64) + Rb, "bf16").astype(np.float32)
+    assert np.array_equal(orc.linear_residual(Xb, np.eye(8), Rb, "bf16"), want)
+
+
+def test_ffn_gate_up_matches_library_silu_and_identities():
+    X, Wg, Wu = _rand(65, (6, 12)), _rand(66, (9, 12), 0.5), _rand(67, (9, 12), 0.5)
+    got = orc.ffn_gate_up(X, Wg, Wu, "f32")
+    g = torch.from_numpy(X).double() @ torch.from_numpy(Wg).double().T
+    u = torch.from_numpy(X).double() @ torch.from_numpy(Wu).double().T
+    assert np.allclose(got, (torch.nn.functional.silu(g) * u).numpy(), atol=1e-6)
+    # gate and up are not interchangeable, and the gate is the one that passes through silu
+    assert not np.allclose(got, orc.ffn_gate_up(X, Wu, Wg, "f32"), atol=1e-3)
+    # identity gate, constant up = 1: silu(x); silu(x) - silu(-x) = x; silu(0) = 0; silu(20) ~ 20
+    I = np.eye(12, dtype=np.float32)
+    x1 = np.zeros((1, 12), np.float32)
+    x1[0, :4] = [0.0, 20.0, -20.0, 1.0]
+    U = np.zeros((12, 12), np.float32)
+    U[:, 3] = 1.0   # u = x[3] = 1 for every output
+    s = orc.ffn_gate_up(x1, I, U, "f32")[0]
+    assert s[0] == 0.0 and abs(s[1] - 20.0) < 1e-6 and abs(s[2]) < 1e-6
+    assert abs(s[3] - 1.0 / (1.0 + math.exp(-1.0))) < 1e-7
+    xs = _rand(68, (4, 12))
+    xs[:, 3] = 1.0
+    a = orc.ffn_gate_up(xs, I, U, "f32").astype(np.float64)
+    xm = -xs
+    xm[:, 3] = 1.0
+    b = orc.ffn_gate_up(xm, I, U, "f32").astype(np.float64)
+    keep = [i for i in range(12) if i != 3]
+    assert np.allclose(a[:, keep] - b[:, keep], xs[:, keep], atol=1e-6)
+
+
+def _tiny_layer(dtype, seed, B=2, S=21, Hq=4, Hkv=2, Dh=8, d=24, F=40, with_bias=True):
+    w = inputs.Workload("tiny", dtype, B, d, Hq, Hkv, Dh, S, 0, d_ff=F)
+    wts = {k: (None if v is None else inputs.as_oracle(v)) for k, v in
+           inputs.layer_weights(w, seed, 0, with_bias).items()}
+    for k in ("w_qkv", "w_out", "w_gate", "w_up", "w_down"):   # larger weights: every module matters
+        wts[k] = inputs.as_oracle(inputs.normal(seed, k + ".big", wts[k].shape, 0.2, dtype))
+    X = inputs.as_oracle(inputs.normal(seed, "x", (B, S, d), 1.0, dtype))
+    return w, wts, X
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_full_layer_refresh_equals_uncached_dense_layer(dtype):
+    from tests.dense_reference import dense_full_layer
+    w, wts, X = _tiny_layer(dtype, 11)
+    B, S = X.shape[0], X.shape[1]
+    cfg = orc.OracleConfig(B, w.hidden, w.n_q_heads, w.n_kv_heads, w.head_dim, S, dtype)
+    Kc = np.full((B, w.n_kv_heads, S, w.head_dim), np.nan, np.float32)
+    Vc = np.full_like(Kc, np.nan)
+    Y, X2 = orc.full_layer_step(cfg, X, wts, _pos(B, 0, S), S, Kc, Vc, 1e-6, want_x2=True)
+    x2, y, k, v = dense_full_layer(X, wts, w.n_q_heads, w.n_kv_heads, w.head_dim, 10000.0, dtype, 1e-6)
+    if dtype == "f32":
+        assert np.allclose(X2, x2, atol=2e-6) and np.allclose(Y, y, atol=1e-5)
+        assert np.allclose(Kc, k, atol=1e-6) and np.allclose(Vc, v, atol=1e-6)
+    else:
+        # equal up to roundings decided the other way by torch's double rounding (rare, one ulp)
+        for got, want in ((X2, x2), (Y, y)):
+            assert np.mean(got == want) > 0.97
+            assert np.all(np.abs(got - want) <= 2.0 ** (np.floor(np.log2(np.maximum(np.abs(want), 1e-3))) - 6))
+    # every module contributes: dropping one changes the result
+    for name in ("w_out", "w_down", "w_gate", "w_up"):
+        z = dict(wts)
+        z[name] = np.zeros_like(wts[name])
+        K2, V2 = np.zeros_like(Kc), np.zeros_like(Vc)
+        assert not np.allclose(orc.full_layer_step(cfg, X, z, _pos(B, 0, S), S, K2, V2, 1e-6), Y, atol=1e-2)
+
+
+def test_full_layer_cached_step_equals_window_rows_of_full_recompute():
+    w, wts, X = _tiny_layer("f32", 12, B=1, S=28, with_bias=False)
+    S, L = 28, 20
+    cfg = orc.OracleConfig(1, w.hidden, w.n_q_heads, w.n_kv_heads, w.head_dim, S, "f32")
+    Kf = np.zeros((1, w.n_kv_heads, S, w.head_dim), np.float32)
+    Vf = np.zeros_like(Kf)
+    Yf = orc.full_layer_step(cfg, X, wts, _pos(1, 0, S), S, Kf, Vf, 1e-6)
+    Kc, Vc = np.zeros_like(Kf), np.zeros_like(Kf)
+    orc.full_layer_step(cfg, X[:, :L], wts, _pos(1, 0, L), L, Kc, Vc, 1e-6)
+    Yc = orc.full_layer_step(cfg, X[:, L:], wts, _pos(1, L, S - L), S, Kc, Vc, 1e-6)
+    assert np.array_equal(Kc, Kf) and np.array_equal(Vc, Vf) and np.array_equal(Yc, Yf[:, L:])
+    # the modules after attention are row-wise: with W_out = 0 a row's output does not depend on the cache
+    z = dict(wts)
+    z["w_out"] = np.zeros_like(wts["w_out"])
+    Ka, Va = _rand(70, Kf.shape), _rand(71, Kf.shape)
+    Kb, Vb = _rand(72, Kf.shape), _rand(73, Kf.shape)
+    ya = orc.full_layer_step(cfg, X[:, L:], z, _pos(1, L, S - L), S, Ka, Va, 1e-6)
+    yb = orc.full_layer_step(cfg, X[:, L:], z, _pos(1, L, S - L), S, Kb, Vb, 1e-6)
+    assert np.array_equal(ya, yb)
+    # and with the feed-forward output matrix zeroed too the layer is the identity on the residual stream
+    z["w_down"] = np.zeros_like(wts["w_down"])
+    assert np.array_equal(orc.full_layer_step(cfg, X[:, L:], z, _pos(1, L, S - L), S, Ka, Va, 1e-6), X[:, L:])
