@@ -168,6 +168,79 @@ fc_status fc_refresh(fc_cache *cache, int32_t layer, const void *x, const void *
                      const void *b_qkv, int32_t start, int32_t R, int32_t kv_len, void *q_scratch,
                      void *out, void *workspace, size_t workspace_bytes, void *stream);
 
+/* ---------------------------------------------------------------------------------------------
+ * The rest of the transformer layer on the window rows (Table 1, rows "Output projection (W_out)",
+ * "FFN W_1" and "FFN W_2": with FreeCache each is evaluated for the A window rows only, so its cost
+ * drops from O(L ...) to O(A ...) exactly like the projections above).  The paper names these
+ * modules without fixing their inner form; the library implements the pre-normalised layer of the
+ * checkpoints the paper evaluates (Dream, LLaDA): RMS normalisation, output projection with
+ * residual, SiLU-gated W_1 (a "gate" and an "up" matrix), W_2 with residual.
+ *
+ * These four calls do not touch a cache; dtype is an fc_dtype and applies to every tensor.  They
+ * enqueue on `stream` like the calls above and validate on the host first.
+ */
+
+/* out[r][k] = x[r][k] / sqrt(mean_k x[r][k]^2 + eps) * weight[k].
+ *   x, out  device [rows][hidden] (out may be x);  weight  device [hidden]
+ * Errors: INVALID_ARG (NULL pointer, rows or hidden < 1, eps < 0, bad dtype), HIP. */
+fc_status fc_rmsnorm(int32_t dtype, const void *x, const void *weight, float eps, int32_t rows,
+                     int32_t hidden, void *out, void *stream);
+
+/* Workspace bytes of fc_linear_residual for this shape (cross-workgroup partial sums); for
+ * fc_ffn_gate_up pass N = 2 F.  0 on bad arguments or when none is needed. */
+size_t fc_linear_workspace_bytes(int32_t dtype, int32_t M, int32_t K, int32_t N);
+
+/* out[m][n] = residual[m][n] + sum_k x[m][k] w[n][k], rounded once (W_out and W_2 of Table 1, each
+ * with the residual connection folded in).
+ *   x  device [M][K];  w  device [N][K];  residual  device [M][N] or NULL;  out  device [M][N]
+ *   (out may be residual);  workspace  device, >= fc_linear_workspace_bytes(dtype, M, K, N) bytes.
+ * Errors: INVALID_ARG, UNSUPPORTED (K not a multiple of 8), WORKSPACE, HIP. */
+fc_status fc_linear_residual(int32_t dtype, const void *x, const void *w, const void *residual,
+                             int32_t M, int32_t K, int32_t N, void *out, void *workspace,
+                             size_t workspace_bytes, void *stream);
+
+/* out[m][f] = silu(sum_k x[m][k] w_gate[f][k]) * (sum_k x[m][k] w_up[f][k]), silu(t) = t / (1 + e^-t)
+ * (the gated form of W_1 of Table 1); the two products stay in fp32, one rounding.
+ *   x  device [M][K];  w_gate, w_up  device [F][K];  out  device [M][F];
+ *   workspace  device, >= fc_linear_workspace_bytes(dtype, M, K, 2 F) bytes.
+ * Errors: as fc_linear_residual. */
+fc_status fc_ffn_gate_up(int32_t dtype, const void *x, const void *w_gate, const void *w_up, int32_t M,
+                         int32_t K, int32_t F, void *out, void *workspace, size_t workspace_bytes,
+                         void *stream);
+
+/* Weights of one layer (all device pointers, element type fc_config.dtype, borrowed). */
+typedef struct {
+    const void *norm1;   /* [hidden]            RMSNorm weight in front of the attention */
+    const void *w_qkv;   /* [N][hidden]         as for fc_qkv_project_scatter */
+    const void *b_qkv;   /* [N] or NULL */
+    const void *w_out;   /* [hidden][Hq*Dh] */
+    const void *norm2;   /* [hidden]            RMSNorm weight in front of the FFN */
+    const void *w_gate;  /* [d_ff][hidden] */
+    const void *w_up;    /* [d_ff][hidden] */
+    const void *w_down;  /* [hidden][d_ff] */
+    int32_t d_ff;
+    float eps;           /* RMSNorm epsilon */
+} fc_layer_weights;
+
+/* Workspace bytes of fc_full_layer_step for windows of up to max_rows rows per sequence
+ * (intermediate activations of B * max_rows rows, the attention workspace, partial sums). */
+size_t fc_full_layer_workspace_bytes(const fc_config *cfg, int32_t d_ff, int32_t max_rows);
+
+/* One cached step of the whole layer on the window rows (section 3.2.1 applied to every module of
+ * Table 1):
+ *   h1 = rmsnorm(x; norm1);   q, cache rows <- fc_qkv_project_scatter(h1);   o = fc_active_attention(q)
+ *   x2 = x + o w_out^T;       h2 = rmsnorm(x2; norm2)
+ *   y  = x2 + (silu(h2 w_gate^T) * (h2 w_up^T)) w_down^T
+ * Every named tensor is rounded to the cache dtype.  Rows with a negative pos entry have o = 0
+ * (nothing cached for them) and are otherwise processed like any other row.
+ *   x, y  device [B][A][hidden] (y may be x);  pos  device int32 [B][A] or NULL = win_start + a
+ *   workspace  device, >= fc_full_layer_workspace_bytes(cfg, d_ff, A) bytes
+ * Errors: those of the calls it is made of; all checks precede the first launch. */
+fc_status fc_full_layer_step(fc_cache *cache, int32_t layer, const fc_layer_weights *weights,
+                             const void *x, int32_t win_start, int32_t A, const int32_t *pos,
+                             int32_t kv_len, void *y, void *workspace, size_t workspace_bytes,
+                             void *stream);
+
 #ifdef __cplusplus
 }
 #endif

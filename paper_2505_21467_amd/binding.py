@@ -21,6 +21,8 @@ EXPORTS = (
     "fc_last_error", "fc_cache_storage_bytes", "fc_cache_alloc", "fc_cache_free", "fc_cache_ptrs",
     "fc_cache_write_rows", "fc_cache_read_rows", "fc_window", "fc_qkv_project_scatter",
     "fc_workspace_bytes", "fc_active_attention", "fc_refresh",
+    "fc_rmsnorm", "fc_linear_workspace_bytes", "fc_linear_residual", "fc_ffn_gate_up",
+    "fc_full_layer_workspace_bytes", "fc_full_layer_step",
 )
 
 
@@ -31,6 +33,12 @@ class fc_config(ctypes.Structure):
         ("max_seq", ctypes.c_int32), ("dtype", ctypes.c_int32), ("rope_base", ctypes.c_float),
         ("softmax_scale", ctypes.c_float),
     ]
+
+
+class fc_layer_weights(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_void_p) for n in
+                ("norm1", "w_qkv", "b_qkv", "w_out", "norm2", "w_gate", "w_up", "w_down")] + [
+        ("d_ff", ctypes.c_int32), ("eps", ctypes.c_float)]
 
 
 class FreeCacheError(RuntimeError):
@@ -75,6 +83,19 @@ def lib():
         L.fc_active_attention.argtypes = [vp, i32, vp, i32, i32, vp, vp, vp, sz, vp]
         L.fc_refresh.restype = ctypes.c_int
         L.fc_refresh.argtypes = [vp, i32, vp, vp, vp, i32, i32, i32, vp, vp, vp, sz, vp]
+        L.fc_rmsnorm.restype = ctypes.c_int
+        L.fc_rmsnorm.argtypes = [i32, vp, vp, ctypes.c_float, i32, i32, vp, vp]
+        L.fc_linear_workspace_bytes.restype = sz
+        L.fc_linear_workspace_bytes.argtypes = [i32, i32, i32, i32]
+        L.fc_linear_residual.restype = ctypes.c_int
+        L.fc_linear_residual.argtypes = [i32, vp, vp, vp, i32, i32, i32, vp, vp, sz, vp]
+        L.fc_ffn_gate_up.restype = ctypes.c_int
+        L.fc_ffn_gate_up.argtypes = [i32, vp, vp, vp, i32, i32, i32, vp, vp, sz, vp]
+        L.fc_full_layer_workspace_bytes.restype = sz
+        L.fc_full_layer_workspace_bytes.argtypes = [cfgp, i32, i32]
+        L.fc_full_layer_step.restype = ctypes.c_int
+        L.fc_full_layer_step.argtypes = [vp, i32, ctypes.POINTER(fc_layer_weights), vp, i32, i32, vp, i32, vp,
+                                         vp, sz, vp]
         _lib = L
     return _lib
 
@@ -170,3 +191,49 @@ def fc_refresh(cache, layer, x, w_qkv, b_qkv, start, R, kv_len, q_scratch, out, 
         workspace_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
     _check(lib().fc_refresh(cache, layer, _ptr(x), _ptr(w_qkv), _ptr(b_qkv), start, R, kv_len,
                             _ptr(q_scratch), _ptr(out), _ptr(workspace), workspace_bytes, _stream(stream)))
+
+
+def _nbytes(t):
+    return 0 if t is None else t.numel() * t.element_size()
+
+
+def fc_rmsnorm(dtype, x, weight, eps, rows, hidden, out, stream=None) -> None:
+    _check(lib().fc_rmsnorm(DTYPE_CODE[dtype], _ptr(x), _ptr(weight), eps, rows, hidden, _ptr(out),
+                            _stream(stream)))
+
+
+def fc_linear_workspace_bytes(dtype, M, K, N) -> int:
+    return int(lib().fc_linear_workspace_bytes(DTYPE_CODE[dtype], M, K, N))
+
+
+def fc_linear_residual(dtype, x, w, residual, M, K, N, out, workspace, workspace_bytes=None,
+                       stream=None) -> None:
+    if workspace_bytes is None:
+        workspace_bytes = _nbytes(workspace)
+    _check(lib().fc_linear_residual(DTYPE_CODE[dtype], _ptr(x), _ptr(w), _ptr(residual), M, K, N, _ptr(out),
+                                    _ptr(workspace), workspace_bytes, _stream(stream)))
+
+
+def fc_ffn_gate_up(dtype, x, w_gate, w_up, M, K, F, out, workspace, workspace_bytes=None, stream=None) -> None:
+    if workspace_bytes is None:
+        workspace_bytes = _nbytes(workspace)
+    _check(lib().fc_ffn_gate_up(DTYPE_CODE[dtype], _ptr(x), _ptr(w_gate), _ptr(w_up), M, K, F, _ptr(out),
+                                _ptr(workspace), workspace_bytes, _stream(stream)))
+
+
+def make_layer_weights(norm1, w_qkv, b_qkv, w_out, norm2, w_gate, w_up, w_down, d_ff, eps) -> fc_layer_weights:
+    """Pointers only: the caller keeps the tensors alive."""
+    return fc_layer_weights(_ptr(norm1), _ptr(w_qkv), _ptr(b_qkv), _ptr(w_out), _ptr(norm2), _ptr(w_gate),
+                            _ptr(w_up), _ptr(w_down), d_ff, eps)
+
+
+def fc_full_layer_workspace_bytes(cfg: fc_config, d_ff: int, max_rows: int) -> int:
+    return int(lib().fc_full_layer_workspace_bytes(ctypes.byref(cfg), d_ff, max_rows))
+
+
+def fc_full_layer_step(cache, layer, weights: fc_layer_weights, x, win_start, A, pos, kv_len, y, workspace,
+                       workspace_bytes=None, stream=None) -> None:
+    if workspace_bytes is None:
+        workspace_bytes = _nbytes(workspace)
+    _check(lib().fc_full_layer_step(cache, layer, ctypes.byref(weights), _ptr(x), win_start, A, _ptr(pos),
+                                    kv_len, _ptr(y), _ptr(workspace), workspace_bytes, _stream(stream)))

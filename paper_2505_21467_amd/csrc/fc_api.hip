@@ -402,4 +402,172 @@ fc_status fc_refresh(fc_cache *cache, int32_t layer, const void *x, const void *
                                stream);
 }
 
+// ---------------------------------------------------------------------------------------------
+// The rest of the layer on the window rows.
+
+static fc_status check_dtype(int32_t dtype)
+{
+    if (dtype != FC_F32 && dtype != FC_BF16)
+        return fail(FC_ERR_INVALID_ARG, "dtype %d is neither FC_F32 nor FC_BF16", dtype);
+    return FC_OK;
+}
+
+fc_status fc_rmsnorm(int32_t dtype, const void *x, const void *weight, float eps, int32_t rows,
+                     int32_t hidden, void *out, void *stream)
+{
+    fc_status st = check_dtype(dtype);
+    if (st != FC_OK) return st;
+    if (!x || !weight || !out) return fail(FC_ERR_INVALID_ARG, "x, weight or out is NULL");
+    if (rows < 1 || hidden < 1) return fail(FC_ERR_INVALID_ARG, "rows and hidden must be >= 1");
+    if (!(eps >= 0.0f) || !isfinite(eps)) return fail(FC_ERR_INVALID_ARG, "eps must be finite and >= 0");
+    hipError_t e = fc_launch_rmsnorm(dtype, x, weight, eps, rows, hidden, out, (hipStream_t)stream);
+    return e == hipSuccess ? FC_OK : hip_fail(e, "rmsnorm launch");
+}
+
+static fc_status check_linear_shape(int32_t M, int32_t K, int32_t N)
+{
+    if (M < 1 || K < 1 || N < 1) return fail(FC_ERR_INVALID_ARG, "M, K and N must be >= 1");
+    if (K % 8 != 0) return fail(FC_ERR_UNSUPPORTED, "K %d is not a multiple of 8", K);
+    if (M > (1 << 24) || N > (1 << 22)) return fail(FC_ERR_UNSUPPORTED, "M is limited to 2^24 rows, N to 2^22");
+    return FC_OK;
+}
+
+size_t fc_linear_workspace_bytes(int32_t dtype, int32_t M, int32_t K, int32_t N)
+{
+    if ((dtype != FC_F32 && dtype != FC_BF16) || M < 1 || K < 1 || N < 1) return 0;
+    // the gated W_1 is planned on its F = N / 2 outputs; its slabs hold half as many outputs, so the
+    // two plans need the same space and one query serves both calls
+    const size_t a = fc_skinny_workspace(fc_plan_skinny(dtype, FC_LIN_RESIDUAL, M, K, N));
+    const size_t b = N % 2 == 0 ? fc_skinny_workspace(fc_plan_skinny(dtype, FC_LIN_GATE_UP, M, K, N / 2)) : 0;
+    return a > b ? a : b;
+}
+
+static fc_status linear_common(int32_t dtype, int mode, const void *x, const void *w, const void *w2,
+                               const void *res, int32_t M, int32_t K, int32_t N, void *out, void *workspace,
+                               size_t workspace_bytes, void *stream)
+{
+    fc_status st = check_dtype(dtype);
+    if (st != FC_OK) return st;
+    if (!x || !w || !out || (mode == FC_LIN_GATE_UP && !w2))
+        return fail(FC_ERR_INVALID_ARG, "x, a weight matrix or out is NULL");
+    st = check_linear_shape(M, K, N);
+    if (st != FC_OK) return st;
+    if (((uintptr_t)x | (uintptr_t)w | (uintptr_t)w2 | (uintptr_t)res | (uintptr_t)out | (uintptr_t)workspace) & 15)
+        return fail(FC_ERR_INVALID_ARG, "pointers must be 16-byte aligned");
+    const FcSkinnyPlan plan = fc_plan_skinny(dtype, mode, M, K, N);
+    const size_t need = fc_skinny_workspace(plan);
+    if (need > 0 && (!workspace || workspace_bytes < need))
+        return fail(FC_ERR_WORKSPACE, "workspace of %zu bytes needed, %zu given", need,
+                    workspace ? workspace_bytes : (size_t)0);
+    hipError_t e;
+    if (plan.kind == 1)
+        e = fc_launch_linear_skinny(plan, mode, x, w, w2, res, M, K, N, out, workspace, (hipStream_t)stream);
+    else
+        e = fc_launch_linear_generic(dtype, mode, x, w, mode == FC_LIN_GATE_UP ? w2 : res, M, K, N, out,
+                                     (hipStream_t)stream);
+    return e == hipSuccess ? FC_OK : hip_fail(e, "linear launch");
+}
+
+fc_status fc_linear_residual(int32_t dtype, const void *x, const void *w, const void *residual, int32_t M,
+                             int32_t K, int32_t N, void *out, void *workspace, size_t workspace_bytes,
+                             void *stream)
+{
+    return linear_common(dtype, FC_LIN_RESIDUAL, x, w, nullptr, residual, M, K, N, out, workspace,
+                         workspace_bytes, stream);
+}
+
+fc_status fc_ffn_gate_up(int32_t dtype, const void *x, const void *w_gate, const void *w_up, int32_t M,
+                         int32_t K, int32_t F, void *out, void *workspace, size_t workspace_bytes, void *stream)
+{
+    return linear_common(dtype, FC_LIN_GATE_UP, x, w_gate, w_up, nullptr, M, K, F, out, workspace,
+                         workspace_bytes, stream);
+}
+
+namespace {
+
+// Carve-up of the whole-layer workspace for M = B * A rows (every part 256-byte aligned).
+struct LayerWs {
+    size_t h, q, o, x2, act, attn, lin, total;
+    size_t attn_bytes, lin_bytes;
+};
+
+size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
+
+LayerWs layer_ws(const fc_config &c, int32_t d_ff, int32_t A)
+{
+    LayerWs w;
+    const size_t es = esize_of(c.dtype);
+    const size_t M = (size_t)c.batch * A, d = c.hidden, E = (size_t)c.n_q_heads * c.head_dim;
+    size_t off = 0;
+    auto take = [&](size_t bytes) {
+        const size_t at = off;
+        off += align256(bytes);
+        return at;
+    };
+    w.h = take(M * d * es);
+    w.q = take(M * E * es);
+    w.o = take(M * E * es);
+    w.x2 = take(M * d * es);
+    w.act = take(M * (size_t)d_ff * es);
+    w.attn_bytes = fc_workspace_bytes(&c, A);
+    w.attn = take(w.attn_bytes);
+    size_t lin = fc_linear_workspace_bytes(c.dtype, (int)M, (int)E, c.hidden);
+    const size_t l2 = fc_linear_workspace_bytes(c.dtype, (int)M, c.hidden, 2 * d_ff);
+    const size_t l3 = fc_linear_workspace_bytes(c.dtype, (int)M, d_ff, c.hidden);
+    if (l2 > lin) lin = l2;
+    if (l3 > lin) lin = l3;
+    w.lin_bytes = lin;
+    w.lin = take(lin);
+    w.total = off;
+    return w;
+}
+
+}  // namespace
+
+size_t fc_full_layer_workspace_bytes(const fc_config *cfg, int32_t d_ff, int32_t max_rows)
+{
+    if (check_config(cfg) != FC_OK || d_ff < 1 || max_rows < 1 || (int64_t)max_rows * cfg->batch > (1 << 24))
+        return 0;
+    return layer_ws(*cfg, d_ff, max_rows).total;
+}
+
+fc_status fc_full_layer_step(fc_cache *cache, int32_t layer, const fc_layer_weights *wt, const void *x,
+                             int32_t win_start, int32_t A, const int32_t *pos, int32_t kv_len, void *y,
+                             void *workspace, size_t workspace_bytes, void *stream)
+{
+    fc_status st = check_cache_layer(cache, layer);
+    if (st != FC_OK) return st;
+    if (!wt || !x || !y) return fail(FC_ERR_INVALID_ARG, "weights, x or y is NULL");
+    if (!wt->norm1 || !wt->w_qkv || !wt->w_out || !wt->norm2 || !wt->w_gate || !wt->w_up || !wt->w_down)
+        return fail(FC_ERR_INVALID_ARG, "a required weight pointer is NULL");
+    if (wt->d_ff < 1 || wt->d_ff % 8 != 0) return fail(FC_ERR_INVALID_ARG, "d_ff %d must be a positive multiple of 8", wt->d_ff);
+    if (!(wt->eps >= 0.0f) || !isfinite(wt->eps)) return fail(FC_ERR_INVALID_ARG, "eps must be finite and >= 0");
+    if (A < 1) return fail(FC_ERR_INVALID_ARG, "A %d must be >= 1", A);
+    const fc_config &c = cache->cfg;
+    if ((int64_t)A * c.batch > (1 << 24)) return fail(FC_ERR_UNSUPPORTED, "batch * A exceeds 2^24 rows");
+    if ((c.n_q_heads * c.head_dim) % 8 != 0) return fail(FC_ERR_UNSUPPORTED, "Hq * Dh must be a multiple of 8");
+    if (!pos && (win_start < 0 || win_start > c.max_seq - A))
+        return fail(FC_ERR_BOUNDS, "window [%d, %d+%d) outside the cache of %d rows", win_start, win_start, A,
+                    c.max_seq);
+    if (kv_len < 1 || kv_len > c.max_seq) return fail(FC_ERR_BOUNDS, "kv_len %d outside [1, %d]", kv_len, c.max_seq);
+    const LayerWs w = layer_ws(c, wt->d_ff, A);
+    if (!workspace || workspace_bytes < w.total)
+        return fail(FC_ERR_WORKSPACE, "workspace of %zu bytes needed, %zu given", w.total,
+                    workspace ? workspace_bytes : (size_t)0);
+    if ((uintptr_t)workspace & 15) return fail(FC_ERR_INVALID_ARG, "workspace must be 16-byte aligned");
+    char *ws = (char *)workspace;
+    const int M = c.batch * A, d = c.hidden, E = c.n_q_heads * c.head_dim;
+    void *h = ws + w.h, *q = ws + w.q, *o = ws + w.o, *x2 = ws + w.x2, *act = ws + w.act;
+    void *lin = w.lin_bytes ? ws + w.lin : nullptr, *attn = w.attn_bytes ? ws + w.attn : nullptr;
+
+    st = fc_rmsnorm(c.dtype, x, wt->norm1, wt->eps, M, d, h, stream);
+    if (st == FC_OK) st = fc_qkv_project_scatter(cache, layer, h, wt->w_qkv, wt->b_qkv, win_start, A, pos, q, stream);
+    if (st == FC_OK) st = fc_active_attention(cache, layer, q, A, kv_len, pos, o, attn, w.attn_bytes, stream);
+    if (st == FC_OK) st = fc_linear_residual(c.dtype, o, wt->w_out, x, M, E, d, x2, lin, w.lin_bytes, stream);
+    if (st == FC_OK) st = fc_rmsnorm(c.dtype, x2, wt->norm2, wt->eps, M, d, h, stream);
+    if (st == FC_OK) st = fc_ffn_gate_up(c.dtype, h, wt->w_gate, wt->w_up, M, d, wt->d_ff, act, lin, w.lin_bytes, stream);
+    if (st == FC_OK) st = fc_linear_residual(c.dtype, act, wt->w_down, x2, M, wt->d_ff, d, y, lin, w.lin_bytes, stream);
+    return st;
+}
+
 }  // extern "C"

@@ -184,6 +184,77 @@ __global__ __launch_bounds__(256) void k_attention_generic(FcGeom G, const T *__
     if (tid < G.Dh) o[tid] = fc_from_float<T>(acc / l);
 }
 
+// ---------------------------------------------------------------------------------------------
+// RMS normalisation, one block per row: out = x / sqrt(mean(x^2) + eps) * weight.
+template <typename T>
+__global__ __launch_bounds__(256) void k_rmsnorm(const T *X, const T *__restrict__ w, float eps, int d, T *out)
+{
+    __shared__ float red[4];
+    const size_t row = blockIdx.x;
+    const T *x = X + row * d;
+    const int tid = threadIdx.x;
+    float ss = 0.f;
+    for (int k = tid; k < d; k += 256) {
+        const float v = fc_to_float(x[k]);
+        ss += v * v;
+    }
+    ss = wave_sum(ss);
+    if ((tid & 63) == 0) red[tid >> 6] = ss;
+    __syncthreads();
+    const float tot = (red[0] + red[1]) + (red[2] + red[3]);
+    const float inv = 1.0f / sqrtf(tot / (float)d + eps);
+    // out may be x: element k is read and written by the same thread only
+    for (int k = tid; k < d; k += 256) out[row * d + k] = fc_from_float<T>(fc_to_float(x[k]) * inv * fc_to_float(w[k]));
+}
+
+// ---------------------------------------------------------------------------------------------
+// Linear layer, block = (4 rows, 64 output columns); each wave owns every 4th column of the block and
+// runs the dot products with lanes along the hidden dimension.  MODE 0: out = aux + x w^T
+// (aux = residual or nullptr); MODE 1: out = silu(x w^T) * (x aux^T) (aux = second weight matrix).
+constexpr int LG_ROWS = 4;
+
+template <typename T, int MODE>
+__global__ __launch_bounds__(256) void k_linear_generic(const T *__restrict__ X, const T *__restrict__ W,
+                                                        const T *aux, int M, int K, int N, T *out)
+{
+    const int m0 = blockIdx.x * LG_ROWS, n0 = blockIdx.y * 64;
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    for (int c = wave; c < 64; c += 4) {
+        const int n = n0 + c;
+        if (n >= N) break;
+        const T *w = W + (size_t)n * K;
+        const T *w2 = MODE == 1 ? aux + (size_t)n * K : nullptr;
+        float acc[LG_ROWS], acc2[LG_ROWS];
+#pragma unroll
+        for (int r = 0; r < LG_ROWS; ++r) acc[r] = acc2[r] = 0.f;
+        for (int k = lane; k < K; k += 64) {
+            const float wv = fc_to_float(w[k]);
+            const float wv2 = MODE == 1 ? fc_to_float(w2[k]) : 0.f;
+#pragma unroll
+            for (int r = 0; r < LG_ROWS; ++r)
+                if (m0 + r < M) {
+                    const float xv = fc_to_float(X[(size_t)(m0 + r) * K + k]);
+                    acc[r] += wv * xv;
+                    if (MODE == 1) acc2[r] += wv2 * xv;
+                }
+        }
+#pragma unroll
+        for (int r = 0; r < LG_ROWS; ++r) {
+            const float a = wave_sum(acc[r]);
+            const float b = MODE == 1 ? wave_sum(acc2[r]) : 0.f;
+            if (lane == 0 && m0 + r < M) {
+                const size_t o = (size_t)(m0 + r) * N + n;
+                float y;
+                if (MODE == 1)
+                    y = a / (1.0f + expf(-a)) * b;
+                else
+                    y = aux ? a + fc_to_float(aux[o]) : a;
+                out[o] = fc_from_float<T>(y);
+            }
+        }
+    }
+}
+
 }  // namespace
 
 hipError_t fc_launch_copy_rows(const FcGeom &G, int dtype, void *k_layer, void *v_layer, void *k_rows,
@@ -236,5 +307,38 @@ hipError_t fc_launch_attention_generic(const FcGeom &G, int dtype, const void *q
                                                                (const bf16_t *)k_layer,
                                                                (const bf16_t *)v_layer, pos, A, kv_len,
                                                                (bf16_t *)out);
+    return hipGetLastError();
+}
+
+hipError_t fc_launch_rmsnorm(int dtype, const void *x, const void *weight, float eps, int rows, int d,
+                             void *out, hipStream_t s)
+{
+    if (dtype == FC_F32)
+        k_rmsnorm<float><<<dim3((unsigned)rows), dim3(256), 0, s>>>((const float *)x, (const float *)weight, eps,
+                                                                    d, (float *)out);
+    else
+        k_rmsnorm<bf16_t><<<dim3((unsigned)rows), dim3(256), 0, s>>>((const bf16_t *)x, (const bf16_t *)weight,
+                                                                     eps, d, (bf16_t *)out);
+    return hipGetLastError();
+}
+
+template <typename T>
+static void launch_linear_t(int mode, const void *x, const void *w, const void *aux, int M, int K, int N,
+                            void *out, hipStream_t s)
+{
+    const dim3 grid((unsigned)((M + LG_ROWS - 1) / LG_ROWS), (unsigned)((N + 63) / 64));
+    if (mode == FC_LIN_GATE_UP)
+        k_linear_generic<T, 1><<<grid, dim3(256), 0, s>>>((const T *)x, (const T *)w, (const T *)aux, M, K, N, (T *)out);
+    else
+        k_linear_generic<T, 0><<<grid, dim3(256), 0, s>>>((const T *)x, (const T *)w, (const T *)aux, M, K, N, (T *)out);
+}
+
+hipError_t fc_launch_linear_generic(int dtype, int mode, const void *x, const void *w, const void *aux,
+                                    int M, int K, int N, void *out, hipStream_t s)
+{
+    if (dtype == FC_F32)
+        launch_linear_t<float>(mode, x, w, aux, M, K, N, out, s);
+    else
+        launch_linear_t<bf16_t>(mode, x, w, aux, M, K, N, out, s);
     return hipGetLastError();
 }

@@ -78,3 +78,28 @@ hipError_t fc_launch_project_gemm(const FcGeom &G, const void *x, const void *w,
 hipError_t fc_launch_attention_mfma(const FcGeom &G, const FcAttnPlan &p, const void *q,
                                     const void *k_layer, const void *v_layer, const int32_t *pos,
                                     int A, int kv_len, void *out, void *workspace, hipStream_t s);
+
+// Rest of the layer on the window rows: RMS normalisation and the linear layers around attention.
+enum { FC_LIN_RESIDUAL = 0, FC_LIN_GATE_UP = 1 };
+hipError_t fc_launch_rmsnorm(int dtype, const void *x, const void *weight, float eps, int rows, int d,
+                             void *out, hipStream_t s);
+// Plain-ALU linear layer for any dtype and shape.  FC_LIN_RESIDUAL: out = aux + x w^T (aux = residual
+// or nullptr); FC_LIN_GATE_UP: out = silu(x w^T) * (x aux^T) (aux = up matrix).
+hipError_t fc_launch_linear_generic(int dtype, int mode, const void *x, const void *w, const void *aux,
+                                    int M, int K, int N, void *out, hipStream_t s);
+// Launch plan of the weight-streaming linear kernels (host, pure function of the shape).
+struct FcSkinnyPlan {
+    int kind;    // 0 = plain kernel (no workspace), 1 = streaming kernels
+    int mt;      // 16-row tiles per pass (1 or 2)
+    int chunks;  // passes of up to 32 rows
+    int slabs;   // 128-row slabs of the weight matrix (64 gate + 64 up rows in gated mode)
+    int S;       // hidden-dimension slices per slab
+    int T;       // work items = slabs * S
+    int G;       // workgroups
+    int maxseg;  // upper bound of the workgroups that meet one slab
+};
+FcSkinnyPlan fc_plan_skinny(int dtype, int mode, int M, int K, int N);
+size_t fc_skinny_workspace(const FcSkinnyPlan &p);
+hipError_t fc_launch_linear_skinny(const FcSkinnyPlan &pl, int mode, const void *x, const void *w,
+                                   const void *w2, const void *res, int M, int K, int N, void *out,
+                                   void *workspace, hipStream_t s);

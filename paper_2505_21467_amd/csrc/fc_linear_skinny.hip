@@ -1,0 +1,310 @@
+// Weight-streaming linear layers for short windows (bf16, at most 32 rows per pass): the output
+// projection and the two feed-forward matrices of the layer evaluated on the window rows only
+// (paper, Table 1, rows "Output projection", "FFN W_1", "FFN W_2" with the row count L replaced by
+// the window size A).
+//
+// With a few dozen rows the product Y^T = W X^T is bound by reading W once from HBM.  The weight
+// matrix is cut into work items of 128 rows x KSL hidden elements (every row piece is 1 KB, or 512 B,
+// of contiguous memory); the items, ordered row slab by row slab, are dealt out in equal contiguous
+// runs to one workgroup per compute unit, so the matrix streams once, evenly, whatever its shape.
+// Inside an item the eight waves own 16 weight rows each and load them straight into the operand
+// registers of v_mfma_f32_16x16x32_bf16 (8 consecutive k per lane); the matching slice of X goes
+// through LDS (direct-to-LDS loads, swizzled) and is shared by the waves.  Loads of item i+1 are
+// issued before the multiplies of item i.
+//
+// A run of items may start and end inside a row slab, so every (slab, workgroup) pair that meet
+// writes an fp32 partial tile; a second kernel sums a slab's partial tiles (a kernel boundary is
+// the only cross-workgroup ordering used) and applies the epilogue: residual add, or the SiLU gate.
+// For the gated W_1 a slab holds 64 rows of the gate matrix and the same 64 rows of the up matrix,
+// laid out so that g and u of one output sit in lanes 32 apart of the same accumulator register.
+#include <stdlib.h>
+#include <string.h>
+
+#include "fc_device.h"
+#include "fc_internal.h"
+
+namespace {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+
+struct LinArgs {
+    const uint16_t *X;    // [M][K]
+    const uint16_t *W;    // [N][K]  (gate matrix in gated mode)
+    const uint16_t *W2;   // up matrix [N][K] in gated mode
+    const uint16_t *res;  // [M][N] or nullptr
+    uint16_t *out;        // [M][N]
+    float *partials;      // [m chunk][slab][maxseg][wave][mt][4][64]
+    int M, K, N;          // N = output columns
+    int S, T, G, maxseg, slabs;
+};
+
+__device__ __forceinline__ bf16x8 ld8(const uint16_t *p)
+{
+    union { uint4 u; bf16x8 v; } x;
+    x.u = *(const uint4 *)p;
+    return x.v;
+}
+
+__device__ __forceinline__ void load_lds16(const void *g, void *l)
+{
+    __builtin_amdgcn_global_load_lds((const void __attribute__((address_space(1))) *)g,
+                                     (void __attribute__((address_space(3))) *)l, 16, 0, 0);
+}
+
+__device__ __forceinline__ float swap32(float v)
+{
+    const unsigned u = __float_as_uint(v);
+    const auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+    return (threadIdx.x & 32) ? __uint_as_float(r[0]) : __uint_as_float(r[1]);
+}
+
+// Workgroup that owns work item i when T items are dealt to G workgroups as runs
+// [floor(w T / G), floor((w + 1) T / G)).
+__device__ __forceinline__ int owner_of(int i, int T, int G)
+{
+    return (int)((((int64_t)i + 1) * G - 1) / T);
+}
+
+template <int MT, int KSL, int MODE>
+__global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) void k_linear_stream(LinArgs p)
+{
+    constexpr int KS = KSL / 32;        // k-steps of 32 per item
+    constexpr int ROWB = KSL * 2;       // bytes of one X row of a slice
+    constexpr int RPL = 1024 / ROWB;    // X rows per wave-wide 1 KB load
+    constexpr int NLD = 16 * MT / RPL / 8;
+    static_assert(NLD >= 1, "slice too narrow for this row count");
+    __shared__ __align__(1024) unsigned char xs[2][16 * MT * ROWB];
+
+    const int wg = blockIdx.x, m0 = blockIdx.y * 32;
+    const int lo = (int)((int64_t)wg * p.T / p.G), hi = (int)(((int64_t)wg + 1) * p.T / p.G);
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int rho = lane & 15, q = lane >> 4;
+
+    auto issue = [&](int item, bf16x8(&wf)[KS], unsigned char *xb) {
+        const int slab = item / p.S, sl = item - slab * p.S;
+#pragma unroll
+        for (int i = 0; i < NLD; ++i) {
+            const int ld = wave * NLD + i;
+            const int mrow = ld * RPL + lane / (64 / RPL);
+            const int c = (lane % (64 / RPL)) ^ (mrow & 15);  // chunk c of row m is stored at c ^ (m & 15)
+            const int mg = min(m0 + mrow, p.M - 1);            // padding rows read a valid row
+            load_lds16(p.X + (size_t)mg * p.K + (size_t)sl * KSL + c * 8, xb + ld * 1024);
+        }
+        const uint16_t *wrow;
+        if (MODE == FC_LIN_GATE_UP)
+            wrow = (rho < 8 ? p.W : p.W2) + (size_t)(slab * 64 + wave * 8 + (rho & 7)) * p.K;
+        else
+            wrow = p.W + (size_t)(slab * 128 + wave * 16 + rho) * p.K;
+        wrow += (size_t)sl * KSL + 8 * q;
+#pragma unroll
+        for (int s = 0; s < KS; ++s) wf[s] = ld8(wrow + 32 * s);
+    };
+
+    f32x4 acc[MT];
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) acc[mt] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    auto compute = [&](const bf16x8(&wf)[KS], const unsigned char *xb) {
+#pragma unroll
+        for (int s = 0; s < KS; ++s)
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt) {
+                const int m = 16 * mt + rho;
+                const bf16x8 xf = *(const bf16x8 *)(xb + m * ROWB + (((4 * s + q) ^ (m & 15)) << 4));
+                acc[mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf[s], xf, acc[mt], 0, 0, 0);
+            }
+    };
+
+    // hand the partial tile over when the run leaves the slab (or ends)
+    auto tail = [&](int item) {
+        if (item + 1 < hi && (item + 1) % p.S != 0) return;
+        const int slab = item / p.S;
+        const int seg = wg - owner_of(slab * p.S, p.T, p.G);
+        float *part = p.partials +
+                      ((((size_t)blockIdx.y * p.slabs + slab) * p.maxseg + seg) * 8 + wave) * (MT * 256);
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                part[mt * 256 + r * 64 + lane] = acc[mt][r];
+                acc[mt][r] = 0.f;
+            }
+    };
+
+    if (lo >= hi) return;
+    bf16x8 wa[KS], wb[KS];
+    issue(lo, wa, xs[0]);
+    int item = lo;
+    for (;;) {
+        __syncthreads();  // the loads of `item` have landed; every wave is done with the other buffers
+        if (item + 1 < hi) issue(item + 1, wb, xs[1]);
+        compute(wa, xs[0]);
+        tail(item);
+        if (++item >= hi) break;
+        __syncthreads();
+        if (item + 1 < hi) issue(item + 1, wa, xs[0]);
+        compute(wb, xs[1]);
+        tail(item);
+        if (++item >= hi) break;
+    }
+}
+
+// Sum of a slab's partial tiles + epilogue; one wave per (slab, 16-row tile of W), grid.y = m chunk.
+template <int MT, int MODE>
+__global__ __launch_bounds__(64) void k_linear_finish(LinArgs p)
+{
+    const int slab = blockIdx.x >> 3, wave = blockIdx.x & 7;
+    const int m0 = blockIdx.y * 32;
+    const int lane = threadIdx.x, rho = lane & 15, q = lane >> 4;
+    const int first = owner_of(slab * p.S, p.T, p.G);
+    const int nseg = owner_of(slab * p.S + p.S - 1, p.T, p.G) - first + 1;
+    const float *base = p.partials + ((((size_t)blockIdx.y * p.slabs + slab) * p.maxseg) * 8 + wave) * (MT * 256);
+    const size_t seg_stride = (size_t)8 * MT * 256;
+
+    f32x4 acc[MT];
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) acc[mt] = f32x4{0.f, 0.f, 0.f, 0.f};
+    for (int s0 = 0; s0 < nseg; s0 += 4) {  // four segments' worth of loads in flight
+        float v[4][MT][4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const float *pp = base + (size_t)min(s0 + u, nseg - 1) * seg_stride;
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) v[u][mt][r] = pp[mt * 256 + r * 64 + lane];
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+            if (s0 + u < nseg) {
+#pragma unroll
+                for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) acc[mt][r] += v[u][mt][r];
+            }
+    }
+
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) {
+        const int m = m0 + 16 * mt + rho;
+        const bool mvalid = m < p.M;
+        float y[4];
+        if (MODE == FC_LIN_GATE_UP) {
+            // lanes q = 0, 1 hold the gate products of outputs 4q + r, lanes q = 2, 3 the up products
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const float other = swap32(acc[mt][r]);
+                const float g = acc[mt][r];
+                y[r] = g / (1.0f + expf(-g)) * other;
+            }
+            if (!mvalid || q >= 2) continue;
+            const int f = slab * 64 + wave * 8 + 4 * q;
+            uint2 w;
+            w.x = (uint32_t)fc_bf16_bits(y[0]) | ((uint32_t)fc_bf16_bits(y[1]) << 16);
+            w.y = (uint32_t)fc_bf16_bits(y[2]) | ((uint32_t)fc_bf16_bits(y[3]) << 16);
+            *(uint2 *)(p.out + (size_t)m * p.N + f) = w;
+        } else {
+            if (!mvalid) continue;
+            const int n = slab * 128 + wave * 16 + 4 * q;
+#pragma unroll
+            for (int r = 0; r < 4; ++r) y[r] = acc[mt][r];
+            if (p.res) {
+                const uint2 rv = *(const uint2 *)(p.res + (size_t)m * p.N + n);
+                y[0] += __uint_as_float(rv.x << 16);
+                y[1] += __uint_as_float(rv.x & 0xffff0000u);
+                y[2] += __uint_as_float(rv.y << 16);
+                y[3] += __uint_as_float(rv.y & 0xffff0000u);
+            }
+            uint2 w;
+            w.x = (uint32_t)fc_bf16_bits(y[0]) | ((uint32_t)fc_bf16_bits(y[1]) << 16);
+            w.y = (uint32_t)fc_bf16_bits(y[2]) | ((uint32_t)fc_bf16_bits(y[3]) << 16);
+            *(uint2 *)(p.out + (size_t)m * p.N + n) = w;
+        }
+    }
+}
+
+constexpr int KSL = 512;  // hidden elements per work item
+
+template <int MODE>
+hipError_t launch_mode(const FcSkinnyPlan &pl, const LinArgs &a, hipStream_t s)
+{
+    const dim3 g1((unsigned)pl.G, (unsigned)pl.chunks), g2((unsigned)pl.slabs * 8, (unsigned)pl.chunks);
+    if (pl.mt == 1) {
+        k_linear_stream<1, KSL, MODE><<<g1, dim3(512), 0, s>>>(a);
+        k_linear_finish<1, MODE><<<g2, dim3(64), 0, s>>>(a);
+    } else {
+        k_linear_stream<2, KSL, MODE><<<g1, dim3(512), 0, s>>>(a);
+        k_linear_finish<2, MODE><<<g2, dim3(64), 0, s>>>(a);
+    }
+    return hipGetLastError();
+}
+
+}  // namespace
+
+FcSkinnyPlan fc_plan_skinny(int dtype, int mode, int M, int K, int N)
+{
+    FcSkinnyPlan p;
+    memset(&p, 0, sizeof p);
+    const int rows_per_slab = mode == FC_LIN_GATE_UP ? 64 : 128;
+    if (dtype != FC_BF16 || M < 1 || K < KSL || K % KSL != 0 || N < rows_per_slab || N % rows_per_slab != 0)
+        return p;  // kind 0: plain kernel, no workspace
+    p.kind = 1;
+    p.mt = M <= 16 ? 1 : 2;
+    p.chunks = M <= 16 ? 1 : (M + 31) / 32;
+    p.slabs = N / rows_per_slab;
+    p.S = K / KSL;
+    const int64_t T = (int64_t)p.slabs * p.S;
+    if (T > (1 << 30) || p.chunks > 65535) {
+        p.kind = 0;
+        return p;
+    }
+    p.T = (int)T;
+    int target = 256;  // one workgroup per compute unit
+    if (const char *e = getenv("FC_LIN_WGS")) {
+        const int v = atoi(e);
+        if (v > 0) target = v;
+    }
+    p.G = p.T < target ? p.T : target;
+    const int ipw = p.T / p.G;  // every workgroup gets at least this many items
+    const int bound = (p.S + ipw - 1) / ipw + 1;
+    p.maxseg = bound < p.S ? bound : p.S;
+    return p;
+}
+
+size_t fc_skinny_workspace(const FcSkinnyPlan &p)
+{
+    if (p.kind == 0) return 0;
+    return (size_t)p.chunks * p.slabs * p.maxseg * 8 * p.mt * 256 * sizeof(float);
+}
+
+hipError_t fc_launch_linear_skinny(const FcSkinnyPlan &pl, int mode, const void *x, const void *w, const void *w2,
+                                   const void *res, int M, int K, int N, void *out, void *workspace,
+                                   hipStream_t s)
+{
+    // The kernels index the partial tiles by (slab, position of the workgroup among those that meet
+    // the slab); make sure on the host that no slab meets more workgroups than the plan reserved.
+    for (int slab = 0; slab < pl.slabs; ++slab) {
+        const int64_t i0 = (int64_t)slab * pl.S, i1 = i0 + pl.S - 1;
+        const int first = (int)(((i0 + 1) * pl.G - 1) / pl.T), last = (int)(((i1 + 1) * pl.G - 1) / pl.T);
+        if (last - first + 1 > pl.maxseg) return hipErrorInvalidValue;
+    }
+    if (pl.kind != 1 || pl.G < 1 || pl.G > pl.T || M > pl.chunks * 32 || !workspace) return hipErrorInvalidValue;
+    LinArgs a;
+    a.X = (const uint16_t *)x;
+    a.W = (const uint16_t *)w;
+    a.W2 = (const uint16_t *)w2;
+    a.res = (const uint16_t *)res;
+    a.out = (uint16_t *)out;
+    a.partials = (float *)workspace;
+    a.M = M;
+    a.K = K;
+    a.N = N;
+    a.S = pl.S;
+    a.T = pl.T;
+    a.G = pl.G;
+    a.maxseg = pl.maxseg;
+    a.slabs = pl.slabs;
+    return mode == FC_LIN_GATE_UP ? launch_mode<FC_LIN_GATE_UP>(pl, a, s) : launch_mode<FC_LIN_RESIDUAL>(pl, a, s);
+}

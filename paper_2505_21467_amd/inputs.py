@@ -116,14 +116,15 @@ def window_positions(batch: int, start: int, rows: int) -> torch.Tensor:
     return torch.arange(start, start + rows, dtype=torch.int32).repeat(batch, 1).contiguous()
 
 
-def layer_weights(w: Workload, seed: int, layer: int = 0, with_bias: bool = False) -> dict:
-    """All weights of one pre-normalised layer: matrices ~ N(0, 0.02), norm weights ~ 1 + N(0, 0.1)."""
+def layer_weights(w: Workload, seed: int, layer: int = 0, with_bias: bool = False, std: float = 0.02) -> dict:
+    """All weights of one pre-normalised layer: matrices ~ N(0, std), norm weights ~ 1 + N(0, 0.1)."""
     e = w.n_q_heads * w.head_dim
-    t = lambda name, shape: normal(seed, "%s.%d" % (name, layer), shape, 0.02, w.dtype)
+    t = lambda name, shape: normal(seed, "%s.%d" % (name, layer), shape, std, w.dtype)
     n = lambda name: (1.0 + 0.1 * torch.randn((w.hidden,), generator=_gen(seed, "%s.%d" % (name, layer)),
                                               dtype=torch.float32)).to(TORCH_DTYPE[w.dtype]).contiguous()
     return {
-        "norm1": n("norm1"), "w_qkv": weights(w, seed, layer), "b_qkv": bias(w, seed, layer) if with_bias else None,
+        "norm1": n("norm1"), "w_qkv": t("w_qkv", (w.qkv_width, w.hidden)),
+        "b_qkv": bias(w, seed, layer) if with_bias else None,
         "w_out": t("w_out", (w.hidden, e)), "norm2": n("norm2"),
         "w_gate": t("w_gate", (w.d_ff, w.hidden)), "w_up": t("w_up", (w.d_ff, w.hidden)),
         "w_down": t("w_down", (w.hidden, w.d_ff)),

@@ -156,3 +156,61 @@ def test_window_schedule_equals_oracle(mode):
     _raises(fc.FC_ERR_INVALID_ARG, fc.fc_window, 0, 0, 32, 32, 0)
     _raises(fc.FC_ERR_INVALID_ARG, fc.fc_window, 0, 0, 32, 32, 1, 0, 2)
     assert fc.lib().fc_window(0, 0, 32, 32, 1, 0, 0, None, None, None) == fc.FC_ERR_INVALID_ARG
+
+
+def test_rest_of_layer_entry_points_reject_bad_arguments_before_any_launch(cache):
+    S, BF = 0, "bf16"
+    N = fc.fc_rmsnorm
+    _raises(fc.FC_ERR_INVALID_ARG, N, BF, None, FAKE, 1e-6, 4, 64, FAKE, S)
+    _raises(fc.FC_ERR_INVALID_ARG, N, BF, FAKE, None, 1e-6, 4, 64, FAKE, S)
+    _raises(fc.FC_ERR_INVALID_ARG, N, BF, FAKE, FAKE, 1e-6, 4, 64, None, S)
+    _raises(fc.FC_ERR_INVALID_ARG, N, BF, FAKE, FAKE, -1.0, 4, 64, FAKE, S)
+    _raises(fc.FC_ERR_INVALID_ARG, N, BF, FAKE, FAKE, 1e-6, 0, 64, FAKE, S)
+    _raises(fc.FC_ERR_INVALID_ARG, N, BF, FAKE, FAKE, 1e-6, 4, 0, FAKE, S)
+    assert fc.lib().fc_rmsnorm(9, FAKE, FAKE, 1e-6, 4, 64, FAKE, None) == fc.FC_ERR_INVALID_ARG
+
+    Lr = fc.fc_linear_residual
+    big = 1 << 30
+    _raises(fc.FC_ERR_INVALID_ARG, Lr, BF, None, FAKE, None, 32, 512, 128, FAKE, FAKE, big, S)
+    _raises(fc.FC_ERR_INVALID_ARG, Lr, BF, FAKE, None, None, 32, 512, 128, FAKE, FAKE, big, S)
+    _raises(fc.FC_ERR_INVALID_ARG, Lr, BF, FAKE, FAKE, None, 32, 512, 128, None, FAKE, big, S)
+    _raises(fc.FC_ERR_INVALID_ARG, Lr, BF, FAKE, FAKE, None, 0, 512, 128, FAKE, FAKE, big, S)
+    _raises(fc.FC_ERR_UNSUPPORTED, Lr, BF, FAKE, FAKE, None, 32, 100, 128, FAKE, FAKE, big, S)
+    _raises(fc.FC_ERR_INVALID_ARG, Lr, BF, FAKE + 2, FAKE, None, 32, 512, 128, FAKE, FAKE, big, S)
+    _raises(fc.FC_ERR_WORKSPACE, Lr, BF, FAKE, FAKE, None, 32, 512, 128, FAKE, None, 0, S)
+    _raises(fc.FC_ERR_WORKSPACE, Lr, BF, FAKE, FAKE, None, 32, 512, 128, FAKE, FAKE, 64, S)
+    Gu = fc.fc_ffn_gate_up
+    _raises(fc.FC_ERR_INVALID_ARG, Gu, BF, FAKE, FAKE, None, 32, 512, 128, FAKE, FAKE, big, S)
+    _raises(fc.FC_ERR_INVALID_ARG, Gu, BF, FAKE, None, FAKE, 32, 512, 128, FAKE, FAKE, big, S)
+    _raises(fc.FC_ERR_WORKSPACE, Gu, BF, FAKE, FAKE, FAKE, 32, 512, 128, FAKE, FAKE, 64, S)
+
+    # workspace sizes: streaming shapes need one, other shapes do not; the gated query is N = 2 F
+    assert fc.fc_linear_workspace_bytes(BF, 32, 3584, 3584) > 0
+    assert fc.fc_linear_workspace_bytes(BF, 32, 3584, 2 * 18944) > 0
+    assert fc.fc_linear_workspace_bytes(BF, 32, 520, 3584) == 0      # K not a multiple of 512
+    assert fc.fc_linear_workspace_bytes("f32", 32, 3584, 3584) == 0
+    assert fc.fc_linear_workspace_bytes(BF, 0, 3584, 3584) == 0
+    assert fc.fc_linear_workspace_bytes(BF, 64, 3584, 3584) >= fc.fc_linear_workspace_bytes(BF, 32, 3584, 3584)
+
+    c = _cfg()
+    need = fc.fc_full_layer_workspace_bytes(c, 512, 32)
+    assert need > 0 and need % 256 == 0
+    assert fc.fc_full_layer_workspace_bytes(c, 0, 32) == 0 and fc.fc_full_layer_workspace_bytes(c, 512, 0) == 0
+    assert fc.fc_full_layer_workspace_bytes(c, 512, 64) > need
+    wt = fc.make_layer_weights(FAKE, FAKE, None, FAKE, FAKE, FAKE, FAKE, FAKE, 512, 1e-6)
+    Fl = fc.fc_full_layer_step
+    _raises(fc.FC_ERR_INVALID_ARG, Fl, None, 0, wt, FAKE, 0, 32, None, 100, FAKE, FAKE, need, S)
+    _raises(fc.FC_ERR_BOUNDS, Fl, cache, 2, wt, FAKE, 0, 32, None, 100, FAKE, FAKE, need, S)
+    _raises(fc.FC_ERR_INVALID_ARG, Fl, cache, 0, wt, None, 0, 32, None, 100, FAKE, FAKE, need, S)
+    _raises(fc.FC_ERR_INVALID_ARG, Fl, cache, 0, wt, FAKE, 0, 32, None, 100, None, FAKE, need, S)
+    _raises(fc.FC_ERR_INVALID_ARG, Fl, cache, 0, wt, FAKE, 0, 0, None, 100, FAKE, FAKE, need, S)
+    _raises(fc.FC_ERR_BOUNDS, Fl, cache, 0, wt, FAKE, 280, 32, None, 300, FAKE, FAKE, need, S)
+    _raises(fc.FC_ERR_BOUNDS, Fl, cache, 0, wt, FAKE, 0, 32, None, 301, FAKE, FAKE, need, S)
+    _raises(fc.FC_ERR_WORKSPACE, Fl, cache, 0, wt, FAKE, 0, 32, None, 100, FAKE, FAKE, need - 1, S)
+    _raises(fc.FC_ERR_WORKSPACE, Fl, cache, 0, wt, FAKE, 0, 32, None, 100, FAKE, None, 0, S)
+    for missing in ("norm1", "w_qkv", "w_out", "norm2", "w_gate", "w_up", "w_down"):
+        bad = fc.make_layer_weights(FAKE, FAKE, None, FAKE, FAKE, FAKE, FAKE, FAKE, 512, 1e-6)
+        setattr(bad, missing, None)
+        _raises(fc.FC_ERR_INVALID_ARG, Fl, cache, 0, bad, FAKE, 0, 32, None, 100, FAKE, FAKE, need, S)
+    bad = fc.make_layer_weights(FAKE, FAKE, None, FAKE, FAKE, FAKE, FAKE, FAKE, 0, 1e-6)
+    _raises(fc.FC_ERR_INVALID_ARG, Fl, cache, 0, bad, FAKE, 0, 32, None, 100, FAKE, FAKE, need, S)
