@@ -207,6 +207,54 @@ __global__ __launch_bounds__(256) void k_rmsnorm(const T *X, const T *__restrict
     for (int k = tid; k < d; k += 256) out[row * d + k] = fc_from_float<T>(fc_to_float(x[k]) * inv * fc_to_float(w[k]));
 }
 
+// bf16 rows whose length is a multiple of 8 and at most 2048 * NJ: every thread keeps its NJ 16-byte
+// pieces of the row in registers, so the row is read once.
+template <int NJ>
+__global__ __launch_bounds__(256) void k_rmsnorm_bf16_row(const uint16_t *X, const uint16_t *__restrict__ w, float eps,
+                                                          int d, uint16_t *out)
+{
+    __shared__ float red[4];
+    const size_t row = blockIdx.x;
+    const int tid = threadIdx.x, chunks = d >> 3;
+    uint4 v[NJ], g[NJ];
+#pragma unroll
+    for (int j = 0; j < NJ; ++j) {
+        const int c = tid + 256 * j;
+        v[j] = c < chunks ? *(const uint4 *)(X + row * d + 8 * c) : make_uint4(0, 0, 0, 0);
+        g[j] = c < chunks ? *(const uint4 *)(w + 8 * c) : make_uint4(0, 0, 0, 0);
+    }
+    float ss = 0.f;
+#pragma unroll
+    for (int j = 0; j < NJ; ++j) {
+        const uint32_t u[4] = {v[j].x, v[j].y, v[j].z, v[j].w};
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const float a = __uint_as_float(u[e] << 16), b = __uint_as_float(u[e] & 0xffff0000u);
+            ss += a * a;
+            ss += b * b;
+        }
+    }
+    ss = wave_sum(ss);
+    if ((tid & 63) == 0) red[tid >> 6] = ss;
+    __syncthreads();
+    const float tot = (red[0] + red[1]) + (red[2] + red[3]);
+    const float inv = 1.0f / sqrtf(tot / (float)d + eps);
+#pragma unroll
+    for (int j = 0; j < NJ; ++j) {
+        const int c = tid + 256 * j;
+        if (c >= chunks) continue;
+        const uint32_t u[4] = {v[j].x, v[j].y, v[j].z, v[j].w}, gw[4] = {g[j].x, g[j].y, g[j].z, g[j].w};
+        uint32_t o[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const float a = __uint_as_float(u[e] << 16) * inv * __uint_as_float(gw[e] << 16);
+            const float b = __uint_as_float(u[e] & 0xffff0000u) * inv * __uint_as_float(gw[e] & 0xffff0000u);
+            o[e] = (uint32_t)fc_bf16_bits(a) | ((uint32_t)fc_bf16_bits(b) << 16);
+        }
+        *(uint4 *)(out + row * d + 8 * c) = make_uint4(o[0], o[1], o[2], o[3]);
+    }
+}
+
 // ---------------------------------------------------------------------------------------------
 // Linear layer, block = (4 rows, 64 output columns); each wave owns every 4th column of the block and
 // runs the dot products with lanes along the hidden dimension.  MODE 0: out = aux + x w^T
@@ -316,7 +364,15 @@ hipError_t fc_launch_rmsnorm(int dtype, const void *x, const void *weight, float
     if (dtype == FC_F32)
         k_rmsnorm<float><<<dim3((unsigned)rows), dim3(256), 0, s>>>((const float *)x, (const float *)weight, eps,
                                                                     d, (float *)out);
-    else
+    else if (d % 8 == 0 && d <= 8192 && (((uintptr_t)x | (uintptr_t)weight | (uintptr_t)out) & 15) == 0) {
+        const uint16_t *xb = (const uint16_t *)x, *wb = (const uint16_t *)weight;
+        if (d <= 2048)
+            k_rmsnorm_bf16_row<1><<<dim3((unsigned)rows), dim3(256), 0, s>>>(xb, wb, eps, d, (uint16_t *)out);
+        else if (d <= 4096)
+            k_rmsnorm_bf16_row<2><<<dim3((unsigned)rows), dim3(256), 0, s>>>(xb, wb, eps, d, (uint16_t *)out);
+        else
+            k_rmsnorm_bf16_row<4><<<dim3((unsigned)rows), dim3(256), 0, s>>>(xb, wb, eps, d, (uint16_t *)out);
+    } else
         k_rmsnorm<bf16_t><<<dim3((unsigned)rows), dim3(256), 0, s>>>((const bf16_t *)x, (const bf16_t *)weight,
                                                                      eps, d, (bf16_t *)out);
     return hipGetLastError();

@@ -37,7 +37,16 @@ struct LinArgs {
     float *partials;      // [m chunk][slab][maxseg][wave][mt][4][64]
     int M, K, N;          // N = output columns
     int S, T, G, maxseg, slabs;
+#ifdef FC_LIN_TIMING
+    unsigned long long *dbg;  // tuning builds only: 16 stamps of the 100 MHz clock per workgroup
+#endif
 };
+
+#ifdef FC_LIN_TIMING
+#define FC_LSTAMP(k) do { if (p.dbg && threadIdx.x == 0 && (k) < 16) p.dbg[(size_t)blockIdx.x * 16 + (k)] = __builtin_amdgcn_s_memrealtime(); } while (0)
+#else
+#define FC_LSTAMP(k) do { } while (0)
+#endif
 
 __device__ __forceinline__ bf16x8 ld8(const uint16_t *p)
 {
@@ -59,11 +68,11 @@ __device__ __forceinline__ float swap32(float v)
     return (threadIdx.x & 32) ? __uint_as_float(r[0]) : __uint_as_float(r[1]);
 }
 
-// Workgroup that owns work item i when T items are dealt to G workgroups as runs
-// [floor(w T / G), floor((w + 1) T / G)).
-__device__ __forceinline__ int owner_of(int i, int T, int G)
+// Workgroup that owns unit u when U units are dealt to G workgroups as runs
+// [floor(w U / G), floor((w + 1) U / G)).  A unit is one k-step (32 hidden elements) of one slab.
+__host__ __device__ __forceinline__ int owner_of(int64_t u, int64_t U, int G)
 {
-    return (int)((((int64_t)i + 1) * G - 1) / T);
+    return (int)(((u + 1) * G - 1) / U);
 }
 
 template <int MT, int KSL, int MODE>
@@ -77,7 +86,12 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     __shared__ __align__(1024) unsigned char xs[2][16 * MT * ROWB];
 
     const int wg = blockIdx.x, m0 = blockIdx.y * 32;
-    const int lo = (int)((int64_t)wg * p.T / p.G), hi = (int)(((int64_t)wg + 1) * p.T / p.G);
+    // this workgroup's run of k-steps [ulo, uhi): whole items except possibly the first and the last
+    const int64_t U = (int64_t)p.T * KS;
+    const int64_t ulo = (int64_t)wg * U / p.G, uhi = ((int64_t)wg + 1) * U / p.G;
+    const int lo = (int)(ulo / KS), hi = (int)((uhi + KS - 1) / KS);
+    const int s_first = (int)(ulo - (int64_t)lo * KS);        // first k-step of item lo
+    const int s_last = (int)(uhi - (int64_t)(hi - 1) * KS);   // end of the k-steps of item hi - 1
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int rho = lane & 15, q = lane >> 4;
@@ -98,8 +112,14 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
         else
             wrow = p.W + (size_t)(slab * 128 + wave * 16 + rho) * p.K;
         wrow += (size_t)sl * KSL + 8 * q;
+        const int sa = item == lo ? s_first : 0, sb = item == hi - 1 ? s_last : KS;
 #pragma unroll
-        for (int s = 0; s < KS; ++s) wf[s] = ld8(wrow + 32 * s);
+        for (int s = 0; s < KS; ++s) {
+            if (s >= sa && s < sb)
+                wf[s] = ld8(wrow + 32 * s);
+            else
+                wf[s] = bf16x8{};  // k-steps of a neighbouring run: contribute nothing
+        }
     };
 
     f32x4 acc[MT];
@@ -121,7 +141,7 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     auto tail = [&](int item) {
         if (item + 1 < hi && (item + 1) % p.S != 0) return;
         const int slab = item / p.S;
-        const int seg = wg - owner_of(slab * p.S, p.T, p.G);
+        const int seg = wg - owner_of((int64_t)slab * p.S * KS, U, p.G);
         float *part = p.partials +
                       ((((size_t)blockIdx.y * p.slabs + slab) * p.maxseg + seg) * 8 + wave) * (MT * 256);
 #pragma unroll
@@ -133,33 +153,39 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
             }
     };
 
-    if (lo >= hi) return;
+    if (ulo >= uhi) return;
+    FC_LSTAMP(0);
     bf16x8 wa[KS], wb[KS];
     issue(lo, wa, xs[0]);
     int item = lo;
     for (;;) {
         __syncthreads();  // the loads of `item` have landed; every wave is done with the other buffers
+        FC_LSTAMP(1 + item - lo);
         if (item + 1 < hi) issue(item + 1, wb, xs[1]);
         compute(wa, xs[0]);
         tail(item);
         if (++item >= hi) break;
         __syncthreads();
+        FC_LSTAMP(1 + item - lo);
         if (item + 1 < hi) issue(item + 1, wa, xs[0]);
         compute(wb, xs[1]);
         tail(item);
         if (++item >= hi) break;
     }
+    FC_LSTAMP(15);
 }
 
 // Sum of a slab's partial tiles + epilogue; one wave per (slab, 16-row tile of W), grid.y = m chunk.
-template <int MT, int MODE>
+template <int MT, int KSL, int MODE>
 __global__ __launch_bounds__(64) void k_linear_finish(LinArgs p)
 {
+    constexpr int KS = KSL / 32;
+    const int64_t U = (int64_t)p.T * KS;
     const int slab = blockIdx.x >> 3, wave = blockIdx.x & 7;
     const int m0 = blockIdx.y * 32;
     const int lane = threadIdx.x, rho = lane & 15, q = lane >> 4;
-    const int first = owner_of(slab * p.S, p.T, p.G);
-    const int nseg = owner_of(slab * p.S + p.S - 1, p.T, p.G) - first + 1;
+    const int first = owner_of((int64_t)slab * p.S * KS, U, p.G);
+    const int nseg = owner_of((int64_t)(slab + 1) * p.S * KS - 1, U, p.G) - first + 1;
     const float *base = p.partials + ((((size_t)blockIdx.y * p.slabs + slab) * p.maxseg) * 8 + wave) * (MT * 256);
     const size_t seg_stride = (size_t)8 * MT * 256;
 
@@ -233,10 +259,10 @@ hipError_t launch_mode(const FcSkinnyPlan &pl, const LinArgs &a, hipStream_t s)
     const dim3 g1((unsigned)pl.G, (unsigned)pl.chunks), g2((unsigned)pl.slabs * 8, (unsigned)pl.chunks);
     if (pl.mt == 1) {
         k_linear_stream<1, KSL, MODE><<<g1, dim3(512), 0, s>>>(a);
-        k_linear_finish<1, MODE><<<g2, dim3(64), 0, s>>>(a);
+        k_linear_finish<1, KSL, MODE><<<g2, dim3(64), 0, s>>>(a);
     } else {
         k_linear_stream<2, KSL, MODE><<<g1, dim3(512), 0, s>>>(a);
-        k_linear_finish<2, MODE><<<g2, dim3(64), 0, s>>>(a);
+        k_linear_finish<2, KSL, MODE><<<g2, dim3(64), 0, s>>>(a);
     }
     return hipGetLastError();
 }
@@ -256,7 +282,7 @@ FcSkinnyPlan fc_plan_skinny(int dtype, int mode, int M, int K, int N)
     p.slabs = N / rows_per_slab;
     p.S = K / KSL;
     const int64_t T = (int64_t)p.slabs * p.S;
-    if (T > (1 << 30) || p.chunks > 65535) {
+    if (T > (1 << 26) || p.chunks > 65535) {
         p.kind = 0;
         return p;
     }
@@ -267,9 +293,11 @@ FcSkinnyPlan fc_plan_skinny(int dtype, int mode, int M, int K, int N)
         if (v > 0) target = v;
     }
     p.G = p.T < target ? p.T : target;
-    const int ipw = p.T / p.G;  // every workgroup gets at least this many items
-    const int bound = (p.S + ipw - 1) / ipw + 1;
-    p.maxseg = bound < p.S ? bound : p.S;
+    // runs are measured in k-steps of 32 hidden elements, so every workgroup streams the same
+    // amount to within one k-step; a slab of S * KS k-steps meets at most this many runs
+    const int64_t per_slab = (int64_t)p.S * (KSL / 32), upw = T * (KSL / 32) / p.G;
+    const int64_t bound = (per_slab + upw - 1) / upw + 1;
+    p.maxseg = (int)(bound < p.G ? bound : p.G);
     return p;
 }
 
@@ -286,8 +314,8 @@ hipError_t fc_launch_linear_skinny(const FcSkinnyPlan &pl, int mode, const void 
     // The kernels index the partial tiles by (slab, position of the workgroup among those that meet
     // the slab); make sure on the host that no slab meets more workgroups than the plan reserved.
     for (int slab = 0; slab < pl.slabs; ++slab) {
-        const int64_t i0 = (int64_t)slab * pl.S, i1 = i0 + pl.S - 1;
-        const int first = (int)(((i0 + 1) * pl.G - 1) / pl.T), last = (int)(((i1 + 1) * pl.G - 1) / pl.T);
+        const int64_t per_slab = (int64_t)pl.S * (KSL / 32), U = (int64_t)pl.T * (KSL / 32);
+        const int first = owner_of(slab * per_slab, U, pl.G), last = owner_of((slab + 1) * per_slab - 1, U, pl.G);
         if (last - first + 1 > pl.maxseg) return hipErrorInvalidValue;
     }
     if (pl.kind != 1 || pl.G < 1 || pl.G > pl.T || M > pl.chunks * 32 || !workspace) return hipErrorInvalidValue;
@@ -306,5 +334,11 @@ hipError_t fc_launch_linear_skinny(const FcSkinnyPlan &pl, int mode, const void 
     a.G = pl.G;
     a.maxseg = pl.maxseg;
     a.slabs = pl.slabs;
+#ifdef FC_LIN_TIMING
+    {
+        const char *env = getenv("FC_LIN_DBG_PTR");
+        a.dbg = env ? (unsigned long long *)strtoull(env, nullptr, 0) : nullptr;
+    }
+#endif
     return mode == FC_LIN_GATE_UP ? launch_mode<FC_LIN_GATE_UP>(pl, a, s) : launch_mode<FC_LIN_RESIDUAL>(pl, a, s);
 }

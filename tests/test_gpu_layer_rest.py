@@ -22,7 +22,10 @@ def _ws(nbytes):
     return torch.empty(max(nbytes, 16), dtype=torch.uint8, device=DEV)
 
 
-@pytest.mark.parametrize("dtype,rows,hidden", [("f32", 5, 200), ("bf16", 5, 200), ("bf16", 32, 3584), ("bf16", 3, 8)])
+@pytest.mark.parametrize("dtype,rows,hidden", [
+    ("f32", 5, 200), ("bf16", 5, 200), ("bf16", 32, 3584), ("bf16", 3, 8), ("bf16", 4, 2048), ("bf16", 3, 4096),
+    ("bf16", 2, 8192), ("bf16", 2, 8200), ("bf16", 3, 100),
+])
 def test_rmsnorm_matches_oracle(dtype, rows, hidden):
     x = inputs.normal(1, "x", (rows, hidden), 1.5, dtype)
     w = (1.0 + 0.1 * inputs.normal(1, "w", (hidden,), 1.0, "f32")).to(inputs.TORCH_DTYPE[dtype])
