@@ -1,6 +1,7 @@
 """Benchmark of the FreeCache cached denoising layer-step on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c4|c2|c3|c5|c5_refresh] [--layers N]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c4|c2|c3|c5|c5_refresh|c4_layer|c2_layer]
+                    [--layers N]
 
 A "step" is one pass of the whole hot path for one layer: QKV projection + RoPE + scatter of the
 active window, then attention of the window's queries over the cache.  The default workload is the
@@ -14,6 +15,10 @@ same loop on a single layer is reported as `single_cache_us` (cache-resident fig
 
 `--workload c5_refresh` times the periodic refresh of configuration 5 instead (one `fc_refresh` of the
 256-row generation region of 8 sequences per step: a dense, matrix-core-bound pass).
+
+`--workload c4_layer` / `c2_layer` time the whole transformer layer on the window rows instead (RMSNorm,
+the path above, output projection + residual, RMSNorm, gated feed-forward network + residual: one
+`fc_full_layer_step` per step, Dream-7B widths), the next row after the attention path.
 
 Prints ONE JSON line (see the fields below).  Inputs are seeded and synthetic.
 """
@@ -45,7 +50,8 @@ def _parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=100)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--workload", default="c4", choices=["c2", "c3", "c4", "c5", "c5_refresh"])
+    ap.add_argument("--workload", default="c4",
+                    choices=["c2", "c3", "c4", "c5", "c5_refresh", "c4_layer", "c2_layer"])
     ap.add_argument("--layers", type=int, default=0, help="distinct layer caches to rotate over (0 = auto)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-single", action="store_true",
@@ -68,6 +74,8 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     fc.lib()
     dev = torch.device("cuda:0")
+    if args.workload.endswith("_layer"):
+        return main_layer(args, torch, fc, inputs, dev)
     refresh = args.workload == "c5_refresh"
     w = {"c2": inputs.C2, "c3": inputs.C3, "c4": inputs.C4, "c5": inputs.C5, "c5_refresh": inputs.C5}[args.workload]
     B, Dh, Hq, Hkv = w.batch, w.head_dim, w.n_q_heads, w.n_kv_heads
@@ -241,6 +249,148 @@ def main():
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(w, inputs, A, refresh)
 
+    torch.cuda.synchronize()
+    fc.fc_cache_free(cache)
+    print(json.dumps(out))
+
+
+def main_layer(args, torch, fc, inputs, dev):
+    """Whole-layer workloads: one fc_full_layer_step per step, rotating over distinct layers."""
+    w = {"c4_layer": inputs.C4, "c2_layer": inputs.C2}[args.workload]
+    B, Dh, Hq, Hkv, d, F = w.batch, w.head_dim, w.n_q_heads, w.n_kv_heads, w.hidden, w.d_ff
+    A, S, E, esz = w.active, w.kv_len, w.n_q_heads * w.head_dim, 2
+    M = B * A
+    tdt = inputs.TORCH_DTYPE[w.dtype]
+    w_bytes = {"w_qkv": w.qkv_width * d * esz, "w_out": d * E * esz, "gate_up": 2 * F * d * esz, "w_down": d * F * esz}
+    kv_bytes_layer = 2 * B * S * Hkv * Dh * esz
+    layer_bytes = sum(w_bytes.values()) + kv_bytes_layer
+    n_layers = args.layers or max(4, math.ceil(2.4e9 / layer_bytes))
+    steps = min(args.steps, 60)
+
+    cfg = fc.make_config(n_layers, B, d, Hq, Hkv, Dh, S, w.dtype, w.rope_base)
+    nbytes = fc.fc_cache_storage_bytes(cfg)
+    k_store = torch.zeros(nbytes // esz, dtype=tdt, device=dev)
+    v_store = torch.zeros(nbytes // esz, dtype=tdt, device=dev)
+    cache = fc.fc_cache_alloc(cfg, k_store, v_store)
+    K0, V0 = inputs.kv_fill(w, 0, S)
+    K0d, V0d = K0.to(dev), V0.to(dev)
+    for layer in range(n_layers):
+        fc.fc_cache_write_rows(cache, layer, K0d, V0d, 0, S)
+    # layer 0 from the shared generators, the other layers are device copies (distinct memory)
+    host = inputs.layer_weights(w, 0)
+    layers = []
+    for layer in range(n_layers):
+        t = {k: (None if v is None else (v.to(dev) if layer == 0 else layers[0][0][k].clone())) for k, v in host.items()}
+        h = fc.make_layer_weights(t["norm1"], t["w_qkv"], t["b_qkv"], t["w_out"], t["norm2"], t["w_gate"], t["w_up"],
+                                  t["w_down"], F, w.norm_eps)
+        layers.append((t, h))
+    ws_bytes = fc.fc_full_layer_workspace_bytes(cfg, F, A)
+    ws = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
+    n_x = 8
+    Xs = [inputs.hidden_states(w, 0, A, tag="x.%d" % i).to(dev) for i in range(n_x)]
+    Y = torch.empty((B, A, d), dtype=tdt, device=dev)
+    if w.gen_len:
+        n_sched = -(-w.gen_len // w.block) * w.steps_per_block
+        sched = [fc.fc_window(s, w.cached_len, w.gen_len, w.block, w.steps_per_block)[0] for s in range(n_sched)]
+    else:
+        sched = [w.cached_len]
+    stream = torch.cuda.current_stream().cuda_stream
+    torch.cuda.synchronize()
+
+    def step(s):
+        layer = s % n_layers
+        fc.fc_full_layer_step(cache, layer, layers[layer][1], Xs[s % n_x], sched[s % len(sched)], A, None, S, Y, ws,
+                              ws_bytes, stream)
+
+    def timed(fn, n):
+        res = []
+        for _ in range(args.repeats):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            torch.cuda.synchronize()
+            e0.record()
+            for s in range(n):
+                fn(s)
+            e1.record()
+            torch.cuda.synchronize()
+            res.append(e0.elapsed_time(e1) * 1000.0 / n)
+        res.sort()
+        return res[len(res) // 2]
+
+    for s in range(min(args.warmup, 2 * n_layers)):
+        step(s)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    t_host0 = time.perf_counter()
+    e0.record()
+    for s in range(steps):
+        step(s)
+    e1.record()
+    torch.cuda.synchronize()
+    t_host = time.perf_counter() - t_host0
+    us_step = e0.elapsed_time(e1) * 1000.0 / steps
+
+    # the three weight-streaming calls on their own, same rotation (each is GPU-bound at these sizes)
+    lin_ws_bytes = max(fc.fc_linear_workspace_bytes(w.dtype, M, E, d), fc.fc_linear_workspace_bytes(w.dtype, M, d, 2 * F),
+                       fc.fc_linear_workspace_bytes(w.dtype, M, F, d))
+    lws = torch.empty(max(lin_ws_bytes, 16), dtype=torch.uint8, device=dev)
+    h = Xs[0].view(M, d)
+    o = torch.randn((M, E), device=dev).to(tdt)
+    act = torch.randn((M, F), device=dev).to(tdt)
+    x2 = torch.empty((M, d), dtype=tdt, device=dev)
+    actb = torch.empty((M, F), dtype=tdt, device=dev)
+    L = lambda s: layers[s % n_layers][0]
+    us_out = timed(lambda s: fc.fc_linear_residual(w.dtype, o, L(s)["w_out"], h, M, E, d, x2, lws, lin_ws_bytes, stream), steps)
+    us_gate = timed(lambda s: fc.fc_ffn_gate_up(w.dtype, h, L(s)["w_gate"], L(s)["w_up"], M, d, F, actb, lws,
+                                                lin_ws_bytes, stream), steps)
+    us_down = timed(lambda s: fc.fc_linear_residual(w.dtype, act, L(s)["w_down"], h, M, F, d, x2, lws, lin_ws_bytes,
+                                                    stream), steps)
+
+    total_w = sum(w_bytes.values())
+    flops = 2.0 * M * (d * w.qkv_width + E * d + 3 * d * F) + 4.0 * M * Hq * S * Dh
+    gbs = lambda nbytes, us: round(nbytes / us * 1e-3, 1)
+    out = {
+        "metric": "us per cached denoising step of one whole transformer layer on the window rows",
+        "value": round(us_step, 3), "unit": "us", "n_gpus": 1, "steps": steps, "warmup": min(args.warmup, 2 * n_layers),
+        "ms_per_step": round(us_step / 1000.0, 6), "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
+        "dtype": w.dtype, "data": "synthetic",
+        "config": {"workload": w.name + "/whole-layer", "batch": B, "hidden": d, "d_ff": F, "n_q_heads": Hq,
+                   "n_kv_heads": Hkv, "head_dim": Dh, "kv_len": S, "active_rows": A, "layers_rotated": n_layers,
+                   "weight_bytes_per_layer": total_w, "kv_bytes_per_layer": kv_bytes_layer},
+        "roofline": {
+            "kernel": "fc_ffn_gate_up (k_linear_stream + k_linear_finish)", "bound": "hbm",
+            "achieved": gbs(w_bytes["gate_up"], us_gate), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+            "frac": round(w_bytes["gate_up"] / us_gate * 1e-3 / HBM_PEAK_GBS, 4), "traffic": None,
+            "algorithmic_bytes_per_launch": w_bytes["gate_up"] + M * (d + F) * esz, "us_per_launch": round(us_gate, 3),
+        },
+        "linear_calls": {
+            "w_out": {"us_per_launch": round(us_out, 3), "weight_stream_gbs": gbs(w_bytes["w_out"], us_out)},
+            "gate_up": {"us_per_launch": round(us_gate, 3), "weight_stream_gbs": gbs(w_bytes["gate_up"], us_gate)},
+            "w_down": {"us_per_launch": round(us_down, 3), "weight_stream_gbs": gbs(w_bytes["w_down"], us_down)},
+        },
+        "layer_stream_gbs": gbs(total_w + kv_bytes_layer, us_step),
+        "layer_frac_of_hbm_peak": round((total_w + kv_bytes_layer) / us_step * 1e-3 / HBM_PEAK_GBS, 4),
+        "active_rows_per_s": round(M / (us_step * 1e-6), 1),
+        "tflops": round(flops / us_step * 1e-6, 2),
+        "host_wall_us_per_step": round(t_host * 1e6 / steps, 2),
+    }
+    if not args.no_cpu_baseline:
+        import numpy as np
+        from oracle import fc_oracle as orc
+        ocfg = orc.OracleConfig(B, d, Hq, Hkv, Dh, S, w.dtype, w.rope_base)
+        Kc, Vc = inputs.as_oracle(K0).copy(), inputs.as_oracle(V0).copy()
+        wts = {k: (None if v is None else inputs.as_oracle(v)) for k, v in host.items()}
+        pos = inputs.as_oracle(inputs.window_positions(B, w.cached_len, A))
+        X = inputs.as_oracle(inputs.hidden_states(w, 0, A, tag="x.0"))
+        n_sample, dt = 0, 0.0
+        while n_sample < 20 and dt < 12.0:
+            t0 = time.perf_counter()
+            orc.full_layer_step(ocfg, X, wts, pos, S, Kc, Vc, w.norm_eps)
+            dt += time.perf_counter() - t0
+            n_sample += 1
+        out["cpu_baseline"] = {"value": round(dt * 1e6 / n_sample, 1), "unit": "us", "cores": orc.get_threads(),
+                               "kind": "oracle", "sample": "%d whole-layer step(s) of %s, fp64, OpenMP" % (n_sample, w.name)}
+        del np
     torch.cuda.synchronize()
     fc.fc_cache_free(cache)
     print(json.dumps(out))
