@@ -432,13 +432,21 @@ static fc_status check_linear_shape(int32_t M, int32_t K, int32_t N)
     return FC_OK;
 }
 
+// Workspace of one linear call: tiled GEMM for more than 32 rows, streaming kernels otherwise.
+static size_t linear_need(int dtype, int mode, int M, int K, int N)
+{
+    const FcWidePlan wide = fc_plan_wide(dtype, mode, M, K, N);
+    if (wide.kind == 1) return fc_wide_workspace(wide, M, N);
+    return fc_skinny_workspace(fc_plan_skinny(dtype, mode, M, K, N));
+}
+
 size_t fc_linear_workspace_bytes(int32_t dtype, int32_t M, int32_t K, int32_t N)
 {
     if ((dtype != FC_F32 && dtype != FC_BF16) || M < 1 || K < 1 || N < 1) return 0;
     // the gated W_1 is planned on its F = N / 2 outputs; its slabs hold half as many outputs, so the
     // two plans need the same space and one query serves both calls
-    const size_t a = fc_skinny_workspace(fc_plan_skinny(dtype, FC_LIN_RESIDUAL, M, K, N));
-    const size_t b = N % 2 == 0 ? fc_skinny_workspace(fc_plan_skinny(dtype, FC_LIN_GATE_UP, M, K, N / 2)) : 0;
+    const size_t a = linear_need(dtype, FC_LIN_RESIDUAL, M, K, N);
+    const size_t b = N % 2 == 0 ? linear_need(dtype, FC_LIN_GATE_UP, M, K, N / 2) : 0;
     return a > b ? a : b;
 }
 
@@ -454,13 +462,16 @@ static fc_status linear_common(int32_t dtype, int mode, const void *x, const voi
     if (st != FC_OK) return st;
     if (((uintptr_t)x | (uintptr_t)w | (uintptr_t)w2 | (uintptr_t)res | (uintptr_t)out | (uintptr_t)workspace) & 15)
         return fail(FC_ERR_INVALID_ARG, "pointers must be 16-byte aligned");
+    const FcWidePlan wide = fc_plan_wide(dtype, mode, M, K, N);
     const FcSkinnyPlan plan = fc_plan_skinny(dtype, mode, M, K, N);
-    const size_t need = fc_skinny_workspace(plan);
+    const size_t need = wide.kind == 1 ? fc_wide_workspace(wide, M, N) : fc_skinny_workspace(plan);
     if (need > 0 && (!workspace || workspace_bytes < need))
         return fail(FC_ERR_WORKSPACE, "workspace of %zu bytes needed, %zu given", need,
                     workspace ? workspace_bytes : (size_t)0);
     hipError_t e;
-    if (plan.kind == 1)
+    if (wide.kind == 1)
+        e = fc_launch_linear_wide(wide, mode, x, w, w2, res, M, K, N, out, workspace, (hipStream_t)stream);
+    else if (plan.kind == 1)
         e = fc_launch_linear_skinny(plan, mode, x, w, w2, res, M, K, N, out, workspace, (hipStream_t)stream);
     else
         e = fc_launch_linear_generic(dtype, mode, x, w, mode == FC_LIN_GATE_UP ? w2 : res, M, K, N, out,

@@ -103,3 +103,13 @@ size_t fc_skinny_workspace(const FcSkinnyPlan &p);
 hipError_t fc_launch_linear_skinny(const FcSkinnyPlan &pl, int mode, const void *x, const void *w,
                                    const void *w2, const void *res, int M, int K, int N, void *out,
                                    void *workspace, hipStream_t s);
+// Tiled-GEMM plan of the same linear layers on more than 32 rows.
+struct FcWidePlan {
+    int kind;    // 0 = not covered, 1 = tiled GEMM
+    int shape;   // 0: 256 rows x slab, 1: 128 rows x slab, 2: 128 rows x half slab
+    int ksplit;  // parts of the hidden dimension (1 = epilogue inside the GEMM, no workspace)
+};
+FcWidePlan fc_plan_wide(int dtype, int mode, int M, int K, int N);
+size_t fc_wide_workspace(const FcWidePlan &p, int M, int N);
+hipError_t fc_launch_linear_wide(const FcWidePlan &pl, int mode, const void *x, const void *w, const void *w2,
+                                 const void *res, int M, int K, int N, void *out, void *workspace, hipStream_t s);

@@ -22,6 +22,7 @@
 // the loads; in the 256-row shapes (two multiplying waves per SIMD) every wave issues its share, a
 // quarter at a time between its multiplies.
 #include <stdlib.h>
+#include <string.h>
 
 #include "fc_device.h"
 #include "fc_internal.h"
@@ -45,7 +46,15 @@ struct GemmArgs {
     int M, A, K, win_start;
     int n_mt;              // row tiles of 32 * NW window rows
     int n_units;           // head slots (NSUB = 4) or half-head slots (NSUB = 2)
+    int n_slots;           // 128-row slabs of W: head slots (EPI 0), N / 128 (EPI 1, 3), d_ff / 64 (EPI 2)
     double log2_base_64;   // log2(rope_base) / 64
+    // plain linear layers of the rest of the layer (EPI != 0)
+    const uint16_t *W2;    // EPI 2: the up matrix [N][K] (W is the gate matrix)
+    const uint16_t *res;   // EPI 1: residual [M][N] or nullptr
+    uint16_t *out;         // EPI 1, 2: [M][N]
+    float *part;           // EPI 3: partial sums [ksplit][M][N]
+    int N;                 // output columns
+    int ksplit;            // EPI 3: parts the hidden dimension is cut into (blockIdx.y)
 #ifdef FC_GEMM_TUNE
     int flags;             // tuning builds only: 1 skip the multiplies, 2 skip the LDS reads, 4 skip the global loads
     unsigned long long *dbg;  // tuning builds only: time stamps (100 MHz), 8 per workgroup
@@ -86,7 +95,13 @@ __device__ __forceinline__ void wait_stages(int k)
 // rotary-paired half head (NSUB = 2).  SLOTS = stages in the LDS ring.
 // NL = 0: every wave also issues its share of the loads; NL > 0: NL extra waves do nothing but issue
 // the loads, so that the multiplying waves never wait for the memory pipeline to take a load.
-template <int KS, int NW, int NSUB, int MW, int NG, int SLOTS, int NL>
+// EPI selects the epilogue: 0 = QKV (bias, rotary embedding, scatter into the cache); the others are
+// the plain linear layers of the rest of the layer, whose 128-row slabs of W take the place of the
+// head slots: 1 = out = residual + x w^T; 2 = out = silu(x w_gate^T) * (x w_up^T), a slab being 64
+// gate rows (sub-tiles 0, 1) and the same 64 up rows (sub-tiles 2, 3), so that both products of an
+// output sit in one lane like a rotary pair; 3 = fp32 partial sums of one part of the hidden dimension
+// (blockIdx.y), for matrices with too few slabs to fill the chip.
+template <int KS, int NW, int NSUB, int MW, int NG, int SLOTS, int NL, int EPI>
 __global__ __launch_bounds__((NW + NL) * 64) void k_proj_gemm(GemmArgs p)
 {
     constexpr int ROWB = KS * 2;               // bytes of one row piece: 128 or 256
@@ -115,7 +130,7 @@ __global__ __launch_bounds__((NW + NL) * 64) void k_proj_gemm(GemmArgs p)
     const int unit = (qd / p.n_mt) * 8 + xcd;
     if (unit >= p.n_units) return;
     const int m0 = mt * XROWS;
-    const int n_slots = G.Hq + 2 * G.Hkv;      // head slots: Hq query heads, Hkv key heads, Hkv value heads
+    const int n_slots = p.n_slots;             // EPI 0: Hq query heads, Hkv key heads, Hkv value heads
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -138,8 +153,14 @@ __global__ __launch_bounds__((NW + NL) * 64) void k_proj_gemm(GemmArgs p)
         const int c = (lane % CPR) ^ (KS == 64 ? (rl >> 1) & 7 : rl & 15);
         if (i < WBW) {
             int n;
-            if (NSUB == 4) n = min(unit * NG + rl / 128, n_slots - 1) * 128 + (rl & 127);
-            else n = hs * 128 + (rl >> 5) * 64 + 32 * half + (rl & 31);
+            if (EPI == 2) {  // row of the gate or of the up matrix (which of the two: see issue_stage)
+                const int u = min(NSUB == 4 ? unit : hs, n_slots - 1);
+                n = u * 64 + (NSUB == 4 ? rl & 63 : 32 * half + (rl & 31));
+            } else if (NSUB == 4) {
+                n = min(unit * NG + rl / 128, n_slots - 1) * 128 + (rl & 127);
+            } else {
+                n = min(hs, n_slots - 1) * 128 + (rl >> 5) * 64 + 32 * half + (rl & 31);
+            }
             goff[i] = (uint32_t)n * (uint32_t)(p.K * 2) + c * 16;
         } else {
             const int m = min(m0 + rl, p.M - 1);    // rows past the end re-read the last row; never stored
@@ -149,6 +170,10 @@ __global__ __launch_bounds__((NW + NL) * 64) void k_proj_gemm(GemmArgs p)
     // The loads of a stage are issued in four parts spread over the multiplies of the stage before,
     // because a wave that issues many of them back to back waits for the memory pipeline to take
     // them before it can issue anything else.  part < 0: all of them.
+    // part of the hidden dimension this workgroup covers (EPI 3 only: blockIdx.y of p.ksplit parts)
+    const int all_stages = p.K / KS;
+    const int st0 = EPI == 3 ? (int)((int64_t)blockIdx.y * all_stages / p.ksplit) : 0;
+    const int n_stages = EPI == 3 ? (int)(((int64_t)blockIdx.y + 1) * all_stages / p.ksplit) - st0 : all_stages;
     auto issue_stage = [&](int st, int part) {
         unsigned char *dst = smem + (st % SLOTS) * STAGE;
 #ifdef FC_GEMM_TUNE
@@ -157,7 +182,13 @@ __global__ __launch_bounds__((NW + NL) * 64) void k_proj_gemm(GemmArgs p)
 #pragma unroll
         for (int i = 0; i < LBW; ++i) {
             if (part >= 0 && (i & 3) != part) continue;
-            const unsigned char *src = (const unsigned char *)(i < WBW ? p.W : p.X) + (size_t)st * ROWB;
+            const uint16_t *mat = p.X;
+            if (i < WBW) {
+                // EPI 2: the second half of the tile rows (a whole number of 1 KB blocks) is the up matrix
+                const bool up = EPI == 2 && RPB * (lw + NLW * i) >= (NSUB == 4 ? 64 : 32);
+                mat = up ? p.W2 : p.W;
+            }
+            const unsigned char *src = (const unsigned char *)mat + (size_t)(st0 + st) * ROWB;
             load_lds16g(src + goff[i], dst + (lw + NLW * i) * 1024);
         }
     };
@@ -206,7 +237,6 @@ __global__ __launch_bounds__((NW + NL) * 64) void k_proj_gemm(GemmArgs p)
                 acc[i][t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[buf][t], xf[buf][i], acc[i][t], 0, 0, 0);
     };
 
-    const int n_stages = p.K / KS;
     FC_GSTAMP(1);
     const int n_pro = min(SLOTS, n_stages);
     if (NL > 0) {
@@ -287,6 +317,45 @@ __global__ __launch_bounds__((NW + NL) * 64) void k_proj_gemm(GemmArgs p)
     // register r of sub-tile t is feature 32 t' + 8 (r >> 2) + 4 hi + (r & 3) of the head, with t' = t
     // for a whole head and {half, half + 2} for a half head.
     if (!head_valid) return;
+    if (EPI != 0) {
+        // Plain linear layers.  Register r of sub-tile t of lane (col, hi) is output column
+        // 32 t' + 8 (r >> 2) + 4 hi + (r & 3) of the slab (of its 64 outputs for EPI 2, t' < 2).
+#pragma unroll
+        for (int i = 0; i < MW; ++i) {
+            const int m = m0 + 32 * (wm * MW + i) + col;
+            if (m >= p.M) continue;
+#pragma unroll
+            for (int t = 0; t < (EPI == 2 ? NSUB / 2 : NSUB); ++t) {
+                const int tq = NSUB == 4 ? t : (EPI == 2 ? half : half + 2 * t);
+#pragma unroll
+                for (int rq = 0; rq < 4; ++rq) {
+                    const size_t at = (size_t)m * p.N + (size_t)hs * (EPI == 2 ? 64 : 128) + 32 * tq + 8 * rq + 4 * hi;
+                    float y[4];
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        y[e] = acc[i][t][4 * rq + e];
+                        if (EPI == 2) y[e] = y[e] / (1.0f + expf(-y[e])) * acc[i][t + NSUB / 2][4 * rq + e];
+                    }
+                    if (EPI == 3) {
+                        *(float4 *)(p.part + (size_t)blockIdx.y * p.M * p.N + at) = make_float4(y[0], y[1], y[2], y[3]);
+                        continue;
+                    }
+                    if (EPI == 1 && p.res) {
+                        const uint2 rv = *(const uint2 *)(p.res + at);
+                        y[0] += __uint_as_float(rv.x << 16);
+                        y[1] += __uint_as_float(rv.x & 0xffff0000u);
+                        y[2] += __uint_as_float(rv.y << 16);
+                        y[3] += __uint_as_float(rv.y & 0xffff0000u);
+                    }
+                    uint2 w;
+                    w.x = (uint32_t)fc_bf16_bits(y[0]) | ((uint32_t)fc_bf16_bits(y[1]) << 16);
+                    w.y = (uint32_t)fc_bf16_bits(y[2]) | ((uint32_t)fc_bf16_bits(y[3]) << 16);
+                    *(uint2 *)(p.out + at) = w;
+                }
+            }
+        }
+        return;
+    }
     const bool rotate = hs < G.Hq + G.Hkv;
     constexpr int NP = NSUB / 2;  // rotary pairs of sub-tiles: (t, t + NP)
     // base^(-1/64) and its powers; base^(-i/64) / (2 pi) = turns per position of pair i
@@ -370,24 +439,130 @@ __global__ __launch_bounds__((NW + NL) * 64) void k_proj_gemm(GemmArgs p)
     FC_GSTAMP(4);
 }
 
-template <int KS, int NW, int NSUB, int MW, int NG, int SLOTS, int NL>
+template <int KS, int NW, int NSUB, int MW, int NG, int SLOTS, int NL, int EPI = 0>
 hipError_t launch_gemm(GemmArgs a, hipStream_t s)
 {
     constexpr int XROWS = 32 * MW * (NW / NG);
     constexpr int LDS = SLOTS * (32 * NSUB * NG + XROWS) * KS * 2;
     static_assert(LDS <= 160 * 1024, "LDS ring too large");
-    static hipError_t attr = hipFuncSetAttribute((const void *)k_proj_gemm<KS, NW, NSUB, MW, NG, SLOTS, NL>,
+    static hipError_t attr = hipFuncSetAttribute((const void *)k_proj_gemm<KS, NW, NSUB, MW, NG, SLOTS, NL, EPI>,
                                                  hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
     if (attr != hipSuccess) return attr;
-    const int slots = a.G.Hq + 2 * a.G.Hkv;
+    const int slots = a.n_slots;
     a.n_units = NSUB == 4 ? (slots + NG - 1) / NG : 2 * slots;
     a.n_mt = (a.M + XROWS - 1) / XROWS;
     const unsigned grid = (unsigned)(((a.n_units + 7) / 8) * 8 * a.n_mt);
-    k_proj_gemm<KS, NW, NSUB, MW, NG, SLOTS, NL><<<dim3(grid), dim3((NW + NL) * 64), LDS, s>>>(a);
+    const unsigned gy = EPI == 3 ? (unsigned)a.ksplit : 1u;
+    k_proj_gemm<KS, NW, NSUB, MW, NG, SLOTS, NL, EPI><<<dim3(grid, gy), dim3((NW + NL) * 64), LDS, s>>>(a);
     return hipGetLastError();
 }
 
+// Sum of the hidden-dimension parts of an EPI 3 launch + residual, four outputs per thread.
+__global__ __launch_bounds__(256) void k_splitk_finish(const float *__restrict__ part, const uint16_t *res,
+                                                       uint16_t *out, size_t quads, size_t plane, int ksplit)
+{
+    const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (i >= quads) return;
+    float4 a = *(const float4 *)(part + 4 * i);
+    for (int k = 1; k < ksplit; ++k) {
+        const float4 b = *(const float4 *)(part + (size_t)k * plane + 4 * i);
+        a.x += b.x;
+        a.y += b.y;
+        a.z += b.z;
+        a.w += b.w;
+    }
+    if (res) {
+        const uint2 rv = *(const uint2 *)(res + 4 * i);
+        a.x += __uint_as_float(rv.x << 16);
+        a.y += __uint_as_float(rv.x & 0xffff0000u);
+        a.z += __uint_as_float(rv.y << 16);
+        a.w += __uint_as_float(rv.y & 0xffff0000u);
+    }
+    uint2 w;
+    w.x = (uint32_t)fc_bf16_bits(a.x) | ((uint32_t)fc_bf16_bits(a.y) << 16);
+    w.y = (uint32_t)fc_bf16_bits(a.z) | ((uint32_t)fc_bf16_bits(a.w) << 16);
+    *(uint2 *)(out + 4 * i) = w;
+}
+
+template <int EPI>
+hipError_t launch_wide_shape(int shape, const GemmArgs &a, hipStream_t s)
+{
+    if (shape == 0) return launch_gemm<64, 8, 4, 1, 1, 3, 0, EPI>(a, s);  // 256 rows x slab
+    if (shape == 1) return launch_gemm<64, 4, 4, 1, 1, 4, 4, EPI>(a, s);  // 128 rows x slab
+    return launch_gemm<64, 4, 2, 1, 1, 4, 4, EPI>(a, s);                  // 128 rows x half slab
+}
+
 }  // namespace
+
+// Tiled-GEMM plan of a plain linear layer on more than 32 rows (host, pure function of the shape).
+FcWidePlan fc_plan_wide(int dtype, int mode, int M, int K, int N)
+{
+    FcWidePlan p;
+    p.kind = 0;
+    p.shape = 0;
+    p.ksplit = 1;
+    const int per_slab = mode == FC_LIN_GATE_UP ? 64 : 128;
+    if (dtype != FC_BF16 || M <= 32 || K < 4 * KS_MIN || K % KS_MIN != 0 || N < per_slab || N % per_slab != 0) return p;
+    // 32-bit byte offsets inside X and each weight matrix
+    if ((int64_t)N * K * 2 >= ((int64_t)1 << 32) || (int64_t)M * K * 2 >= ((int64_t)1 << 32)) return p;
+    p.kind = 1;
+    const int64_t units = N / per_slab, t256 = (M + 255) / 256, t128 = (M + 127) / 128;
+    // the largest tile that still gives the chip about one workgroup per compute unit
+    if (units * t256 >= 192) p.shape = 0;
+    else if (units * t128 >= 144) p.shape = 1;
+    else p.shape = 2;
+    // too few slabs even for the smallest tile: also cut the hidden dimension (partial sums in fp32)
+    const int64_t wgs = 2 * units * t128;
+    if (mode == FC_LIN_RESIDUAL && p.shape == 2 && wgs < 192) {
+        int64_t ks = (256 + wgs / 2) / wgs;
+        const int64_t stages = K / KS_MIN;
+        if (ks > stages / 8) ks = stages / 8;
+        if (ks > 16) ks = 16;
+        if (ks > 1) p.ksplit = (int)ks;
+    }
+    if (const char *e = getenv("FC_LIN_WIDE_SHAPE")) {  // tuning knobs
+        const int v = atoi(e);
+        if (v >= 0 && v <= 2) p.shape = v;
+    }
+    if (const char *e = getenv("FC_LIN_KSPLIT")) {
+        const int v = atoi(e);
+        if (v >= 1 && v <= 16 && v <= K / KS_MIN / 4 && mode == FC_LIN_RESIDUAL) p.ksplit = v;
+    }
+    return p;
+}
+
+size_t fc_wide_workspace(const FcWidePlan &p, int M, int N)
+{
+    return p.kind == 1 && p.ksplit > 1 ? (size_t)p.ksplit * M * N * sizeof(float) : 0;
+}
+
+hipError_t fc_launch_linear_wide(const FcWidePlan &pl, int mode, const void *x, const void *w, const void *w2,
+                                 const void *res, int M, int K, int N, void *out, void *workspace, hipStream_t s)
+{
+    if (pl.kind != 1 || (pl.ksplit > 1 && !workspace)) return hipErrorInvalidValue;
+    GemmArgs a;
+    memset(&a, 0, sizeof a);
+    a.X = (const uint16_t *)x;
+    a.W = (const uint16_t *)w;
+    a.W2 = (const uint16_t *)w2;
+    a.res = (const uint16_t *)res;
+    a.out = (uint16_t *)out;
+    a.part = (float *)workspace;
+    a.M = M;
+    a.A = M;
+    a.K = K;
+    a.N = N;
+    a.n_slots = mode == FC_LIN_GATE_UP ? N / 64 : N / 128;
+    a.ksplit = pl.ksplit;
+    if (mode == FC_LIN_GATE_UP) return launch_wide_shape<2>(pl.shape, a, s);
+    if (pl.ksplit <= 1) return launch_wide_shape<1>(pl.shape, a, s);
+    hipError_t e = launch_wide_shape<3>(pl.shape, a, s);
+    if (e != hipSuccess) return e;
+    const size_t quads = (size_t)M * N / 4;
+    k_splitk_finish<<<dim3((unsigned)((quads + 255) / 256)), dim3(256), 0, s>>>((const float *)workspace, a.res, a.out,
+                                                                                  quads, (size_t)M * N, pl.ksplit);
+    return hipGetLastError();
+}
 
 bool fc_project_gemm_supported(const fc_config &cfg, int M)
 {
@@ -415,6 +590,12 @@ hipError_t fc_launch_project_gemm(const FcGeom &G, const void *x, const void *w,
     a.K = G.d;
     a.win_start = win_start;
     a.n_mt = a.n_units = 0;
+    a.n_slots = G.Hq + 2 * G.Hkv;
+    a.W2 = a.res = nullptr;
+    a.out = nullptr;
+    a.part = nullptr;
+    a.N = 0;
+    a.ksplit = 1;
     a.log2_base_64 = G.log_base * 1.4426950408889634074 / 64.0;
 #ifdef FC_GEMM_TUNE
     a.flags = getenv("FC_GEMM_FLAGS") ? atoi(getenv("FC_GEMM_FLAGS")) : 0;

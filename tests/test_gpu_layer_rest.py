@@ -105,6 +105,73 @@ def test_ffn_gate_up_matches_oracle(dtype, M, K, F):
     assert_close(inputs.as_oracle(out), ref, dtype, "ffn_gate_up")
 
 
+@pytest.mark.parametrize("shape", ["0", "1", "2"])
+@pytest.mark.parametrize("ksplit", ["1", "3"])
+def test_linear_residual_wide_window_tile_shapes(shape, ksplit, monkeypatch):
+    # more than 32 rows: tiled GEMM, every tile shape, with and without a split of the hidden dimension;
+    # ragged row count, an odd number of 128-row slabs
+    monkeypatch.setenv("FC_LIN_WIDE_SHAPE", shape)
+    monkeypatch.setenv("FC_LIN_KSPLIT", ksplit)
+    M, K, N = 200, 1024, 384
+    x = inputs.normal(12, "x", (M, K), 1.0, "bf16")
+    w = inputs.normal(12, "w", (N, K), 0.05, "bf16")
+    r = inputs.normal(12, "r", (M, N), 1.0, "bf16")
+    ref = orc.linear_residual(inputs.as_oracle(x), inputs.as_oracle(w), inputs.as_oracle(r), "bf16")
+    need = fc.fc_linear_workspace_bytes("bf16", M, K, N)
+    assert (need > 0) == (ksplit != "1")
+    ws = _ws(need)
+    rd = _dev(r)
+    out = torch.full((M, N), float("nan"), dtype=torch.bfloat16, device=DEV)
+    fc.fc_linear_residual("bf16", _dev(x), _dev(w), rd, M, K, N, out, ws, need)
+    torch.cuda.synchronize()
+    assert_close(inputs.as_oracle(out), ref, "bf16", "wide linear_residual shape %s ksplit %s" % (shape, ksplit))
+    fc.fc_linear_residual("bf16", _dev(x), _dev(w), rd, M, K, N, rd, ws, need)  # in place
+    torch.cuda.synchronize()
+    assert torch.equal(rd, out)
+
+
+@pytest.mark.parametrize("shape", ["0", "1", "2"])
+def test_ffn_gate_up_wide_window_tile_shapes(shape, monkeypatch):
+    monkeypatch.setenv("FC_LIN_WIDE_SHAPE", shape)
+    M, K, F = 100, 1024, 320
+    x = inputs.normal(13, "x", (M, K), 1.0, "bf16")
+    wg = inputs.normal(13, "wg", (F, K), 0.05, "bf16")
+    wu = inputs.normal(13, "wu", (F, K), 0.05, "bf16")
+    ref = orc.ffn_gate_up(inputs.as_oracle(x), inputs.as_oracle(wg), inputs.as_oracle(wu), "bf16")
+    need = fc.fc_linear_workspace_bytes("bf16", M, K, 2 * F)
+    ws = _ws(need)
+    out = torch.full((M, F), float("nan"), dtype=torch.bfloat16, device=DEV)
+    fc.fc_ffn_gate_up("bf16", _dev(x), _dev(wg), _dev(wu), M, K, F, out, ws, need)
+    torch.cuda.synchronize()
+    assert_close(inputs.as_oracle(out), ref, "bf16", "wide ffn_gate_up shape " + shape)
+
+
+def test_linear_calls_default_plan_at_block_widths():
+    # the shapes of a 256-row block at the 7B widths, default plan: W_out and W_2 (28 slabs: hidden
+    # dimension split), gated W_1 (296 slabs); rows sampled for the oracle
+    M = 256
+    for K, N, gated in ((3584, 3584, False), (18944, 3584, False), (3584, 18944, True)):
+        x = inputs.normal(14, "x%d" % K, (M, K), 1.0, "bf16")
+        w = inputs.normal(14, "w%d%d" % (K, N), (N, K), 0.02, "bf16")
+        rows = [0, 31, 32, 127, 128, 200, 255]
+        xo, wo = inputs.as_oracle(x)[rows], inputs.as_oracle(w)
+        need = fc.fc_linear_workspace_bytes("bf16", M, K, 2 * N if gated else N)
+        ws = _ws(need)
+        out = torch.full((M, N), float("nan"), dtype=torch.bfloat16, device=DEV)
+        if gated:
+            wu = inputs.normal(14, "wu", (N, K), 0.02, "bf16")
+            fc.fc_ffn_gate_up("bf16", _dev(x), _dev(w), _dev(wu), M, K, N, out, ws, need)
+            ref = orc.ffn_gate_up(xo, wo, inputs.as_oracle(wu), "bf16")
+        else:
+            r = inputs.normal(14, "r", (M, N), 1.0, "bf16")
+            fc.fc_linear_residual("bf16", _dev(x), _dev(w), _dev(r), M, K, N, out, ws, need)
+            ref = orc.linear_residual(xo, wo, inputs.as_oracle(r)[rows], "bf16")
+        torch.cuda.synchronize()
+        got = inputs.as_oracle(out)
+        assert np.all(np.isfinite(got))
+        assert_close(got[rows], ref, "bf16", "block-width linear K=%d N=%d" % (K, N))
+
+
 class FullLayer:
     """One layer's weights on the GPU and on the oracle side."""
 
@@ -247,6 +314,7 @@ def test_full_layer_step_streaming_kernels_bf16():
     w = inputs.Workload("narrow", "bf16", 1, 512, 4, 2, 128, 0, 0, d_ff=1024)
     _run_full_layer(w, 300, 32, seed=7, std=0.04)
     _run_full_layer(w.scaled(batch=2), 130, 16, seed=8, pad=True, std=0.04)
+    _run_full_layer(w.scaled(batch=3), 90, 40, seed=10, pad=True, std=0.04)   # 120 rows: tiled GEMM everywhere
 
 
 def test_full_layer_step_dream7b_geometry():
