@@ -1,7 +1,7 @@
 """Benchmark of the FreeCache cached denoising layer-step on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c4|c2|c3|c5|c5_refresh|c4_layer|c2_layer]
-                    [--layers N]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--layers N]
+                    [--workload c4|c2|c3|c5|c5_refresh|c4_layer|c2_layer|c3_layer|c5_layer|c5_refresh_layer]
 
 A "step" is one pass of the whole hot path for one layer: QKV projection + RoPE + scatter of the
 active window, then attention of the window's queries over the cache.  The default workload is the
@@ -16,9 +16,10 @@ same loop on a single layer is reported as `single_cache_us` (cache-resident fig
 `--workload c5_refresh` times the periodic refresh of configuration 5 instead (one `fc_refresh` of the
 256-row generation region of 8 sequences per step: a dense, matrix-core-bound pass).
 
-`--workload c4_layer` / `c2_layer` time the whole transformer layer on the window rows instead (RMSNorm,
-the path above, output projection + residual, RMSNorm, gated feed-forward network + residual: one
-`fc_full_layer_step` per step, Dream-7B widths), the next row after the attention path.
+`--workload <c>_layer` time the whole transformer layer on the window rows instead (RMSNorm, the path
+above, output projection + residual, RMSNorm, gated feed-forward network + residual: one
+`fc_full_layer_step` per step), the next row after the attention path; `c5_refresh_layer` does so for
+the 256-row refresh of 8 sequences (2048 rows).
 
 Prints ONE JSON line (see the fields below).  Inputs are seeded and synthetic.
 """
@@ -51,7 +52,8 @@ def _parse():
     ap.add_argument("--steps", type=int, default=100)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="c4",
-                    choices=["c2", "c3", "c4", "c5", "c5_refresh", "c4_layer", "c2_layer"])
+                    choices=["c2", "c3", "c4", "c5", "c5_refresh", "c4_layer", "c2_layer", "c3_layer", "c5_layer",
+                             "c5_refresh_layer"])
     ap.add_argument("--layers", type=int, default=0, help="distinct layer caches to rotate over (0 = auto)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-single", action="store_true",
@@ -256,9 +258,11 @@ def main():
 
 def main_layer(args, torch, fc, inputs, dev):
     """Whole-layer workloads: one fc_full_layer_step per step, rotating over distinct layers."""
-    w = {"c4_layer": inputs.C4, "c2_layer": inputs.C2}[args.workload]
+    w = {"c4_layer": inputs.C4, "c2_layer": inputs.C2, "c3_layer": inputs.C3, "c5_layer": inputs.C5,
+         "c5_refresh_layer": inputs.C5}[args.workload]
+    refresh = args.workload == "c5_refresh_layer"
     B, Dh, Hq, Hkv, d, F = w.batch, w.head_dim, w.n_q_heads, w.n_kv_heads, w.hidden, w.d_ff
-    A, S, E, esz = w.active, w.kv_len, w.n_q_heads * w.head_dim, 2
+    A, S, E, esz = (w.gen_len if refresh else w.active), w.kv_len, w.n_q_heads * w.head_dim, 2
     M = B * A
     tdt = inputs.TORCH_DTYPE[w.dtype]
     w_bytes = {"w_qkv": w.qkv_width * d * esz, "w_out": d * E * esz, "gate_up": 2 * F * d * esz, "w_down": d * F * esz}
@@ -289,7 +293,7 @@ def main_layer(args, torch, fc, inputs, dev):
     n_x = 8
     Xs = [inputs.hidden_states(w, 0, A, tag="x.%d" % i).to(dev) for i in range(n_x)]
     Y = torch.empty((B, A, d), dtype=tdt, device=dev)
-    if w.gen_len:
+    if w.gen_len and not refresh:
         n_sched = -(-w.gen_len // w.block) * w.steps_per_block
         sched = [fc.fc_window(s, w.cached_len, w.gen_len, w.block, w.steps_per_block)[0] for s in range(n_sched)]
     else:
@@ -348,25 +352,38 @@ def main_layer(args, torch, fc, inputs, dev):
 
     total_w = sum(w_bytes.values())
     flops = 2.0 * M * (d * w.qkv_width + E * d + 3 * d * F) + 4.0 * M * Hq * S * Dh
+    gate_flops = 4.0 * M * d * F
     gbs = lambda nbytes, us: round(nbytes / us * 1e-3, 1)
+    # the gated W_1 is the longest call: bound by the weight stream for a block of rows, by the matrix
+    # cores for a refresh of thousands of rows
+    if M >= 1024:
+        roof = {"kernel": "fc_ffn_gate_up (k_proj_gemm, SiLU-gate epilogue)", "bound": "mfma",
+                "achieved": round(gate_flops / us_gate * 1e-6, 1), "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                "frac": round(gate_flops / us_gate * 1e-6 / MFMA_BF16_PEAK_TFLOPS, 4), "traffic": None,
+                "algorithmic_flops_per_launch": gate_flops, "us_per_launch": round(us_gate, 3)}
+    else:
+        roof = {"kernel": "fc_ffn_gate_up (%s)" % ("k_linear_stream + k_linear_finish" if M <= 32 else
+                                                   "k_proj_gemm, SiLU-gate epilogue"), "bound": "hbm",
+                "achieved": gbs(w_bytes["gate_up"], us_gate), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": round(w_bytes["gate_up"] / us_gate * 1e-3 / HBM_PEAK_GBS, 4), "traffic": None,
+                "algorithmic_bytes_per_launch": w_bytes["gate_up"] + M * (d + F) * esz,
+                "us_per_launch": round(us_gate, 3), "tflops": round(gate_flops / us_gate * 1e-6, 1)}
     out = {
         "metric": "us per cached denoising step of one whole transformer layer on the window rows",
         "value": round(us_step, 3), "unit": "us", "n_gpus": 1, "steps": steps, "warmup": min(args.warmup, 2 * n_layers),
         "ms_per_step": round(us_step / 1000.0, 6), "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
         "dtype": w.dtype, "data": "synthetic",
-        "config": {"workload": w.name + "/whole-layer", "batch": B, "hidden": d, "d_ff": F, "n_q_heads": Hq,
+        "config": {"workload": w.name + ("/refresh" if refresh else "") + "/whole-layer", "batch": B, "hidden": d, "d_ff": F, "n_q_heads": Hq,
                    "n_kv_heads": Hkv, "head_dim": Dh, "kv_len": S, "active_rows": A, "layers_rotated": n_layers,
                    "weight_bytes_per_layer": total_w, "kv_bytes_per_layer": kv_bytes_layer},
-        "roofline": {
-            "kernel": "fc_ffn_gate_up (k_linear_stream + k_linear_finish)", "bound": "hbm",
-            "achieved": gbs(w_bytes["gate_up"], us_gate), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-            "frac": round(w_bytes["gate_up"] / us_gate * 1e-3 / HBM_PEAK_GBS, 4), "traffic": None,
-            "algorithmic_bytes_per_launch": w_bytes["gate_up"] + M * (d + F) * esz, "us_per_launch": round(us_gate, 3),
-        },
+        "roofline": roof,
         "linear_calls": {
-            "w_out": {"us_per_launch": round(us_out, 3), "weight_stream_gbs": gbs(w_bytes["w_out"], us_out)},
-            "gate_up": {"us_per_launch": round(us_gate, 3), "weight_stream_gbs": gbs(w_bytes["gate_up"], us_gate)},
-            "w_down": {"us_per_launch": round(us_down, 3), "weight_stream_gbs": gbs(w_bytes["w_down"], us_down)},
+            "w_out": {"us_per_launch": round(us_out, 3), "weight_stream_gbs": gbs(w_bytes["w_out"], us_out),
+                      "tflops": round(2.0 * M * E * d / us_out * 1e-6, 1)},
+            "gate_up": {"us_per_launch": round(us_gate, 3), "weight_stream_gbs": gbs(w_bytes["gate_up"], us_gate),
+                        "tflops": round(gate_flops / us_gate * 1e-6, 1)},
+            "w_down": {"us_per_launch": round(us_down, 3), "weight_stream_gbs": gbs(w_bytes["w_down"], us_down),
+                       "tflops": round(2.0 * M * F * d / us_down * 1e-6, 1)},
         },
         "layer_stream_gbs": gbs(total_w + kv_bytes_layer, us_step),
         "layer_frac_of_hbm_peak": round((total_w + kv_bytes_layer) / us_step * 1e-3 / HBM_PEAK_GBS, 4),
@@ -377,19 +394,26 @@ def main_layer(args, torch, fc, inputs, dev):
     if not args.no_cpu_baseline:
         import numpy as np
         from oracle import fc_oracle as orc
-        ocfg = orc.OracleConfig(B, d, Hq, Hkv, Dh, S, w.dtype, w.rope_base)
-        Kc, Vc = inputs.as_oracle(K0).copy(), inputs.as_oracle(V0).copy()
+        # bounded sample: the first sequence of the batch and at most 32 of its window rows (the layer is
+        # row-wise apart from attention, whose cost per row does not depend on the row count); the value
+        # is the sample's time scaled to all B * A rows
+        As = min(A, 32)
+        ocfg = orc.OracleConfig(1, d, Hq, Hkv, Dh, S, w.dtype, w.rope_base)
+        Kc, Vc = inputs.as_oracle(K0)[:1].copy(), inputs.as_oracle(V0)[:1].copy()
         wts = {k: (None if v is None else inputs.as_oracle(v)) for k, v in host.items()}
-        pos = inputs.as_oracle(inputs.window_positions(B, w.cached_len, A))
-        X = inputs.as_oracle(inputs.hidden_states(w, 0, A, tag="x.0"))
+        pos = inputs.as_oracle(inputs.window_positions(1, w.cached_len, As))
+        X = inputs.as_oracle(inputs.hidden_states(w, 0, A, tag="x.0"))[:1, :As].copy()
         n_sample, dt = 0, 0.0
         while n_sample < 20 and dt < 12.0:
             t0 = time.perf_counter()
             orc.full_layer_step(ocfg, X, wts, pos, S, Kc, Vc, w.norm_eps)
             dt += time.perf_counter() - t0
             n_sample += 1
-        out["cpu_baseline"] = {"value": round(dt * 1e6 / n_sample, 1), "unit": "us", "cores": orc.get_threads(),
-                               "kind": "oracle", "sample": "%d whole-layer step(s) of %s, fp64, OpenMP" % (n_sample, w.name)}
+        scale = M / float(As)
+        out["cpu_baseline"] = {"value": round(dt * 1e6 / n_sample * scale, 1), "unit": "us", "cores": orc.get_threads(),
+                               "kind": "oracle",
+                               "sample": "%d whole-layer step(s) of %d row(s) of one sequence of %s, fp64, OpenMP; "
+                                         "scaled by %g to the %d rows of a step" % (n_sample, As, w.name, scale, M)}
         del np
     torch.cuda.synchronize()
     fc.fc_cache_free(cache)
