@@ -394,3 +394,83 @@ int fco_full_layer_step(const fco_config *c, int32_t A, const float *X, const fc
     free(act);
     return rc;
 }
+
+/* -------------------------------------------------------------------------
+ * Unmasking step of a diffusion language model on the window rows (paper, section 3.1, the three
+ * equations that define M_t, z_t and the arg-max fill of the selected positions U_t; section 3.2.1
+ * for the window the rows come from).
+ */
+
+/* Vocabulary projection of M rows and, per row, the arg-max token and its softmax probability:
+ *   z[m][v] = sum_k X[m][k] Wv[v][k]          (double, never rounded)
+ *   tok[m]  = the smallest v with z[m][v] = max_v z[m][v]
+ *   conf[m] = softmax(z[m])[tok[m]] = 1 / sum_v exp(z[m][v] - z[m][tok[m]])
+ * logits (optional, [M][V] doubles) receives z. */
+int fco_lm_head_argmax(const float *X, const float *Wv, int64_t M, int32_t K, int32_t V,
+                       int32_t *tok, double *conf, double *logits)
+{
+    if (!X || !Wv || !tok || !conf || M < 1 || K < 1 || V < 1) return 1;
+#pragma omp parallel for schedule(static)
+    for (int64_t m = 0; m < M; ++m) {
+        const float *x = X + (size_t)m * K;
+        double *z = (double *)malloc(sizeof(double) * (size_t)V);
+        int best = 0;
+        for (int v = 0; v < V; ++v) {
+            const float *w = Wv + (size_t)v * K;
+            double acc = 0.0;
+            for (int k = 0; k < K; ++k) acc += (double)x[k] * (double)w[k];
+            z[v] = acc;
+            if (acc > z[best]) best = v;
+        }
+        double sum = 0.0;
+        for (int v = 0; v < V; ++v) sum += exp(z[v] - z[best]);
+        tok[m] = best;
+        conf[m] = 1.0 / sum;
+        if (logits) memcpy(logits + (size_t)m * V, z, sizeof(double) * (size_t)V);
+        free(z);
+    }
+    return 0;
+}
+
+/* Confidence-ranked unmasking of one step.  For every sequence b the candidates are the window
+ * rows a with pos[b][a] >= 0 whose token is still the mask (tokens[b][pos[b][a]] == mask_id: the
+ * set M_t restricted to the window).  The n_unmask candidates with the largest confidence (ties:
+ * the smaller a first) form U_t and receive their arg-max token; all of them if fewer remain.
+ * pos_next[b][.] lists the positions of the window rows that are still masked afterwards, in row
+ * order, padded with -1; count_next[b] is their number.
+ * tokens [B][L] is updated in place.  Returns 2 if a position is >= L. */
+int fco_unmask_select(const int32_t *tok, const double *conf, const int32_t *pos, int32_t B, int32_t A,
+                      int32_t n_unmask, int32_t mask_id, int32_t *tokens, int32_t L, int32_t *pos_next,
+                      int32_t *count_next)
+{
+    if (!tok || !conf || !pos || !tokens || !pos_next || !count_next || B < 1 || A < 1 || L < 1 || n_unmask < 0)
+        return 1;
+    for (int64_t i = 0; i < (int64_t)B * A; ++i)
+        if (pos[i] >= L) return 2;
+    for (int b = 0; b < B; ++b) {
+        const int32_t *p = pos + (size_t)b * A;
+        int32_t *seq = tokens + (size_t)b * L;
+        char *cand = (char *)calloc((size_t)A, 1);
+        int n_cand = 0;
+        for (int a = 0; a < A; ++a)
+            if (p[a] >= 0 && seq[p[a]] == mask_id) {
+                cand[a] = 1;
+                ++n_cand;
+            }
+        int take = n_unmask < n_cand ? n_unmask : n_cand;
+        while (take-- > 0) { /* repeated selection of the best remaining candidate */
+            int best = -1;
+            for (int a = 0; a < A; ++a)
+                if (cand[a] && (best < 0 || conf[(size_t)b * A + a] > conf[(size_t)b * A + best])) best = a;
+            cand[best] = 0;
+            seq[p[best]] = tok[(size_t)b * A + best];
+        }
+        int n = 0;
+        for (int a = 0; a < A; ++a)
+            if (cand[a]) pos_next[(size_t)b * A + n++] = p[a];
+        count_next[b] = n;
+        for (; n < A; ++n) pos_next[(size_t)b * A + n] = -1;
+        free(cand);
+    }
+    return 0;
+}

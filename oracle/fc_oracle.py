@@ -67,7 +67,8 @@ def lib():
         L.fco_round_to_storage.argtypes = [ctypes.c_double, ctypes.c_int32]
         L.fco_round_array.restype = None
         for name in ("fco_project_rope", "fco_scatter", "fco_attend", "fco_layer_step", "fco_window",
-                     "fco_rmsnorm", "fco_linear_residual", "fco_ffn_gate_up", "fco_full_layer_step"):
+                     "fco_rmsnorm", "fco_linear_residual", "fco_ffn_gate_up", "fco_full_layer_step",
+                     "fco_lm_head_argmax", "fco_unmask_select"):
             getattr(L, name).restype = ctypes.c_int
         _lib = L
     return _lib
@@ -300,3 +301,42 @@ def full_layer_step(cfg: OracleConfig, X, weights: dict, pos, kv_len, Kc, Vc, ep
                                    _p(Y, ctypes.c_float), _p(X2, ctypes.c_float))
     _check(rc, "fco_full_layer_step")
     return (Y, X2) if want_x2 else Y
+
+
+# --- unmasking step on the window rows (section 3.1: M_t, z_t, arg-max fill of U_t) ---------------
+
+def lm_head_argmax(X, Wv, want_logits=False):
+    """Vocabulary projection of X [M, K] with Wv [V, K]: (tok int32 [M], conf float64 [M]) (+ logits)."""
+    X, Wv = _f32(X), _f32(Wv)
+    M, K = X.shape
+    V = Wv.shape[0]
+    assert Wv.shape == (V, K)
+    tok = np.empty((M,), np.int32)
+    conf = np.empty((M,), np.float64)
+    logits = np.empty((M, V), np.float64) if want_logits else None
+    rc = lib().fco_lm_head_argmax(_p(X, ctypes.c_float), _p(Wv, ctypes.c_float), ctypes.c_int64(M),
+                                  ctypes.c_int32(K), ctypes.c_int32(V), _p(tok, ctypes.c_int32),
+                                  _p(conf, ctypes.c_double), _p(logits, ctypes.c_double))
+    _check(rc, "fco_lm_head_argmax")
+    return (tok, conf, logits) if want_logits else (tok, conf)
+
+
+def unmask_select(tok, conf, pos, n_unmask, mask_id, tokens):
+    """One confidence-ranked unmasking step; tokens [B, L] int32 updated in place.
+    Returns (pos_next [B, A] int32 padded with -1, count_next [B] int32)."""
+    pos = np.ascontiguousarray(pos, dtype=np.int32)
+    B, A = pos.shape
+    tok = np.ascontiguousarray(tok, dtype=np.int32).reshape(B, A)
+    conf = np.ascontiguousarray(conf, dtype=np.float64).reshape(B, A)
+    assert tokens.dtype == np.int32 and tokens.flags.c_contiguous and tokens.shape[0] == B
+    L = tokens.shape[1]
+    pos_next = np.empty((B, A), np.int32)
+    count = np.empty((B,), np.int32)
+    rc = lib().fco_unmask_select(_p(tok, ctypes.c_int32), _p(conf, ctypes.c_double), _p(pos, ctypes.c_int32),
+                                 ctypes.c_int32(B), ctypes.c_int32(A), ctypes.c_int32(n_unmask),
+                                 ctypes.c_int32(mask_id), _p(tokens, ctypes.c_int32), ctypes.c_int32(L),
+                                 _p(pos_next, ctypes.c_int32), _p(count, ctypes.c_int32))
+    if rc == 2:
+        raise IndexError("position beyond the sequence")
+    _check(rc, "fco_unmask_select")
+    return pos_next, count

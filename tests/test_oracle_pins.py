@@ -570,3 +570,115 @@ def test_full_layer_cached_step_equals_window_rows_of_full_recompute():
     # and with the feed-forward output matrix zeroed too the layer is the identity on the residual stream
     z["w_down"] = np.zeros_like(wts["w_down"])
     assert np.array_equal(orc.full_layer_step(cfg, X[:, L:], z, _pos(1, L, S - L), S, Ka, Va, 1e-6), X[:, L:])
+
+
+# --------------------------------------------------------------------------- unmasking step
+
+def test_lm_head_argmax_matches_library_softmax_and_closed_forms():
+    X, W = _rand(80, (9, 24)), _rand(81, (50, 24), 0.7)
+    tok, conf, z = orc.lm_head_argmax(X, W, want_logits=True)
+    zt = torch.from_numpy(X).double() @ torch.from_numpy(W).double().T
+    assert np.allclose(z, zt.numpy(), atol=1e-12)
+    p = torch.softmax(zt, dim=-1)
+    assert np.array_equal(tok, p.argmax(dim=-1).numpy().astype(np.int32))
+    assert np.allclose(conf, p.max(dim=-1).values.numpy(), rtol=1e-12)
+    # one-hot rows against an identity vocabulary: token = the hot index, conf = e^c / (e^c + V - 1)
+    V, c = 7, 3.0
+    t2, c2 = orc.lm_head_argmax(np.eye(V, dtype=np.float32)[[4, 0, 6]] * c, np.eye(V, dtype=np.float32))
+    assert list(t2) == [4, 0, 6] and np.allclose(c2, math.exp(c) / (math.exp(c) + V - 1), rtol=1e-12)
+    # a zero row: all logits equal -> the smallest index wins, conf = 1 / V
+    t3, c3 = orc.lm_head_argmax(np.zeros((1, 24), np.float32), W)
+    assert t3[0] == 0 and abs(c3[0] - 1.0 / 50) < 1e-15
+    # duplicated vocabulary rows tie exactly: the smaller index is returned
+    other = 37 if int(tok[0]) != 37 else 36
+    W3 = W.copy()
+    W3[other] = W[int(tok[0])]
+    assert orc.lm_head_argmax(X[:1], W3)[0][0] == min(other, int(tok[0]))
+    # a large common offset in the logits changes nothing (softmax is shift invariant, no overflow)
+    Xb = np.concatenate([X, np.full((9, 1), 1.0, np.float32)], axis=1)
+    Wb = np.concatenate([W, np.full((50, 1), 900.0, np.float32)], axis=1)
+    t4, c4 = orc.lm_head_argmax(Xb, Wb)
+    assert np.array_equal(t4, tok) and np.allclose(c4, conf, rtol=1e-9)
+
+
+def _select_reference(tok, conf, pos, k, mask_id, tokens):
+    """Plain-Python restatement: sort the masked window rows by (-confidence, row) and fill the first k."""
+    B, A = pos.shape
+    tokens = tokens.copy()
+    nxt = np.full((B, A), -1, np.int32)
+    cnt = np.zeros((B,), np.int32)
+    for b in range(B):
+        cand = [a for a in range(A) if pos[b, a] >= 0 and tokens[b, pos[b, a]] == mask_id]
+        chosen = sorted(cand, key=lambda a: (-conf[b, a], a))[:k]
+        for a in chosen:
+            tokens[b, pos[b, a]] = tok[b, a]
+        rest = [a for a in cand if a not in chosen]
+        nxt[b, :len(rest)] = [pos[b, a] for a in rest]
+        cnt[b] = len(rest)
+    return tokens, nxt, cnt
+
+
+def test_unmask_select_worked_example_and_brute_force():
+    MASK = 99
+    # one sequence of 10 tokens, window rows at positions 4..9, of which 5, 6, 8, 9 are masked
+    tokens = np.array([[1, 2, 3, 4, 10, MASK, MASK, 11, MASK, MASK]], np.int32)
+    pos = np.array([[4, 5, 6, 7, 8, 9]], np.int32)
+    tok = np.array([[50, 51, 52, 53, 54, 55]], np.int32)
+    conf = np.array([[0.99, 0.2, 0.9, 0.95, 0.9, 0.1]])
+    t = tokens.copy()
+    nxt, cnt = orc.unmask_select(tok, conf, pos, 2, MASK, t)
+    # candidates: rows 1 (0.2), 2 (0.9), 4 (0.9), 5 (0.1); the tie at 0.9 goes to the smaller row: rows 2, 4
+    assert list(t[0]) == [1, 2, 3, 4, 10, MASK, 52, 11, 54, MASK]
+    assert list(nxt[0]) == [5, 9, -1, -1, -1, -1] and cnt[0] == 2
+    # unmasked rows with high confidence (row 0, row 3) are never touched; k = 0 changes nothing
+    t0 = tokens.copy()
+    nxt0, cnt0 = orc.unmask_select(tok, conf, pos, 0, MASK, t0)
+    assert np.array_equal(t0, tokens) and list(nxt0[0]) == [5, 6, 8, 9, -1, -1] and cnt0[0] == 4
+    # k beyond the candidates: all of them
+    t9 = tokens.copy()
+    nxt9, cnt9 = orc.unmask_select(tok, conf, pos, 9, MASK, t9)
+    assert list(t9[0]) == [1, 2, 3, 4, 10, 51, 52, 11, 54, 55] and cnt9[0] == 0 and np.all(nxt9 == -1)
+
+    rng = np.random.default_rng(5)
+    for trial in range(40):
+        B, A, L = int(rng.integers(1, 4)), int(rng.integers(1, 20)), 40
+        pos = np.stack([np.sort(rng.choice(L, A, replace=False)) for _ in range(B)]).astype(np.int32)
+        pos[rng.random((B, A)) < 0.15] = -1                      # padded rows
+        tokens = rng.integers(0, 50, (B, L)).astype(np.int32)
+        tokens[rng.random((B, L)) < 0.6] = MASK
+        tok = rng.integers(0, 50, (B, A)).astype(np.int32)
+        conf = np.round(rng.random((B, A)), 1)                   # coarse values: many ties
+        k = int(rng.integers(0, 6))
+        want_t, want_n, want_c = _select_reference(tok, conf, pos, k, MASK, tokens)
+        got_t = tokens.copy()
+        got_n, got_c = orc.unmask_select(tok, conf, pos, k, MASK, got_t)
+        assert np.array_equal(got_t, want_t) and np.array_equal(got_n, want_n) and np.array_equal(got_c, want_c)
+        # invariants: only masked window positions change; min(k, candidates) of them per sequence
+        changed = got_t != tokens
+        for b in range(B):
+            win = set(int(p) for p in pos[b] if p >= 0)
+            assert all(tokens[b, i] == MASK and i in win for i in np.nonzero(changed[b])[0])
+            n_cand = sum(1 for p in win if tokens[b, p] == MASK)
+            # a filled position may receive the mask id's value only if tok says so; count by selection instead
+            assert got_c[b] == n_cand - min(k, n_cand)
+    with pytest.raises(IndexError):
+        orc.unmask_select(tok[:1, :1], conf[:1, :1], np.array([[40]], np.int32), 1, MASK, tokens[:1].copy())
+
+
+def test_unmask_steps_terminate_and_fill_every_masked_window_position():
+    MASK, A, k = -7, 13, 3
+    tokens = np.full((2, 20), MASK, np.int32)
+    tokens[:, :5] = 1
+    pos = np.tile(np.arange(5, 5 + A, dtype=np.int32), (2, 1))
+    rng = np.random.default_rng(9)
+    steps = 0
+    cur = pos.copy()
+    while True:
+        tok = rng.integers(0, 100, (2, A)).astype(np.int32)
+        conf = rng.random((2, A))
+        cur, cnt = orc.unmask_select(tok, conf, cur, k, MASK, tokens)
+        steps += 1
+        assert np.all(cnt == max(0, A - k * steps))
+        if np.all(cnt == 0):
+            break
+    assert steps == -(-A // k) and not np.any(tokens[:, 5:5 + A] == MASK) and np.all(tokens[:, 18:] == MASK)
