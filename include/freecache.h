@@ -241,6 +241,42 @@ fc_status fc_full_layer_step(fc_cache *cache, int32_t layer, const fc_layer_weig
                              int32_t kv_len, void *y, void *workspace, size_t workspace_bytes,
                              void *stream);
 
+/* ---------------------------------------------------------------------------------------------
+ * Unmasking step on the window rows (section 3.1: the masked set M_t = {i : x_t[i] = MASK}, the
+ * logits z_t of the masked positions, and the fill x_{t-1}[i] = argmax_v softmax(z_t[i]) of a subset
+ * U_t of M_t "selected e.g. by confidence"; with FreeCache only the rows of the active window are
+ * evaluated).  The library's reading: confidence = the softmax probability of the arg-max token;
+ * U_t = the n most confident masked window positions of each sequence.
+ */
+
+/* Workspace bytes of fc_lm_head_argmax for this shape; 0 on bad arguments. */
+size_t fc_lm_head_workspace_bytes(int32_t dtype, int32_t M, int32_t K, int32_t V);
+
+/* Vocabulary projection of M rows without materialising the logits:
+ *   z[m][v] = sum_k x[m][k] w_vocab[v][k] (fp32),  tok[m] = argmax_v z[m][v] (smallest v on ties),
+ *   conf[m] = softmax(z[m])[tok[m]] = 1 / sum_v exp(z[m][v] - z[m][tok[m]]).
+ *   x  device [M][K];  w_vocab  device [V][K] (element type dtype);  tok  device int32 [M];
+ *   conf  device float [M];  workspace  device, >= fc_lm_head_workspace_bytes(dtype, M, K, V) bytes.
+ * Errors: INVALID_ARG, UNSUPPORTED (K not a multiple of 8), WORKSPACE, HIP. */
+fc_status fc_lm_head_argmax(int32_t dtype, const void *x, const void *w_vocab, int32_t M, int32_t K,
+                            int32_t V, int32_t *tok, float *conf, void *workspace, size_t workspace_bytes,
+                            void *stream);
+
+/* One confidence-ranked unmasking step.  For every sequence b the candidates are the window rows a
+ * whose position p = pos[b][a] (or win_start + a when pos is NULL) satisfies 0 <= p < L and
+ * tokens[b][p] == mask_id.  The n_unmask candidates with the largest conf (ties: smaller a first; all
+ * of them if fewer remain) get tokens[b][p] = tok[b][a].  pos_next[b][.] receives the positions of the
+ * candidates that stay masked, in row order, padded with -1 (it is a valid `pos` argument of the
+ * next step's calls), count_next[b] their number.
+ *   tok  device int32 [B][A];  conf  device float [B][A], values >= 0;  pos  device int32 [B][A] or NULL;
+ *   tokens  device int32 [B][L], updated in place;  pos_next  device int32 [B][A] (not pos itself);
+ *   count_next  device int32 [B].  A is limited to 8192 rows.  Duplicate positions are undefined.
+ * Integer work: bit-exact.  Errors: INVALID_ARG, UNSUPPORTED (A too large), BOUNDS (pos NULL and
+ * win_start < 0 or win_start + A > L), HIP. */
+fc_status fc_unmask_select(const int32_t *tok, const float *conf, const int32_t *pos, int32_t win_start,
+                           int32_t B, int32_t A, int32_t n_unmask, int32_t mask_id, int32_t *tokens,
+                           int32_t L, int32_t *pos_next, int32_t *count_next, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

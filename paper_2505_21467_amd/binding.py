@@ -23,6 +23,7 @@ EXPORTS = (
     "fc_workspace_bytes", "fc_active_attention", "fc_refresh",
     "fc_rmsnorm", "fc_linear_workspace_bytes", "fc_linear_residual", "fc_ffn_gate_up",
     "fc_full_layer_workspace_bytes", "fc_full_layer_step",
+    "fc_lm_head_workspace_bytes", "fc_lm_head_argmax", "fc_unmask_select",
 )
 
 
@@ -96,6 +97,12 @@ def lib():
         L.fc_full_layer_step.restype = ctypes.c_int
         L.fc_full_layer_step.argtypes = [vp, i32, ctypes.POINTER(fc_layer_weights), vp, i32, i32, vp, i32, vp,
                                          vp, sz, vp]
+        L.fc_lm_head_workspace_bytes.restype = sz
+        L.fc_lm_head_workspace_bytes.argtypes = [i32, i32, i32, i32]
+        L.fc_lm_head_argmax.restype = ctypes.c_int
+        L.fc_lm_head_argmax.argtypes = [i32, vp, vp, i32, i32, i32, vp, vp, vp, sz, vp]
+        L.fc_unmask_select.restype = ctypes.c_int
+        L.fc_unmask_select.argtypes = [vp, vp, vp, i32, i32, i32, i32, i32, vp, i32, vp, vp, vp]
         _lib = L
     return _lib
 
@@ -237,3 +244,20 @@ def fc_full_layer_step(cache, layer, weights: fc_layer_weights, x, win_start, A,
         workspace_bytes = _nbytes(workspace)
     _check(lib().fc_full_layer_step(cache, layer, ctypes.byref(weights), _ptr(x), win_start, A, _ptr(pos),
                                     kv_len, _ptr(y), _ptr(workspace), workspace_bytes, _stream(stream)))
+
+
+def fc_lm_head_workspace_bytes(dtype, M, K, V) -> int:
+    return int(lib().fc_lm_head_workspace_bytes(DTYPE_CODE[dtype], M, K, V))
+
+
+def fc_lm_head_argmax(dtype, x, w_vocab, M, K, V, tok, conf, workspace, workspace_bytes=None, stream=None) -> None:
+    if workspace_bytes is None:
+        workspace_bytes = _nbytes(workspace)
+    _check(lib().fc_lm_head_argmax(DTYPE_CODE[dtype], _ptr(x), _ptr(w_vocab), M, K, V, _ptr(tok), _ptr(conf),
+                                   _ptr(workspace), workspace_bytes, _stream(stream)))
+
+
+def fc_unmask_select(tok, conf, pos, win_start, B, A, n_unmask, mask_id, tokens, L, pos_next, count_next,
+                     stream=None) -> None:
+    _check(lib().fc_unmask_select(_ptr(tok), _ptr(conf), _ptr(pos), win_start, B, A, n_unmask, mask_id,
+                                  _ptr(tokens), L, _ptr(pos_next), _ptr(count_next), _stream(stream)))

@@ -581,4 +581,91 @@ fc_status fc_full_layer_step(fc_cache *cache, int32_t layer, const fc_layer_weig
     return st;
 }
 
+// ---------------------------------------------------------------------------------------------
+// Unmasking step.
+
+namespace {
+
+// Carve-up of the lm-head workspace: [partial tiles of the streaming kernels][mx][arg][sm], each
+// [parts][M].
+struct LmHeadWs {
+    FcSkinnyPlan plan;
+    int parts;
+    size_t tiles, mx, arg, sm, total;
+};
+
+LmHeadWs lm_head_ws(int dtype, int M, int K, int V)
+{
+    LmHeadWs w;
+    w.plan = fc_plan_skinny(dtype, FC_LIN_VOCAB, M, K, V);
+    w.parts = w.plan.kind == 1 ? w.plan.slabs : (V + FC_LMHEAD_GENERIC_CHUNK - 1) / FC_LMHEAD_GENERIC_CHUNK;
+    size_t off = 0;
+    auto take = [&](size_t bytes) {
+        const size_t at = off;
+        off += align256(bytes);
+        return at;
+    };
+    w.tiles = take(fc_skinny_workspace(w.plan));
+    w.mx = take((size_t)w.parts * M * 4);
+    w.arg = take((size_t)w.parts * M * 4);
+    w.sm = take((size_t)w.parts * M * 4);
+    w.total = off;
+    return w;
+}
+
+}  // namespace
+
+size_t fc_lm_head_workspace_bytes(int32_t dtype, int32_t M, int32_t K, int32_t V)
+{
+    if ((dtype != FC_F32 && dtype != FC_BF16) || M < 1 || K < 1 || V < 1 || M > (1 << 24) || V > (1 << 24)) return 0;
+    return lm_head_ws(dtype, M, K, V).total;
+}
+
+fc_status fc_lm_head_argmax(int32_t dtype, const void *x, const void *w_vocab, int32_t M, int32_t K, int32_t V,
+                            int32_t *tok, float *conf, void *workspace, size_t workspace_bytes, void *stream)
+{
+    fc_status st = check_dtype(dtype);
+    if (st != FC_OK) return st;
+    if (!x || !w_vocab || !tok || !conf) return fail(FC_ERR_INVALID_ARG, "x, w_vocab, tok or conf is NULL");
+    if (M < 1 || K < 1 || V < 1) return fail(FC_ERR_INVALID_ARG, "M, K and V must be >= 1");
+    if (K % 8 != 0) return fail(FC_ERR_UNSUPPORTED, "K %d is not a multiple of 8", K);
+    if (M > (1 << 24) || V > (1 << 24)) return fail(FC_ERR_UNSUPPORTED, "M and V are limited to 2^24");
+    if (((uintptr_t)x | (uintptr_t)w_vocab | (uintptr_t)workspace) & 15)
+        return fail(FC_ERR_INVALID_ARG, "pointers must be 16-byte aligned");
+    const LmHeadWs w = lm_head_ws(dtype, M, K, V);
+    if (!workspace || workspace_bytes < w.total)
+        return fail(FC_ERR_WORKSPACE, "workspace of %zu bytes needed, %zu given", w.total,
+                    workspace ? workspace_bytes : (size_t)0);
+    char *ws = (char *)workspace;
+    FcArgmaxPart am;
+    am.mx = (float *)(ws + w.mx);
+    am.arg = (int32_t *)(ws + w.arg);
+    am.sm = (float *)(ws + w.sm);
+    hipError_t e;
+    if (w.plan.kind == 1)
+        e = fc_launch_linear_skinny(w.plan, FC_LIN_VOCAB, x, w_vocab, nullptr, nullptr, M, K, V, nullptr, ws + w.tiles,
+                                    (hipStream_t)stream, &am);
+    else
+        e = fc_launch_lmhead_generic(dtype, x, w_vocab, M, K, V, am, (hipStream_t)stream);
+    if (e == hipSuccess) e = fc_launch_lmhead_reduce(am, w.parts, M, tok, conf, (hipStream_t)stream);
+    return e == hipSuccess ? FC_OK : hip_fail(e, "lm-head launch");
+}
+
+fc_status fc_unmask_select(const int32_t *tok, const float *conf, const int32_t *pos, int32_t win_start, int32_t B,
+                           int32_t A, int32_t n_unmask, int32_t mask_id, int32_t *tokens, int32_t L,
+                           int32_t *pos_next, int32_t *count_next, void *stream)
+{
+    if (!tok || !conf || !tokens || !pos_next || !count_next)
+        return fail(FC_ERR_INVALID_ARG, "tok, conf, tokens, pos_next or count_next is NULL");
+    if (B < 1 || A < 1 || L < 1 || n_unmask < 0) return fail(FC_ERR_INVALID_ARG, "B, A, L >= 1 and n_unmask >= 0 required");
+    if (B > 65535) return fail(FC_ERR_UNSUPPORTED, "B is limited to 65535");
+    if (A > FC_UNMASK_MAX_ROWS) return fail(FC_ERR_UNSUPPORTED, "A %d exceeds %d rows", A, FC_UNMASK_MAX_ROWS);
+    if (pos == pos_next) return fail(FC_ERR_INVALID_ARG, "pos_next must not be pos");
+    if (!pos && (win_start < 0 || win_start > L - A))
+        return fail(FC_ERR_BOUNDS, "window [%d, %d+%d) outside the sequence of %d tokens", win_start, win_start, A, L);
+    hipError_t e = fc_launch_unmask_select(tok, conf, pos, win_start, B, A, n_unmask, mask_id, tokens, L, pos_next,
+                                           count_next, (hipStream_t)stream);
+    return e == hipSuccess ? FC_OK : hip_fail(e, "unmask launch");
+}
+
 }  // extern "C"

@@ -80,7 +80,29 @@ hipError_t fc_launch_attention_mfma(const FcGeom &G, const FcAttnPlan &p, const 
                                     int A, int kv_len, void *out, void *workspace, hipStream_t s);
 
 // Rest of the layer on the window rows: RMS normalisation and the linear layers around attention.
-enum { FC_LIN_RESIDUAL = 0, FC_LIN_GATE_UP = 1 };
+enum { FC_LIN_RESIDUAL = 0, FC_LIN_GATE_UP = 1, FC_LIN_VOCAB = 2 };
+// Vocabulary mode: per (part of the vocabulary, row) the largest logit, its index and the sum of
+// exp(logit - largest) over the part, each array [parts][M].
+struct FcArgmaxPart {
+    float *mx;
+    int32_t *arg;
+    float *sm;
+};
+// (largest, index, sum) of a union of two parts; equal maxima keep the smaller index.
+__host__ __device__ inline void fc_argmax_merge(float &mx, int &arg, float &sm, float mx2, int arg2, float sm2)
+{
+    if (mx2 > mx || (mx2 == mx && arg2 < arg)) {
+        const float t = mx;
+        mx = mx2;
+        mx2 = t;
+        const float u = sm;
+        sm = sm2;
+        sm2 = u;
+        arg = arg2;
+    }
+    // now mx >= mx2; a part that is still empty has mx2 = -inf and sm2 = 0
+    if (sm2 != 0.f) sm += sm2 * expf(mx2 - mx);
+}
 hipError_t fc_launch_rmsnorm(int dtype, const void *x, const void *weight, float eps, int rows, int d,
                              void *out, hipStream_t s);
 // Plain-ALU linear layer for any dtype and shape.  FC_LIN_RESIDUAL: out = aux + x w^T (aux = residual
@@ -102,7 +124,18 @@ FcSkinnyPlan fc_plan_skinny(int dtype, int mode, int M, int K, int N);
 size_t fc_skinny_workspace(const FcSkinnyPlan &p);
 hipError_t fc_launch_linear_skinny(const FcSkinnyPlan &pl, int mode, const void *x, const void *w,
                                    const void *w2, const void *res, int M, int K, int N, void *out,
-                                   void *workspace, hipStream_t s);
+                                   void *workspace, hipStream_t s, const FcArgmaxPart *am = nullptr);
+// Unmasking step: plain vocabulary projection (any dtype / shape), merge of the vocabulary parts, and
+// the confidence-ranked fill.
+hipError_t fc_launch_lmhead_generic(int dtype, const void *x, const void *w, int M, int K, int V,
+                                    const FcArgmaxPart &am, hipStream_t s);
+#define FC_LMHEAD_GENERIC_CHUNK 256  // vocabulary entries per part of the plain kernel
+hipError_t fc_launch_lmhead_reduce(const FcArgmaxPart &am, int parts, int M, int32_t *tok, float *conf,
+                                   hipStream_t s);
+#define FC_UNMASK_MAX_ROWS 8192
+hipError_t fc_launch_unmask_select(const int32_t *tok, const float *conf, const int32_t *pos, int win_start,
+                                   int B, int A, int n_unmask, int mask_id, int32_t *tokens, int L,
+                                   int32_t *pos_next, int32_t *count_next, hipStream_t s);
 // Tiled-GEMM plan of the same linear layers on more than 32 rows.
 struct FcWidePlan {
     int kind;    // 0 = not covered, 1 = tiled GEMM

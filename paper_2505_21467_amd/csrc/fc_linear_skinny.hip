@@ -34,6 +34,7 @@ struct LinArgs {
     const uint16_t *W2;   // up matrix [N][K] in gated mode
     const uint16_t *res;  // [M][N] or nullptr
     uint16_t *out;        // [M][N]
+    FcArgmaxPart am;      // vocabulary mode: per (slab, row) running maximum, its index, sum of exponentials
     float *partials;      // [m chunk][slab][maxseg][wave][mt][4][64]
     int M, K, N;          // N = output columns
     int S, T, G, maxseg, slabs;
@@ -251,6 +252,72 @@ __global__ __launch_bounds__(64) void k_linear_finish(LinArgs p)
     }
 }
 
+// Vocabulary mode (the unmasking step, section 3.1): the outputs of a slab are 128 logits per row, of
+// which only the largest, its index and the sum of exp(logit - largest) are kept, per (slab, row); a
+// last kernel merges the slabs.  One wave per slab walks over the slab's eight 16-row weight tiles, so
+// that a lane meets its logits in ascending vocabulary order (ties go to the smaller index).
+template <int MT, int KSL>
+__global__ __launch_bounds__(64) void k_lmhead_finish(LinArgs p)
+{
+    constexpr int KS = KSL / 32;
+    const int64_t U = (int64_t)p.T * KS;
+    const int slab = blockIdx.x, m0 = blockIdx.y * 32;
+    const int lane = threadIdx.x, rho = lane & 15, q = lane >> 4;
+    const int first = owner_of((int64_t)slab * p.S * KS, U, p.G);
+    const int nseg = owner_of((int64_t)(slab + 1) * p.S * KS - 1, U, p.G) - first + 1;
+    const size_t seg_stride = (size_t)8 * MT * 256;
+    float mx[MT], sm[MT];
+    int arg[MT];
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) {
+        mx[mt] = -INFINITY;
+        sm[mt] = 0.f;
+        arg[mt] = 0;
+    }
+    for (int wt = 0; wt < 8; ++wt) {
+        const float *base = p.partials + ((((size_t)blockIdx.y * p.slabs + slab) * p.maxseg) * 8 + wt) * (MT * 256);
+        f32x4 acc[MT];
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) acc[mt] = f32x4{0.f, 0.f, 0.f, 0.f};
+        for (int sg = 0; sg < nseg; ++sg)
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) acc[mt][r] += base[(size_t)sg * seg_stride + mt * 256 + r * 64 + lane];
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const float z = acc[mt][r];
+                const int v = slab * 128 + wt * 16 + 4 * q + r;
+                if (z > mx[mt]) {
+                    sm[mt] = sm[mt] * expf(mx[mt] - z) + 1.0f;
+                    mx[mt] = z;
+                    arg[mt] = v;
+                } else {
+                    sm[mt] += expf(z - mx[mt]);
+                }
+            }
+    }
+    // merge the four lanes (q = 0..3) that hold the same row
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) {
+#pragma unroll
+        for (int off = 16; off < 64; off <<= 1) {
+            const float mx2 = __shfl_xor(mx[mt], off, 64), sm2 = __shfl_xor(sm[mt], off, 64);
+            const int arg2 = __shfl_xor(arg[mt], off, 64);
+            fc_argmax_merge(mx[mt], arg[mt], sm[mt], mx2, arg2, sm2);
+        }
+        const int m = m0 + 16 * mt + rho;
+        if (q == 0 && m < p.M) {
+            const size_t at = (size_t)slab * p.M + m;
+            p.am.mx[at] = mx[mt];
+            p.am.arg[at] = arg[mt];
+            p.am.sm[at] = sm[mt];
+        }
+    }
+}
+
 constexpr int KSL = 512;  // hidden elements per work item
 
 template <int MODE>
@@ -273,7 +340,7 @@ FcSkinnyPlan fc_plan_skinny(int dtype, int mode, int M, int K, int N)
 {
     FcSkinnyPlan p;
     memset(&p, 0, sizeof p);
-    const int rows_per_slab = mode == FC_LIN_GATE_UP ? 64 : 128;
+    const int rows_per_slab = mode == FC_LIN_GATE_UP ? 64 : 128;  // FC_LIN_VOCAB: slabs of 128 vocabulary rows
     if (dtype != FC_BF16 || M < 1 || K < KSL || K % KSL != 0 || N < rows_per_slab || N % rows_per_slab != 0)
         return p;  // kind 0: plain kernel, no workspace
     p.kind = 1;
@@ -309,7 +376,7 @@ size_t fc_skinny_workspace(const FcSkinnyPlan &p)
 
 hipError_t fc_launch_linear_skinny(const FcSkinnyPlan &pl, int mode, const void *x, const void *w, const void *w2,
                                    const void *res, int M, int K, int N, void *out, void *workspace,
-                                   hipStream_t s)
+                                   hipStream_t s, const FcArgmaxPart *am)
 {
     // The kernels index the partial tiles by (slab, position of the workgroup among those that meet
     // the slab); make sure on the host that no slab meets more workgroups than the plan reserved.
@@ -320,6 +387,7 @@ hipError_t fc_launch_linear_skinny(const FcSkinnyPlan &pl, int mode, const void 
     }
     if (pl.kind != 1 || pl.G < 1 || pl.G > pl.T || M > pl.chunks * 32 || !workspace) return hipErrorInvalidValue;
     LinArgs a;
+    memset(&a, 0, sizeof a);
     a.X = (const uint16_t *)x;
     a.W = (const uint16_t *)w;
     a.W2 = (const uint16_t *)w2;
@@ -340,5 +408,18 @@ hipError_t fc_launch_linear_skinny(const FcSkinnyPlan &pl, int mode, const void 
         a.dbg = env ? (unsigned long long *)strtoull(env, nullptr, 0) : nullptr;
     }
 #endif
+    if (mode == FC_LIN_VOCAB) {
+        if (!am) return hipErrorInvalidValue;
+        a.am = *am;
+        const dim3 g1((unsigned)pl.G, (unsigned)pl.chunks), g2((unsigned)pl.slabs, (unsigned)pl.chunks);
+        if (pl.mt == 1) {
+            k_linear_stream<1, KSL, FC_LIN_RESIDUAL><<<g1, dim3(512), 0, s>>>(a);
+            k_lmhead_finish<1, KSL><<<g2, dim3(64), 0, s>>>(a);
+        } else {
+            k_linear_stream<2, KSL, FC_LIN_RESIDUAL><<<g1, dim3(512), 0, s>>>(a);
+            k_lmhead_finish<2, KSL><<<g2, dim3(64), 0, s>>>(a);
+        }
+        return hipGetLastError();
+    }
     return mode == FC_LIN_GATE_UP ? launch_mode<FC_LIN_GATE_UP>(pl, a, s) : launch_mode<FC_LIN_RESIDUAL>(pl, a, s);
 }

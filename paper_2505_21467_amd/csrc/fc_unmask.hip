@@ -1,0 +1,169 @@
+// Unmasking step of a diffusion language model on the window rows (paper, section 3.1: the masked set
+// M_t, the logits z_t of the masked positions, the arg-max fill of the selected subset U_t; with
+// FreeCache, section 3.2.1, only the rows of the active window are evaluated).
+//
+// The vocabulary projection never writes its logits: every kernel that produces a part of a row's
+// logits keeps (largest, its index, sum of exp(logit - largest)) of that part; k_lmhead_reduce merges
+// the parts into the arg-max token and its softmax probability 1 / sum.  k_unmask_select then fills,
+// per sequence, the n most confident still-masked window positions and lists the positions that stay
+// masked (the next step's active rows).
+#include "fc_device.h"
+#include "fc_internal.h"
+
+namespace {
+
+__device__ __forceinline__ float wave_sum_f(float v)
+{
+    for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
+    return v;
+}
+
+// Plain vocabulary projection, block = (row, FC_LMHEAD_GENERIC_CHUNK vocabulary entries); wave w owns
+// entries w, w + 4, ... of the chunk (ascending), lanes run along the hidden dimension.
+template <typename T>
+__global__ __launch_bounds__(256) void k_lmhead_generic(const T *__restrict__ X, const T *__restrict__ W, int M,
+                                                        int K, int V, FcArgmaxPart am)
+{
+    __shared__ float s_mx[4], s_sm[4];
+    __shared__ int s_arg[4];
+    const int m = blockIdx.x, part = blockIdx.y;
+    const int v0 = part * FC_LMHEAD_GENERIC_CHUNK;
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const T *x = X + (size_t)m * K;
+    float mx = -INFINITY, sm = 0.f;
+    int arg = 0;
+    for (int c = wave; c < FC_LMHEAD_GENERIC_CHUNK; c += 4) {
+        const int v = v0 + c;
+        if (v >= V) break;
+        const T *w = W + (size_t)v * K;
+        float acc = 0.f;
+        for (int k = lane; k < K; k += 64) acc += fc_to_float(w[k]) * fc_to_float(x[k]);
+        const float z = wave_sum_f(acc);
+        fc_argmax_merge(mx, arg, sm, z, v, 1.0f);
+    }
+    if (lane == 0) {
+        s_mx[wave] = mx;
+        s_sm[wave] = sm;
+        s_arg[wave] = arg;
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        for (int w2 = 1; w2 < 4; ++w2) fc_argmax_merge(mx, arg, sm, s_mx[w2], s_arg[w2], s_sm[w2]);
+        const size_t at = (size_t)part * M + m;
+        am.mx[at] = mx;
+        am.arg[at] = arg;
+        am.sm[at] = sm;
+    }
+}
+
+// Merge of the vocabulary parts of one row: one wave per row.
+__global__ __launch_bounds__(64) void k_lmhead_reduce(FcArgmaxPart am, int parts, int M, int32_t *tok, float *conf)
+{
+    const int m = blockIdx.x, lane = threadIdx.x;
+    float mx = -INFINITY, sm = 0.f;
+    int arg = 0x7fffffff;
+    for (int pt = lane; pt < parts; pt += 64) {
+        const size_t at = (size_t)pt * M + m;
+        fc_argmax_merge(mx, arg, sm, am.mx[at], am.arg[at], am.sm[at]);
+    }
+    for (int off = 32; off > 0; off >>= 1) {
+        const float mx2 = __shfl_xor(mx, off, 64), sm2 = __shfl_xor(sm, off, 64);
+        const int arg2 = __shfl_xor(arg, off, 64);
+        fc_argmax_merge(mx, arg, sm, mx2, arg2, sm2);
+    }
+    if (lane == 0) {
+        tok[m] = arg;
+        conf[m] = 1.0f / sm;
+    }
+}
+
+// Confidence-ranked fill, one block per sequence.  A candidate is a window row whose position is valid
+// and whose token is still the mask.  Its rank is the number of candidates that come before it in the
+// order (larger confidence first, then smaller row); ranks below n_unmask are filled.  The remaining
+// candidates are listed in row order (block-wide prefix sum over chunks of 256 rows).
+__global__ __launch_bounds__(256) void k_unmask_select(const int32_t *__restrict__ tok, const float *__restrict__ conf,
+                                                       const int32_t *__restrict__ pos, int win_start, int A,
+                                                       int n_unmask, int mask_id, int32_t *tokens, int L,
+                                                       int32_t *pos_next, int32_t *count_next)
+{
+    extern __shared__ unsigned char sm_raw[];
+    float *s_conf = (float *)sm_raw;            // [A]; -1 marks "not a candidate" (confidences are > 0)
+    int *s_scan = (int *)(s_conf + A);          // [256]
+    __shared__ int s_base;
+    const int b = blockIdx.x, tid = threadIdx.x;
+    int32_t *seq = tokens + (size_t)b * L;
+    auto position = [&](int a) { return pos ? pos[(size_t)b * A + a] : win_start + a; };
+
+    for (int a = tid; a < A; a += 256) {
+        const int p = position(a);
+        const bool cand = p >= 0 && p < L && seq[p] == mask_id;
+        s_conf[a] = cand ? conf[(size_t)b * A + a] : -1.0f;
+    }
+    if (tid == 0) s_base = 0;
+    __syncthreads();
+
+    for (int a0 = 0; a0 < A; a0 += 256) {
+        const int a = a0 + tid;
+        bool keep = false;  // candidate that stays masked
+        if (a < A && s_conf[a] >= 0.f) {
+            const float c = s_conf[a];
+            int rank = 0;
+            for (int o = 0; o < A; ++o) {
+                const float co = s_conf[o];
+                rank += (co > c || (co == c && o < a)) ? 1 : 0;  // non-candidates hold -1 and never count
+            }
+            if (rank < n_unmask)
+                seq[position(a)] = tok[(size_t)b * A + a];
+            else
+                keep = true;
+        }
+        // inclusive scan of `keep` over the 256 rows of this chunk
+        s_scan[tid] = keep ? 1 : 0;
+        __syncthreads();
+        for (int off = 1; off < 256; off <<= 1) {
+            const int v = tid >= off ? s_scan[tid - off] : 0;
+            __syncthreads();
+            s_scan[tid] += v;
+            __syncthreads();
+        }
+        const int base = s_base;
+        if (keep) pos_next[(size_t)b * A + base + s_scan[tid] - 1] = position(a);
+        __syncthreads();
+        if (tid == 255) s_base = base + s_scan[255];
+        __syncthreads();
+    }
+    const int n = s_base;
+    for (int a = n + tid; a < A; a += 256) pos_next[(size_t)b * A + a] = -1;
+    if (tid == 0) count_next[b] = n;
+}
+
+}  // namespace
+
+hipError_t fc_launch_lmhead_generic(int dtype, const void *x, const void *w, int M, int K, int V,
+                                    const FcArgmaxPart &am, hipStream_t s)
+{
+    const dim3 grid((unsigned)M, (unsigned)((V + FC_LMHEAD_GENERIC_CHUNK - 1) / FC_LMHEAD_GENERIC_CHUNK));
+    if (dtype == FC_F32)
+        k_lmhead_generic<float><<<grid, dim3(256), 0, s>>>((const float *)x, (const float *)w, M, K, V, am);
+    else
+        k_lmhead_generic<bf16_t><<<grid, dim3(256), 0, s>>>((const bf16_t *)x, (const bf16_t *)w, M, K, V, am);
+    return hipGetLastError();
+}
+
+hipError_t fc_launch_lmhead_reduce(const FcArgmaxPart &am, int parts, int M, int32_t *tok, float *conf,
+                                   hipStream_t s)
+{
+    k_lmhead_reduce<<<dim3((unsigned)M), dim3(64), 0, s>>>(am, parts, M, tok, conf);
+    return hipGetLastError();
+}
+
+hipError_t fc_launch_unmask_select(const int32_t *tok, const float *conf, const int32_t *pos, int win_start,
+                                   int B, int A, int n_unmask, int mask_id, int32_t *tokens, int L,
+                                   int32_t *pos_next, int32_t *count_next, hipStream_t s)
+{
+    if (A > FC_UNMASK_MAX_ROWS) return hipErrorInvalidValue;
+    const size_t lds = (size_t)A * sizeof(float) + 256 * sizeof(int);
+    k_unmask_select<<<dim3((unsigned)B), dim3(256), lds, s>>>(tok, conf, pos, win_start, A, n_unmask, mask_id, tokens, L,
+                                                               pos_next, count_next);
+    return hipGetLastError();
+}

@@ -214,3 +214,36 @@ def test_rest_of_layer_entry_points_reject_bad_arguments_before_any_launch(cache
         _raises(fc.FC_ERR_INVALID_ARG, Fl, cache, 0, bad, FAKE, 0, 32, None, 100, FAKE, FAKE, need, S)
     bad = fc.make_layer_weights(FAKE, FAKE, None, FAKE, FAKE, FAKE, FAKE, FAKE, 0, 1e-6)
     _raises(fc.FC_ERR_INVALID_ARG, Fl, cache, 0, bad, FAKE, 0, 32, None, 100, FAKE, FAKE, need, S)
+
+
+def test_unmasking_entry_points_reject_bad_arguments_before_any_launch():
+    S, BF, big = 0, "bf16", 1 << 30
+    H = fc.fc_lm_head_argmax
+    _raises(fc.FC_ERR_INVALID_ARG, H, BF, None, FAKE, 32, 512, 1024, FAKE, FAKE, FAKE, big, S)
+    _raises(fc.FC_ERR_INVALID_ARG, H, BF, FAKE, None, 32, 512, 1024, FAKE, FAKE, FAKE, big, S)
+    _raises(fc.FC_ERR_INVALID_ARG, H, BF, FAKE, FAKE, 32, 512, 1024, None, FAKE, FAKE, big, S)
+    _raises(fc.FC_ERR_INVALID_ARG, H, BF, FAKE, FAKE, 32, 512, 1024, FAKE, None, FAKE, big, S)
+    _raises(fc.FC_ERR_INVALID_ARG, H, BF, FAKE, FAKE, 0, 512, 1024, FAKE, FAKE, FAKE, big, S)
+    _raises(fc.FC_ERR_INVALID_ARG, H, BF, FAKE, FAKE, 32, 512, 0, FAKE, FAKE, FAKE, big, S)
+    _raises(fc.FC_ERR_UNSUPPORTED, H, BF, FAKE, FAKE, 32, 100, 1024, FAKE, FAKE, FAKE, big, S)
+    _raises(fc.FC_ERR_WORKSPACE, H, BF, FAKE, FAKE, 32, 512, 1024, FAKE, FAKE, None, 0, S)
+    need = fc.fc_lm_head_workspace_bytes(BF, 32, 512, 1024)
+    assert need > 0 and need % 256 == 0
+    _raises(fc.FC_ERR_WORKSPACE, H, BF, FAKE, FAKE, 32, 512, 1024, FAKE, FAKE, FAKE, need - 1, S)
+    assert fc.fc_lm_head_workspace_bytes(BF, 0, 512, 1024) == 0
+    assert fc.fc_lm_head_workspace_bytes("f32", 4, 40, 300) > 0          # the plain kernel keeps per-part state too
+    assert fc.fc_lm_head_workspace_bytes(BF, 32, 3584, 152064) > fc.fc_lm_head_workspace_bytes(BF, 32, 3584, 1024)
+
+    U = fc.fc_unmask_select
+    _raises(fc.FC_ERR_INVALID_ARG, U, None, FAKE, FAKE, 0, 2, 32, 4, 9, FAKE, 100, FAKE + 256, FAKE, S)
+    _raises(fc.FC_ERR_INVALID_ARG, U, FAKE, None, FAKE, 0, 2, 32, 4, 9, FAKE, 100, FAKE + 256, FAKE, S)
+    _raises(fc.FC_ERR_INVALID_ARG, U, FAKE, FAKE, FAKE, 0, 2, 32, 4, 9, None, 100, FAKE + 256, FAKE, S)
+    _raises(fc.FC_ERR_INVALID_ARG, U, FAKE, FAKE, FAKE, 0, 2, 32, 4, 9, FAKE, 100, None, FAKE, S)
+    _raises(fc.FC_ERR_INVALID_ARG, U, FAKE, FAKE, FAKE, 0, 2, 32, 4, 9, FAKE, 100, FAKE + 256, None, S)
+    _raises(fc.FC_ERR_INVALID_ARG, U, FAKE, FAKE, FAKE, 0, 0, 32, 4, 9, FAKE, 100, FAKE + 256, FAKE, S)
+    _raises(fc.FC_ERR_INVALID_ARG, U, FAKE, FAKE, FAKE, 0, 2, 0, 4, 9, FAKE, 100, FAKE + 256, FAKE, S)
+    _raises(fc.FC_ERR_INVALID_ARG, U, FAKE, FAKE, FAKE, 0, 2, 32, -1, 9, FAKE, 100, FAKE + 256, FAKE, S)
+    _raises(fc.FC_ERR_INVALID_ARG, U, FAKE, FAKE, FAKE, 0, 2, 32, 4, 9, FAKE, 100, FAKE, FAKE, S)      # pos_next == pos
+    _raises(fc.FC_ERR_UNSUPPORTED, U, FAKE, FAKE, FAKE, 0, 2, 9000, 4, 9, FAKE, 10000, FAKE + 256, FAKE, S)
+    _raises(fc.FC_ERR_BOUNDS, U, FAKE, FAKE, None, 80, 2, 32, 4, 9, FAKE, 100, FAKE + 256, FAKE, S)
+    _raises(fc.FC_ERR_BOUNDS, U, FAKE, FAKE, None, -1, 2, 32, 4, 9, FAKE, 100, FAKE + 256, FAKE, S)

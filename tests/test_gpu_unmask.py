@@ -1,0 +1,163 @@
+"""GPU parity of the unmasking step (vocabulary projection with arg-max and confidence, confidence-ranked
+fill and list of the still masked positions) against the CPU oracle, through the C-ABI binding.
+
+Integer results are compared bit for bit.  Where floating point decides an integer (the arg-max over
+the vocabulary), the GPU decides in its own precision (fp32 logits), the oracle in fp64: the two must
+agree wherever the oracle's two largest logits are further apart than the float error bound, and
+otherwise the GPU's choice must be a token whose oracle logit lies within that bound of the largest.
+The selection step is fed the same fp32 confidences on both sides, so it is exact everywhere."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import fc_oracle as orc
+from paper_2505_21467_amd import binding as fc
+from paper_2505_21467_amd import inputs
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+LOGIT_TOL = {"f32": 2e-5, "bf16": 2e-4}   # fp32 accumulation over K <= 4096 products of magnitude <= ~1
+CONF_RTOL = {"f32": 2e-4, "bf16": 2e-3}
+
+
+def _dev(t):
+    return None if t is None else t.to(DEV).contiguous()
+
+
+def _lm_head(dtype, x, w):
+    M, K = x.shape
+    V = w.shape[0]
+    need = fc.fc_lm_head_workspace_bytes(dtype, M, K, V)
+    assert need > 0
+    ws = torch.empty(need, dtype=torch.uint8, device=DEV)
+    tok = torch.full((M,), -5, dtype=torch.int32, device=DEV)
+    conf = torch.full((M,), float("nan"), dtype=torch.float32, device=DEV)
+    fc.fc_lm_head_argmax(dtype, _dev(x), _dev(w), M, K, V, tok, conf, ws, need)
+    torch.cuda.synchronize()
+    return tok.cpu().numpy(), conf.cpu().numpy()
+
+
+def _check_lm_head(dtype, x, w, what):
+    tok, conf = _lm_head(dtype, x, w)
+    rt, rc, z = orc.lm_head_argmax(inputs.as_oracle(x), inputs.as_oracle(w), want_logits=True)
+    tol = LOGIT_TOL[dtype]
+    top = z.max(axis=1)
+    second = np.partition(z, -2, axis=1)[:, -2]
+    clear = top - second > tol
+    assert np.all((tok >= 0) & (tok < w.shape[0])), what
+    assert np.array_equal(tok[clear], rt[clear]), what + ": arg-max differs where the margin is clear"
+    picked = z[np.arange(len(tok)), tok]
+    assert np.all(top - picked <= tol), what + ": picked token is not within the error bound of the largest logit"
+    assert np.all(np.isfinite(conf)) and np.allclose(conf, rc, rtol=CONF_RTOL[dtype]), what + ": confidence"
+    return tok, conf
+
+
+@pytest.mark.parametrize("dtype,M,K,V", [
+    ("f32", 5, 40, 300),          # plain kernel
+    ("bf16", 6, 136, 1000),       # bf16 shape the streaming kernels do not cover (vocabulary not a multiple of 128)
+    ("bf16", 7, 512, 128),        # one slab, one item
+    ("bf16", 32, 1024, 2048),
+    ("bf16", 40, 1024, 640),      # two passes of rows
+    ("bf16", 32, 3584, 8192),     # the 7B hidden width, a slice of the vocabulary
+])
+def test_lm_head_argmax_matches_oracle(dtype, M, K, V):
+    x = inputs.normal(21, "x", (M, K), 1.0, dtype)
+    w = inputs.normal(21, "w", (V, K), 0.03, dtype)
+    _check_lm_head(dtype, x, w, "lm_head %s %dx%dx%d" % (dtype, M, K, V))
+
+
+def test_lm_head_exact_ties_go_to_the_smaller_index():
+    # identical vocabulary rows give bit-identical logits on both sides: the smaller index must win, also
+    # across slabs and across the lanes / waves that hold one row's logits
+    M, K, V = 16, 512, 1024
+    x = inputs.normal(22, "x", (M, K), 1.0, "bf16")
+    w = inputs.normal(22, "w", (V, K), 0.01, "bf16")
+    big = inputs.normal(22, "big", (K,), 1.0, "bf16")
+    for v in (900, 130, 131, 517, 77):     # the same dominant row at several places: 77 is the smallest
+        w[v] = big
+    x[:] = (x.float() * 0.05 + big.float()).to(torch.bfloat16)   # every row prefers the dominant direction
+    tok, conf = _lm_head("bf16", x, w)
+    rt, rc = orc.lm_head_argmax(inputs.as_oracle(x), inputs.as_oracle(w))
+    assert np.all(rt == 77) and np.array_equal(tok, rt)
+    assert np.allclose(conf, rc, rtol=2e-3) and np.all(conf <= 0.2 + 1e-6)   # five tokens share the mass
+
+
+def _random_case(rng, B, A, L, mask, frac_masked=0.6, pad=0.15):
+    pos = np.stack([np.sort(rng.choice(L, A, replace=False)) for _ in range(B)]).astype(np.int32)
+    pos[rng.random((B, A)) < pad] = -1
+    tokens = rng.integers(0, 50, (B, L)).astype(np.int32)
+    tokens[rng.random((B, L)) < frac_masked] = mask
+    tok = rng.integers(0, 50, (B, A)).astype(np.int32)
+    conf = np.round(rng.random((B, A)), 2).astype(np.float32)   # coarse: plenty of ties
+    return pos, tokens, tok, conf
+
+
+def _gpu_select(tok, conf, pos, win_start, k, mask, tokens):
+    B, A = tok.shape
+    L = tokens.shape[1]
+    td = torch.from_numpy(tokens.copy()).to(DEV)
+    pn = torch.full((B, A), -9, dtype=torch.int32, device=DEV)
+    cn = torch.full((B,), -9, dtype=torch.int32, device=DEV)
+    posd = None if pos is None else torch.from_numpy(pos).to(DEV)
+    fc.fc_unmask_select(torch.from_numpy(tok).to(DEV), torch.from_numpy(conf).to(DEV), posd, win_start, B, A, k, mask,
+                        td, L, pn, cn)
+    torch.cuda.synchronize()
+    return td.cpu().numpy(), pn.cpu().numpy(), cn.cpu().numpy()
+
+
+@pytest.mark.parametrize("B,A,L", [(1, 1, 5), (3, 17, 64), (2, 256, 600), (2, 700, 1500), (8, 32, 2304)])
+def test_unmask_select_is_bit_exact(B, A, L):
+    rng = np.random.default_rng(B * 1000 + A)
+    MASK = 151666
+    for k in (0, 1, 4, 10 ** 6):
+        pos, tokens, tok, conf = _random_case(rng, B, A, L, MASK)
+        want_t = tokens.copy()
+        want_n, want_c = orc.unmask_select(tok, conf.astype(np.float64), pos, min(k, A), MASK, want_t)
+        got_t, got_n, got_c = _gpu_select(tok, conf, pos, 0, min(k, 2 ** 31 - 1), MASK, tokens)
+        assert np.array_equal(got_t, want_t) and np.array_equal(got_n, want_n) and np.array_equal(got_c, want_c)
+
+
+def test_unmask_select_window_given_by_its_start():
+    rng = np.random.default_rng(77)
+    B, A, L, MASK = 2, 40, 100, -1
+    _, tokens, tok, conf = _random_case(rng, B, A, L, MASK)
+    pos = np.tile(np.arange(50, 50 + A, dtype=np.int32), (B, 1))
+    want_t = tokens.copy()
+    want_n, want_c = orc.unmask_select(tok, conf.astype(np.float64), pos, 5, MASK, want_t)
+    got_t, got_n, got_c = _gpu_select(tok, conf, None, 50, 5, MASK, tokens)
+    assert np.array_equal(got_t, want_t) and np.array_equal(got_n, want_n) and np.array_equal(got_c, want_c)
+    # nothing outside the window is touched
+    assert np.array_equal(got_t[:, :50], tokens[:, :50]) and np.array_equal(got_t[:, 90:], tokens[:, 90:])
+
+
+def test_unmasking_steps_chained_until_the_block_is_filled():
+    # a block of 32 masked positions per sequence; every step: vocabulary projection of the still
+    # masked rows, then the 5 most confident are filled.  The oracle follows with the GPU's own fp32
+    # confidences and tokens, so every integer of every step must agree.
+    B, A, K, V, MASK, k = 2, 32, 512, 1024, 5000, 5
+    L, P = 80, 40
+    tokens = np.full((B, L), MASK, np.int32)
+    tokens[:, :P] = 7
+    w = inputs.normal(31, "w", (V, K), 0.05, "bf16")
+    pos = np.tile(np.arange(P, P + A, dtype=np.int32), (B, 1))
+    td = torch.from_numpy(tokens.copy()).to(DEV)
+    pos_d = torch.from_numpy(pos).to(DEV)
+    host_tokens = tokens.copy()
+    steps = 0
+    while True:
+        x = inputs.normal(31, "x.%d" % steps, (B * A, K), 1.0, "bf16")
+        tok, conf = _check_lm_head("bf16", x, w, "step %d" % steps)
+        tok, conf = tok.reshape(B, A), conf.reshape(B, A)
+        pn = torch.empty((B, A), dtype=torch.int32, device=DEV)
+        cn = torch.empty((B,), dtype=torch.int32, device=DEV)
+        fc.fc_unmask_select(torch.from_numpy(tok).to(DEV), torch.from_numpy(conf).to(DEV), pos_d, 0, B, A, k, MASK, td, L,
+                            pn, cn)
+        torch.cuda.synchronize()
+        want_n, want_c = orc.unmask_select(tok, conf.astype(np.float64), pos, k, MASK, host_tokens)
+        assert np.array_equal(td.cpu().numpy(), host_tokens)
+        assert np.array_equal(pn.cpu().numpy(), want_n) and np.array_equal(cn.cpu().numpy(), want_c)
+        pos, pos_d = want_n, pn
+        steps += 1
+        if np.all(want_c == 0):
+            break
+    assert steps == -(-A // k) and not np.any(host_tokens[:, P:P + A] == MASK) and np.all(host_tokens[:, P + A:] == MASK)
