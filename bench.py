@@ -1,7 +1,8 @@
 """Benchmark of the FreeCache cached denoising layer-step on one MI355X.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--layers N]
-                    [--workload c4|c2|c3|c5|c5_refresh|c4_layer|c2_layer|c3_layer|c5_layer|c5_refresh_layer]
+                    [--workload c4|c2|c3|c5|c5_refresh|c4_layer|c2_layer|c3_layer|c5_layer|c5_refresh_layer|
+                                c4_unmask|c5_unmask]
 
 A "step" is one pass of the whole hot path for one layer: QKV projection + RoPE + scatter of the
 active window, then attention of the window's queries over the cache.  The default workload is the
@@ -20,6 +21,10 @@ same loop on a single layer is reported as `single_cache_us` (cache-resident fig
 above, output projection + residual, RMSNorm, gated feed-forward network + residual: one
 `fc_full_layer_step` per step), the next row after the attention path; `c5_refresh_layer` does so for
 the 256-row refresh of 8 sequences (2048 rows).
+
+`--workload c4_unmask` / `c5_unmask` time the unmasking step of a block (vocabulary projection of the
+block's rows with arg-max and confidence, `fc_lm_head_argmax`, then `fc_unmask_select`; vocabulary
+152064 x hidden 3584, the Dream-7B sizes).
 
 Prints ONE JSON line (see the fields below).  Inputs are seeded and synthetic.
 """
@@ -53,7 +58,7 @@ def _parse():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="c4",
                     choices=["c2", "c3", "c4", "c5", "c5_refresh", "c4_layer", "c2_layer", "c3_layer", "c5_layer",
-                             "c5_refresh_layer"])
+                             "c5_refresh_layer", "c4_unmask", "c5_unmask"])
     ap.add_argument("--layers", type=int, default=0, help="distinct layer caches to rotate over (0 = auto)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-single", action="store_true",
@@ -78,6 +83,8 @@ def main():
     dev = torch.device("cuda:0")
     if args.workload.endswith("_layer"):
         return main_layer(args, torch, fc, inputs, dev)
+    if args.workload.endswith("_unmask"):
+        return main_unmask(args, torch, fc, inputs, dev)
     refresh = args.workload == "c5_refresh"
     w = {"c2": inputs.C2, "c3": inputs.C3, "c4": inputs.C4, "c5": inputs.C5, "c5_refresh": inputs.C5}[args.workload]
     B, Dh, Hq, Hkv = w.batch, w.head_dim, w.n_q_heads, w.n_kv_heads
@@ -417,6 +424,92 @@ def main_layer(args, torch, fc, inputs, dev):
         del np
     torch.cuda.synchronize()
     fc.fc_cache_free(cache)
+    print(json.dumps(out))
+
+
+def main_unmask(args, torch, fc, inputs, dev):
+    """Unmasking step of one block: vocabulary projection (arg-max + confidence) and confidence-ranked fill."""
+    w = {"c4_unmask": inputs.C4, "c5_unmask": inputs.C5}[args.workload]
+    B, A, d, V, esz = w.batch, w.active, w.hidden, 152064, 2
+    M, L, MASK, k = B * A, w.kv_len, V - 1, 4
+    tdt = inputs.TORCH_DTYPE[w.dtype]
+    n_mats = args.layers or 3                      # 1.09 GB each: the stream always comes from HBM
+    steps = min(args.steps, 30)
+    W0 = inputs.normal(0, "w_vocab", (V, d), 0.02, w.dtype).to(dev)
+    Ws = [W0] + [W0.clone() for _ in range(n_mats - 1)]
+    Xs = [inputs.hidden_states(w, 0, A, tag="h.%d" % i).to(dev).view(M, d) for i in range(4)]
+    need = fc.fc_lm_head_workspace_bytes(w.dtype, M, d, V)
+    ws = torch.empty(need, dtype=torch.uint8, device=dev)
+    tok = torch.empty((M,), dtype=torch.int32, device=dev)
+    conf = torch.empty((M,), dtype=torch.float32, device=dev)
+    tokens = torch.full((B, L), MASK, dtype=torch.int32, device=dev)
+    pos_next = torch.empty((B, A), dtype=torch.int32, device=dev)
+    count = torch.empty((B,), dtype=torch.int32, device=dev)
+    stream = torch.cuda.current_stream().cuda_stream
+    torch.cuda.synchronize()
+
+    def step(s, head=True, select=True):
+        if head:
+            fc.fc_lm_head_argmax(w.dtype, Xs[s % 4], Ws[s % n_mats], M, d, V, tok, conf, ws, need, stream)
+        if select:
+            fc.fc_unmask_select(tok, conf, None, w.cached_len, B, A, k, MASK, tokens, L, pos_next, count, stream)
+
+    def timed(n, **kw):
+        res = []
+        for _ in range(args.repeats):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            torch.cuda.synchronize()
+            e0.record()
+            for s in range(n):
+                step(s, **kw)
+            e1.record()
+            torch.cuda.synchronize()
+            res.append(e0.elapsed_time(e1) * 1000.0 / n)
+        res.sort()
+        return res[len(res) // 2]
+
+    for s in range(min(args.warmup, 6)):
+        step(s)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for s in range(steps):
+        step(s)
+    e1.record()
+    torch.cuda.synchronize()
+    us_step = e0.elapsed_time(e1) * 1000.0 / steps
+    us_head = timed(steps, select=False)
+    us_sel = timed(steps, head=False)
+    w_bytes = V * d * esz
+    out = {
+        "metric": "us per unmasking step of one block (vocabulary projection with arg-max + confidence-ranked fill)",
+        "value": round(us_step, 3), "unit": "us", "n_gpus": 1, "steps": steps, "warmup": min(args.warmup, 6),
+        "ms_per_step": round(us_step / 1000.0, 6), "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
+        "dtype": w.dtype, "data": "synthetic",
+        "config": {"workload": w.name + "/unmask", "batch": B, "block_rows": A, "hidden": d, "vocab": V,
+                   "unmasked_per_step": k, "matrices_rotated": n_mats},
+        "roofline": {"kernel": "fc_lm_head_argmax (%s + k_lmhead_reduce)" % (
+                         "k_linear_stream + k_lmhead_finish" if M <= 32 else "k_proj_gemm with the arg-max epilogue"),
+                     "bound": "hbm",
+                     "achieved": round(w_bytes / us_head * 1e-3, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": round(w_bytes / us_head * 1e-3 / HBM_PEAK_GBS, 4), "traffic": None,
+                     "algorithmic_bytes_per_launch": w_bytes + M * d * esz + M * 8, "us_per_launch": round(us_head, 3),
+                     "tflops": round(2.0 * M * d * V / us_head * 1e-6, 1)},
+        "unmask_select_us": round(us_sel, 3),
+    }
+    if not args.no_cpu_baseline:
+        import numpy as np
+        from oracle import fc_oracle as orc
+        rows = 2   # bounded sample: two rows of the block against the whole vocabulary, scaled to M rows
+        X = inputs.as_oracle(inputs.hidden_states(w, 0, A, tag="h.0")).reshape(M, d)[:rows].copy()
+        Wv = inputs.as_oracle(inputs.normal(0, "w_vocab", (V, d), 0.02, w.dtype))
+        t0 = time.perf_counter()
+        orc.lm_head_argmax(X, Wv)
+        dt = time.perf_counter() - t0
+        out["cpu_baseline"] = {"value": round(dt * 1e6 * M / rows, 1), "unit": "us", "cores": orc.get_threads(),
+                               "kind": "oracle", "sample": "vocabulary projection + arg-max of %d rows of %s, fp64, "
+                               "OpenMP over rows; scaled by %g to the %d rows of a step" % (rows, w.name, M / rows, M)}
+        del np
     print(json.dumps(out))
 
 

@@ -589,6 +589,7 @@ namespace {
 // Carve-up of the lm-head workspace: [partial tiles of the streaming kernels][mx][arg][sm], each
 // [parts][M].
 struct LmHeadWs {
+    FcWidePlan wide;
     FcSkinnyPlan plan;
     int parts;
     size_t tiles, mx, arg, sm, total;
@@ -597,8 +598,12 @@ struct LmHeadWs {
 LmHeadWs lm_head_ws(int dtype, int M, int K, int V)
 {
     LmHeadWs w;
+    w.wide = fc_plan_wide(dtype, FC_LIN_VOCAB, M, K, V);  // more than 32 rows: tiled GEMM
     w.plan = fc_plan_skinny(dtype, FC_LIN_VOCAB, M, K, V);
-    w.parts = w.plan.kind == 1 ? w.plan.slabs : (V + FC_LMHEAD_GENERIC_CHUNK - 1) / FC_LMHEAD_GENERIC_CHUNK;
+    if (w.wide.kind == 1) w.plan.kind = 0;
+    w.parts = w.wide.kind == 1 ? V / 128
+                               : (w.plan.kind == 1 ? w.plan.slabs
+                                                   : (V + FC_LMHEAD_GENERIC_CHUNK - 1) / FC_LMHEAD_GENERIC_CHUNK);
     size_t off = 0;
     auto take = [&](size_t bytes) {
         const size_t at = off;
@@ -642,7 +647,10 @@ fc_status fc_lm_head_argmax(int32_t dtype, const void *x, const void *w_vocab, i
     am.arg = (int32_t *)(ws + w.arg);
     am.sm = (float *)(ws + w.sm);
     hipError_t e;
-    if (w.plan.kind == 1)
+    if (w.wide.kind == 1)
+        e = fc_launch_linear_wide(w.wide, FC_LIN_VOCAB, x, w_vocab, nullptr, nullptr, M, K, V, nullptr, nullptr,
+                                  (hipStream_t)stream, &am);
+    else if (w.plan.kind == 1)
         e = fc_launch_linear_skinny(w.plan, FC_LIN_VOCAB, x, w_vocab, nullptr, nullptr, M, K, V, nullptr, ws + w.tiles,
                                     (hipStream_t)stream, &am);
     else

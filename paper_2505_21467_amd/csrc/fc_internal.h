@@ -145,4 +145,5 @@ struct FcWidePlan {
 FcWidePlan fc_plan_wide(int dtype, int mode, int M, int K, int N);
 size_t fc_wide_workspace(const FcWidePlan &p, int M, int N);
 hipError_t fc_launch_linear_wide(const FcWidePlan &pl, int mode, const void *x, const void *w, const void *w2,
-                                 const void *res, int M, int K, int N, void *out, void *workspace, hipStream_t s);
+                                 const void *res, int M, int K, int N, void *out, void *workspace, hipStream_t s,
+                                 const FcArgmaxPart *am = nullptr);

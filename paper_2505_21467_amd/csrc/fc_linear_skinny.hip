@@ -254,67 +254,60 @@ __global__ __launch_bounds__(64) void k_linear_finish(LinArgs p)
 
 // Vocabulary mode (the unmasking step, section 3.1): the outputs of a slab are 128 logits per row, of
 // which only the largest, its index and the sum of exp(logit - largest) are kept, per (slab, row); a
-// last kernel merges the slabs.  One wave per slab walks over the slab's eight 16-row weight tiles, so
-// that a lane meets its logits in ascending vocabulary order (ties go to the smaller index).
+// last kernel merges the slabs.  One workgroup per slab: wave wt sums the partial tiles of the slab's
+// weight tile wt, the lanes that share a row merge, and one thread per row merges the eight tiles
+// (the merge keeps the smaller index on equal maxima, so its order does not matter).
 template <int MT, int KSL>
-__global__ __launch_bounds__(64) void k_lmhead_finish(LinArgs p)
+__global__ __launch_bounds__(512) void k_lmhead_finish(LinArgs p)
 {
     constexpr int KS = KSL / 32;
+    __shared__ float s_mx[8][16 * MT], s_sm[8][16 * MT];
+    __shared__ int s_arg[8][16 * MT];
     const int64_t U = (int64_t)p.T * KS;
     const int slab = blockIdx.x, m0 = blockIdx.y * 32;
-    const int lane = threadIdx.x, rho = lane & 15, q = lane >> 4;
+    const int lane = threadIdx.x & 63, wt = threadIdx.x >> 6;  // wave wt sums the slab's weight tile wt
+    const int rho = lane & 15, q = lane >> 4;
     const int first = owner_of((int64_t)slab * p.S * KS, U, p.G);
     const int nseg = owner_of((int64_t)(slab + 1) * p.S * KS - 1, U, p.G) - first + 1;
     const size_t seg_stride = (size_t)8 * MT * 256;
-    float mx[MT], sm[MT];
-    int arg[MT];
+    const float *base = p.partials + ((((size_t)blockIdx.y * p.slabs + slab) * p.maxseg) * 8 + wt) * (MT * 256);
+    f32x4 acc[MT];
 #pragma unroll
-    for (int mt = 0; mt < MT; ++mt) {
-        mx[mt] = -INFINITY;
-        sm[mt] = 0.f;
-        arg[mt] = 0;
-    }
-    for (int wt = 0; wt < 8; ++wt) {
-        const float *base = p.partials + ((((size_t)blockIdx.y * p.slabs + slab) * p.maxseg) * 8 + wt) * (MT * 256);
-        f32x4 acc[MT];
-#pragma unroll
-        for (int mt = 0; mt < MT; ++mt) acc[mt] = f32x4{0.f, 0.f, 0.f, 0.f};
-        for (int sg = 0; sg < nseg; ++sg)
-#pragma unroll
-            for (int mt = 0; mt < MT; ++mt)
-#pragma unroll
-                for (int r = 0; r < 4; ++r) acc[mt][r] += base[(size_t)sg * seg_stride + mt * 256 + r * 64 + lane];
+    for (int mt = 0; mt < MT; ++mt) acc[mt] = f32x4{0.f, 0.f, 0.f, 0.f};
+    for (int sg = 0; sg < nseg; ++sg)
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                const float z = acc[mt][r];
-                const int v = slab * 128 + wt * 16 + 4 * q + r;
-                if (z > mx[mt]) {
-                    sm[mt] = sm[mt] * expf(mx[mt] - z) + 1.0f;
-                    mx[mt] = z;
-                    arg[mt] = v;
-                } else {
-                    sm[mt] += expf(z - mx[mt]);
-                }
-            }
-    }
-    // merge the four lanes (q = 0..3) that hold the same row
+            for (int r = 0; r < 4; ++r) acc[mt][r] += base[(size_t)sg * seg_stride + mt * 256 + r * 64 + lane];
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) {
+        // lane (rho, q) holds logits 4q .. 4q + 3 of the tile for row rho, in ascending order
+        float mx = -INFINITY, sm = 0.f;
+        int arg = 0;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) fc_argmax_merge(mx, arg, sm, acc[mt][r], slab * 128 + wt * 16 + 4 * q + r, 1.0f);
 #pragma unroll
         for (int off = 16; off < 64; off <<= 1) {
-            const float mx2 = __shfl_xor(mx[mt], off, 64), sm2 = __shfl_xor(sm[mt], off, 64);
-            const int arg2 = __shfl_xor(arg[mt], off, 64);
-            fc_argmax_merge(mx[mt], arg[mt], sm[mt], mx2, arg2, sm2);
+            const float mx2 = __shfl_xor(mx, off, 64), sm2 = __shfl_xor(sm, off, 64);
+            const int arg2 = __shfl_xor(arg, off, 64);
+            fc_argmax_merge(mx, arg, sm, mx2, arg2, sm2);
         }
-        const int m = m0 + 16 * mt + rho;
-        if (q == 0 && m < p.M) {
-            const size_t at = (size_t)slab * p.M + m;
-            p.am.mx[at] = mx[mt];
-            p.am.arg[at] = arg[mt];
-            p.am.sm[at] = sm[mt];
+        if (q == 0) {
+            s_mx[wt][16 * mt + rho] = mx;
+            s_sm[wt][16 * mt + rho] = sm;
+            s_arg[wt][16 * mt + rho] = arg;
         }
+    }
+    __syncthreads();
+    const int row = threadIdx.x;  // one thread per row merges the eight tiles
+    if (row < 16 * MT && m0 + row < p.M) {
+        float mx = s_mx[0][row], sm = s_sm[0][row];
+        int arg = s_arg[0][row];
+        for (int w2 = 1; w2 < 8; ++w2) fc_argmax_merge(mx, arg, sm, s_mx[w2][row], s_arg[w2][row], s_sm[w2][row]);
+        const size_t at = (size_t)slab * p.M + m0 + row;
+        p.am.mx[at] = mx;
+        p.am.arg[at] = arg;
+        p.am.sm[at] = sm;
     }
 }
 
@@ -414,10 +407,10 @@ hipError_t fc_launch_linear_skinny(const FcSkinnyPlan &pl, int mode, const void 
         const dim3 g1((unsigned)pl.G, (unsigned)pl.chunks), g2((unsigned)pl.slabs, (unsigned)pl.chunks);
         if (pl.mt == 1) {
             k_linear_stream<1, KSL, FC_LIN_RESIDUAL><<<g1, dim3(512), 0, s>>>(a);
-            k_lmhead_finish<1, KSL><<<g2, dim3(64), 0, s>>>(a);
+            k_lmhead_finish<1, KSL><<<g2, dim3(512), 0, s>>>(a);
         } else {
             k_linear_stream<2, KSL, FC_LIN_RESIDUAL><<<g1, dim3(512), 0, s>>>(a);
-            k_lmhead_finish<2, KSL><<<g2, dim3(64), 0, s>>>(a);
+            k_lmhead_finish<2, KSL><<<g2, dim3(512), 0, s>>>(a);
         }
         return hipGetLastError();
     }

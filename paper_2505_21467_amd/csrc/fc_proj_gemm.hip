@@ -55,6 +55,7 @@ struct GemmArgs {
     float *part;           // EPI 3: partial sums [ksplit][M][N]
     int N;                 // output columns
     int ksplit;            // EPI 3: parts the hidden dimension is cut into (blockIdx.y)
+    FcArgmaxPart am;       // EPI 4: per (slab, row) largest logit, its index, sum of exponentials
 #ifdef FC_GEMM_TUNE
     int flags;             // tuning builds only: 1 skip the multiplies, 2 skip the LDS reads, 4 skip the global loads
     unsigned long long *dbg;  // tuning builds only: time stamps (100 MHz), 8 per workgroup
@@ -100,7 +101,9 @@ __device__ __forceinline__ void wait_stages(int k)
 // head slots: 1 = out = residual + x w^T; 2 = out = silu(x w_gate^T) * (x w_up^T), a slab being 64
 // gate rows (sub-tiles 0, 1) and the same 64 up rows (sub-tiles 2, 3), so that both products of an
 // output sit in one lane like a rotary pair; 3 = fp32 partial sums of one part of the hidden dimension
-// (blockIdx.y), for matrices with too few slabs to fill the chip.
+// (blockIdx.y), for matrices with too few slabs to fill the chip; 4 = vocabulary projection of the
+// unmasking step: of the 128 logits of a slab only the largest, its index and the sum of
+// exp(logit - largest) are kept per row (NSUB = 4 only).
 template <int KS, int NW, int NSUB, int MW, int NG, int SLOTS, int NL, int EPI>
 __global__ __launch_bounds__((NW + NL) * 64) void k_proj_gemm(GemmArgs p)
 {
@@ -317,6 +320,41 @@ __global__ __launch_bounds__((NW + NL) * 64) void k_proj_gemm(GemmArgs p)
     // register r of sub-tile t is feature 32 t' + 8 (r >> 2) + 4 hi + (r & 3) of the head, with t' = t
     // for a whole head and {half, half + 2} for a half head.
     if (!head_valid) return;
+    if (EPI == 4) {
+        // Lane (col, hi) holds, for window row col, the logits 32 t + 8 (r >> 2) + 4 hi + (r & 3) of the
+        // slab: ascending in (t, r), so ties keep the smaller index; the other half is in lane ^ 32.
+        static_assert(EPI != 4 || NSUB == 4, "vocabulary mode uses whole slabs");
+#pragma unroll
+        for (int i = 0; i < MW; ++i) {
+            const int m = m0 + 32 * (wm * MW + i) + col;
+            float mx = -INFINITY, sm = 0.f;
+            int arg = 0;
+#pragma unroll
+            for (int t = 0; t < NSUB; ++t)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const float z = acc[i][t][r];
+                    const int v = hs * 128 + 32 * t + 8 * (r >> 2) + 4 * hi + (r & 3);
+                    if (z > mx) {
+                        sm = sm * expf(mx - z) + 1.0f;
+                        mx = z;
+                        arg = v;
+                    } else {
+                        sm += expf(z - mx);
+                    }
+                }
+            const float mx2 = __shfl_xor(mx, 32, 64), sm2 = __shfl_xor(sm, 32, 64);
+            const int arg2 = __shfl_xor(arg, 32, 64);
+            fc_argmax_merge(mx, arg, sm, mx2, arg2, sm2);
+            if (hi == 0 && m < p.M) {
+                const size_t at = (size_t)hs * p.M + m;
+                p.am.mx[at] = mx;
+                p.am.arg[at] = arg;
+                p.am.sm[at] = sm;
+            }
+        }
+        return;
+    }
     if (EPI != 0) {
         // Plain linear layers.  Register r of sub-tile t of lane (col, hi) is output column
         // 32 t' + 8 (r >> 2) + 4 hi + (r & 3) of the slab (of its 64 outputs for EPI 2, t' < 2).
@@ -501,7 +539,7 @@ FcWidePlan fc_plan_wide(int dtype, int mode, int M, int K, int N)
     p.kind = 0;
     p.shape = 0;
     p.ksplit = 1;
-    const int per_slab = mode == FC_LIN_GATE_UP ? 64 : 128;
+    const int per_slab = mode == FC_LIN_GATE_UP ? 64 : 128;  // FC_LIN_VOCAB: slabs of 128 vocabulary rows
     if (dtype != FC_BF16 || M <= 32 || K < 4 * KS_MIN || K % KS_MIN != 0 || N < per_slab || N % per_slab != 0) return p;
     // 32-bit byte offsets inside X and each weight matrix
     if ((int64_t)N * K * 2 >= ((int64_t)1 << 32) || (int64_t)M * K * 2 >= ((int64_t)1 << 32)) return p;
@@ -509,7 +547,7 @@ FcWidePlan fc_plan_wide(int dtype, int mode, int M, int K, int N)
     const int64_t units = N / per_slab, t256 = (M + 255) / 256, t128 = (M + 127) / 128;
     // the largest tile that still gives the chip about one workgroup per compute unit
     if (units * t256 >= 192) p.shape = 0;
-    else if (units * t128 >= 144) p.shape = 1;
+    else if (units * t128 >= 144 || mode == FC_LIN_VOCAB) p.shape = 1;
     else p.shape = 2;
     // too few slabs even for the smallest tile: also cut the hidden dimension (partial sums in fp32)
     const int64_t wgs = 2 * units * t128;
@@ -522,7 +560,7 @@ FcWidePlan fc_plan_wide(int dtype, int mode, int M, int K, int N)
     }
     if (const char *e = getenv("FC_LIN_WIDE_SHAPE")) {  // tuning knobs
         const int v = atoi(e);
-        if (v >= 0 && v <= 2) p.shape = v;
+        if (v >= 0 && v <= (mode == FC_LIN_VOCAB ? 1 : 2)) p.shape = v;
     }
     if (const char *e = getenv("FC_LIN_KSPLIT")) {
         const int v = atoi(e);
@@ -537,7 +575,8 @@ size_t fc_wide_workspace(const FcWidePlan &p, int M, int N)
 }
 
 hipError_t fc_launch_linear_wide(const FcWidePlan &pl, int mode, const void *x, const void *w, const void *w2,
-                                 const void *res, int M, int K, int N, void *out, void *workspace, hipStream_t s)
+                                 const void *res, int M, int K, int N, void *out, void *workspace, hipStream_t s,
+                                 const FcArgmaxPart *am)
 {
     if (pl.kind != 1 || (pl.ksplit > 1 && !workspace)) return hipErrorInvalidValue;
     GemmArgs a;
@@ -554,6 +593,11 @@ hipError_t fc_launch_linear_wide(const FcWidePlan &pl, int mode, const void *x, 
     a.N = N;
     a.n_slots = mode == FC_LIN_GATE_UP ? N / 64 : N / 128;
     a.ksplit = pl.ksplit;
+    if (mode == FC_LIN_VOCAB) {
+        if (!am || pl.shape > 1) return hipErrorInvalidValue;
+        a.am = *am;
+        return pl.shape == 0 ? launch_gemm<64, 8, 4, 1, 1, 3, 0, 4>(a, s) : launch_gemm<64, 4, 4, 1, 1, 4, 4, 4>(a, s);
+    }
     if (mode == FC_LIN_GATE_UP) return launch_wide_shape<2>(pl.shape, a, s);
     if (pl.ksplit <= 1) return launch_wide_shape<1>(pl.shape, a, s);
     hipError_t e = launch_wide_shape<3>(pl.shape, a, s);

@@ -56,13 +56,15 @@ __global__ __launch_bounds__(256) void k_lmhead_generic(const T *__restrict__ X,
     }
 }
 
-// Merge of the vocabulary parts of one row: one wave per row.
-__global__ __launch_bounds__(64) void k_lmhead_reduce(FcArgmaxPart am, int parts, int M, int32_t *tok, float *conf)
+// Merge of the vocabulary parts of one row: one workgroup per row.
+__global__ __launch_bounds__(256) void k_lmhead_reduce(FcArgmaxPart am, int parts, int M, int32_t *tok, float *conf)
 {
-    const int m = blockIdx.x, lane = threadIdx.x;
+    __shared__ float s_mx[4], s_sm[4];
+    __shared__ int s_arg[4];
+    const int m = blockIdx.x, tid = threadIdx.x;
     float mx = -INFINITY, sm = 0.f;
     int arg = 0x7fffffff;
-    for (int pt = lane; pt < parts; pt += 64) {
+    for (int pt = tid; pt < parts; pt += 256) {
         const size_t at = (size_t)pt * M + m;
         fc_argmax_merge(mx, arg, sm, am.mx[at], am.arg[at], am.sm[at]);
     }
@@ -71,7 +73,14 @@ __global__ __launch_bounds__(64) void k_lmhead_reduce(FcArgmaxPart am, int parts
         const int arg2 = __shfl_xor(arg, off, 64);
         fc_argmax_merge(mx, arg, sm, mx2, arg2, sm2);
     }
-    if (lane == 0) {
+    if ((tid & 63) == 0) {
+        s_mx[tid >> 6] = mx;
+        s_sm[tid >> 6] = sm;
+        s_arg[tid >> 6] = arg;
+    }
+    __syncthreads();
+    if (tid == 0) {
+        for (int w2 = 1; w2 < 4; ++w2) fc_argmax_merge(mx, arg, sm, s_mx[w2], s_arg[w2], s_sm[w2]);
         tok[m] = arg;
         conf[m] = 1.0f / sm;
     }
@@ -153,7 +162,7 @@ hipError_t fc_launch_lmhead_generic(int dtype, const void *x, const void *w, int
 hipError_t fc_launch_lmhead_reduce(const FcArgmaxPart &am, int parts, int M, int32_t *tok, float *conf,
                                    hipStream_t s)
 {
-    k_lmhead_reduce<<<dim3((unsigned)M), dim3(64), 0, s>>>(am, parts, M, tok, conf);
+    k_lmhead_reduce<<<dim3((unsigned)M), dim3(256), 0, s>>>(am, parts, M, tok, conf);
     return hipGetLastError();
 }
 

@@ -66,6 +66,16 @@ def test_lm_head_argmax_matches_oracle(dtype, M, K, V):
     _check_lm_head(dtype, x, w, "lm_head %s %dx%dx%d" % (dtype, M, K, V))
 
 
+@pytest.mark.parametrize("shape", ["0", "1"])
+def test_lm_head_argmax_wide_window(shape, monkeypatch):
+    # more than 32 rows: the tiled GEMM keeps arg-max and confidence per slab in its epilogue
+    monkeypatch.setenv("FC_LIN_WIDE_SHAPE", shape)
+    for M, K, V in ((100, 1024, 640), (256, 3584, 2048)):
+        x = inputs.normal(23, "x", (M, K), 1.0, "bf16")
+        w = inputs.normal(23, "w", (V, K), 0.03, "bf16")
+        _check_lm_head("bf16", x, w, "wide lm_head shape %s %dx%dx%d" % (shape, M, K, V))
+
+
 def test_lm_head_exact_ties_go_to_the_smaller_index():
     # identical vocabulary rows give bit-identical logits on both sides: the smaller index must win, also
     # across slabs and across the lanes / waves that hold one row's logits
@@ -80,6 +90,10 @@ def test_lm_head_exact_ties_go_to_the_smaller_index():
     rt, rc = orc.lm_head_argmax(inputs.as_oracle(x), inputs.as_oracle(w))
     assert np.all(rt == 77) and np.array_equal(tok, rt)
     assert np.allclose(conf, rc, rtol=2e-3) and np.all(conf <= 0.2 + 1e-6)   # five tokens share the mass
+    # the same on the tiled-GEMM path (more than 32 rows)
+    x2 = torch.cat([x] * 5)
+    tok2, conf2 = _lm_head("bf16", x2, w)
+    assert np.all(tok2 == 77) and np.allclose(conf2, np.tile(rc, 5), rtol=2e-3)
 
 
 def _random_case(rng, B, A, L, mask, frac_masked=0.6, pad=0.15):
