@@ -277,6 +277,16 @@ fc_status fc_unmask_select(const int32_t *tok, const float *conf, const int32_t 
                            int32_t B, int32_t A, int32_t n_unmask, int32_t mask_id, int32_t *tokens,
                            int32_t L, int32_t *pos_next, int32_t *count_next, void *stream);
 
+/* Row gather: out[i][:] = table[idx[i]][:], zeros where idx[i] is negative (or >= rows: the kernel
+ * never reads out of bounds).  With table = the embedding matrix and idx = the token ids of the
+ * window rows it forms the layer input of a step (x_t restricted to the window, section 3.1); with
+ * table = the hidden states it compacts the rows of a block.  Pure bit copies.
+ *   table  device [rows][width] (element type dtype);  idx  device int32 [n];  out  device [n][width]
+ *   width * element size must be a multiple of 16 bytes.
+ * Errors: INVALID_ARG, UNSUPPORTED (row size not a multiple of 16 bytes), HIP. */
+fc_status fc_gather_rows(int32_t dtype, const void *table, int32_t rows, int32_t width, const int32_t *idx,
+                         int32_t n, void *out, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

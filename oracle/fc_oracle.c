@@ -474,3 +474,20 @@ int fco_unmask_select(const int32_t *tok, const double *conf, const int32_t *pos
     }
     return 0;
 }
+
+/* Row gather: out[i][:] = table[idx[i]][:] for idx[i] in [0, R), zeros for a negative idx[i].  It is the
+ * embedding lookup of the token ids of the window rows (x_t restricted to the window, section 3.1) and
+ * the compaction of a block's rows.  Returns 2 if an index is >= R. */
+int fco_gather_rows(const float *table, int64_t R, int32_t d, const int32_t *idx, int64_t n, float *out)
+{
+    if (!table || !idx || !out || R < 1 || d < 1 || n < 1) return 1;
+    for (int64_t i = 0; i < n; ++i)
+        if (idx[i] >= R) return 2;
+    for (int64_t i = 0; i < n; ++i) {
+        if (idx[i] < 0)
+            memset(out + (size_t)i * d, 0, sizeof(float) * (size_t)d);
+        else
+            memcpy(out + (size_t)i * d, table + (size_t)idx[i] * d, sizeof(float) * (size_t)d);
+    }
+    return 0;
+}

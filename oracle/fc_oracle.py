@@ -68,7 +68,7 @@ def lib():
         L.fco_round_array.restype = None
         for name in ("fco_project_rope", "fco_scatter", "fco_attend", "fco_layer_step", "fco_window",
                      "fco_rmsnorm", "fco_linear_residual", "fco_ffn_gate_up", "fco_full_layer_step",
-                     "fco_lm_head_argmax", "fco_unmask_select"):
+                     "fco_lm_head_argmax", "fco_unmask_select", "fco_gather_rows"):
             getattr(L, name).restype = ctypes.c_int
         _lib = L
     return _lib
@@ -340,3 +340,17 @@ def unmask_select(tok, conf, pos, n_unmask, mask_id, tokens):
         raise IndexError("position beyond the sequence")
     _check(rc, "fco_unmask_select")
     return pos_next, count
+
+
+def gather_rows(table, idx):
+    """out[i] = table[idx[i]] (zeros for a negative index); table [R, d] float32, idx int32 [n]."""
+    table = _f32(table)
+    R, d = table.shape
+    idx = np.ascontiguousarray(idx, dtype=np.int32).reshape(-1)
+    out = np.empty((idx.size, d), np.float32)
+    rc = lib().fco_gather_rows(_p(table, ctypes.c_float), ctypes.c_int64(R), ctypes.c_int32(d),
+                               _p(idx, ctypes.c_int32), ctypes.c_int64(idx.size), _p(out, ctypes.c_float))
+    if rc == 2:
+        raise IndexError("row index beyond the table")
+    _check(rc, "fco_gather_rows")
+    return out

@@ -23,7 +23,7 @@ EXPORTS = (
     "fc_workspace_bytes", "fc_active_attention", "fc_refresh",
     "fc_rmsnorm", "fc_linear_workspace_bytes", "fc_linear_residual", "fc_ffn_gate_up",
     "fc_full_layer_workspace_bytes", "fc_full_layer_step",
-    "fc_lm_head_workspace_bytes", "fc_lm_head_argmax", "fc_unmask_select",
+    "fc_lm_head_workspace_bytes", "fc_lm_head_argmax", "fc_unmask_select", "fc_gather_rows",
 )
 
 
@@ -103,6 +103,8 @@ def lib():
         L.fc_lm_head_argmax.argtypes = [i32, vp, vp, i32, i32, i32, vp, vp, vp, sz, vp]
         L.fc_unmask_select.restype = ctypes.c_int
         L.fc_unmask_select.argtypes = [vp, vp, vp, i32, i32, i32, i32, i32, vp, i32, vp, vp, vp]
+        L.fc_gather_rows.restype = ctypes.c_int
+        L.fc_gather_rows.argtypes = [i32, vp, i32, i32, vp, i32, vp, vp]
         _lib = L
     return _lib
 
@@ -261,3 +263,7 @@ def fc_unmask_select(tok, conf, pos, win_start, B, A, n_unmask, mask_id, tokens,
                      stream=None) -> None:
     _check(lib().fc_unmask_select(_ptr(tok), _ptr(conf), _ptr(pos), win_start, B, A, n_unmask, mask_id,
                                   _ptr(tokens), L, _ptr(pos_next), _ptr(count_next), _stream(stream)))
+
+
+def fc_gather_rows(dtype, table, rows, width, idx, n, out, stream=None) -> None:
+    _check(lib().fc_gather_rows(DTYPE_CODE[dtype], _ptr(table), rows, width, _ptr(idx), n, _ptr(out), _stream(stream)))

@@ -676,4 +676,18 @@ fc_status fc_unmask_select(const int32_t *tok, const float *conf, const int32_t 
     return e == hipSuccess ? FC_OK : hip_fail(e, "unmask launch");
 }
 
+fc_status fc_gather_rows(int32_t dtype, const void *table, int32_t rows, int32_t width, const int32_t *idx, int32_t n,
+                         void *out, void *stream)
+{
+    fc_status st = check_dtype(dtype);
+    if (st != FC_OK) return st;
+    if (!table || !idx || !out) return fail(FC_ERR_INVALID_ARG, "table, idx or out is NULL");
+    if (rows < 1 || width < 1 || n < 1) return fail(FC_ERR_INVALID_ARG, "rows, width and n must be >= 1");
+    const size_t row_bytes = (size_t)width * esize_of(dtype);
+    if (row_bytes % 16 != 0) return fail(FC_ERR_UNSUPPORTED, "row size %zu is not a multiple of 16 bytes", row_bytes);
+    if (((uintptr_t)table | (uintptr_t)out) & 15) return fail(FC_ERR_INVALID_ARG, "pointers must be 16-byte aligned");
+    hipError_t e = fc_launch_gather_rows(table, rows, (int)row_bytes, idx, n, out, (hipStream_t)stream);
+    return e == hipSuccess ? FC_OK : hip_fail(e, "gather launch");
+}
+
 }  // extern "C"

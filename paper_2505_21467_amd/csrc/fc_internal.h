@@ -147,3 +147,5 @@ size_t fc_wide_workspace(const FcWidePlan &p, int M, int N);
 hipError_t fc_launch_linear_wide(const FcWidePlan &pl, int mode, const void *x, const void *w, const void *w2,
                                  const void *res, int M, int K, int N, void *out, void *workspace, hipStream_t s,
                                  const FcArgmaxPart *am = nullptr);
+hipError_t fc_launch_gather_rows(const void *table, int64_t R, int row_bytes, const int32_t *idx, int64_t n, void *out,
+                                 hipStream_t s);

@@ -146,7 +146,25 @@ __global__ __launch_bounds__(256) void k_unmask_select(const int32_t *__restrict
     if (tid == 0) count_next[b] = n;
 }
 
+// Row gather in 16-byte pieces: out[i] = table[idx[i]], zeros for a negative or too large index.
+__global__ __launch_bounds__(256) void k_gather_rows(const uint4 *__restrict__ table, int64_t R, int pieces,
+                                                     const int32_t *__restrict__ idx, uint4 *__restrict__ out)
+{
+    const int64_t i = blockIdx.x;
+    const int32_t r = idx[i];
+    const bool ok = r >= 0 && r < R;
+    for (int c = threadIdx.x; c < pieces; c += 256)
+        out[i * pieces + c] = ok ? table[(int64_t)r * pieces + c] : make_uint4(0, 0, 0, 0);
+}
+
 }  // namespace
+
+hipError_t fc_launch_gather_rows(const void *table, int64_t R, int row_bytes, const int32_t *idx, int64_t n, void *out,
+                                 hipStream_t s)
+{
+    k_gather_rows<<<dim3((unsigned)n), dim3(256), 0, s>>>((const uint4 *)table, R, row_bytes / 16, idx, (uint4 *)out);
+    return hipGetLastError();
+}
 
 hipError_t fc_launch_lmhead_generic(int dtype, const void *x, const void *w, int M, int K, int V,
                                     const FcArgmaxPart &am, hipStream_t s)

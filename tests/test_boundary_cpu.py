@@ -247,3 +247,14 @@ def test_unmasking_entry_points_reject_bad_arguments_before_any_launch():
     _raises(fc.FC_ERR_UNSUPPORTED, U, FAKE, FAKE, FAKE, 0, 2, 9000, 4, 9, FAKE, 10000, FAKE + 256, FAKE, S)
     _raises(fc.FC_ERR_BOUNDS, U, FAKE, FAKE, None, 80, 2, 32, 4, 9, FAKE, 100, FAKE + 256, FAKE, S)
     _raises(fc.FC_ERR_BOUNDS, U, FAKE, FAKE, None, -1, 2, 32, 4, 9, FAKE, 100, FAKE + 256, FAKE, S)
+
+
+def test_gather_rows_rejects_bad_arguments_before_any_launch():
+    G = fc.fc_gather_rows
+    _raises(fc.FC_ERR_INVALID_ARG, G, "bf16", None, 10, 64, FAKE, 4, FAKE, 0)
+    _raises(fc.FC_ERR_INVALID_ARG, G, "bf16", FAKE, 10, 64, None, 4, FAKE, 0)
+    _raises(fc.FC_ERR_INVALID_ARG, G, "bf16", FAKE, 10, 64, FAKE, 4, None, 0)
+    _raises(fc.FC_ERR_INVALID_ARG, G, "bf16", FAKE, 0, 64, FAKE, 4, FAKE, 0)
+    _raises(fc.FC_ERR_INVALID_ARG, G, "bf16", FAKE, 10, 64, FAKE, 0, FAKE, 0)
+    _raises(fc.FC_ERR_UNSUPPORTED, G, "bf16", FAKE, 10, 12, FAKE, 4, FAKE, 0)   # 24-byte rows
+    _raises(fc.FC_ERR_INVALID_ARG, G, "bf16", FAKE + 8, 10, 64, FAKE, 4, FAKE, 0)

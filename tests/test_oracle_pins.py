@@ -682,3 +682,14 @@ def test_unmask_steps_terminate_and_fill_every_masked_window_position():
         if np.all(cnt == 0):
             break
     assert steps == -(-A // k) and not np.any(tokens[:, 5:5 + A] == MASK) and np.all(tokens[:, 18:] == MASK)
+
+
+def test_gather_rows_equals_fancy_indexing():
+    table = _rand(90, (11, 6))
+    idx = np.array([3, 3, 0, 10, -1, 7], np.int32)
+    got = orc.gather_rows(table, idx)
+    want = table[np.maximum(idx, 0)].copy()
+    want[idx < 0] = 0
+    assert np.array_equal(got, want)
+    with pytest.raises(IndexError):
+        orc.gather_rows(table, np.array([11], np.int32))
