@@ -491,3 +491,74 @@ int fco_gather_rows(const float *table, int64_t R, int32_t d, const int32_t *idx
     }
     return 0;
 }
+
+/* -------------------------------------------------------------------------
+ * Guided Diffusion acceptance (paper, section 3.2.2 and Algorithm 1; Top-K match and the guidance
+ * threshold tau from the appendix "Implementation Details").
+ *
+ * For every sequence b let i_1 < ... < i_m be the still masked window rows (pos >= 0 and
+ * tokens[b][pos] == mask_id), in row order.  For row i_j:
+ *   t_j   = argmax_v dlm[b][i_j][v]  (smallest v on ties),  zd_j = that largest logit,
+ *   top_j = the topk token ids of ar[b][i_j][.] with the largest logits (ties: smaller id first),
+ *           za_j = the largest AR logit,
+ *   match_j = t_j in top_j  and  (tau <= 0 or zd_j > (float)(tau * za_j))   -- float32 product.
+ * k = the largest prefix length with match_1 .. match_k all true.  The first max(k, 1) masked rows
+ * are filled with their DLM tokens (if no prefix agrees only i_1 is filled); n_accept[b] is that number
+ * (0 when nothing is masked).  pos_next / count_next list the rows that stay masked, as in
+ * fco_unmask_select.  Returns 2 if a position is >= L.
+ */
+int fco_guided_accept(const float *dlm, const float *ar, const int32_t *pos, int32_t B, int32_t A, int32_t V,
+                      int32_t topk, float tau, int32_t mask_id, int32_t *tokens, int32_t L, int32_t *n_accept,
+                      int32_t *pos_next, int32_t *count_next)
+{
+    if (!dlm || !ar || !pos || !tokens || !n_accept || !pos_next || !count_next || B < 1 || A < 1 || V < 1 || L < 1 ||
+        topk < 1 || topk > V)
+        return 1;
+    for (int64_t i = 0; i < (int64_t)B * A; ++i)
+        if (pos[i] >= L) return 2;
+    for (int b = 0; b < B; ++b) {
+        const int32_t *p = pos + (size_t)b * A;
+        int32_t *seq = tokens + (size_t)b * L;
+        int *rows = (int *)malloc(sizeof(int) * (size_t)A), *tdlm = (int *)malloc(sizeof(int) * (size_t)A);
+        char *used = (char *)malloc((size_t)V);
+        int m = 0;
+        for (int a = 0; a < A; ++a)
+            if (p[a] >= 0 && seq[p[a]] == mask_id) rows[m++] = a;
+        int k = 0, prefix_open = 1;
+        for (int j = 0; j < m; ++j) {
+            const float *zd = dlm + ((size_t)b * A + rows[j]) * V, *za = ar + ((size_t)b * A + rows[j]) * V;
+            int t = 0;
+            for (int v = 1; v < V; ++v)
+                if (zd[v] > zd[t]) t = v;
+            tdlm[j] = t;
+            /* the topk largest AR logits by repeated selection */
+            memset(used, 0, (size_t)V);
+            int in_top = 0, best0 = -1;
+            for (int r = 0; r < topk; ++r) {
+                int best = -1;
+                for (int v = 0; v < V; ++v)
+                    if (!used[v] && (best < 0 || za[v] > za[best])) best = v;
+                used[best] = 1;
+                if (r == 0) best0 = best;
+                if (best == t) in_top = 1;
+            }
+            const float thr = tau * za[best0]; /* float32 product */
+            const int match = in_top && (!(tau > 0.0f) || zd[t] > thr);
+            if (prefix_open && match)
+                ++k;
+            else
+                prefix_open = 0;
+        }
+        const int n = m == 0 ? 0 : (k > 0 ? k : 1);
+        for (int j = 0; j < n; ++j) seq[p[rows[j]]] = tdlm[j];
+        n_accept[b] = n;
+        int c = 0;
+        for (int j = n; j < m; ++j) pos_next[(size_t)b * A + c++] = p[rows[j]];
+        count_next[b] = c;
+        for (; c < A; ++c) pos_next[(size_t)b * A + c] = -1;
+        free(rows);
+        free(tdlm);
+        free(used);
+    }
+    return 0;
+}

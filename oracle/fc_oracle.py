@@ -68,7 +68,8 @@ def lib():
         L.fco_round_array.restype = None
         for name in ("fco_project_rope", "fco_scatter", "fco_attend", "fco_layer_step", "fco_window",
                      "fco_rmsnorm", "fco_linear_residual", "fco_ffn_gate_up", "fco_full_layer_step",
-                     "fco_lm_head_argmax", "fco_unmask_select", "fco_gather_rows"):
+                     "fco_lm_head_argmax", "fco_unmask_select", "fco_gather_rows",
+                     "fco_guided_accept"):
             getattr(L, name).restype = ctypes.c_int
         _lib = L
     return _lib
@@ -354,3 +355,27 @@ def gather_rows(table, idx):
         raise IndexError("row index beyond the table")
     _check(rc, "fco_gather_rows")
     return out
+
+
+def guided_accept(dlm, ar, pos, topk, tau, mask_id, tokens):
+    """Guided Diffusion acceptance (Algorithm 1 with Top-K match and threshold tau); tokens [B, L] int32
+    updated in place.  dlm, ar: float32 logits [B, A, V].  Returns (n_accept [B], pos_next [B, A], count [B])."""
+    pos = np.ascontiguousarray(pos, dtype=np.int32)
+    B, A = pos.shape
+    dlm, ar = _f32(dlm), _f32(ar)
+    V = dlm.shape[-1]
+    assert dlm.shape == (B, A, V) == ar.shape
+    assert tokens.dtype == np.int32 and tokens.flags.c_contiguous and tokens.shape[0] == B
+    L = tokens.shape[1]
+    n_acc = np.empty((B,), np.int32)
+    pos_next = np.empty((B, A), np.int32)
+    count = np.empty((B,), np.int32)
+    rc = lib().fco_guided_accept(_p(dlm, ctypes.c_float), _p(ar, ctypes.c_float), _p(pos, ctypes.c_int32),
+                                 ctypes.c_int32(B), ctypes.c_int32(A), ctypes.c_int32(V), ctypes.c_int32(topk),
+                                 ctypes.c_float(tau), ctypes.c_int32(mask_id), _p(tokens, ctypes.c_int32),
+                                 ctypes.c_int32(L), _p(n_acc, ctypes.c_int32), _p(pos_next, ctypes.c_int32),
+                                 _p(count, ctypes.c_int32))
+    if rc == 2:
+        raise IndexError("position beyond the sequence")
+    _check(rc, "fco_guided_accept")
+    return n_acc, pos_next, count

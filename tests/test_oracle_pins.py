@@ -693,3 +693,88 @@ def test_gather_rows_equals_fancy_indexing():
     assert np.array_equal(got, want)
     with pytest.raises(IndexError):
         orc.gather_rows(table, np.array([11], np.int32))
+
+
+# --------------------------------------------------------------------------- Guided Diffusion acceptance
+
+def _accept_reference(dlm, ar, pos, topk, tau, mask_id, tokens):
+    """Plain-Python restatement of Algorithm 1 with Top-K match: numpy argsort instead of selection loops."""
+    B, A = pos.shape
+    tokens = tokens.copy()
+    n_acc = np.zeros((B,), np.int32)
+    nxt = np.full((B, A), -1, np.int32)
+    cnt = np.zeros((B,), np.int32)
+    for b in range(B):
+        rows = [a for a in range(A) if pos[b, a] >= 0 and tokens[b, pos[b, a]] == mask_id]
+        k = 0
+        t = {}
+        for j, a in enumerate(rows):
+            t[a] = int(np.argmax(dlm[b, a]))                                  # first maximum = smallest id
+            order = np.lexsort((np.arange(dlm.shape[-1]), -ar[b, a].astype(np.float64)))  # by (-logit, id)
+            top = set(int(v) for v in order[:topk])
+            ok = t[a] in top and (tau <= 0 or dlm[b, a, t[a]] > np.float32(tau) * ar[b, a, order[0]])
+            if ok and k == j:
+                k += 1
+        n = 0 if not rows else max(k, 1)
+        for a in rows[:n]:
+            tokens[b, pos[b, a]] = t[a]
+        n_acc[b] = n
+        rest = rows[n:]
+        nxt[b, :len(rest)] = [pos[b, a] for a in rest]
+        cnt[b] = len(rest)
+    return tokens, n_acc, nxt, cnt
+
+
+def test_guided_accept_worked_example():
+    MASK, V = 9, 6
+    # one sequence, window rows at positions 2..6; position 3 is already unmasked
+    tokens = np.array([[1, 1, MASK, 4, MASK, MASK, MASK]], np.int32)
+    pos = np.array([[2, 3, 4, 5, 6]], np.int32)
+    dlm = np.full((1, 5, V), -1.0, np.float32)
+    ar = np.full((1, 5, V), -1.0, np.float32)
+    dlm[0, 0, 2] = 3.0; ar[0, 0, 2] = 5.0                      # row 0: both say 2 -> match
+    dlm[0, 1, 0] = 9.0; ar[0, 1, 5] = 9.0                      # row 1 is not masked: ignored
+    dlm[0, 2, 4] = 3.0; ar[0, 2, 1] = 5.0; ar[0, 2, 4] = 4.0   # row 2: DLM's 4 is the AR's second choice
+    dlm[0, 3, 3] = 3.0; ar[0, 3, 0] = 5.0                      # row 3: disagree
+    dlm[0, 4, 1] = 3.0; ar[0, 4, 1] = 5.0                      # row 4: agree, but behind a disagreement
+    t = tokens.copy()
+    n, nxt, cnt = orc.guided_accept(dlm, ar, pos, 1, 0.0, MASK, t)         # Top-1: prefix = row 0 only
+    assert n[0] == 1 and list(t[0]) == [1, 1, 2, 4, MASK, MASK, MASK] and list(nxt[0]) == [4, 5, 6, -1, -1]
+    t = tokens.copy()
+    n, nxt, cnt = orc.guided_accept(dlm, ar, pos, 2, 0.0, MASK, t)         # Top-2: rows 0 and 2, stops at row 3
+    assert n[0] == 2 and list(t[0]) == [1, 1, 2, 4, 4, MASK, MASK] and list(nxt[0]) == [5, 6, -1, -1, -1] and cnt[0] == 2
+    # no agreement at the first masked row: only that one is filled, with the DLM's token
+    d2 = dlm.copy(); d2[0, 0, 2] = -1.0; d2[0, 0, 5] = 3.0
+    t = tokens.copy()
+    n, nxt, cnt = orc.guided_accept(d2, ar, pos, 2, 0.0, MASK, t)
+    assert n[0] == 1 and t[0, 2] == 5 and cnt[0] == 3
+    # threshold: DLM logit 3 must exceed tau * AR maximum 5: tau 0.5 passes (3 > 2.5), tau 0.7 fails (3 < 3.5)
+    t = tokens.copy()
+    assert orc.guided_accept(dlm, ar, pos, 2, 0.5, MASK, t)[0][0] == 2
+    t = tokens.copy()
+    n, _, _ = orc.guided_accept(dlm, ar, pos, 2, 0.7, MASK, t)
+    assert n[0] == 1 and t[0, 2] == 2 and t[0, 4] == MASK                   # fallback: first masked row only
+    # nothing masked: nothing happens
+    t = np.array([[1, 1, 2, 4, 4, 3, 1]], np.int32)
+    n, nxt, cnt = orc.guided_accept(dlm, ar, pos, 2, 0.0, MASK, t)
+    assert n[0] == 0 and cnt[0] == 0 and np.all(nxt == -1) and list(t[0]) == [1, 1, 2, 4, 4, 3, 1]
+
+
+def test_guided_accept_brute_force():
+    rng = np.random.default_rng(11)
+    MASK = 77
+    for trial in range(30):
+        B, A, V, L = int(rng.integers(1, 4)), int(rng.integers(1, 12)), int(rng.integers(3, 20)), 30
+        pos = np.stack([np.sort(rng.choice(L, A, replace=False)) for _ in range(B)]).astype(np.int32)
+        pos[rng.random((B, A)) < 0.1] = -1
+        tokens = rng.integers(0, V, (B, L)).astype(np.int32)
+        tokens[rng.random((B, L)) < 0.7] = MASK
+        dlm = np.round(rng.normal(0, 2, (B, A, V)), 0).astype(np.float32)    # integer-valued: many ties
+        ar = dlm + np.round(rng.normal(0, 1, (B, A, V)), 0).astype(np.float32)
+        topk, tau = int(rng.integers(1, min(V, 5) + 1)), float(rng.choice([0.0, 0.5, 1.0]))
+        want = _accept_reference(dlm, ar, pos, topk, tau, MASK, tokens)
+        got_t = tokens.copy()
+        n, nxt, cnt = orc.guided_accept(dlm, ar, pos, topk, tau, MASK, got_t)
+        assert np.array_equal(got_t, want[0]) and np.array_equal(n, want[1])
+        assert np.array_equal(nxt, want[2]) and np.array_equal(cnt, want[3])
+        assert np.all((n >= 1) | (cnt + n == 0))          # progress whenever something is masked
