@@ -287,6 +287,29 @@ fc_status fc_unmask_select(const int32_t *tok, const float *conf, const int32_t 
 fc_status fc_gather_rows(int32_t dtype, const void *table, int32_t rows, int32_t width, const int32_t *idx,
                          int32_t n, void *out, void *stream);
 
+/* ---------------------------------------------------------------------------------------------
+ * Guided Diffusion acceptance (section 3.2.2 and Algorithm 1: the diffusion model proposes a token
+ * for every masked position, an auto-regressive guide scores the proposal, and the longest prefix of
+ * masked positions on which both agree is unmasked; if they disagree at the first one, only that one
+ * is unmasked, with the diffusion model's token.  "Top-K match" and the guidance threshold tau are
+ * from the paper's implementation details).
+ * For every sequence b, over its still masked window rows i_1 < i_2 < ... (position valid and
+ * tokens[b][p] == mask_id):  t_j = argmax_v dlm[b][i_j][v] (smallest v on ties);  row j matches when
+ * t_j is among the topk largest entries of ar[b][i_j][.] (ties: smaller id first) and, if tau > 0,
+ * max_v dlm[b][i_j][v] > tau * max_v ar[b][i_j][v] (float product).  With k = the longest prefix of
+ * matching rows, the first max(k, 1) masked rows get tokens[b][p] = t_j.
+ *   dlm, ar  device float [B][A][V] logits;  pos  device int32 [B][A] or NULL = win_start + a;
+ *   tokens  device int32 [B][L], updated in place;  n_accept  device int32 [B] (0 if nothing was masked);
+ *   pos_next  device int32 [B][A], count_next  device int32 [B]: the rows that stay masked (as for
+ *   fc_unmask_select);  workspace  device, >= fc_guided_accept_workspace_bytes(B, A) bytes.
+ * topk is limited to 8.  Integer work on given floats: bit-exact.
+ * Errors: INVALID_ARG, UNSUPPORTED (topk > 8), BOUNDS (pos NULL and window outside [0, L)), WORKSPACE, HIP. */
+size_t fc_guided_accept_workspace_bytes(int32_t B, int32_t A);
+fc_status fc_guided_accept(const float *dlm, const float *ar, const int32_t *pos, int32_t win_start, int32_t B,
+                           int32_t A, int32_t V, int32_t topk, float tau, int32_t mask_id, int32_t *tokens,
+                           int32_t L, int32_t *n_accept, int32_t *pos_next, int32_t *count_next, void *workspace,
+                           size_t workspace_bytes, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

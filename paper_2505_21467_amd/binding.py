@@ -24,6 +24,7 @@ EXPORTS = (
     "fc_rmsnorm", "fc_linear_workspace_bytes", "fc_linear_residual", "fc_ffn_gate_up",
     "fc_full_layer_workspace_bytes", "fc_full_layer_step",
     "fc_lm_head_workspace_bytes", "fc_lm_head_argmax", "fc_unmask_select", "fc_gather_rows",
+    "fc_guided_accept_workspace_bytes", "fc_guided_accept",
 )
 
 
@@ -105,6 +106,11 @@ def lib():
         L.fc_unmask_select.argtypes = [vp, vp, vp, i32, i32, i32, i32, i32, vp, i32, vp, vp, vp]
         L.fc_gather_rows.restype = ctypes.c_int
         L.fc_gather_rows.argtypes = [i32, vp, i32, i32, vp, i32, vp, vp]
+        L.fc_guided_accept_workspace_bytes.restype = sz
+        L.fc_guided_accept_workspace_bytes.argtypes = [i32, i32]
+        L.fc_guided_accept.restype = ctypes.c_int
+        L.fc_guided_accept.argtypes = [vp, vp, vp, i32, i32, i32, i32, i32, ctypes.c_float, i32, vp, i32, vp, vp, vp, vp,
+                                       sz, vp]
         _lib = L
     return _lib
 
@@ -267,3 +273,16 @@ def fc_unmask_select(tok, conf, pos, win_start, B, A, n_unmask, mask_id, tokens,
 
 def fc_gather_rows(dtype, table, rows, width, idx, n, out, stream=None) -> None:
     _check(lib().fc_gather_rows(DTYPE_CODE[dtype], _ptr(table), rows, width, _ptr(idx), n, _ptr(out), _stream(stream)))
+
+
+def fc_guided_accept_workspace_bytes(B, A) -> int:
+    return int(lib().fc_guided_accept_workspace_bytes(B, A))
+
+
+def fc_guided_accept(dlm, ar, pos, win_start, B, A, V, topk, tau, mask_id, tokens, L, n_accept, pos_next, count_next,
+                     workspace, workspace_bytes=None, stream=None) -> None:
+    if workspace_bytes is None:
+        workspace_bytes = _nbytes(workspace)
+    _check(lib().fc_guided_accept(_ptr(dlm), _ptr(ar), _ptr(pos), win_start, B, A, V, topk, tau, mask_id, _ptr(tokens),
+                                  L, _ptr(n_accept), _ptr(pos_next), _ptr(count_next), _ptr(workspace),
+                                  workspace_bytes, _stream(stream)))

@@ -690,4 +690,32 @@ fc_status fc_gather_rows(int32_t dtype, const void *table, int32_t rows, int32_t
     return e == hipSuccess ? FC_OK : hip_fail(e, "gather launch");
 }
 
+size_t fc_guided_accept_workspace_bytes(int32_t B, int32_t A)
+{
+    if (B < 1 || A < 1 || B > 65535 || A > 65535) return 0;
+    return (size_t)2 * B * A * sizeof(int32_t);
+}
+
+fc_status fc_guided_accept(const float *dlm, const float *ar, const int32_t *pos, int32_t win_start, int32_t B, int32_t A,
+                           int32_t V, int32_t topk, float tau, int32_t mask_id, int32_t *tokens, int32_t L,
+                           int32_t *n_accept, int32_t *pos_next, int32_t *count_next, void *workspace,
+                           size_t workspace_bytes, void *stream)
+{
+    if (!dlm || !ar || !tokens || !n_accept || !pos_next || !count_next)
+        return fail(FC_ERR_INVALID_ARG, "dlm, ar, tokens, n_accept, pos_next or count_next is NULL");
+    if (B < 1 || A < 1 || V < 1 || L < 1 || topk < 1 || topk > V) return fail(FC_ERR_INVALID_ARG, "B, A, V, L >= 1 and 1 <= topk <= V required");
+    if (!isfinite(tau)) return fail(FC_ERR_INVALID_ARG, "tau must be finite");
+    if (topk > FC_ACCEPT_MAX_TOPK) return fail(FC_ERR_UNSUPPORTED, "topk %d exceeds %d", topk, FC_ACCEPT_MAX_TOPK);
+    if (B > 65535 || A > 65535) return fail(FC_ERR_UNSUPPORTED, "B and A are limited to 65535");
+    if (pos == pos_next) return fail(FC_ERR_INVALID_ARG, "pos_next must not be pos");
+    if (!pos && (win_start < 0 || win_start > L - A))
+        return fail(FC_ERR_BOUNDS, "window [%d, %d+%d) outside the sequence of %d tokens", win_start, win_start, A, L);
+    const size_t need = fc_guided_accept_workspace_bytes(B, A);
+    if (!workspace || workspace_bytes < need)
+        return fail(FC_ERR_WORKSPACE, "workspace of %zu bytes needed, %zu given", need, workspace ? workspace_bytes : (size_t)0);
+    hipError_t e = fc_launch_guided_accept(dlm, ar, pos, win_start, B, A, V, topk, tau, mask_id, tokens, L, n_accept,
+                                           pos_next, count_next, workspace, (hipStream_t)stream);
+    return e == hipSuccess ? FC_OK : hip_fail(e, "acceptance launch");
+}
+
 }  // extern "C"

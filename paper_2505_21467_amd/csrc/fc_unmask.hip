@@ -146,6 +146,189 @@ __global__ __launch_bounds__(256) void k_unmask_select(const int32_t *__restrict
     if (tid == 0) count_next[b] = n;
 }
 
+// -------------------------------------------------------------------------------------------------
+// Guided Diffusion acceptance (paper, section 3.2.2, Algorithm 1; Top-K match and threshold tau from the
+// implementation details).  First kernel: one workgroup per window row that is still masked scans the
+// row's two logit vectors (DLM and AR guide): arg-max of the DLM row, the topk best ids of the AR row
+// (every thread keeps its own best list, the lists are merged by topk rounds of a block-wide arg-max),
+// and decides whether the row matches.  Second kernel: one workgroup per sequence finds the longest
+// matching prefix of the masked rows, fills it (or the first masked row) and lists the rest.
+constexpr int ACC_MAXK = 8;
+
+// (value, id) order: larger value first, then smaller id
+__device__ __forceinline__ bool acc_before(float v1, int i1, float v2, int i2) { return v1 > v2 || (v1 == v2 && i1 < i2); }
+
+__global__ __launch_bounds__(256) void k_accept_rows(const float *__restrict__ dlm, const float *__restrict__ ar,
+                                                     const int32_t *__restrict__ pos, int win_start, int A, int V,
+                                                     int topk, float tau, int mask_id, const int32_t *tokens, int L,
+                                                     int32_t *row_tok, int32_t *row_match)
+{
+    __shared__ float s_v[256];
+    __shared__ int s_i[256];
+    __shared__ int s_who;
+    const int a = blockIdx.x, b = blockIdx.y, tid = threadIdx.x;
+    const int p = pos ? pos[(size_t)b * A + a] : win_start + a;
+    const size_t at = (size_t)b * A + a;
+    if (!(p >= 0 && p < L && tokens[(size_t)b * L + p] == mask_id)) {  // not a candidate: nothing to scan
+        if (tid == 0) {
+            row_tok[at] = -1;
+            row_match[at] = -1;
+        }
+        return;
+    }
+    const float *zd = dlm + at * V, *za = ar + at * V;
+    // DLM arg-max and this thread's topk best AR entries (sorted best first; ids ascend within a thread)
+    float dv = -INFINITY;
+    int di = 0x7fffffff;
+    float tv[ACC_MAXK];
+    int ti[ACC_MAXK];
+#pragma unroll
+    for (int r = 0; r < ACC_MAXK; ++r) {
+        tv[r] = -INFINITY;
+        ti[r] = 0x7fffffff;
+    }
+    for (int v = tid; v < V; v += 256) {
+        const float d = zd[v];
+        if (acc_before(d, v, dv, di)) {
+            dv = d;
+            di = v;
+        }
+        float x = za[v];
+        int xi = v;
+#pragma unroll
+        for (int r = 0; r < ACC_MAXK; ++r) {  // insertion into the sorted list
+            if (r < topk && acc_before(x, xi, tv[r], ti[r])) {
+                const float t0 = tv[r];
+                const int t1 = ti[r];
+                tv[r] = x;
+                ti[r] = xi;
+                x = t0;
+                xi = t1;
+            }
+        }
+    }
+    // block arg-max of the DLM row
+    s_v[tid] = dv;
+    s_i[tid] = di;
+    __syncthreads();
+    for (int off = 128; off > 0; off >>= 1) {
+        if (tid < off && acc_before(s_v[tid + off], s_i[tid + off], s_v[tid], s_i[tid])) {
+            s_v[tid] = s_v[tid + off];
+            s_i[tid] = s_i[tid + off];
+        }
+        __syncthreads();
+    }
+    const float zd_max = s_v[0];
+    const int t_dlm = s_i[0];
+    __syncthreads();
+    // topk rounds: the best head among the threads' lists is the next of the row's top list
+    bool in_top = false;
+    float za_max = 0.f;
+    for (int r = 0; r < topk; ++r) {
+        s_v[tid] = tv[0];
+        s_i[tid] = ti[0];
+        __syncthreads();
+        for (int off = 128; off > 0; off >>= 1) {
+            if (tid < off && acc_before(s_v[tid + off], s_i[tid + off], s_v[tid], s_i[tid])) {
+                s_v[tid] = s_v[tid + off];
+                s_i[tid] = s_i[tid + off];
+            }
+            __syncthreads();
+        }
+        const float bv = s_v[0];
+        const int bi = s_i[0];
+        if (r == 0) za_max = bv;
+        if (bi == t_dlm) in_top = true;
+        if (tid == 0) s_who = -1;
+        __syncthreads();
+        if (ti[0] == bi) s_who = tid;  // ids are unique: exactly one thread owns the winner
+        __syncthreads();
+        if (s_who == tid) {  // pop the head
+#pragma unroll
+            for (int q = 0; q + 1 < ACC_MAXK; ++q) {
+                tv[q] = tv[q + 1];
+                ti[q] = ti[q + 1];
+            }
+            tv[ACC_MAXK - 1] = -INFINITY;
+            ti[ACC_MAXK - 1] = 0x7fffffff;
+        }
+        __syncthreads();
+    }
+    if (tid == 0) {
+        const float thr = tau * za_max;
+        row_tok[at] = t_dlm;
+        row_match[at] = (in_top && (!(tau > 0.0f) || zd_max > thr)) ? 1 : 0;
+    }
+}
+
+__global__ __launch_bounds__(256) void k_accept_seq(const int32_t *__restrict__ row_tok, const int32_t *__restrict__ row_match,
+                                                    const int32_t *__restrict__ pos, int win_start, int A,
+                                                    int32_t *tokens, int L, int32_t *n_accept, int32_t *pos_next,
+                                                    int32_t *count_next)
+{
+    __shared__ int s_scan[256];
+    __shared__ int s_base, s_first_miss;
+    const int b = blockIdx.x, tid = threadIdx.x;
+    int32_t *seq = tokens + (size_t)b * L;
+    auto position = [&](int a) { return pos ? pos[(size_t)b * A + a] : win_start + a; };
+    if (tid == 0) {
+        s_base = 0;
+        s_first_miss = 0x7fffffff;
+    }
+    __syncthreads();
+    // pass 1: index j of every masked row among the masked rows; the first j that does not match
+    for (int a0 = 0; a0 < A; a0 += 256) {
+        const int a = a0 + tid;
+        const int mt = a < A ? row_match[(size_t)b * A + a] : -1;
+        s_scan[tid] = mt >= 0 ? 1 : 0;
+        __syncthreads();
+        for (int off = 1; off < 256; off <<= 1) {
+            const int v = tid >= off ? s_scan[tid - off] : 0;
+            __syncthreads();
+            s_scan[tid] += v;
+            __syncthreads();
+        }
+        if (mt == 0) atomicMin(&s_first_miss, s_base + s_scan[tid] - 1);
+        __syncthreads();
+        if (tid == 255) s_base += s_scan[255];
+        __syncthreads();
+    }
+    const int m = s_base;                                  // masked rows
+    const int k = min(s_first_miss, m);                    // longest matching prefix
+    const int n = m == 0 ? 0 : (k > 0 ? k : 1);
+    __syncthreads();
+    if (tid == 0) s_base = 0;
+    __syncthreads();
+    // pass 2: fill the first n masked rows, list the others
+    for (int a0 = 0; a0 < A; a0 += 256) {
+        const int a = a0 + tid;
+        const int mt = a < A ? row_match[(size_t)b * A + a] : -1;
+        s_scan[tid] = mt >= 0 ? 1 : 0;
+        __syncthreads();
+        for (int off = 1; off < 256; off <<= 1) {
+            const int v = tid >= off ? s_scan[tid - off] : 0;
+            __syncthreads();
+            s_scan[tid] += v;
+            __syncthreads();
+        }
+        if (mt >= 0) {
+            const int j = s_base + s_scan[tid] - 1;
+            if (j < n)
+                seq[position(a)] = row_tok[(size_t)b * A + a];
+            else
+                pos_next[(size_t)b * A + (j - n)] = position(a);
+        }
+        __syncthreads();
+        if (tid == 255) s_base += s_scan[255];
+        __syncthreads();
+    }
+    for (int a = m - n + tid; a < A; a += 256) pos_next[(size_t)b * A + a] = -1;
+    if (tid == 0) {
+        n_accept[b] = n;
+        count_next[b] = m - n;
+    }
+}
+
 // Row gather in 16-byte pieces: out[i] = table[idx[i]], zeros for a negative or too large index.
 __global__ __launch_bounds__(256) void k_gather_rows(const uint4 *__restrict__ table, int64_t R, int pieces,
                                                      const int32_t *__restrict__ idx, uint4 *__restrict__ out)
@@ -158,6 +341,19 @@ __global__ __launch_bounds__(256) void k_gather_rows(const uint4 *__restrict__ t
 }
 
 }  // namespace
+
+hipError_t fc_launch_guided_accept(const float *dlm, const float *ar, const int32_t *pos, int win_start, int B, int A,
+                                   int V, int topk, float tau, int mask_id, int32_t *tokens, int L, int32_t *n_accept,
+                                   int32_t *pos_next, int32_t *count_next, void *workspace, hipStream_t s)
+{
+    if (topk < 1 || topk > ACC_MAXK || !workspace) return hipErrorInvalidValue;
+    int32_t *row_tok = (int32_t *)workspace, *row_match = row_tok + (size_t)B * A;
+    k_accept_rows<<<dim3((unsigned)A, (unsigned)B), dim3(256), 0, s>>>(dlm, ar, pos, win_start, A, V, topk, tau, mask_id,
+                                                                       tokens, L, row_tok, row_match);
+    k_accept_seq<<<dim3((unsigned)B), dim3(256), 0, s>>>(row_tok, row_match, pos, win_start, A, tokens, L, n_accept,
+                                                         pos_next, count_next);
+    return hipGetLastError();
+}
 
 hipError_t fc_launch_gather_rows(const void *table, int64_t R, int row_bytes, const int32_t *idx, int64_t n, void *out,
                                  hipStream_t s)

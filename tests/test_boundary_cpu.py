@@ -258,3 +258,27 @@ def test_gather_rows_rejects_bad_arguments_before_any_launch():
     _raises(fc.FC_ERR_INVALID_ARG, G, "bf16", FAKE, 10, 64, FAKE, 0, FAKE, 0)
     _raises(fc.FC_ERR_UNSUPPORTED, G, "bf16", FAKE, 10, 12, FAKE, 4, FAKE, 0)   # 24-byte rows
     _raises(fc.FC_ERR_INVALID_ARG, G, "bf16", FAKE + 8, 10, 64, FAKE, 4, FAKE, 0)
+
+
+def test_guided_accept_rejects_bad_arguments_before_any_launch():
+    Gd = fc.fc_guided_accept
+    ok = dict(dlm=FAKE, ar=FAKE, pos=FAKE, win_start=0, B=2, A=32, V=1000, topk=2, tau=0.5, mask_id=9, tokens=FAKE, L=100,
+              n_accept=FAKE, pos_next=FAKE + 256, count_next=FAKE, workspace=FAKE, workspace_bytes=1 << 20, stream=0)
+    need = fc.fc_guided_accept_workspace_bytes(2, 32)
+    assert need == 2 * 2 * 32 * 4 and fc.fc_guided_accept_workspace_bytes(0, 32) == 0
+
+    def call(**kw):
+        a = dict(ok)
+        a.update(kw)
+        return lambda: Gd(**a)
+    for kw, st in [
+        (dict(dlm=None), fc.FC_ERR_INVALID_ARG), (dict(ar=None), fc.FC_ERR_INVALID_ARG),
+        (dict(tokens=None), fc.FC_ERR_INVALID_ARG), (dict(n_accept=None), fc.FC_ERR_INVALID_ARG),
+        (dict(pos_next=None), fc.FC_ERR_INVALID_ARG), (dict(count_next=None), fc.FC_ERR_INVALID_ARG),
+        (dict(B=0), fc.FC_ERR_INVALID_ARG), (dict(V=0), fc.FC_ERR_INVALID_ARG), (dict(topk=0), fc.FC_ERR_INVALID_ARG),
+        (dict(topk=9), fc.FC_ERR_UNSUPPORTED), (dict(V=1, topk=2), fc.FC_ERR_INVALID_ARG),
+        (dict(tau=float("nan")), fc.FC_ERR_INVALID_ARG), (dict(pos_next=FAKE), fc.FC_ERR_INVALID_ARG),
+        (dict(pos=None, win_start=80), fc.FC_ERR_BOUNDS), (dict(workspace=None), fc.FC_ERR_WORKSPACE),
+        (dict(workspace_bytes=need - 1), fc.FC_ERR_WORKSPACE),
+    ]:
+        _raises(st, call(**kw))

@@ -175,3 +175,70 @@ def test_unmasking_steps_chained_until_the_block_is_filled():
         if np.all(want_c == 0):
             break
     assert steps == -(-A // k) and not np.any(host_tokens[:, P:P + A] == MASK) and np.all(host_tokens[:, P + A:] == MASK)
+
+
+# --------------------------------------------------------------------------- Guided Diffusion acceptance
+
+def _gpu_accept(dlm, ar, pos, win_start, topk, tau, mask, tokens):
+    B, A, V = dlm.shape
+    L = tokens.shape[1]
+    td = torch.from_numpy(tokens.copy()).to(DEV)
+    n = torch.full((B,), -9, dtype=torch.int32, device=DEV)
+    pn = torch.full((B, A), -9, dtype=torch.int32, device=DEV)
+    cn = torch.full((B,), -9, dtype=torch.int32, device=DEV)
+    need = fc.fc_guided_accept_workspace_bytes(B, A)
+    ws = torch.empty(need, dtype=torch.uint8, device=DEV)
+    posd = None if pos is None else torch.from_numpy(pos).to(DEV)
+    fc.fc_guided_accept(torch.from_numpy(dlm).to(DEV), torch.from_numpy(ar).to(DEV), posd, win_start, B, A, V, topk, tau,
+                        mask, td, L, n, pn, cn, ws, need)
+    torch.cuda.synchronize()
+    return td.cpu().numpy(), n.cpu().numpy(), pn.cpu().numpy(), cn.cpu().numpy()
+
+
+@pytest.mark.parametrize("B,A,V,L", [(1, 1, 3, 4), (3, 9, 7, 40), (2, 32, 1000, 100), (2, 300, 50, 700), (1, 4, 152064, 16)])
+def test_guided_accept_is_bit_exact(B, A, V, L):
+    rng = np.random.default_rng(A * 31 + V)
+    MASK = 200000
+    for topk, tau in ((1, 0.0), (2, 0.5), (5, 0.0), (8, 1.0)):
+        topk = min(topk, V)
+        pos = np.stack([np.sort(rng.choice(L, A, replace=False)) for _ in range(B)]).astype(np.int32)
+        pos[rng.random((B, A)) < 0.1] = -1
+        tokens = rng.integers(0, V, (B, L)).astype(np.int32)
+        tokens[rng.random((B, L)) < 0.7] = MASK
+        # integer-valued logits: exact ties everywhere; the guide mostly agrees with the proposal
+        dlm = np.round(rng.normal(0, 3, (B, A, V))).astype(np.float32)
+        ar = (dlm + np.round(rng.normal(0, 0.7, (B, A, V)))).astype(np.float32)
+        want_t = tokens.copy()
+        want = orc.guided_accept(dlm, ar, pos, topk, tau, MASK, want_t)
+        got_t, n, pn, cn = _gpu_accept(dlm, ar, pos, 0, topk, tau, MASK, tokens)
+        assert np.array_equal(got_t, want_t) and np.array_equal(n, want[0])
+        assert np.array_equal(pn, want[1]) and np.array_equal(cn, want[2])
+
+
+def test_guided_accept_until_everything_is_unmasked():
+    # Algorithm 1's loop: proposals and guide logits are redrawn each round; every round makes progress
+    rng = np.random.default_rng(3)
+    B, A, V, L, MASK, P = 2, 32, 500, 48, 9999, 16
+    tokens = np.full((B, L), MASK, np.int32)
+    tokens[:, :P] = 1
+    host = tokens.copy()
+    td = torch.from_numpy(tokens).to(DEV)
+    need = fc.fc_guided_accept_workspace_bytes(B, A)
+    ws = torch.empty(need, dtype=torch.uint8, device=DEV)
+    n = torch.empty((B,), dtype=torch.int32, device=DEV)
+    pn = torch.empty((B, A), dtype=torch.int32, device=DEV)
+    cn = torch.empty((B,), dtype=torch.int32, device=DEV)
+    pos = np.tile(np.arange(P, P + A, dtype=np.int32), (B, 1))
+    rounds = 0
+    while np.any(host == MASK):
+        dlm = rng.normal(0, 3, (B, A, V)).astype(np.float32)
+        ar = (dlm + rng.normal(0, 2.0, (B, A, V))).astype(np.float32)
+        want = orc.guided_accept(dlm, ar, pos, 2, 0.5, MASK, host)
+        fc.fc_guided_accept(torch.from_numpy(dlm).to(DEV), torch.from_numpy(ar).to(DEV), None, P, B, A, V, 2, 0.5, MASK,
+                            td, L, n, pn, cn, ws, need)
+        torch.cuda.synchronize()
+        assert np.array_equal(td.cpu().numpy(), host) and np.array_equal(n.cpu().numpy(), want[0])
+        assert np.array_equal(pn.cpu().numpy(), want[1]) and np.array_equal(cn.cpu().numpy(), want[2])
+        rounds += 1
+        assert rounds <= A
+    assert rounds >= 2
