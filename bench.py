@@ -2,7 +2,7 @@
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--layers N]
                     [--workload c4|c2|c3|c5|c5_refresh|c4_layer|c2_layer|c3_layer|c5_layer|c5_refresh_layer|
-                                c4_unmask|c5_unmask]
+                                c4_unmask|c5_unmask|c4_accept]
 
 A "step" is one pass of the whole hot path for one layer: QKV projection + RoPE + scatter of the
 active window, then attention of the window's queries over the cache.  The default workload is the
@@ -24,7 +24,8 @@ the 256-row refresh of 8 sequences (2048 rows).
 
 `--workload c4_unmask` / `c5_unmask` time the unmasking step of a block (vocabulary projection of the
 block's rows with arg-max and confidence, `fc_lm_head_argmax`, then `fc_unmask_select`; vocabulary
-152064 x hidden 3584, the Dream-7B sizes).
+152064 x hidden 3584, the Dream-7B sizes).  `--workload c4_accept` times the Guided Diffusion acceptance of
+one 32-token speculation block on synthetic DLM / AR logits (`fc_guided_accept`, Top-2 match, tau 0.5).
 
 Prints ONE JSON line (see the fields below).  Inputs are seeded and synthetic.
 """
@@ -58,7 +59,7 @@ def _parse():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="c4",
                     choices=["c2", "c3", "c4", "c5", "c5_refresh", "c4_layer", "c2_layer", "c3_layer", "c5_layer",
-                             "c5_refresh_layer", "c4_unmask", "c5_unmask"])
+                             "c5_refresh_layer", "c4_unmask", "c5_unmask", "c4_accept"])
     ap.add_argument("--layers", type=int, default=0, help="distinct layer caches to rotate over (0 = auto)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-single", action="store_true",
@@ -85,6 +86,8 @@ def main():
         return main_layer(args, torch, fc, inputs, dev)
     if args.workload.endswith("_unmask"):
         return main_unmask(args, torch, fc, inputs, dev)
+    if args.workload.endswith("_accept"):
+        return main_accept(args, torch, fc, inputs, dev)
     refresh = args.workload == "c5_refresh"
     w = {"c2": inputs.C2, "c3": inputs.C3, "c4": inputs.C4, "c5": inputs.C5, "c5_refresh": inputs.C5}[args.workload]
     B, Dh, Hq, Hkv = w.batch, w.head_dim, w.n_q_heads, w.n_kv_heads
@@ -509,6 +512,87 @@ def main_unmask(args, torch, fc, inputs, dev):
         out["cpu_baseline"] = {"value": round(dt * 1e6 * M / rows, 1), "unit": "us", "cores": orc.get_threads(),
                                "kind": "oracle", "sample": "vocabulary projection + arg-max of %d rows of %s, fp64, "
                                "OpenMP over rows; scaled by %g to the %d rows of a step" % (rows, w.name, M / rows, M)}
+        del np
+    print(json.dumps(out))
+
+
+def main_accept(args, torch, fc, inputs, dev):
+    """Guided Diffusion acceptance of one speculation block on synthetic logits (fp32, vocabulary 152064)."""
+    w = inputs.C4
+    B, A, V, topk, tau = w.batch, 32, 152064, 2, 0.5
+    L, P, MASK = 64, 16, V + 1
+    n_sets = args.layers or 16                     # 38.9 MB of logits each: 620 MB rotated
+    steps = min(args.steps, 64)
+    dlm0 = inputs.normal(0, "dlm_logits", (B, A, V), 3.0, "f32")
+    ar0 = dlm0 + inputs.normal(0, "ar_noise", (B, A, V), 1.5, "f32")
+    dlm = [dlm0.to(dev)] + [None] * (n_sets - 1)
+    ar = [ar0.to(dev)] + [None] * (n_sets - 1)
+    for i in range(1, n_sets):
+        dlm[i], ar[i] = dlm[0].clone(), ar[0].clone()
+    tokens0 = torch.full((B, L), MASK, dtype=torch.int32, device=dev)
+    tokens0[:, :P] = 1
+    tokens = tokens0.clone()
+    need = fc.fc_guided_accept_workspace_bytes(B, A, V)
+    ws = torch.empty(need, dtype=torch.uint8, device=dev)
+    n_acc = torch.empty((B,), dtype=torch.int32, device=dev)
+    pos_next = torch.empty((B, A), dtype=torch.int32, device=dev)
+    count = torch.empty((B,), dtype=torch.int32, device=dev)
+    stream = torch.cuda.current_stream().cuda_stream
+    torch.cuda.synchronize()
+
+    def step(s):
+        # every call sees the whole block masked (the timed work does not shrink from step to step)
+        tokens.copy_(tokens0)
+        fc.fc_guided_accept(dlm[s % n_sets], ar[s % n_sets], None, P, B, A, V, topk, tau, MASK, tokens, L, n_acc,
+                            pos_next, count, ws, need, stream)
+
+    def run(n):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        e0.record()
+        for s in range(n):
+            step(s)
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) * 1000.0 / n
+
+    for s in range(min(args.warmup, n_sets)):
+        step(s)
+    us_step = run(steps)
+    # the token reset alone, to subtract it
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    e0.record()
+    for s in range(steps):
+        tokens.copy_(tokens0)
+    e1.record()
+    torch.cuda.synchronize()
+    us_reset = e0.elapsed_time(e1) * 1000.0 / steps
+    us_call = sorted(run(steps) for _ in range(args.repeats))[args.repeats // 2] - us_reset
+    nbytes = 2 * B * A * V * 4
+    out = {
+        "metric": "us per Guided Diffusion acceptance step of one speculation block (synthetic logits)",
+        "value": round(us_step, 3), "unit": "us", "n_gpus": 1, "steps": steps, "warmup": min(args.warmup, n_sets),
+        "ms_per_step": round(us_step / 1000.0, 6), "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": "c4_guided_accept_B%d_block%d_V%d" % (B, A, V), "batch": B, "block_rows": A, "vocab": V,
+                   "topk": topk, "tau": tau, "logit_sets_rotated": n_sets, "includes_token_reset_us": round(us_reset, 3)},
+        "roofline": {"kernel": "fc_guided_accept (k_accept_scan + k_accept_rowmerge + k_accept_seq)", "bound": "hbm",
+                     "achieved": round(nbytes / us_call * 1e-3, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": round(nbytes / us_call * 1e-3 / HBM_PEAK_GBS, 4), "traffic": None,
+                     "algorithmic_bytes_per_launch": nbytes, "us_per_launch": round(us_call, 3)},
+        "accepted_first_call": int(n_acc.sum().item()),
+    }
+    if not args.no_cpu_baseline:
+        import numpy as np
+        from oracle import fc_oracle as orc
+        host_tokens = tokens0.cpu().numpy().copy()
+        pos = inputs.as_oracle(inputs.window_positions(B, P, A))
+        t0 = time.perf_counter()
+        orc.guided_accept(dlm0.numpy(), ar0.numpy(), pos, topk, tau, MASK, host_tokens)
+        dt = time.perf_counter() - t0
+        out["cpu_baseline"] = {"value": round(dt * 1e6, 1), "unit": "us", "cores": 1, "kind": "oracle",
+                               "sample": "one acceptance step of the same block and logits, single thread"}
         del np
     print(json.dumps(out))
 

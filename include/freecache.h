@@ -301,10 +301,10 @@ fc_status fc_gather_rows(int32_t dtype, const void *table, int32_t rows, int32_t
  *   dlm, ar  device float [B][A][V] logits;  pos  device int32 [B][A] or NULL = win_start + a;
  *   tokens  device int32 [B][L], updated in place;  n_accept  device int32 [B] (0 if nothing was masked);
  *   pos_next  device int32 [B][A], count_next  device int32 [B]: the rows that stay masked (as for
- *   fc_unmask_select);  workspace  device, >= fc_guided_accept_workspace_bytes(B, A) bytes.
+ *   fc_unmask_select);  workspace  device, >= fc_guided_accept_workspace_bytes(B, A, V) bytes.
  * topk is limited to 8.  Integer work on given floats: bit-exact.
  * Errors: INVALID_ARG, UNSUPPORTED (topk > 8), BOUNDS (pos NULL and window outside [0, L)), WORKSPACE, HIP. */
-size_t fc_guided_accept_workspace_bytes(int32_t B, int32_t A);
+size_t fc_guided_accept_workspace_bytes(int32_t B, int32_t A, int32_t V);
 fc_status fc_guided_accept(const float *dlm, const float *ar, const int32_t *pos, int32_t win_start, int32_t B,
                            int32_t A, int32_t V, int32_t topk, float tau, int32_t mask_id, int32_t *tokens,
                            int32_t L, int32_t *n_accept, int32_t *pos_next, int32_t *count_next, void *workspace,

@@ -107,7 +107,7 @@ def lib():
         L.fc_gather_rows.restype = ctypes.c_int
         L.fc_gather_rows.argtypes = [i32, vp, i32, i32, vp, i32, vp, vp]
         L.fc_guided_accept_workspace_bytes.restype = sz
-        L.fc_guided_accept_workspace_bytes.argtypes = [i32, i32]
+        L.fc_guided_accept_workspace_bytes.argtypes = [i32, i32, i32]
         L.fc_guided_accept.restype = ctypes.c_int
         L.fc_guided_accept.argtypes = [vp, vp, vp, i32, i32, i32, i32, i32, ctypes.c_float, i32, vp, i32, vp, vp, vp, vp,
                                        sz, vp]
@@ -275,8 +275,8 @@ def fc_gather_rows(dtype, table, rows, width, idx, n, out, stream=None) -> None:
     _check(lib().fc_gather_rows(DTYPE_CODE[dtype], _ptr(table), rows, width, _ptr(idx), n, _ptr(out), _stream(stream)))
 
 
-def fc_guided_accept_workspace_bytes(B, A) -> int:
-    return int(lib().fc_guided_accept_workspace_bytes(B, A))
+def fc_guided_accept_workspace_bytes(B, A, V) -> int:
+    return int(lib().fc_guided_accept_workspace_bytes(B, A, V))
 
 
 def fc_guided_accept(dlm, ar, pos, win_start, B, A, V, topk, tau, mask_id, tokens, L, n_accept, pos_next, count_next,

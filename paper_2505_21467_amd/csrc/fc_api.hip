@@ -690,10 +690,10 @@ fc_status fc_gather_rows(int32_t dtype, const void *table, int32_t rows, int32_t
     return e == hipSuccess ? FC_OK : hip_fail(e, "gather launch");
 }
 
-size_t fc_guided_accept_workspace_bytes(int32_t B, int32_t A)
+size_t fc_guided_accept_workspace_bytes(int32_t B, int32_t A, int32_t V)
 {
-    if (B < 1 || A < 1 || B > 65535 || A > 65535) return 0;
-    return (size_t)2 * B * A * sizeof(int32_t);
+    if (B < 1 || A < 1 || V < 1 || B > 65535 || A > 65535) return 0;
+    return fc_accept_workspace(B, A, V);
 }
 
 fc_status fc_guided_accept(const float *dlm, const float *ar, const int32_t *pos, int32_t win_start, int32_t B, int32_t A,
@@ -710,9 +710,11 @@ fc_status fc_guided_accept(const float *dlm, const float *ar, const int32_t *pos
     if (pos == pos_next) return fail(FC_ERR_INVALID_ARG, "pos_next must not be pos");
     if (!pos && (win_start < 0 || win_start > L - A))
         return fail(FC_ERR_BOUNDS, "window [%d, %d+%d) outside the sequence of %d tokens", win_start, win_start, A, L);
-    const size_t need = fc_guided_accept_workspace_bytes(B, A);
+    const size_t need = fc_guided_accept_workspace_bytes(B, A, V);
     if (!workspace || workspace_bytes < need)
         return fail(FC_ERR_WORKSPACE, "workspace of %zu bytes needed, %zu given", need, workspace ? workspace_bytes : (size_t)0);
+    if (((uintptr_t)dlm | (uintptr_t)ar | (uintptr_t)workspace) & 15)
+        return fail(FC_ERR_INVALID_ARG, "dlm, ar and workspace must be 16-byte aligned");
     hipError_t e = fc_launch_guided_accept(dlm, ar, pos, win_start, B, A, V, topk, tau, mask_id, tokens, L, n_accept,
                                            pos_next, count_next, workspace, (hipStream_t)stream);
     return e == hipSuccess ? FC_OK : hip_fail(e, "acceptance launch");

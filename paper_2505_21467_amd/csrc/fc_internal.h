@@ -150,6 +150,7 @@ hipError_t fc_launch_linear_wide(const FcWidePlan &pl, int mode, const void *x, 
 hipError_t fc_launch_gather_rows(const void *table, int64_t R, int row_bytes, const int32_t *idx, int64_t n, void *out,
                                  hipStream_t s);
 #define FC_ACCEPT_MAX_TOPK 8
+size_t fc_accept_workspace(int B, int A, int V);
 hipError_t fc_launch_guided_accept(const float *dlm, const float *ar, const int32_t *pos, int win_start, int B, int A,
                                    int V, int topk, float tau, int mask_id, int32_t *tokens, int L, int32_t *n_accept,
                                    int32_t *pos_next, int32_t *count_next, void *workspace, hipStream_t s);

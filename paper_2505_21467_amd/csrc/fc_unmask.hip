@@ -148,36 +148,41 @@ __global__ __launch_bounds__(256) void k_unmask_select(const int32_t *__restrict
 
 // -------------------------------------------------------------------------------------------------
 // Guided Diffusion acceptance (paper, section 3.2.2, Algorithm 1; Top-K match and threshold tau from the
-// implementation details).  First kernel: one workgroup per window row that is still masked scans the
-// row's two logit vectors (DLM and AR guide): arg-max of the DLM row, the topk best ids of the AR row
-// (every thread keeps its own best list, the lists are merged by topk rounds of a block-wide arg-max),
-// and decides whether the row matches.  Second kernel: one workgroup per sequence finds the longest
-// matching prefix of the masked rows, fills it (or the first masked row) and lists the rest.
+// implementation details).  k_accept_scan: several workgroups per still masked window row, each scans a
+// part of the row's two logit vectors (DLM and AR guide): largest DLM logit, the topk best entries of
+// the AR row (every thread keeps its own best list; the lists are merged by topk rounds of a block-wide
+// arg-max).  k_accept_rowmerge: one wave per row merges the parts the same way and decides whether the
+// row matches.  k_accept_seq: one workgroup per sequence finds the longest matching prefix of the masked
+// rows, fills it (or the first masked row) and lists the rest.
 constexpr int ACC_MAXK = 8;
 
 // (value, id) order: larger value first, then smaller id
 __device__ __forceinline__ bool acc_before(float v1, int i1, float v2, int i2) { return v1 > v2 || (v1 == v2 && i1 < i2); }
 
-__global__ __launch_bounds__(256) void k_accept_rows(const float *__restrict__ dlm, const float *__restrict__ ar,
+// Partial results of one part of a row's vocabulary: DLM (largest, id) and the AR's topk best, best first.
+struct AccPart {
+    float dv;
+    int di;
+    float tv[ACC_MAXK];
+    int ti[ACC_MAXK];
+};
+
+// grid (parts, A, B): workgroup (part, a, b) scans entries [part * chunk, (part + 1) * chunk) of row (b, a).
+__global__ __launch_bounds__(256) void k_accept_scan(const float *__restrict__ dlm, const float *__restrict__ ar,
                                                      const int32_t *__restrict__ pos, int win_start, int A, int V,
-                                                     int topk, float tau, int mask_id, const int32_t *tokens, int L,
-                                                     int32_t *row_tok, int32_t *row_match)
+                                                     int chunk, int topk, int mask_id, const int32_t *tokens, int L,
+                                                     AccPart *parts)
 {
     __shared__ float s_v[256];
     __shared__ int s_i[256];
     __shared__ int s_who;
-    const int a = blockIdx.x, b = blockIdx.y, tid = threadIdx.x;
+    const int part = blockIdx.x, a = blockIdx.y, b = blockIdx.z, tid = threadIdx.x;
     const int p = pos ? pos[(size_t)b * A + a] : win_start + a;
     const size_t at = (size_t)b * A + a;
-    if (!(p >= 0 && p < L && tokens[(size_t)b * L + p] == mask_id)) {  // not a candidate: nothing to scan
-        if (tid == 0) {
-            row_tok[at] = -1;
-            row_match[at] = -1;
-        }
-        return;
-    }
+    if (!(p >= 0 && p < L && tokens[(size_t)b * L + p] == mask_id)) return;  // not a candidate: nothing to scan
     const float *zd = dlm + at * V, *za = ar + at * V;
-    // DLM arg-max and this thread's topk best AR entries (sorted best first; ids ascend within a thread)
+    const int v0 = part * chunk, v1 = min(V, v0 + chunk);
+    // DLM arg-max and this thread's topk best AR entries (sorted best first)
     float dv = -INFINITY;
     int di = 0x7fffffff;
     float tv[ACC_MAXK];
@@ -187,13 +192,14 @@ __global__ __launch_bounds__(256) void k_accept_rows(const float *__restrict__ d
         tv[r] = -INFINITY;
         ti[r] = 0x7fffffff;
     }
-    for (int v = tid; v < V; v += 256) {
-        const float d = zd[v];
+    float worst_v = -INFINITY;  // the list's last kept entry: most elements fail against it and cost two compares
+    int worst_i = 0x7fffffff;
+    auto visit = [&](float d, float x, int v) {
         if (acc_before(d, v, dv, di)) {
             dv = d;
             di = v;
         }
-        float x = za[v];
+        if (!acc_before(x, v, worst_v, worst_i)) return;
         int xi = v;
 #pragma unroll
         for (int r = 0; r < ACC_MAXK; ++r) {  // insertion into the sorted list
@@ -206,8 +212,26 @@ __global__ __launch_bounds__(256) void k_accept_rows(const float *__restrict__ d
                 xi = t1;
             }
         }
+#pragma unroll
+        for (int r = 0; r < ACC_MAXK; ++r)
+            if (r == topk - 1) {
+                worst_v = tv[r];
+                worst_i = ti[r];
+            }
+    };
+    // rows of V floats are 16-byte aligned when V is a multiple of 4 (chunk always is): four entries per load
+    if ((V & 3) == 0) {
+        for (int v = v0 + 4 * tid; v < v1; v += 1024) {
+            const float4 d4 = *(const float4 *)(zd + v), x4 = *(const float4 *)(za + v);
+            visit(d4.x, x4.x, v);
+            visit(d4.y, x4.y, v + 1);
+            visit(d4.z, x4.z, v + 2);
+            visit(d4.w, x4.w, v + 3);
+        }
+    } else {
+        for (int v = v0 + tid; v < v1; v += 256) visit(zd[v], za[v], v);
     }
-    // block arg-max of the DLM row
+    // block arg-max of the DLM part
     s_v[tid] = dv;
     s_i[tid] = di;
     __syncthreads();
@@ -218,12 +242,13 @@ __global__ __launch_bounds__(256) void k_accept_rows(const float *__restrict__ d
         }
         __syncthreads();
     }
-    const float zd_max = s_v[0];
-    const int t_dlm = s_i[0];
+    AccPart *out = parts + at * gridDim.x + part;
+    if (tid == 0) {
+        out->dv = s_v[0];
+        out->di = s_i[0];
+    }
     __syncthreads();
-    // topk rounds: the best head among the threads' lists is the next of the row's top list
-    bool in_top = false;
-    float za_max = 0.f;
+    // topk rounds: the best head among the threads' lists is the next entry of the part's list
     for (int r = 0; r < topk; ++r) {
         s_v[tid] = tv[0];
         s_i[tid] = ti[0];
@@ -237,11 +262,13 @@ __global__ __launch_bounds__(256) void k_accept_rows(const float *__restrict__ d
         }
         const float bv = s_v[0];
         const int bi = s_i[0];
-        if (r == 0) za_max = bv;
-        if (bi == t_dlm) in_top = true;
-        if (tid == 0) s_who = -1;
+        if (tid == 0) {
+            out->tv[r] = bv;  // (-inf, int max) once the part is exhausted
+            out->ti[r] = bi;
+            s_who = -1;
+        }
         __syncthreads();
-        if (ti[0] == bi) s_who = tid;  // ids are unique: exactly one thread owns the winner
+        if (ti[0] == bi && bi != 0x7fffffff) s_who = tid;  // ids are unique: one thread owns the winner
         __syncthreads();
         if (s_who == tid) {  // pop the head
 #pragma unroll
@@ -254,10 +281,81 @@ __global__ __launch_bounds__(256) void k_accept_rows(const float *__restrict__ d
         }
         __syncthreads();
     }
-    if (tid == 0) {
+}
+
+// One wave per row merges the parts (at most 64, one per lane) and decides whether the row matches.
+__global__ __launch_bounds__(64) void k_accept_rowmerge(const AccPart *__restrict__ parts, int n_parts,
+                                                        const int32_t *__restrict__ pos, int win_start, int A, int topk,
+                                                        float tau, int mask_id, const int32_t *tokens, int L,
+                                                        int32_t *row_tok, int32_t *row_match)
+{
+    const int a = blockIdx.x, b = blockIdx.y, lane = threadIdx.x;
+    const int p = pos ? pos[(size_t)b * A + a] : win_start + a;
+    const size_t at = (size_t)b * A + a;
+    if (!(p >= 0 && p < L && tokens[(size_t)b * L + p] == mask_id)) {
+        if (lane == 0) {
+            row_tok[at] = -1;
+            row_match[at] = -1;
+        }
+        return;
+    }
+    float dv = -INFINITY;
+    int di = 0x7fffffff;
+    float tv[ACC_MAXK];
+    int ti[ACC_MAXK];
+#pragma unroll
+    for (int r = 0; r < ACC_MAXK; ++r) {
+        tv[r] = -INFINITY;
+        ti[r] = 0x7fffffff;
+    }
+    if (lane < n_parts) {
+        const AccPart *pt = parts + at * n_parts + lane;
+        dv = pt->dv;
+        di = pt->di;
+#pragma unroll
+        for (int r = 0; r < ACC_MAXK; ++r)
+            if (r < topk) {
+                tv[r] = pt->tv[r];
+                ti[r] = pt->ti[r];
+            }
+    }
+    for (int off = 32; off > 0; off >>= 1) {
+        const float v2 = __shfl_xor(dv, off, 64);
+        const int i2 = __shfl_xor(di, off, 64);
+        if (acc_before(v2, i2, dv, di)) {
+            dv = v2;
+            di = i2;
+        }
+    }
+    bool in_top = false;
+    float za_max = 0.f;
+    for (int r = 0; r < topk; ++r) {
+        float bv = tv[0];
+        int bi = ti[0];
+        for (int off = 32; off > 0; off >>= 1) {
+            const float v2 = __shfl_xor(bv, off, 64);
+            const int i2 = __shfl_xor(bi, off, 64);
+            if (acc_before(v2, i2, bv, bi)) {
+                bv = v2;
+                bi = i2;
+            }
+        }
+        if (r == 0) za_max = bv;
+        if (bi == di) in_top = true;
+        if (ti[0] == bi && bi != 0x7fffffff) {  // this lane owns the winner: pop
+#pragma unroll
+            for (int q = 0; q + 1 < ACC_MAXK; ++q) {
+                tv[q] = tv[q + 1];
+                ti[q] = ti[q + 1];
+            }
+            tv[ACC_MAXK - 1] = -INFINITY;
+            ti[ACC_MAXK - 1] = 0x7fffffff;
+        }
+    }
+    if (lane == 0) {
         const float thr = tau * za_max;
-        row_tok[at] = t_dlm;
-        row_match[at] = (in_top && (!(tau > 0.0f) || zd_max > thr)) ? 1 : 0;
+        row_tok[at] = di;
+        row_match[at] = (in_top && (!(tau > 0.0f) || dv > thr)) ? 1 : 0;
     }
 }
 
@@ -342,14 +440,35 @@ __global__ __launch_bounds__(256) void k_gather_rows(const uint4 *__restrict__ t
 
 }  // namespace
 
+// Parts a row's vocabulary is cut into: enough workgroups to fill the chip, chunks of whole float4s.
+int fc_accept_parts(int B, int A, int V)
+{
+    int64_t parts = 512 / ((int64_t)B * A);
+    if (parts > 64) parts = 64;
+    if (parts > (V + 4095) / 4096) parts = (V + 4095) / 4096;  // at least 4096 entries per part
+    if (parts < 1) parts = 1;
+    return (int)parts;
+}
+
+size_t fc_accept_workspace(int B, int A, int V)
+{
+    return (size_t)2 * B * A * sizeof(int32_t) + (size_t)B * A * fc_accept_parts(B, A, V) * sizeof(AccPart);
+}
+
 hipError_t fc_launch_guided_accept(const float *dlm, const float *ar, const int32_t *pos, int win_start, int B, int A,
                                    int V, int topk, float tau, int mask_id, int32_t *tokens, int L, int32_t *n_accept,
                                    int32_t *pos_next, int32_t *count_next, void *workspace, hipStream_t s)
 {
     if (topk < 1 || topk > ACC_MAXK || !workspace) return hipErrorInvalidValue;
+    const int n_parts = fc_accept_parts(B, A, V);
+    const int chunk = (((V + n_parts - 1) / n_parts) + 3) & ~3;
     int32_t *row_tok = (int32_t *)workspace, *row_match = row_tok + (size_t)B * A;
-    k_accept_rows<<<dim3((unsigned)A, (unsigned)B), dim3(256), 0, s>>>(dlm, ar, pos, win_start, A, V, topk, tau, mask_id,
-                                                                       tokens, L, row_tok, row_match);
+    AccPart *parts = (AccPart *)(row_match + (size_t)B * A);
+    k_accept_scan<<<dim3((unsigned)n_parts, (unsigned)A, (unsigned)B), dim3(256), 0, s>>>(dlm, ar, pos, win_start, A, V,
+                                                                                          chunk, topk, mask_id, tokens, L,
+                                                                                          parts);
+    k_accept_rowmerge<<<dim3((unsigned)A, (unsigned)B), dim3(64), 0, s>>>(parts, n_parts, pos, win_start, A, topk, tau,
+                                                                          mask_id, tokens, L, row_tok, row_match);
     k_accept_seq<<<dim3((unsigned)B), dim3(256), 0, s>>>(row_tok, row_match, pos, win_start, A, tokens, L, n_accept,
                                                          pos_next, count_next);
     return hipGetLastError();

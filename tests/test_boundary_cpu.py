@@ -264,8 +264,9 @@ def test_guided_accept_rejects_bad_arguments_before_any_launch():
     Gd = fc.fc_guided_accept
     ok = dict(dlm=FAKE, ar=FAKE, pos=FAKE, win_start=0, B=2, A=32, V=1000, topk=2, tau=0.5, mask_id=9, tokens=FAKE, L=100,
               n_accept=FAKE, pos_next=FAKE + 256, count_next=FAKE, workspace=FAKE, workspace_bytes=1 << 20, stream=0)
-    need = fc.fc_guided_accept_workspace_bytes(2, 32)
-    assert need == 2 * 2 * 32 * 4 and fc.fc_guided_accept_workspace_bytes(0, 32) == 0
+    need = fc.fc_guided_accept_workspace_bytes(2, 32, 1000)
+    assert need >= 2 * 2 * 32 * 4 and fc.fc_guided_accept_workspace_bytes(0, 32, 1000) == 0
+    assert fc.fc_guided_accept_workspace_bytes(1, 32, 152064) > fc.fc_guided_accept_workspace_bytes(1, 32, 1000)
 
     def call(**kw):
         a = dict(ok)

@@ -186,7 +186,7 @@ def _gpu_accept(dlm, ar, pos, win_start, topk, tau, mask, tokens):
     n = torch.full((B,), -9, dtype=torch.int32, device=DEV)
     pn = torch.full((B, A), -9, dtype=torch.int32, device=DEV)
     cn = torch.full((B,), -9, dtype=torch.int32, device=DEV)
-    need = fc.fc_guided_accept_workspace_bytes(B, A)
+    need = fc.fc_guided_accept_workspace_bytes(B, A, V)
     ws = torch.empty(need, dtype=torch.uint8, device=DEV)
     posd = None if pos is None else torch.from_numpy(pos).to(DEV)
     fc.fc_guided_accept(torch.from_numpy(dlm).to(DEV), torch.from_numpy(ar).to(DEV), posd, win_start, B, A, V, topk, tau,
@@ -223,7 +223,7 @@ def test_guided_accept_until_everything_is_unmasked():
     tokens[:, :P] = 1
     host = tokens.copy()
     td = torch.from_numpy(tokens).to(DEV)
-    need = fc.fc_guided_accept_workspace_bytes(B, A)
+    need = fc.fc_guided_accept_workspace_bytes(B, A, V)
     ws = torch.empty(need, dtype=torch.uint8, device=DEV)
     n = torch.empty((B,), dtype=torch.int32, device=DEV)
     pn = torch.empty((B, A), dtype=torch.int32, device=DEV)
