@@ -562,3 +562,36 @@ int fco_guided_accept(const float *dlm, const float *ar, const int32_t *pos, int
     }
     return 0;
 }
+
+/* -------------------------------------------------------------------------
+ * KV drift diagnostic (paper, section 3.2.1, the figure that motivates FreeCache: the similarity of a
+ * token's K / V projection to its projection at the previous step).  For rows [start, start + rows)
+ * of the cache and a snapshot of the same rows taken earlier (plain layout [B][Hkv][rows][Dh]):
+ *   sim[b][j][r] = <now, prev> / (|now| |prev|)   (cosine similarity over the head dimension),
+ * 0 when either vector is zero.  sim_k, sim_v: [B][Hkv][rows] doubles.
+ */
+int fco_kv_similarity(const fco_config *c, const float *Kc, const float *Vc, const float *k_prev,
+                      const float *v_prev, int32_t start, int32_t rows, double *sim_k, double *sim_v)
+{
+    if (!cfg_ok(c) || !Kc || !Vc || !k_prev || !v_prev || !sim_k || !sim_v || rows < 1) return 1;
+    if (start < 0 || start > c->max_seq - rows) return 2;
+    const int B = c->batch, Hkv = c->n_kv_heads, Dh = c->head_dim, Smax = c->max_seq;
+    for (int b = 0; b < B; ++b)
+        for (int j = 0; j < Hkv; ++j)
+            for (int r = 0; r < rows; ++r) {
+                const size_t now = (((size_t)b * Hkv + j) * Smax + start + r) * Dh;
+                const size_t old = (((size_t)b * Hkv + j) * rows + r) * Dh;
+                for (int which = 0; which < 2; ++which) {
+                    const float *x = (which ? Vc : Kc) + now, *y = (which ? v_prev : k_prev) + old;
+                    double dot = 0.0, nx = 0.0, ny = 0.0;
+                    for (int i = 0; i < Dh; ++i) {
+                        dot += (double)x[i] * (double)y[i];
+                        nx += (double)x[i] * (double)x[i];
+                        ny += (double)y[i] * (double)y[i];
+                    }
+                    const double s = (nx > 0.0 && ny > 0.0) ? dot / (sqrt(nx) * sqrt(ny)) : 0.0;
+                    (which ? sim_v : sim_k)[((size_t)b * Hkv + j) * rows + r] = s;
+                }
+            }
+    return 0;
+}

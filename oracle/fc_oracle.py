@@ -69,7 +69,7 @@ def lib():
         for name in ("fco_project_rope", "fco_scatter", "fco_attend", "fco_layer_step", "fco_window",
                      "fco_rmsnorm", "fco_linear_residual", "fco_ffn_gate_up", "fco_full_layer_step",
                      "fco_lm_head_argmax", "fco_unmask_select", "fco_gather_rows",
-                     "fco_guided_accept"):
+                     "fco_guided_accept", "fco_kv_similarity"):
             getattr(L, name).restype = ctypes.c_int
         _lib = L
     return _lib
@@ -379,3 +379,23 @@ def guided_accept(dlm, ar, pos, topk, tau, mask_id, tokens):
         raise IndexError("position beyond the sequence")
     _check(rc, "fco_guided_accept")
     return n_acc, pos_next, count
+
+
+def kv_similarity(cfg: OracleConfig, Kc, Vc, k_prev, v_prev, start):
+    """Cosine similarity of cache rows [start, start+rows) to an earlier snapshot [B, Hkv, rows, Dh].
+    Returns (sim_k, sim_v), float64 [B, Hkv, rows]."""
+    B, Hkv, Dh = cfg.batch, cfg.n_kv_heads, cfg.head_dim
+    Kc, Vc = _f32(Kc, (B, Hkv, cfg.max_seq, Dh)), _f32(Vc, (B, Hkv, cfg.max_seq, Dh))
+    k_prev, v_prev = _f32(k_prev), _f32(v_prev)
+    rows = k_prev.shape[2]
+    assert k_prev.shape == (B, Hkv, rows, Dh) == v_prev.shape
+    sk = np.empty((B, Hkv, rows), np.float64)
+    sv = np.empty((B, Hkv, rows), np.float64)
+    c = cfg.c()
+    rc = lib().fco_kv_similarity(ctypes.byref(c), _p(Kc, ctypes.c_float), _p(Vc, ctypes.c_float),
+                                 _p(k_prev, ctypes.c_float), _p(v_prev, ctypes.c_float), ctypes.c_int32(start),
+                                 ctypes.c_int32(rows), _p(sk, ctypes.c_double), _p(sv, ctypes.c_double))
+    if rc == 2:
+        raise IndexError("rows outside the cache")
+    _check(rc, "fco_kv_similarity")
+    return sk, sv

@@ -778,3 +778,53 @@ def test_guided_accept_brute_force():
         assert np.array_equal(got_t, want[0]) and np.array_equal(n, want[1])
         assert np.array_equal(nxt, want[2]) and np.array_equal(cnt, want[3])
         assert np.all((n >= 1) | (cnt + n == 0))          # progress whenever something is masked
+
+
+# --------------------------------------------------------------------------- KV drift diagnostic
+
+def test_kv_similarity_closed_forms_and_library_formula():
+    cfg = _cfg(B=2, d=16, Hq=4, Hkv=2, Dh=8, Smax=12)
+    Kc, Vc = _rand(95, (2, 2, 12, 8)), _rand(96, (2, 2, 12, 8))
+    start, rows = 3, 5
+    now_k, now_v = Kc[:, :, start:start + rows], Vc[:, :, start:start + rows]
+    # identical snapshot -> 1; negated -> -1; positively scaled -> 1
+    sk, sv = orc.kv_similarity(cfg, Kc, Vc, now_k.copy(), now_v.copy(), start)
+    assert np.allclose(sk, 1.0, atol=1e-12) and np.allclose(sv, 1.0, atol=1e-12)
+    sk, sv = orc.kv_similarity(cfg, Kc, Vc, -now_k, 3.5 * now_v, start)
+    assert np.allclose(sk, -1.0, atol=1e-12) and np.allclose(sv, 1.0, atol=1e-12)
+    # a random snapshot: numpy's formula; K and V are not mixed up, rows are not shifted
+    pk, pv = _rand(97, now_k.shape), _rand(98, now_v.shape)
+    sk, sv = orc.kv_similarity(cfg, Kc, Vc, pk, pv, start)
+    cos = lambda x, y: np.sum(x.astype(np.float64) * y, -1) / (np.linalg.norm(x.astype(np.float64), axis=-1) *
+                                                               np.linalg.norm(y.astype(np.float64), axis=-1))
+    assert np.allclose(sk, cos(now_k, pk), atol=1e-12) and np.allclose(sv, cos(now_v, pv), atol=1e-12)
+    assert not np.allclose(sk, cos(now_v, pv), atol=1e-3)
+    # orthogonal vectors -> 0; a zero vector -> 0 by definition
+    e = np.zeros_like(now_k)
+    e[..., 0] = 1.0
+    K2 = Kc.copy()
+    K2[:, :, start:start + rows] = 0.0
+    K2[:, :, start:start + rows, 1] = 2.0
+    sk, _ = orc.kv_similarity(cfg, K2, Vc, e, pv, start)
+    assert np.all(sk == 0.0)
+    sk, _ = orc.kv_similarity(cfg, K2, Vc, np.zeros_like(e), pv, start)
+    assert np.all(sk == 0.0)
+    with pytest.raises(IndexError):
+        orc.kv_similarity(cfg, Kc, Vc, pk, pv, 8)
+
+
+def test_kv_similarity_of_a_cached_step_on_unchanged_inputs_is_one():
+    # the signal of the paper's figure: re-projecting unchanged tokens reproduces their K / V exactly,
+    # re-projecting changed ones does not
+    cfg = _cfg(B=1, d=32, Hq=4, Hkv=2, Dh=8, Smax=20)
+    X, W = _rand(99, (1, 20, 32)), _rand(100, (cfg.qkv_width, 32), 0.3)
+    Kc, Vc = np.zeros((1, 2, 20, 8), np.float32), np.zeros((1, 2, 20, 8), np.float32)
+    orc.refresh(cfg, X, W, None, 0, 20, Kc, Vc)
+    pk, pv = Kc[:, :, 12:20].copy(), Vc[:, :, 12:20].copy()
+    orc.layer_step(cfg, X[:, 12:20], W, None, _pos(1, 12, 8), 20, Kc, Vc)
+    sk, sv = orc.kv_similarity(cfg, Kc, Vc, pk, pv, 12)
+    assert np.all(sk == 1.0) or np.allclose(sk, 1.0, atol=1e-15)
+    X2 = X[:, 12:20] + _rand(101, (1, 8, 32))
+    orc.layer_step(cfg, X2, W, None, _pos(1, 12, 8), 20, Kc, Vc)
+    sk, sv = orc.kv_similarity(cfg, Kc, Vc, pk, pv, 12)
+    assert np.all(sk < 0.999) and np.all(sv < 0.999) and np.all(sv > -1.0)
