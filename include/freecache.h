@@ -310,6 +310,18 @@ fc_status fc_guided_accept(const float *dlm, const float *ar, const int32_t *pos
                            int32_t L, int32_t *n_accept, int32_t *pos_next, int32_t *count_next, void *workspace,
                            size_t workspace_bytes, void *stream);
 
+/* ---------------------------------------------------------------------------------------------
+ * KV drift diagnostic (section 3.2.1: the figure that motivates FreeCache shows, per token position
+ * and denoising step, the similarity of the token's K / V projection to its projection one step
+ * earlier; clean tokens stay near 1).  Compares rows [start, start+rows) of a layer's cache with a
+ * snapshot of the same rows taken earlier with fc_cache_read_rows (before the step that re-projected
+ * them):  sim[b][j][r] = <now, prev> / (|now| |prev|) over the head dimension, 0 if either is zero.
+ * A runtime signal for choosing the refresh period; not part of the step itself.
+ *   k_prev, v_prev  device [B][Hkv][rows][Dh] (cache dtype);  sim_k, sim_v  device float [B][Hkv][rows]
+ * Errors: INVALID_ARG, BOUNDS (layer; rows outside the cache), HIP. */
+fc_status fc_kv_similarity(const fc_cache *cache, int32_t layer, const void *k_prev, const void *v_prev,
+                           int32_t start, int32_t rows, float *sim_k, float *sim_v, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

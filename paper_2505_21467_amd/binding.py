@@ -24,7 +24,7 @@ EXPORTS = (
     "fc_rmsnorm", "fc_linear_workspace_bytes", "fc_linear_residual", "fc_ffn_gate_up",
     "fc_full_layer_workspace_bytes", "fc_full_layer_step",
     "fc_lm_head_workspace_bytes", "fc_lm_head_argmax", "fc_unmask_select", "fc_gather_rows",
-    "fc_guided_accept_workspace_bytes", "fc_guided_accept",
+    "fc_guided_accept_workspace_bytes", "fc_guided_accept", "fc_kv_similarity",
 )
 
 
@@ -111,6 +111,8 @@ def lib():
         L.fc_guided_accept.restype = ctypes.c_int
         L.fc_guided_accept.argtypes = [vp, vp, vp, i32, i32, i32, i32, i32, ctypes.c_float, i32, vp, i32, vp, vp, vp, vp,
                                        sz, vp]
+        L.fc_kv_similarity.restype = ctypes.c_int
+        L.fc_kv_similarity.argtypes = [vp, i32, vp, vp, i32, i32, vp, vp, vp]
         _lib = L
     return _lib
 
@@ -286,3 +288,8 @@ def fc_guided_accept(dlm, ar, pos, win_start, B, A, V, topk, tau, mask_id, token
     _check(lib().fc_guided_accept(_ptr(dlm), _ptr(ar), _ptr(pos), win_start, B, A, V, topk, tau, mask_id, _ptr(tokens),
                                   L, _ptr(n_accept), _ptr(pos_next), _ptr(count_next), _ptr(workspace),
                                   workspace_bytes, _stream(stream)))
+
+
+def fc_kv_similarity(cache, layer, k_prev, v_prev, start, rows, sim_k, sim_v, stream=None) -> None:
+    _check(lib().fc_kv_similarity(cache, layer, _ptr(k_prev), _ptr(v_prev), start, rows, _ptr(sim_k), _ptr(sim_v),
+                                  _stream(stream)))

@@ -720,4 +720,20 @@ fc_status fc_guided_accept(const float *dlm, const float *ar, const int32_t *pos
     return e == hipSuccess ? FC_OK : hip_fail(e, "acceptance launch");
 }
 
+fc_status fc_kv_similarity(const fc_cache *cache, int32_t layer, const void *k_prev, const void *v_prev, int32_t start,
+                           int32_t rows, float *sim_k, float *sim_v, void *stream)
+{
+    fc_status st = check_cache_layer(cache, layer);
+    if (st != FC_OK) return st;
+    if (!k_prev || !v_prev || !sim_k || !sim_v) return fail(FC_ERR_INVALID_ARG, "k_prev, v_prev, sim_k or sim_v is NULL");
+    if (rows < 1) return fail(FC_ERR_INVALID_ARG, "rows %d must be >= 1", rows);
+    if (start < 0 || start > cache->cfg.max_seq - rows)
+        return fail(FC_ERR_BOUNDS, "rows [%d, %d+%d) outside the cache of %d rows", start, start, rows,
+                    cache->cfg.max_seq);
+    hipError_t e = fc_launch_kv_similarity(geom_of(cache), cache->cfg.dtype, layer_ptr(cache, cache->k, layer),
+                                           layer_ptr(cache, cache->v, layer), k_prev, v_prev, start, rows, sim_k, sim_v,
+                                           (hipStream_t)stream);
+    return e == hipSuccess ? FC_OK : hip_fail(e, "similarity launch");
+}
+
 }  // extern "C"

@@ -303,7 +303,58 @@ __global__ __launch_bounds__(256) void k_linear_generic(const T *__restrict__ X,
     }
 }
 
+// ---------------------------------------------------------------------------------------------
+// KV drift diagnostic: cosine similarity over the head dimension between rows of the cache and an
+// earlier snapshot of the same rows in the plain [B][Hkv][rows][Dh] layout.  One wave per
+// (sequence, kv head, row); lanes run along the head dimension.
+template <typename T>
+__global__ __launch_bounds__(64) void k_kv_similarity(FcGeom G, const T *__restrict__ kc, const T *__restrict__ vc,
+                                                      const T *__restrict__ k_prev, const T *__restrict__ v_prev,
+                                                      int start, int rows, float *sim_k, float *sim_v)
+{
+    const int r = blockIdx.x, j = blockIdx.y, b = blockIdx.z, lane = threadIdx.x;
+    const size_t old = (((size_t)b * G.Hkv + j) * rows + r) * G.Dh;
+    float dk = 0.f, nk = 0.f, pk = 0.f, dv = 0.f, nv = 0.f, pv = 0.f;
+    for (int i = lane; i < G.Dh; i += 64) {
+        const float xk = fc_to_float(kc[fc_k_index(G, b, j, start + r, i)]), yk = fc_to_float(k_prev[old + i]);
+        const float xv = fc_to_float(vc[fc_v_index(G, b, j, start + r, i)]), yv = fc_to_float(v_prev[old + i]);
+        dk += xk * yk;
+        nk += xk * xk;
+        pk += yk * yk;
+        dv += xv * yv;
+        nv += xv * xv;
+        pv += yv * yv;
+    }
+    dk = wave_sum(dk);
+    nk = wave_sum(nk);
+    pk = wave_sum(pk);
+    dv = wave_sum(dv);
+    nv = wave_sum(nv);
+    pv = wave_sum(pv);
+    if (lane == 0) {
+        const size_t o = ((size_t)b * G.Hkv + j) * rows + r;
+        sim_k[o] = (nk > 0.f && pk > 0.f) ? dk / (sqrtf(nk) * sqrtf(pk)) : 0.f;
+        sim_v[o] = (nv > 0.f && pv > 0.f) ? dv / (sqrtf(nv) * sqrtf(pv)) : 0.f;
+    }
+}
+
 }  // namespace
+
+hipError_t fc_launch_kv_similarity(const FcGeom &G, int dtype, const void *k_layer, const void *v_layer,
+                                   const void *k_prev, const void *v_prev, int start, int rows, float *sim_k,
+                                   float *sim_v, hipStream_t s)
+{
+    const dim3 grid((unsigned)rows, (unsigned)G.Hkv, (unsigned)G.B);
+    if (dtype == FC_F32)
+        k_kv_similarity<float><<<grid, dim3(64), 0, s>>>(G, (const float *)k_layer, (const float *)v_layer,
+                                                         (const float *)k_prev, (const float *)v_prev, start, rows, sim_k,
+                                                         sim_v);
+    else
+        k_kv_similarity<bf16_t><<<grid, dim3(64), 0, s>>>(G, (const bf16_t *)k_layer, (const bf16_t *)v_layer,
+                                                          (const bf16_t *)k_prev, (const bf16_t *)v_prev, start, rows,
+                                                          sim_k, sim_v);
+    return hipGetLastError();
+}
 
 hipError_t fc_launch_copy_rows(const FcGeom &G, int dtype, void *k_layer, void *v_layer, void *k_rows,
                                void *v_rows, int start, int rows, bool to_cache, hipStream_t s)

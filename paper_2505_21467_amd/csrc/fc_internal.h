@@ -154,3 +154,6 @@ size_t fc_accept_workspace(int B, int A, int V);
 hipError_t fc_launch_guided_accept(const float *dlm, const float *ar, const int32_t *pos, int win_start, int B, int A,
                                    int V, int topk, float tau, int mask_id, int32_t *tokens, int L, int32_t *n_accept,
                                    int32_t *pos_next, int32_t *count_next, void *workspace, hipStream_t s);
+hipError_t fc_launch_kv_similarity(const FcGeom &G, int dtype, const void *k_layer, const void *v_layer,
+                                   const void *k_prev, const void *v_prev, int start, int rows, float *sim_k,
+                                   float *sim_v, hipStream_t s);

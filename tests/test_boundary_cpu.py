@@ -283,3 +283,14 @@ def test_guided_accept_rejects_bad_arguments_before_any_launch():
         (dict(workspace_bytes=need - 1), fc.FC_ERR_WORKSPACE),
     ]:
         _raises(st, call(**kw))
+
+
+def test_kv_similarity_rejects_bad_arguments_before_any_launch(cache):
+    Sm = fc.fc_kv_similarity
+    _raises(fc.FC_ERR_INVALID_ARG, Sm, None, 0, FAKE, FAKE, 0, 4, FAKE, FAKE, 0)
+    _raises(fc.FC_ERR_BOUNDS, Sm, cache, 2, FAKE, FAKE, 0, 4, FAKE, FAKE, 0)
+    _raises(fc.FC_ERR_INVALID_ARG, Sm, cache, 0, None, FAKE, 0, 4, FAKE, FAKE, 0)
+    _raises(fc.FC_ERR_INVALID_ARG, Sm, cache, 0, FAKE, FAKE, 0, 4, None, FAKE, 0)
+    _raises(fc.FC_ERR_INVALID_ARG, Sm, cache, 0, FAKE, FAKE, 0, 0, FAKE, FAKE, 0)
+    _raises(fc.FC_ERR_BOUNDS, Sm, cache, 0, FAKE, FAKE, 298, 4, FAKE, FAKE, 0)
+    _raises(fc.FC_ERR_BOUNDS, Sm, cache, 0, FAKE, FAKE, -1, 4, FAKE, FAKE, 0)

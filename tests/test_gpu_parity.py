@@ -277,3 +277,47 @@ def test_multi_layer_caches_are_independent():
         Kl, Vl = g.read_rows(layer, 0, L + A)
         assert np.all(Kl == 0.5) and np.all(Vl == 0.5)
     g.close()
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("dtype,Dh", [("f32", 64), ("bf16", 128)])
+def test_kv_drift_similarity_matches_oracle(dtype, Dh):
+    """KV drift diagnostic: snapshot the window rows, re-project them from changed inputs, compare the
+    similarity of the cache's new rows to the snapshot with the oracle's on the same bits; rows
+    re-projected from unchanged inputs have similarity 1."""
+    import torch
+    from paper_2505_21467_amd import binding as fcb
+    B, d, Hq, Hkv, S, A, start = 2, 256, 4, 2, 200, 40, 100
+    w = inputs.Workload("drift", dtype, B, d, Hq, Hkv, Dh, S, A)
+    g = GpuLayerCache(dtype, B, d, Hq, Hkv, Dh, S, max_rows=A)
+    W = inputs.weights(w, 3)
+    X0 = inputs.hidden_states(w, 3, S)
+    g.refresh(0, X0, W, None, 0, S, want_out=False)
+    tdt = inputs.TORCH_DTYPE[dtype]
+    kp = torch.empty((B, Hkv, A, Dh), dtype=tdt, device=g.dev)
+    vp = torch.empty_like(kp)
+    fcb.fc_cache_read_rows(g.handle, 0, kp, vp, start, A)
+    sk = torch.full((B, Hkv, A), float("nan"), dtype=torch.float32, device=g.dev)
+    sv = torch.full_like(sk, float("nan"))
+
+    def similarity():
+        fcb.fc_kv_similarity(g.handle, 0, kp, vp, start, A, sk, sv)
+        torch.cuda.synchronize()
+        Kg, Vg = g.read_rows(0, 0, S)
+        ocfg = orc.OracleConfig(B, d, Hq, Hkv, Dh, S, dtype)
+        rk, rv = orc.kv_similarity(ocfg, Kg, Vg, inputs.as_oracle(kp), inputs.as_oracle(vp), start)
+        assert np.allclose(sk.cpu().numpy(), rk, atol=2e-6) and np.allclose(sv.cpu().numpy(), rv, atol=2e-6)
+        return sk.cpu().numpy(), sv.cpu().numpy()
+
+    # unchanged inputs: the re-projection reproduces the rows bit for bit -> similarity 1
+    g.project(0, X0[:, start:start + A].contiguous(), W, None, start)
+    k1, v1 = similarity()
+    assert np.allclose(k1, 1.0, atol=2e-6) and np.allclose(v1, 1.0, atol=2e-6)
+    # half of the window rows get new inputs: those drift, the others stay at 1
+    X1 = X0[:, start:start + A].clone()
+    X1[:, ::2] = inputs.hidden_states(w, 4, A, tag="x.new")[:, ::2]
+    g.project(0, X1.contiguous(), W, None, start)
+    k2, v2 = similarity()
+    assert np.all(k2[:, :, ::2] < 0.9) and np.all(v2[:, :, ::2] < 0.9)
+    assert np.allclose(k2[:, :, 1::2], 1.0, atol=2e-6) and np.allclose(v2[:, :, 1::2], 1.0, atol=2e-6)
+    g.close()
