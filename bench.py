@@ -2,7 +2,7 @@
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--layers N]
                     [--workload c4|c2|c3|c5|c5_refresh|c4_layer|c2_layer|c3_layer|c5_layer|c5_refresh_layer|
-                                c4_unmask|c5_unmask|c4_accept]
+                                c4_unmask|c5_unmask|c4_accept|c5_drift]
 
 A "step" is one pass of the whole hot path for one layer: QKV projection + RoPE + scatter of the
 active window, then attention of the window's queries over the cache.  The default workload is the
@@ -26,6 +26,8 @@ the 256-row refresh of 8 sequences (2048 rows).
 block's rows with arg-max and confidence, `fc_lm_head_argmax`, then `fc_unmask_select`; vocabulary
 152064 x hidden 3584, the Dream-7B sizes).  `--workload c4_accept` times the Guided Diffusion acceptance of
 one 32-token speculation block on synthetic DLM / AR logits (`fc_guided_accept`, Top-2 match, tau 0.5).
+`--workload c5_drift` times the KV drift diagnostic around a step (snapshot of the window rows with
+`fc_cache_read_rows`, then `fc_kv_similarity`) for the 256-row generation region of 8 sequences.
 
 Prints ONE JSON line (see the fields below).  Inputs are seeded and synthetic.
 """
@@ -59,7 +61,7 @@ def _parse():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="c4",
                     choices=["c2", "c3", "c4", "c5", "c5_refresh", "c4_layer", "c2_layer", "c3_layer", "c5_layer",
-                             "c5_refresh_layer", "c4_unmask", "c5_unmask", "c4_accept"])
+                             "c5_refresh_layer", "c4_unmask", "c5_unmask", "c4_accept", "c5_drift"])
     ap.add_argument("--layers", type=int, default=0, help="distinct layer caches to rotate over (0 = auto)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-single", action="store_true",
@@ -88,6 +90,8 @@ def main():
         return main_unmask(args, torch, fc, inputs, dev)
     if args.workload.endswith("_accept"):
         return main_accept(args, torch, fc, inputs, dev)
+    if args.workload.endswith("_drift"):
+        return main_drift(args, torch, fc, inputs, dev)
     refresh = args.workload == "c5_refresh"
     w = {"c2": inputs.C2, "c3": inputs.C3, "c4": inputs.C4, "c5": inputs.C5, "c5_refresh": inputs.C5}[args.workload]
     B, Dh, Hq, Hkv = w.batch, w.head_dim, w.n_q_heads, w.n_kv_heads
@@ -594,6 +598,75 @@ def main_accept(args, torch, fc, inputs, dev):
         out["cpu_baseline"] = {"value": round(dt * 1e6, 1), "unit": "us", "cores": 1, "kind": "oracle",
                                "sample": "one acceptance step of the same block and logits, single thread"}
         del np
+    print(json.dumps(out))
+
+
+def main_drift(args, torch, fc, inputs, dev):
+    """KV drift diagnostic of the generation region: snapshot before a step, similarity after it."""
+    w = inputs.C5
+    B, Hkv, Dh, S, rows, start, esz = w.batch, w.n_kv_heads, w.head_dim, w.kv_len, w.gen_len, w.cached_len, 2
+    n_layers = args.layers or 28
+    tdt = inputs.TORCH_DTYPE[w.dtype]
+    cfg = fc.make_config(n_layers, B, w.hidden, w.n_q_heads, Hkv, Dh, S, w.dtype, w.rope_base)
+    nbytes = fc.fc_cache_storage_bytes(cfg)
+    k_store = torch.randn(nbytes // esz, device=dev).to(tdt)
+    v_store = torch.randn(nbytes // esz, device=dev).to(tdt)
+    cache = fc.fc_cache_alloc(cfg, k_store, v_store)
+    kp = torch.empty((B, Hkv, rows, Dh), dtype=tdt, device=dev)
+    vp = torch.empty_like(kp)
+    sk = torch.empty((B, Hkv, rows), dtype=torch.float32, device=dev)
+    sv = torch.empty_like(sk)
+    stream = torch.cuda.current_stream().cuda_stream
+    steps = args.steps
+
+    def timed(fn):
+        res = []
+        for _ in range(args.repeats):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            torch.cuda.synchronize()
+            e0.record()
+            for s in range(steps):
+                fn(s % n_layers)
+            e1.record()
+            torch.cuda.synchronize()
+            res.append(e0.elapsed_time(e1) * 1000.0 / steps)
+        res.sort()
+        return res[len(res) // 2]
+
+    snap = lambda l: fc.fc_cache_read_rows(cache, l, kp, vp, start, rows, stream)
+    sim = lambda l: fc.fc_kv_similarity(cache, l, kp, vp, start, rows, sk, sv, stream)
+    for l in range(min(args.warmup, n_layers)):
+        snap(l)
+        sim(l)
+    us_both = timed(lambda l: (snap(l), sim(l)))
+    us_snap, us_sim = timed(snap), timed(sim)
+    row_bytes = 2 * B * Hkv * rows * Dh * esz          # K and V rows of the region
+    out = {
+        "metric": "us per layer for the KV drift diagnostic of the generation region (snapshot + similarity)",
+        "value": round(us_both, 3), "unit": "us", "n_gpus": 1, "steps": steps, "warmup": min(args.warmup, n_layers),
+        "ms_per_step": round(us_both / 1000.0, 6), "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
+        "dtype": w.dtype, "data": "synthetic",
+        "config": {"workload": w.name + "/kv-drift", "batch": B, "n_kv_heads": Hkv, "head_dim": Dh, "rows": rows,
+                   "layers_rotated": n_layers},
+        "roofline": {"kernel": "fc_kv_similarity (k_kv_similarity)", "bound": "hbm",
+                     "achieved": round(2 * row_bytes / us_sim * 1e-3, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": round(2 * row_bytes / us_sim * 1e-3 / HBM_PEAK_GBS, 4), "traffic": None,
+                     "algorithmic_bytes_per_launch": 2 * row_bytes, "us_per_launch": round(us_sim, 3)},
+        "snapshot_us": round(us_snap, 3),
+    }
+    if not args.no_cpu_baseline:
+        import numpy as np
+        from oracle import fc_oracle as orc
+        ocfg = orc.OracleConfig(B, w.hidden, w.n_q_heads, Hkv, Dh, S, w.dtype)
+        Kg = np.zeros((B, Hkv, S, Dh), np.float32)
+        Kg[:] = np.random.default_rng(0).normal(size=Kg.shape)
+        prev = Kg[:, :, start:start + rows].copy()
+        t0 = time.perf_counter()
+        orc.kv_similarity(ocfg, Kg, Kg, prev, prev, start)
+        out["cpu_baseline"] = {"value": round((time.perf_counter() - t0) * 1e6, 1), "unit": "us", "cores": 1,
+                               "kind": "oracle", "sample": "similarity of the same 256-row region of one layer, single thread"}
+    torch.cuda.synchronize()
+    fc.fc_cache_free(cache)
     print(json.dumps(out))
 
 
