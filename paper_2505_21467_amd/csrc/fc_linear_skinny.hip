@@ -77,7 +77,7 @@ __host__ __device__ __forceinline__ int owner_of(int64_t u, int64_t U, int G)
 }
 
 template <int MT, int KSL, int MODE>
-__global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) void k_linear_stream(LinArgs p)
+__global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(KSL >= 512 ? 2 : 4, KSL >= 512 ? 2 : 4))) void k_linear_stream(LinArgs p)
 {
     constexpr int KS = KSL / 32;        // k-steps of 32 per item
     constexpr int ROWB = KSL * 2;       // bytes of one X row of a slice
@@ -311,7 +311,10 @@ __global__ __launch_bounds__(512) void k_lmhead_finish(LinArgs p)
     }
 }
 
-constexpr int KSL = 512;  // hidden elements per work item
+#ifndef FC_LIN_KSL
+#define FC_LIN_KSL 512
+#endif
+constexpr int KSL = FC_LIN_KSL;  // hidden elements per work item
 
 template <int MODE>
 hipError_t launch_mode(const FcSkinnyPlan &pl, const LinArgs &a, hipStream_t s)
