@@ -156,3 +156,62 @@ def test_config5_one_layer_of_28_cached_step_and_block_refresh():
     K0, V0 = g.read_rows(0, 0, 64)  # other layers untouched
     assert np.all(K0 == 0) and np.all(V0 == 0)
     g.close()
+
+
+def _dev(t):
+    return t.to("cuda:0").contiguous()
+
+
+def test_refresh_width_linear_layers_sampled_rows():
+    """The linear layers of the whole-layer refresh (2048 rows at the 7B widths) in the launch
+    configuration the bench uses; the oracle checks sampled rows (the layers are row-wise)."""
+    M, d, F = 2048, 3584, 18944
+    rows = [0, 1, 255, 256, 1023, 1500, 2047]
+    _say("refresh-width linear layers bf16 M2048 d3584 d_ff18944")
+    x = inputs.normal(51, "x", (M, d), 1.0, "bf16")
+    wg = inputs.normal(51, "wg", (F, d), 0.02, "bf16")
+    wu = inputs.normal(51, "wu", (F, d), 0.02, "bf16")
+    need = max(fc.fc_linear_workspace_bytes("bf16", M, d, 2 * F), fc.fc_linear_workspace_bytes("bf16", M, F, d))
+    ws = torch.empty(max(need, 16), dtype=torch.uint8, device="cuda:0")
+    act = torch.full((M, F), float("nan"), dtype=torch.bfloat16, device="cuda:0")
+    xd = _dev(x)
+    fc.fc_ffn_gate_up("bf16", xd, _dev(wg), _dev(wu), M, d, F, act, ws, need)
+    torch.cuda.synchronize()
+    got = inputs.as_oracle(act)
+    assert np.all(np.isfinite(got))
+    ref = orc.ffn_gate_up(inputs.as_oracle(x)[rows], inputs.as_oracle(wg), inputs.as_oracle(wu), "bf16")
+    assert_close(got[rows], ref, "bf16", "gated W_1, 2048 rows")
+    del wg, wu
+    wd = inputs.normal(51, "wd", (d, F), 0.02, "bf16")
+    y = torch.full((M, d), float("nan"), dtype=torch.bfloat16, device="cuda:0")
+    fc.fc_linear_residual("bf16", act, _dev(wd), xd, M, F, d, y, ws, need)
+    torch.cuda.synchronize()
+    goty = inputs.as_oracle(y)
+    assert np.all(np.isfinite(goty))
+    refy = orc.linear_residual(got[rows], inputs.as_oracle(wd), inputs.as_oracle(x)[rows], "bf16")
+    assert_close(goty[rows], refy, "bf16", "W_2 + residual, 2048 rows")
+
+
+def test_vocabulary_projection_at_full_vocabulary():
+    """fc_lm_head_argmax at the Dream-7B sizes (32 rows, hidden 3584, vocabulary 152064), as the bench
+    runs it; the oracle computes three of the rows against the whole vocabulary."""
+    M, K, V = 32, 3584, 152064
+    rows = [0, 13, 31]
+    _say("vocabulary projection bf16 M32 K3584 V152064")
+    x = inputs.normal(52, "h", (M, K), 1.0, "bf16")
+    w = inputs.normal(52, "w_vocab", (V, K), 0.02, "bf16")
+    need = fc.fc_lm_head_workspace_bytes("bf16", M, K, V)
+    ws = torch.empty(need, dtype=torch.uint8, device="cuda:0")
+    tok = torch.full((M,), -1, dtype=torch.int32, device="cuda:0")
+    conf = torch.full((M,), float("nan"), dtype=torch.float32, device="cuda:0")
+    fc.fc_lm_head_argmax("bf16", _dev(x), _dev(w), M, K, V, tok, conf, ws, need)
+    torch.cuda.synchronize()
+    tok, conf = tok.cpu().numpy(), conf.cpu().numpy()
+    assert np.all((tok >= 0) & (tok < V)) and np.all(np.isfinite(conf)) and np.all(conf > 0) and np.all(conf <= 1)
+    rt, rc, z = orc.lm_head_argmax(inputs.as_oracle(x)[rows], inputs.as_oracle(w), want_logits=True)
+    top = z.max(axis=1)
+    second = np.partition(z, -2, axis=1)[:, -2]
+    clear = top - second > 2e-4
+    assert np.array_equal(tok[rows][clear], rt[clear])
+    assert np.all(top - z[np.arange(len(rows)), tok[rows]] <= 2e-4)
+    assert np.allclose(conf[rows], rc, rtol=2e-3)
