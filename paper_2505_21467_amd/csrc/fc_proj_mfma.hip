@@ -451,7 +451,8 @@ hipError_t fc_launch_project_mfma(const FcGeom &G, const double *inv_freq, const
     a.counters = (unsigned *)scratch;
     a.partials = scratch ? (float *)((char *)scratch + FC_SCRATCH_COUNTER_BYTES) : nullptr;
     const int slots = G.Hq + 2 * G.Hkv;
-    if (scratch && a.M <= 32 && a.K % HS_K == 0 && (size_t)slots * sizeof(unsigned) <= FC_SCRATCH_COUNTER_BYTES / 2 &&
+    static const bool no_headsplit = getenv("FC_PROJ_NO_HEADSPLIT") != nullptr;  // tuning knob
+    if (!no_headsplit && scratch && a.M <= 32 && a.K % HS_K == 0 && (size_t)slots * sizeof(unsigned) <= FC_SCRATCH_COUNTER_BYTES / 2 &&
         (size_t)slots * (a.K / HS_K) * 8 * 2 * 256 * sizeof(float) <= FC_SCRATCH_PARTIAL_BYTES) {
         const unsigned grid = (unsigned)(slots * (a.K / HS_K));
         if (a.M <= 16) {
