@@ -47,6 +47,9 @@ struct GemmArgs {
     int n_mt;              // row tiles of 32 * NW window rows
     int n_units;           // head slots (NSUB = 4) or half-head slots (NSUB = 2)
     int n_slots;           // 128-row slabs of W: head slots (EPI 0), N / 128 (EPI 1, 3), d_ff / 64 (EPI 2)
+    // The part of the problem this launch covers (a problem may be cut into two launches with different
+    // tile shapes, see launch_pieces): slabs [slot_base, slot_base + slots_here), rows [m_base, m_end).
+    int slot_base, slots_here, m_base, m_end;
     double log2_base_64;   // log2(rope_base) / 64
     // plain linear layers of the rest of the layer (EPI != 0)
     const uint16_t *W2;    // EPI 2: the up matrix [N][K] (W is the gate matrix)
@@ -121,6 +124,7 @@ __global__ __launch_bounds__((NW + NL) * 64) void k_proj_gemm(GemmArgs p)
     static_assert(KS == 64 || KS == 128, "stage depth");
     static_assert(NW % NG == 0 && NBLK % NLW == 0 && (WROWS / RPB) % NLW == 0 && (NSUB == 4 || NG == 1), "tile shape");
     static_assert((SLOTS - 1) * LBW < 64 && SLOTS >= 2 && SLOTS <= 4, "vmcnt range");
+    static_assert(EPI == 0 || NG == 1, "the plain linear layers use one slab per workgroup");
     extern __shared__ __align__(1024) unsigned char smem[];
     const FcGeom &G = p.G;
     FC_GSTAMP(0);
@@ -132,7 +136,7 @@ __global__ __launch_bounds__((NW + NL) * 64) void k_proj_gemm(GemmArgs p)
     const int mt = qd % p.n_mt;
     const int unit = (qd / p.n_mt) * 8 + xcd;
     if (unit >= p.n_units) return;
-    const int m0 = mt * XROWS;
+    const int m0 = p.m_base + mt * XROWS;
     const int n_slots = p.n_slots;             // EPI 0: Hq query heads, Hkv key heads, Hkv value heads
 
     const int tid = threadIdx.x, lane = tid & 63;
@@ -141,7 +145,7 @@ __global__ __launch_bounds__((NW + NL) * 64) void k_proj_gemm(GemmArgs p)
     const bool is_loader = NL > 0 && wave >= NW;  // wave-uniform
     const int lw = NL > 0 ? wave - NW : wave;     // index among the loading waves
     const int wn = (wave % NW) / WM, wm = wave % WM;  // this wave's head group and row group
-    const int hs = NSUB == 4 ? unit * NG + wn : unit >> 1;
+    const int hs = p.slot_base + (NSUB == 4 ? unit * NG + wn : unit >> 1);
     const int half = NSUB == 4 ? 0 : unit & 1;  // which rotary-paired half of the head
     const bool head_valid = hs < n_slots;       // an odd number of heads leaves the last pair half empty
 
@@ -157,16 +161,16 @@ __global__ __launch_bounds__((NW + NL) * 64) void k_proj_gemm(GemmArgs p)
         if (i < WBW) {
             int n;
             if (EPI == 2) {  // row of the gate or of the up matrix (which of the two: see issue_stage)
-                const int u = min(NSUB == 4 ? unit : hs, n_slots - 1);
+                const int u = min(hs, n_slots - 1);  // NG = 1 here: hs is the slab of the whole workgroup
                 n = u * 64 + (NSUB == 4 ? rl & 63 : 32 * half + (rl & 31));
             } else if (NSUB == 4) {
-                n = min(unit * NG + rl / 128, n_slots - 1) * 128 + (rl & 127);
+                n = min(p.slot_base + unit * NG + rl / 128, n_slots - 1) * 128 + (rl & 127);
             } else {
                 n = min(hs, n_slots - 1) * 128 + (rl >> 5) * 64 + 32 * half + (rl & 31);
             }
             goff[i] = (uint32_t)n * (uint32_t)(p.K * 2) + c * 16;
         } else {
-            const int m = min(m0 + rl, p.M - 1);    // rows past the end re-read the last row; never stored
+            const int m = min(m0 + rl, p.m_end - 1);  // rows past the end re-read the last row; never stored
             goff[i] = (uint32_t)m * (uint32_t)(p.K * 2) + c * 16;
         }
     }
@@ -346,7 +350,7 @@ __global__ __launch_bounds__((NW + NL) * 64) void k_proj_gemm(GemmArgs p)
             const float mx2 = __shfl_xor(mx, 32, 64), sm2 = __shfl_xor(sm, 32, 64);
             const int arg2 = __shfl_xor(arg, 32, 64);
             fc_argmax_merge(mx, arg, sm, mx2, arg2, sm2);
-            if (hi == 0 && m < p.M) {
+            if (hi == 0 && m < p.m_end) {
                 const size_t at = (size_t)hs * p.M + m;
                 p.am.mx[at] = mx;
                 p.am.arg[at] = arg;
@@ -361,7 +365,7 @@ __global__ __launch_bounds__((NW + NL) * 64) void k_proj_gemm(GemmArgs p)
 #pragma unroll
         for (int i = 0; i < MW; ++i) {
             const int m = m0 + 32 * (wm * MW + i) + col;
-            if (m >= p.M) continue;
+            if (m >= p.m_end) continue;
 #pragma unroll
             for (int t = 0; t < (EPI == 2 ? NSUB / 2 : NSUB); ++t) {
                 const int tq = NSUB == 4 ? t : (EPI == 2 ? half : half + 2 * t);
@@ -403,7 +407,7 @@ __global__ __launch_bounds__((NW + NL) * 64) void k_proj_gemm(GemmArgs p)
 #pragma unroll
     for (int i = 0; i < MW; ++i) {
         const int m = m0 + 32 * (wm * MW + i) + col;
-        const bool mvalid = m < p.M;
+        const bool mvalid = m < p.m_end;
         const int mm = mvalid ? m : 0;
         const int b = mm / p.A, a = mm - b * p.A;
         const int pp = p.pos ? p.pos[mm] : p.win_start + a;
@@ -486,9 +490,11 @@ hipError_t launch_gemm(GemmArgs a, hipStream_t s)
     static hipError_t attr = hipFuncSetAttribute((const void *)k_proj_gemm<KS, NW, NSUB, MW, NG, SLOTS, NL, EPI>,
                                                  hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
     if (attr != hipSuccess) return attr;
-    const int slots = a.n_slots;
+    const int slots = a.slots_here;
     a.n_units = NSUB == 4 ? (slots + NG - 1) / NG : 2 * slots;
-    a.n_mt = (a.M + XROWS - 1) / XROWS;
+    a.n_mt = (a.m_end - a.m_base + XROWS - 1) / XROWS;
+    if (slots < 1 || a.n_mt < 1 || a.slot_base < 0 || a.slot_base + slots > a.n_slots || a.m_base < 0 || a.m_end > a.M)
+        return hipErrorInvalidValue;
     const unsigned grid = (unsigned)(((a.n_units + 7) / 8) * 8 * a.n_mt);
     const unsigned gy = EPI == 3 ? (unsigned)a.ksplit : 1u;
     k_proj_gemm<KS, NW, NSUB, MW, NG, SLOTS, NL, EPI><<<dim3(grid, gy), dim3((NW + NL) * 64), LDS, s>>>(a);
@@ -528,6 +534,52 @@ hipError_t launch_wide_shape(int shape, const GemmArgs &a, hipStream_t s)
     if (shape == 0) return launch_gemm<64, 8, 4, 1, 1, 3, 0, EPI>(a, s);  // 256 rows x slab
     if (shape == 1) return launch_gemm<64, 4, 4, 1, 1, 4, 4, EPI>(a, s);  // 128 rows x slab
     return launch_gemm<64, 4, 2, 1, 1, 4, 4, EPI>(a, s);                  // 128 rows x half slab
+}
+
+// Tile choice: the largest tile that still gives the chip about one workgroup per compute unit.
+// 0: 256 rows x slab, 1: 128 rows x slab, 2: 128 rows x half slab.
+int pick_shape(int64_t slots, int64_t rows, bool allow_half)
+{
+    if (slots * ((rows + 255) / 256) >= 192) return 0;
+    if (slots * ((rows + 127) / 128) >= 144 || !allow_half) return 1;
+    return 2;
+}
+
+// One workgroup of the 256-row shape fills a compute unit, so a grid of a little more than 256 such
+// workgroups ends with a nearly empty second round.  A problem with a single row tile and a few slabs
+// more than 256 is therefore cut in two: 256 slabs in the 256-row shape, the other slabs as a second
+// launch with the (smaller) tile that suits them (measured at 256 rows x 296 slabs: 115 -> 96 us).
+// Cutting along the rows (several row tiles, e.g. 36 slabs x 8 row tiles = 288 workgroups) and cutting
+// grids of several rounds were measured slower than the plain launch and are not done.
+struct GemmPiece {
+    int shape, slot_base, slots, m_base, m_end;
+};
+int plan_pieces(int slots, int M, bool allow_half, GemmPiece out[2])
+{
+    out[0] = GemmPiece{pick_shape(slots, M, allow_half), 0, slots, 0, M};
+    static const bool no_split = getenv("FC_GEMM_NO_SPLIT") != nullptr;  // tuning knob
+    if (out[0].shape != 0 || no_split) return 1;
+    const int64_t mt = (M + 255) / 256, tiles = (int64_t)slots * mt, rounds = tiles / 256, rem = tiles % 256;
+    if (mt != 1 || rounds != 1 || rem == 0 || rem > 160) return 1;
+    out[0].slots = 256;
+    out[1] = GemmPiece{pick_shape(slots - 256, M, allow_half), 256, slots - 256, 0, M};
+    return 2;
+}
+
+template <int EPI>
+hipError_t launch_pieces(GemmArgs a, bool allow_half, hipStream_t s)
+{
+    GemmPiece pc[2];
+    const int n = plan_pieces(a.n_slots, a.M, allow_half, pc);
+    for (int i = 0; i < n; ++i) {
+        a.slot_base = pc[i].slot_base;
+        a.slots_here = pc[i].slots;
+        a.m_base = pc[i].m_base;
+        a.m_end = pc[i].m_end;
+        const hipError_t e = launch_wide_shape<EPI>(pc[i].shape, a, s);
+        if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
 }
 
 }  // namespace
@@ -593,13 +645,18 @@ hipError_t fc_launch_linear_wide(const FcWidePlan &pl, int mode, const void *x, 
     a.N = N;
     a.n_slots = mode == FC_LIN_GATE_UP ? N / 64 : N / 128;
     a.ksplit = pl.ksplit;
+    a.slot_base = 0;
+    a.slots_here = a.n_slots;
+    a.m_base = 0;
+    a.m_end = M;
+    const bool forced = getenv("FC_LIN_WIDE_SHAPE") != nullptr;  // a forced shape is used for the whole problem
     if (mode == FC_LIN_VOCAB) {
         if (!am || pl.shape > 1) return hipErrorInvalidValue;
         a.am = *am;
         return pl.shape == 0 ? launch_gemm<64, 8, 4, 1, 1, 3, 0, 4>(a, s) : launch_gemm<64, 4, 4, 1, 1, 4, 4, 4>(a, s);
     }
-    if (mode == FC_LIN_GATE_UP) return launch_wide_shape<2>(pl.shape, a, s);
-    if (pl.ksplit <= 1) return launch_wide_shape<1>(pl.shape, a, s);
+    if (mode == FC_LIN_GATE_UP) return forced ? launch_wide_shape<2>(pl.shape, a, s) : launch_pieces<2>(a, true, s);
+    if (pl.ksplit <= 1) return forced ? launch_wide_shape<1>(pl.shape, a, s) : launch_pieces<1>(a, true, s);
     hipError_t e = launch_wide_shape<3>(pl.shape, a, s);
     if (e != hipSuccess) return e;
     const size_t quads = (size_t)M * N / 4;
@@ -645,16 +702,29 @@ hipError_t fc_launch_project_gemm(const FcGeom &G, const void *x, const void *w,
     a.flags = getenv("FC_GEMM_FLAGS") ? atoi(getenv("FC_GEMM_FLAGS")) : 0;
     a.dbg = getenv("FC_GEMM_DBG_PTR") ? (unsigned long long *)strtoull(getenv("FC_GEMM_DBG_PTR"), nullptr, 0) : nullptr;
 #endif
-    // Tile choice: the largest tile that still gives the chip about one workgroup per compute unit.
-    const int slots = G.Hq + 2 * G.Hkv;
-    int shape = 0;  // 0: 256 rows x head, 1: 128 rows x head, 2: 128 rows x half head
-    if ((int64_t)slots * ((a.M + 255) / 256) < 192) shape = (int64_t)slots * ((a.M + 127) / 128) >= 144 ? 1 : 2;
-    if (const char *e = getenv("FC_PROJ_GEMM_SHAPE")) shape = atoi(e);  // tuning knob
     // The two 128-row shapes get four extra waves that only issue the loads (their four multiplying
     // waves are alone on their SIMDs); the half-head shape also takes 128 hidden elements per stage.
-    if (shape == 3) return launch_gemm<64, 8, 4, 2, 2, 2, 0>(a, s);   // 256 rows x two heads
-    if (shape == 0) return launch_gemm<64, 8, 4, 1, 1, 3, 0>(a, s);   // 256 rows x head
-    if (shape == 1) return launch_gemm<64, 4, 4, 1, 1, 4, 4>(a, s);   // 128 rows x head
-    if (a.K % 128 == 0) return launch_gemm<128, 4, 2, 1, 1, 3, 4>(a, s);  // 128 rows x half head
-    return launch_gemm<64, 4, 2, 1, 1, 4, 4>(a, s);
+    auto launch_shape = [&](int shape, const GemmArgs &g) -> hipError_t {
+        if (shape == 3) return launch_gemm<64, 8, 4, 2, 2, 2, 0>(g, s);   // 256 rows x two heads
+        if (shape == 0) return launch_gemm<64, 8, 4, 1, 1, 3, 0>(g, s);   // 256 rows x head
+        if (shape == 1) return launch_gemm<64, 4, 4, 1, 1, 4, 4>(g, s);   // 128 rows x head
+        if (g.K % 128 == 0) return launch_gemm<128, 4, 2, 1, 1, 3, 4>(g, s);  // 128 rows x half head
+        return launch_gemm<64, 4, 2, 1, 1, 4, 4>(g, s);
+    };
+    a.slot_base = 0;
+    a.slots_here = a.n_slots;
+    a.m_base = 0;
+    a.m_end = a.M;
+    if (const char *e = getenv("FC_PROJ_GEMM_SHAPE")) return launch_shape(atoi(e), a);  // tuning knob: one shape for all
+    GemmPiece pc[2];
+    const int n = plan_pieces(a.n_slots, a.M, true, pc);
+    for (int i = 0; i < n; ++i) {
+        a.slot_base = pc[i].slot_base;
+        a.slots_here = pc[i].slots;
+        a.m_base = pc[i].m_base;
+        a.m_end = pc[i].m_end;
+        const hipError_t e = launch_shape(pc[i].shape, a);
+        if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
 }

@@ -146,6 +146,30 @@ def test_ffn_gate_up_wide_window_tile_shapes(shape, monkeypatch):
     assert_close(inputs.as_oracle(out), ref, "bf16", "wide ffn_gate_up shape " + shape)
 
 
+def test_wide_linear_layers_cut_into_two_launches():
+    # 260 slabs x one row tile of the 256-row shape are 260 workgroups: 256 slabs run in that shape, the
+    # last 4 in a second launch with a smaller tile; both modes, every output checked
+    M, K = 100, 256
+    x = inputs.normal(15, "x", (M, K), 1.0, "bf16")
+    N = 128 * 260
+    w = inputs.normal(15, "w", (N, K), 0.05, "bf16")
+    r = inputs.normal(15, "r", (M, N), 1.0, "bf16")
+    assert fc.fc_linear_workspace_bytes("bf16", M, K, N) == 0
+    out = torch.full((M, N), float("nan"), dtype=torch.bfloat16, device=DEV)
+    fc.fc_linear_residual("bf16", _dev(x), _dev(w), _dev(r), M, K, N, out, None, 0)
+    torch.cuda.synchronize()
+    assert_close(inputs.as_oracle(out), orc.linear_residual(inputs.as_oracle(x), inputs.as_oracle(w), inputs.as_oracle(r),
+                                                            "bf16"), "bf16", "two-launch linear_residual")
+    F = 64 * 260
+    wg = inputs.normal(15, "wg", (F, K), 0.05, "bf16")
+    wu = inputs.normal(15, "wu", (F, K), 0.05, "bf16")
+    act = torch.full((M, F), float("nan"), dtype=torch.bfloat16, device=DEV)
+    fc.fc_ffn_gate_up("bf16", _dev(x), _dev(wg), _dev(wu), M, K, F, act, None, 0)
+    torch.cuda.synchronize()
+    assert_close(inputs.as_oracle(act), orc.ffn_gate_up(inputs.as_oracle(x), inputs.as_oracle(wg), inputs.as_oracle(wu),
+                                                        "bf16"), "bf16", "two-launch ffn_gate_up")
+
+
 def test_linear_calls_default_plan_at_block_widths():
     # the shapes of a 256-row block at the 7B widths, default plan: W_out and W_2 (28 slabs: hidden
     # dimension split), gated W_1 (296 slabs); rows sampled for the oracle
