@@ -49,7 +49,7 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0
 # from `rocprofv3 --pmc FETCH_SIZE` / `--pmc WRITE_SIZE` runs of this command, scaled by what the same
 # counters read for the plain 256 MiB copy at the end of this file (profiles/ holds the summary).
 MEASURED_ATTENTION_TRAFFIC_BYTES = {
-    "c4_dream7b_long_L16384_A32": 54_470_000,   # 36.47 + 7.31 MB (main kernel), 10.47 + 0.23 MB (merge)
+    "c4_dream7b_long_L16384_A32": 54_380_000,   # 36.45 + 7.31 MB (main kernel), 10.39 + 0.23 MB (merge)
     "c3_llada8b_B4_L4096_A64": 289_900_000,     # 277.0 + 4.46 MB, 6.35 + 2.10 MB
 }
 

@@ -482,16 +482,21 @@ __global__ __launch_bounds__(W * 64) __attribute__((amdgpu_waves_per_eu(2, 2))) 
     FC_STAMP(5);
 }
 
-// Merge the per-split partials: one wave per (row tile, pair of 16-byte accumulator slots).  Lane
-// (col, hi) owns row `col` of the tile and two groups of four consecutive head-dim elements, exactly
-// as in the first kernel's accumulators, so every load is a wave-wide contiguous 1 KB and all the
-// loads of a batch of CB splits are in flight together (CB covers all the splits whenever there are
-// at most 32).
-template <int CB>
-__global__ __launch_bounds__(64) void k_attn_combine(AttnArgs p)
+// Merge the per-split partials: one workgroup of NWV waves per (row tile, pair of 16-byte accumulator
+// slots).  Lane (col, hi) owns row `col` of the tile and two groups of four consecutive head-dim
+// elements, exactly as in the first kernel's accumulators, so every load is a wave-wide contiguous
+// 1 KB.  Each wave merges an equal share of the splits, CB of them per batch with all their loads in
+// flight together (the launch picks NWV and CB so that one batch per wave covers every split up to
+// 128: the merge is one memory round trip); the waves' states are then merged through LDS.
+template <int CB, int NWV>
+__global__ __launch_bounds__(64 * NWV) void k_attn_combine(AttnArgs p)
 {
     FC_STAMP(6);
-    const int lane = threadIdx.x, col = lane & 31, hi = lane >> 5;
+    __shared__ float xw[NWV > 1 ? NWV : 1][10][64];
+    const int lane = threadIdx.x & 63, col = lane & 31, hi = lane >> 5;
+    const int wv = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int per = (p.splits + NWV - 1) / NWV;
+    const int s_lo = min(wv * per, p.splits), s_hi = min(s_lo + per, p.splits);
     const int q2 = blockIdx.x & 7;           // accumulator slots 2 q2 and 2 q2 + 1: dt = q2 >> 1, rq = 2 (q2 & 1) + {0, 1}
     const size_t tg = blockIdx.x >> 3;       // (b * Hkv + j) * row_tiles + rt
     const int rt = (int)(tg % p.row_tiles);
@@ -504,12 +509,12 @@ __global__ __launch_bounds__(64) void k_attn_combine(AttnArgs p)
     float num[8];
 #pragma unroll
     for (int e = 0; e < 8; ++e) num[e] = 0.f;
-    for (int sb = 0; sb < p.splits; sb += CB) {
+    for (int sb = s_lo; sb < s_hi; sb += CB) {
         uint4 v[CB];
         float4 mlv[CB];  // (max in the log2 domain, sum, exponent of the half-float scaling, -)
 #pragma unroll
         for (int u = 0; u < CB; ++u) {
-            const int s = min(sb + u, p.splits - 1);
+            const int s = min(sb + u, s_hi - 1);
             v[u] = po[(size_t)s * (8 * 64)];
             mlv[u] = ml[(size_t)s * 32];
         }
@@ -524,7 +529,7 @@ __global__ __launch_bounds__(64) void k_attn_combine(AttnArgs p)
 #pragma unroll
         for (int u = 0; u < CB; ++u) {
             // weight of the split's sum; its stored values are (partial / sum) * 2^k
-            const float w = (sb + u < p.splits) ? __builtin_amdgcn_exp2f(mlv[u].x - m_new) * mlv[u].y : 0.f;
+            const float w = (sb + u < s_hi) ? __builtin_amdgcn_exp2f(mlv[u].x - m_new) * mlv[u].y : 0.f;
             const float wn = __builtin_amdgcn_ldexpf(w, -(int)mlv[u].z);
             union { uint4 u4; _Float16 h[8]; } x;
             x.u4 = v[u];
@@ -533,6 +538,29 @@ __global__ __launch_bounds__(64) void k_attn_combine(AttnArgs p)
             den += w;
         }
         m_run = m_new;
+    }
+    if (NWV > 1) {
+        // wave 0 (which always has a split) merges the states; a wave without splits holds (-inf, 0, 0)
+        xw[wv][0][lane] = m_run;
+        xw[wv][1][lane] = den;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) xw[wv][2 + e][lane] = num[e];
+        __syncthreads();
+        if (wv != 0) return;
+        float m_all = m_run;
+#pragma unroll
+        for (int w2 = 1; w2 < NWV; ++w2) m_all = fmaxf(m_all, xw[w2][0][lane]);
+        const float k0 = __builtin_amdgcn_exp2f(m_run - m_all);
+        den *= k0;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) num[e] *= k0;
+#pragma unroll
+        for (int w2 = 1; w2 < NWV; ++w2) {
+            const float kw2 = __builtin_amdgcn_exp2f(xw[w2][0][lane] - m_all);
+            den += kw2 * xw[w2][1][lane];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) num[e] += kw2 * xw[w2][2 + e][lane];
+        }
     }
 
     const int rho = rt * 32 + col;
@@ -619,9 +647,12 @@ hipError_t fc_launch_attention_mfma(const FcGeom &G, const FcAttnPlan &pl, const
 #ifdef FC_ATTN_TIMING
     if (a.dbg_flags & 8) return e;
 #endif
-    const dim3 cgrid((unsigned)(tiles * 8)), cblock(64);
-    if (pl.splits <= 8) k_attn_combine<8><<<cgrid, cblock, 0, s>>>(a);
-    else if (pl.splits <= 16) k_attn_combine<16><<<cgrid, cblock, 0, s>>>(a);
-    else k_attn_combine<32><<<cgrid, cblock, 0, s>>>(a);
+    const dim3 cgrid((unsigned)(tiles * 8));
+    if (pl.splits <= 2) k_attn_combine<2, 1><<<cgrid, dim3(64), 0, s>>>(a);
+    else if (pl.splits <= 8) k_attn_combine<8, 1><<<cgrid, dim3(64), 0, s>>>(a);
+    else if (pl.splits <= 16) k_attn_combine<8, 2><<<cgrid, dim3(128), 0, s>>>(a);
+    else if (pl.splits <= 32) k_attn_combine<8, 4><<<cgrid, dim3(256), 0, s>>>(a);
+    else if (pl.splits <= 64) k_attn_combine<16, 4><<<cgrid, dim3(256), 0, s>>>(a);
+    else k_attn_combine<32, 4><<<cgrid, dim3(256), 0, s>>>(a);
     return hipGetLastError();
 }
