@@ -167,13 +167,16 @@ __global__ __launch_bounds__(W * 64) __attribute__((amdgpu_waves_per_eu(2, 2))) 
     extern __shared__ __align__(1024) unsigned char smem[];
 
     FC_STAMP(0);
-    // Workgroup -> (unit, row group): the n_rg workgroups that stream the same keys get ids that are
-    // equal modulo 8, i.e. land on the same XCD and share its L2.
+    // Workgroup -> (unit, row group).  Workgroup ids that are equal modulo 8 land on the same XCD; the
+    // (unit, row group) pairs, ordered unit by unit, are dealt to the eight XCDs in equal contiguous
+    // runs, so the workgroups that stream the same keys share an L2 and every XCD gets the same number
+    // of workgroups whatever the number of units.
     const int id = blockIdx.x;
     const int xcd = id & 7, qd = id >> 3;
-    const int rg = qd % p.n_rg;
-    const int unit = (qd / p.n_rg) * 8 + xcd;
-    if (unit >= p.n_units) return;
+    const int64_t n_tiles = (int64_t)p.n_units * p.n_rg;
+    const int tile = (int)(xcd * n_tiles / 8) + qd;
+    if (tile >= (int)((xcd + 1) * n_tiles / 8)) return;
+    const int unit = tile / p.n_rg, rg = tile - unit * p.n_rg;
     const int split = unit % p.splits, bj = unit / p.splits;
     const int b = bj / p.Hkv, j = bj % p.Hkv;
 
@@ -587,8 +590,7 @@ hipError_t launch(const AttnArgs &args, hipStream_t s)
     static hipError_t attr = hipFuncSetAttribute((const void *)k_attn_mfma<T, W, KW>,
                                                  hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
     if (attr != hipSuccess) return attr;
-    const int groups8 = (args.n_units + 7) / 8;
-    const unsigned grid = (unsigned)(groups8 * 8 * args.n_rg);
+    const unsigned grid = (unsigned)(((int64_t)args.n_units * args.n_rg + 7) / 8 * 8);
     k_attn_mfma<T, W, KW><<<dim3(grid), dim3(W * 64), LDS_BYTES, s>>>(args);
     return hipGetLastError();
 }

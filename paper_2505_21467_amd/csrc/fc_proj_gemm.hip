@@ -129,13 +129,17 @@ __global__ __launch_bounds__((NW + NL) * 64) void k_proj_gemm(GemmArgs p)
     const FcGeom &G = p.G;
     FC_GSTAMP(0);
 
-    // Workgroup -> (unit, row tile): the n_mt workgroups that stream the same weight rows get ids that
-    // are equal modulo 8, i.e. land on the same XCD and share its L2.
+    // Workgroup -> (unit, row tile).  Workgroup ids that are equal modulo 8 land on the same XCD; the
+    // tiles, ordered unit by unit, are dealt to the eight XCDs in equal contiguous runs, so the
+    // workgroups that stream the same weight rows share an L2 and every XCD gets the same number of
+    // tiles (dealing whole units instead left 35 tiles on four XCDs and 28 on the others for 36 head
+    // slots x 7 row tiles: two rounds of 32 compute units instead of one, 100 us instead of 62).
     const int id = blockIdx.x;
     const int xcd = id & 7, qd = id >> 3;
-    const int mt = qd % p.n_mt;
-    const int unit = (qd / p.n_mt) * 8 + xcd;
-    if (unit >= p.n_units) return;
+    const int64_t n_tiles = (int64_t)p.n_units * p.n_mt;
+    const int tile = (int)(xcd * n_tiles / 8) + qd;
+    if (tile >= (int)((xcd + 1) * n_tiles / 8)) return;
+    const int unit = tile / p.n_mt, mt = tile - unit * p.n_mt;
     const int m0 = p.m_base + mt * XROWS;
     const int n_slots = p.n_slots;             // EPI 0: Hq query heads, Hkv key heads, Hkv value heads
 
@@ -495,7 +499,9 @@ hipError_t launch_gemm(GemmArgs a, hipStream_t s)
     a.n_mt = (a.m_end - a.m_base + XROWS - 1) / XROWS;
     if (slots < 1 || a.n_mt < 1 || a.slot_base < 0 || a.slot_base + slots > a.n_slots || a.m_base < 0 || a.m_end > a.M)
         return hipErrorInvalidValue;
-    const unsigned grid = (unsigned)(((a.n_units + 7) / 8) * 8 * a.n_mt);
+    const int64_t n_tiles = (int64_t)a.n_units * a.n_mt;
+    if (n_tiles > (1 << 30)) return hipErrorInvalidValue;
+    const unsigned grid = (unsigned)((n_tiles + 7) / 8 * 8);
     const unsigned gy = EPI == 3 ? (unsigned)a.ksplit : 1u;
     k_proj_gemm<KS, NW, NSUB, MW, NG, SLOTS, NL, EPI><<<dim3(grid, gy), dim3((NW + NL) * 64), LDS, s>>>(a);
     return hipGetLastError();
@@ -546,11 +552,11 @@ int pick_shape(int64_t slots, int64_t rows, bool allow_half)
 }
 
 // One workgroup of the 256-row shape fills a compute unit, so a grid of a little more than 256 such
-// workgroups ends with a nearly empty second round.  A problem with a single row tile and a few slabs
-// more than 256 is therefore cut in two: 256 slabs in the 256-row shape, the other slabs as a second
-// launch with the (smaller) tile that suits them (measured at 256 rows x 296 slabs: 115 -> 96 us).
-// Cutting along the rows (several row tiles, e.g. 36 slabs x 8 row tiles = 288 workgroups) and cutting
-// grids of several rounds were measured slower than the plain launch and are not done.
+// workgroups ends with a nearly empty second round.  Such a problem is cut in two: one round in the
+// 256-row shape and the rest -- the other slabs when there is one row tile (256 rows x 296 slabs:
+// 115 -> 96 us), else the last rows (36 slabs x 8 row tiles: 7 row tiles, then the last 256 rows) -- as
+// a second launch with the (smaller) tile that suits it.  Grids of several rounds are left alone
+// (cutting them was measured slower).
 struct GemmPiece {
     int shape, slot_base, slots, m_base, m_end;
 };
@@ -560,9 +566,16 @@ int plan_pieces(int slots, int M, bool allow_half, GemmPiece out[2])
     static const bool no_split = getenv("FC_GEMM_NO_SPLIT") != nullptr;  // tuning knob
     if (out[0].shape != 0 || no_split) return 1;
     const int64_t mt = (M + 255) / 256, tiles = (int64_t)slots * mt, rounds = tiles / 256, rem = tiles % 256;
-    if (mt != 1 || rounds != 1 || rem == 0 || rem > 160) return 1;
-    out[0].slots = 256;
-    out[1] = GemmPiece{pick_shape(slots - 256, M, allow_half), 256, slots - 256, 0, M};
+    if (rounds != 1 || rem == 0 || rem > 160) return 1;
+    if (mt == 1) {
+        out[0].slots = 256;
+        out[1] = GemmPiece{pick_shape(slots - 256, M, allow_half), 256, slots - 256, 0, M};
+    } else {
+        const int mt1 = 256 / slots;  // row tiles of the first round
+        if (mt1 * slots < 224) return 1;
+        out[0].m_end = mt1 * 256;
+        out[1] = GemmPiece{pick_shape(slots, M - mt1 * 256, allow_half), 0, slots, mt1 * 256, M};
+    }
     return 2;
 }
 

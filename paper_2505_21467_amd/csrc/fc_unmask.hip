@@ -66,9 +66,20 @@ __global__ __launch_bounds__(256) void k_lmhead_reduce(FcArgmaxPart am, int part
     const int m = blockIdx.x, tid = threadIdx.x;
     float mx = -INFINITY, sm = 0.f;
     int arg = 0x7fffffff;
-    for (int pt = tid; pt < parts; pt += 256) {
-        const size_t at = (size_t)pt * M + m;
-        fc_argmax_merge(mx, arg, sm, am.mx[at], am.arg[at], am.sm[at]);
+    for (int base = 0; base < parts; base += 256 * 8) {  // eight parts per thread in flight at a time
+        float vmx[8], vsm[8];
+        int varg[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const int pt = base + 256 * u + tid;
+            const size_t at = (size_t)min(pt, parts - 1) * M + m;
+            vmx[u] = am.mx[at];
+            varg[u] = am.arg[at];
+            vsm[u] = am.sm[at];
+        }
+#pragma unroll
+        for (int u = 0; u < 8; ++u)
+            if (base + 256 * u + tid < parts) fc_argmax_merge(mx, arg, sm, vmx[u], varg[u], vsm[u]);
     }
     for (int off = 32; off > 0; off >>= 1) {
         const float mx2 = __shfl_xor(mx, off, 64), sm2 = __shfl_xor(sm, off, 64);

@@ -321,3 +321,23 @@ def test_kv_drift_similarity_matches_oracle(dtype, Dh):
     assert np.all(k2[:, :, ::2] < 0.9) and np.all(v2[:, :, ::2] < 0.9)
     assert np.allclose(k2[:, :, 1::2], 1.0, atol=2e-6) and np.allclose(v2[:, :, 1::2], 1.0, atol=2e-6)
     g.close()
+
+
+@pytest.mark.gpu
+def test_wide_window_projection_cut_into_two_launches():
+    """36 head slots x 8 row tiles of 256 rows are 288 workgroups of the 256-row shape: the projection
+    runs as 7 row tiles of that shape plus the last 256 rows with a smaller tile.  Every row checked."""
+    _say("wide-window projection in two launches, B8 A256 d192 28/4")
+    dtype, B, d, Hq, Hkv, Dh, L, A = "bf16", 8, 192, 28, 4, 128, 40, 256
+    w = inputs.Workload("t2", dtype, B, d, Hq, Hkv, Dh, L, A)
+    S = L + A
+    g, o = _pair(dtype, B, d, Hq, Hkv, Dh, S, max_rows=A, fill=0.5)
+    W, b = inputs.weights(w, 12), inputs.bias(w, 12)
+    X = inputs.hidden_states(w, 12, A)
+    Qg = inputs.as_oracle(g.project(0, X, W, b, L))
+    Qo = o.project_only(X, W, b, L)
+    assert_close(Qg, Qo, dtype, "Q")
+    written = np.zeros((B, S), bool)
+    written[:, L:S] = True
+    _compare_cache(g, o, dtype, written=written, what="two-launch projection")
+    g.close()
