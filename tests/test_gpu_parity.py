@@ -134,6 +134,35 @@ def test_cached_step_matches_oracle(dtype, B, d, Hq, Hkv, Dh, L, A):
     g.close()
 
 
+@pytest.mark.parametrize("B,d,Hq,Hkv,L,A", [
+    (1, 1024, 4, 1, 50, 33),    # 33 window rows: one ragged row tile
+    (3, 768, 6, 3, 90, 37),     # 111 rows
+    (5, 512, 8, 2, 64, 51),     # 255 rows: one padding row
+    (2, 1280, 2, 1, 40, 128),   # 256 rows exactly
+])
+def test_mid_window_projection(B, d, Hq, Hkv, L, A):
+    """Windows of 33..256 rows with hidden sizes that are multiples of 256, default tile choice (every
+    row and head checked)."""
+    _say("mid-window projection B%d d%d Hq%d Hkv%d L%d A%d" % (B, d, Hq, Hkv, L, A))
+    dtype, Dh = "bf16", 128
+    w = inputs.Workload("t", dtype, B, d, Hq, Hkv, Dh, L, A)
+    S = L + A
+    g, o = _pair(dtype, B, d, Hq, Hkv, Dh, S + 5, max_rows=A, fill=0.25)
+    K, V = inputs.kv_fill(w, 13, L)
+    g.write_rows(0, K, V, 0)
+    o.write_rows(K, V, 0)
+    W, b = inputs.weights(w, 13), inputs.bias(w, 13)
+    X = inputs.hidden_states(w, 13, A)
+    Qg, Og = g.step(0, X, W, b, L, S)
+    Qo, Oo = o.step(X, W, b, L, S)
+    assert_close(Qg, Qo, dtype, "Q")
+    assert_close(Og, Oo, dtype, "O")
+    written = np.zeros((B, S + 5), bool)
+    written[:, L:S] = True
+    _compare_cache(g, o, dtype, written=written, what="mid-window step")
+    g.close()
+
+
 @pytest.mark.parametrize("shape", [0, 1, 2, 3])
 @pytest.mark.parametrize("B,d,Hq,Hkv,L,A", [
     (3, 192, 8, 2, 100, 23),   # 69 window rows: one ragged row tile, three hidden stages
