@@ -289,6 +289,25 @@ def test_split_partials_keep_extreme_value_scales():
     g.close()
 
 
+@pytest.mark.parametrize("S", [1500, 6000, 12000, 32000])
+def test_merge_of_many_key_splits(S):
+    """One KV head, one row tile, long cache: the planner cuts the keys into 12, 47, 94 and 250 splits,
+    one for each launch variant of the merge kernel (2, 4 waves; 8, 16, 32 splits per wave and batch;
+    two batches per wave at 250)."""
+    dtype, B, Hq, Hkv, Dh, A = "bf16", 1, 2, 1, 128, 8
+    _say("attention over %d keys, one KV head: many key splits" % S)
+    w = inputs.Workload("t", dtype, B, 256, Hq, Hkv, Dh, 0, A)
+    g, o = _pair(dtype, B, 256, Hq, Hkv, Dh, S, max_rows=64)
+    K, V = inputs.kv_fill(w, 17, S)
+    g.write_rows(0, K, V, 0)
+    o.write_rows(K, V, 0)
+    Q = inputs.normal(17, "q", (B, Hq, A, Dh), 1.0, dtype)
+    Og = inputs.as_oracle(g.attend(0, g.dev_t(Q), S))
+    Oo = orc.attend(o.cfg, inputs.as_oracle(Q), o.Kc, o.Vc, S)
+    assert_close(Og, Oo, dtype, "O over %d keys" % S)
+    g.close()
+
+
 def test_multi_layer_caches_are_independent():
     dtype, B, d, Hq, Hkv, Dh, L, A = "bf16", 1, 256, 8, 2, 128, 96, 32
     _say("3 layers, step on layer 1 only")
