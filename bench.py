@@ -2,7 +2,7 @@
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--layers N]
                     [--workload c4|c2|c3|c5|c5_refresh|c4_layer|c2_layer|c3_layer|c5_layer|c5_refresh_layer|
-                                c4_unmask|c5_unmask|c4_accept|c5_drift]
+                                c4_unmask|c5_unmask|c4_accept|c5_drift|c5_decode|c5_decode_model]
 
 A "step" is one pass of the whole hot path for one layer: QKV projection + RoPE + scatter of the
 active window, then attention of the window's queries over the cache.  The default workload is the
@@ -28,6 +28,14 @@ block's rows with arg-max and confidence, `fc_lm_head_argmax`, then `fc_unmask_s
 one 32-token speculation block on synthetic DLM / AR logits (`fc_guided_accept`, Top-2 match, tau 0.5).
 `--workload c5_drift` times the KV drift diagnostic around a step (snapshot of the window rows with
 `fc_cache_read_rows`, then `fc_kv_similarity`) for the 256-row generation region of 8 sequences.
+
+`--workload c5_decode` runs the whole block schedule of configuration 5 on the hot path: 28 layers, 8
+sequences, prompt 2048 + 256 generated tokens in blocks of 32; a step is one denoising step of all 28
+layers (projection + scatter + attention of the active block, per-layer synthetic inputs) plus, after
+every 8th step, the refresh of the generation region in all layers; value = decoded tokens/s.
+`--workload c5_decode_model` does the same with whole layers and the unmasking step (token embeddings,
+28 x `fc_full_layer_step`, final norm, vocabulary projection, confidence-ranked fill): the decoding loop
+of a synthetic 7B-shaped model.
 
 Prints ONE JSON line (see the fields below).  Inputs are seeded and synthetic.
 """
@@ -57,11 +65,12 @@ MEASURED_ATTENTION_TRAFFIC_BYTES = {
 def _parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--steps", type=int, default=None, help="timed steps (default 100; 64 for the decode workloads)")
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="c4",
                     choices=["c2", "c3", "c4", "c5", "c5_refresh", "c4_layer", "c2_layer", "c3_layer", "c5_layer",
-                             "c5_refresh_layer", "c4_unmask", "c5_unmask", "c4_accept", "c5_drift"])
+                             "c5_refresh_layer", "c4_unmask", "c5_unmask", "c4_accept", "c5_drift", "c5_decode",
+                             "c5_decode_model"])
     ap.add_argument("--layers", type=int, default=0, help="distinct layer caches to rotate over (0 = auto)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-single", action="store_true",
@@ -84,6 +93,10 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     fc.lib()
     dev = torch.device("cuda:0")
+    if args.workload.startswith("c5_decode"):
+        args.steps = 64 if args.steps is None else args.steps
+        return main_decode(args, torch, fc, inputs, dev)
+    args.steps = 100 if args.steps is None else args.steps
     if args.workload.endswith("_layer"):
         return main_layer(args, torch, fc, inputs, dev)
     if args.workload.endswith("_unmask"):
@@ -429,6 +442,198 @@ def main_layer(args, torch, fc, inputs, dev):
                                "sample": "%d whole-layer step(s) of %d row(s) of one sequence of %s, fp64, OpenMP; "
                                          "scaled by %g to the %d rows of a step" % (n_sample, As, w.name, scale, M)}
         del np
+    torch.cuda.synchronize()
+    fc.fc_cache_free(cache)
+    print(json.dumps(out))
+
+
+def main_decode(args, torch, fc, inputs, dev):
+    """The block schedule of configuration 5 over all 28 layers; value = decoded tokens/s.
+
+    A step is one denoising step (section 3.2.1: the active block of 32 rows in every layer) and, when
+    the step completes a block (every 8th), the refresh of the 256-row generation region in every
+    layer.  `c5_decode`: projection + scatter + attention only, per-layer synthetic activations.
+    `c5_decode_model`: token embeddings -> 28 whole layers -> final norm -> vocabulary projection with
+    arg-max -> confidence-ranked fill of 4 tokens per sequence (section 3.1)."""
+    w = inputs.C5
+    whole = args.workload == "c5_decode_model"
+    B, Dh, Hq, Hkv, d, F, NL = w.batch, w.head_dim, w.n_q_heads, w.n_kv_heads, w.hidden, w.d_ff, w.n_layers
+    P, G, Bk, spb = w.cached_len, w.gen_len, w.block, w.steps_per_block
+    S, A, esz, V = P + G, Bk, 2, 152064
+    k_fill, MASK = Bk // spb, V
+    n_sched = (G // Bk) * spb
+    tdt = inputs.TORCH_DTYPE[w.dtype]
+    stream = torch.cuda.current_stream().cuda_stream
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(20250521)
+    rnd = lambda shape, std: (torch.randn(shape, generator=gen, device=dev, dtype=torch.float32) * std).to(tdt)
+
+    cfg = fc.make_config(NL, B, d, Hq, Hkv, Dh, S, w.dtype, w.rope_base)
+    nbytes = fc.fc_cache_storage_bytes(cfg)
+    k_store = torch.zeros(nbytes // esz, dtype=tdt, device=dev)
+    v_store = torch.zeros(nbytes // esz, dtype=tdt, device=dev)
+    cache = fc.fc_cache_alloc(cfg, k_store, v_store)
+
+    if whole:
+        layers = []
+        for layer in range(NL):
+            t = {"norm1": (1.0 + 0.1 * torch.randn(d, generator=gen, device=dev)).to(tdt), "w_qkv": rnd((w.qkv_width, d), 0.02),
+                 "w_out": rnd((d, Hq * Dh), 0.02), "norm2": (1.0 + 0.1 * torch.randn(d, generator=gen, device=dev)).to(tdt),
+                 "w_gate": rnd((F, d), 0.02), "w_up": rnd((F, d), 0.02), "w_down": rnd((d, F), 0.02)}
+            layers.append((t, fc.make_layer_weights(t["norm1"], t["w_qkv"], None, t["w_out"], t["norm2"], t["w_gate"],
+                                                    t["w_up"], t["w_down"], F, w.norm_eps)))
+        emb = rnd((V + 1, d), 1.0)                     # row V = the mask embedding
+        w_vocab = rnd((V, d), 0.02)
+        final_norm = (1.0 + 0.1 * torch.randn(d, generator=gen, device=dev)).to(tdt)
+        tokens0 = torch.full((B, S), MASK, dtype=torch.int32, device=dev)
+        tokens0[:, :P] = torch.randint(0, V, (B, P), generator=gen, device=dev, dtype=torch.int32)
+        tokens = tokens0.clone()
+        ws_bytes = fc.fc_full_layer_workspace_bytes(cfg, F, S)
+        lm_bytes = fc.fc_lm_head_workspace_bytes(w.dtype, B * A, d, V)
+        lm_ws = torch.empty(max(lm_bytes, 16), dtype=torch.uint8, device=dev)
+        tok = torch.empty((B * A,), dtype=torch.int32, device=dev)
+        conf = torch.empty((B * A,), dtype=torch.float32, device=dev)
+        pos_next = torch.empty((B, A), dtype=torch.int32, device=dev)
+        count = torch.empty((B,), dtype=torch.int32, device=dev)
+        bufs = {r: (torch.empty((B, r, d), dtype=tdt, device=dev), torch.empty((B, r, d), dtype=tdt, device=dev))
+                for r in (A, G, S)}
+    else:
+        W0 = inputs.weights(w, 0).to(dev)
+        Ws = [W0] + [W0.clone() for _ in range(NL - 1)]
+        Xs = [inputs.hidden_states(w, 0, A, tag="x.%d" % i).to(dev) for i in range(8)]
+        Xr = [rnd((B, G, d), 1.0) for _ in range(2)]
+        Xall = rnd((B, S, d), 1.0)
+        ws_bytes = fc.fc_workspace_bytes(cfg, S)
+        Q = {r: torch.empty((B, Hq, r, Dh), dtype=tdt, device=dev) for r in (A, G, S)}
+        O = {r: torch.empty((B, r, Hq * Dh), dtype=tdt, device=dev) for r in (A, G, S)}
+    ws = torch.empty(max(ws_bytes, 16), dtype=torch.uint8, device=dev)
+    torch.cuda.synchronize()
+
+    def forward(start, rows, n):
+        """All layers on the window [start, start + rows) of every sequence; returns the last hidden states."""
+        if not whole:
+            x = Xs[n % 8] if rows == A else (Xr[n % 2] if rows == G else Xall)
+            for layer in range(NL):
+                fc.fc_qkv_project_scatter(cache, layer, x, Ws[layer], None, start, rows, None, Q[rows], stream)
+                fc.fc_active_attention(cache, layer, Q[rows], rows, S, None, O[rows], ws, ws_bytes, stream)
+            return None
+        x, y = bufs[rows]
+        for b in range(B):  # the window's token ids of a sequence are contiguous: one embedding gather each
+            fc.fc_gather_rows(w.dtype, emb, V + 1, d, tokens[b, start:start + rows], rows, x[b], stream)
+        for layer in range(NL):
+            fc.fc_full_layer_step(cache, layer, layers[layer][1], x, start, rows, None, S, y, ws, ws_bytes, stream)
+            x, y = y, x
+        return x
+
+    def step(n):
+        s_idx = n % n_sched
+        if whole and s_idx == 0:
+            tokens.copy_(tokens0)                                  # a new generation: everything masked again
+        start, rows, _ = fc.fc_window(s_idx, P, G, Bk, spb, 0, 0)
+        h = forward(start, rows, n)
+        if whole:
+            hb = h.view(B * A, d)
+            fc.fc_rmsnorm(w.dtype, hb, final_norm, w.norm_eps, B * A, d, hb, stream)
+            fc.fc_lm_head_argmax(w.dtype, hb, w_vocab, B * A, d, V, tok, conf, lm_ws, lm_bytes, stream)
+            fc.fc_unmask_select(tok, conf, None, start, B, A, k_fill, MASK, tokens, S, pos_next, count, stream)
+        if s_idx % spb == spb - 1:
+            forward(P, G, n)                                       # the block is complete: refresh the generation region
+
+    # initial pass over prompt + generation region (all rows projected and cached), untimed but reported
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    forward(0, S, 0)
+    torch.cuda.synchronize()
+    init_ms = (time.perf_counter() - t0) * 1e3
+
+    for n in range(args.warmup):
+        step(n)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t_host0 = time.perf_counter()
+    e0.record()
+    for n in range(args.steps):
+        step(n)
+    e1.record()
+    torch.cuda.synchronize()
+    t_host = time.perf_counter() - t_host0
+    ms_total = e0.elapsed_time(e1)
+    tokens_done = args.steps * B * k_fill
+    n_refresh = sum(1 for n in range(args.steps) if (n % n_sched) % spb == spb - 1)
+
+    # the attention call of the cached step on its own (rotating over the 28 layers), for the roofline
+    if whole:
+        Qa = torch.randn((B, Hq, A, Dh), generator=gen, device=dev).to(tdt)
+        Oa = torch.empty((B, A, Hq * Dh), dtype=tdt, device=dev)
+    else:
+        Qa, Oa = Q[A], O[A]
+    res = []
+    for _ in range(args.repeats):
+        a0, a1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        a0.record()
+        for n in range(2 * NL):
+            fc.fc_active_attention(cache, n % NL, Qa, A, S, None, Oa, ws, ws_bytes, stream)
+        a1.record()
+        torch.cuda.synchronize()
+        res.append(a0.elapsed_time(a1) * 1000.0 / (2 * NL))
+    us_attn = sorted(res)[len(res) // 2]
+    attn_bytes = 2 * B * S * Hkv * Dh * esz + 2 * B * A * Hq * Dh * esz
+    roof = {"kernel": "fc_active_attention of the cached step (k_attn_mfma + k_attn_combine)", "bound": "hbm",
+            "achieved": round(attn_bytes / us_attn * 1e-3, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+            "frac": round(attn_bytes / us_attn * 1e-3 / HBM_PEAK_GBS, 4), "traffic": None,
+            "algorithmic_bytes_per_launch": attn_bytes, "us_per_launch": round(us_attn, 3)}
+    if whole:
+        # the longest call of a whole-layer cached step is the gated W_1 on the 256 window rows
+        M = B * A
+        lin_bytes = fc.fc_linear_workspace_bytes(w.dtype, M, d, 2 * F)
+        lws = torch.empty(max(lin_bytes, 16), dtype=torch.uint8, device=dev)
+        hx, actb = bufs[A][0].view(M, d), torch.empty((M, F), dtype=tdt, device=dev)
+        res = []
+        for _ in range(args.repeats):
+            a0, a1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            torch.cuda.synchronize()
+            a0.record()
+            for n in range(2 * NL):
+                t = layers[n % NL][0]
+                fc.fc_ffn_gate_up(w.dtype, hx, t["w_gate"], t["w_up"], M, d, F, actb, lws, lin_bytes, stream)
+            a1.record()
+            torch.cuda.synchronize()
+            res.append(a0.elapsed_time(a1) * 1000.0 / (2 * NL))
+        us_gate = sorted(res)[len(res) // 2]
+        gate_bytes = 2 * F * d * esz + M * (d + F) * esz
+        roof = {"kernel": "fc_ffn_gate_up of the cached step (k_proj_gemm, SiLU-gate epilogue, 256 rows)", "bound": "hbm",
+                "achieved": round(gate_bytes / us_gate * 1e-3, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": round(gate_bytes / us_gate * 1e-3 / HBM_PEAK_GBS, 4), "traffic": None,
+                "algorithmic_bytes_per_launch": gate_bytes, "us_per_launch": round(us_gate, 3),
+                "tflops": round(4.0 * M * d * F / us_gate * 1e-6, 1), "attention_us_per_launch": round(us_attn, 3)}
+
+    if whole:
+        # bookkeeping check: every step of the last generation filled 4 tokens per sequence
+        done = (args.steps - 1) % n_sched + 1
+        assert int((tokens[:, P:] == MASK).sum()) == B * G - done * B * k_fill, "fill bookkeeping"
+    out = {
+        "metric": "decoded tokens/s, 28-layer block schedule (%s)" % (
+            "whole layers + unmasking, synthetic 7B-shaped model" if whole else "projection + scatter + attention per layer"),
+        "value": round(tokens_done / (ms_total * 1e-3), 1), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": round(ms_total / args.steps, 4), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": w.dtype, "data": "synthetic",
+        "config": {"workload": w.name + ("/decode-model" if whole else "/decode"), "batch": B, "layers": NL, "prompt": P,
+                   "generated": G, "block": Bk, "steps_per_block": spb, "tokens_per_step_and_sequence": k_fill,
+                   "refreshes_in_timed_region": n_refresh, "hidden": d, "d_ff": F if whole else None,
+                   "vocab": V if whole else None},
+        "roofline": roof,
+        "initial_pass_ms": round(init_ms, 2),
+        "host_wall_ms_per_step": round(t_host * 1e3 / args.steps, 4),
+    }
+    if not args.no_cpu_baseline:
+        # bounded sample: cached layer-steps of the hot path (projection + scatter + attention) on the
+        # oracle, scaled to 28 layers; the refreshes and (for the model variant) the rest of the layer and
+        # the vocabulary projection are left out, so the oracle's real rate is lower still
+        cb = cpu_baseline(w, inputs, A, False)
+        out["cpu_baseline"] = {"value": round(B * k_fill / (NL * cb["value"] * 1e-6), 3), "unit": "tokens/s",
+                               "cores": cb["cores"], "kind": "oracle",
+                               "sample": cb["sample"] + "; scaled to 28 layers per step, refreshes not included"}
     torch.cuda.synchronize()
     fc.fc_cache_free(cache)
     print(json.dumps(out))
