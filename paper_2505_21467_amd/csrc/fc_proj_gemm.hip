@@ -57,7 +57,7 @@ struct GemmArgs {
     uint16_t *out;         // EPI 1, 2: [M][N]
     float *part;           // EPI 3: partial sums [ksplit][M][N]
     int N;                 // output columns
-    int ksplit;            // EPI 3: parts the hidden dimension is cut into (blockIdx.y)
+    int ksplit;            // EPI 3: parts the hidden dimension is cut into
     FcArgmaxPart am;       // EPI 4: per (slab, row) largest logit, its index, sum of exponentials
 #ifdef FC_GEMM_TUNE
     int flags;             // tuning builds only: 1 skip the multiplies, 2 skip the LDS reads, 4 skip the global loads
@@ -104,7 +104,7 @@ __device__ __forceinline__ void wait_stages(int k)
 // head slots: 1 = out = residual + x w^T; 2 = out = silu(x w_gate^T) * (x w_up^T), a slab being 64
 // gate rows (sub-tiles 0, 1) and the same 64 up rows (sub-tiles 2, 3), so that both products of an
 // output sit in one lane like a rotary pair; 3 = fp32 partial sums of one part of the hidden dimension
-// (blockIdx.y), for matrices with too few slabs to fill the chip; 4 = vocabulary projection of the
+// (the parts are tiles of their own), for matrices with too few slabs to fill the chip; 4 = vocabulary projection of the
 // unmasking step: of the 128 logits of a slab only the largest, its index and the sum of
 // exp(logit - largest) are kept per row (NSUB = 4 only).
 template <int KS, int NW, int NSUB, int MW, int NG, int SLOTS, int NL, int EPI>
@@ -136,9 +136,12 @@ __global__ __launch_bounds__((NW + NL) * 64) void k_proj_gemm(GemmArgs p)
     // slots x 7 row tiles: two rounds of 32 compute units instead of one, 100 us instead of 62).
     const int id = blockIdx.x;
     const int xcd = id & 7, qd = id >> 3;
-    const int64_t n_tiles = (int64_t)p.n_units * p.n_mt;
-    const int tile = (int)(xcd * n_tiles / 8) + qd;
-    if (tile >= (int)((xcd + 1) * n_tiles / 8)) return;
+    // (EPI 3: the parts of the hidden dimension count as tiles too, so that they are dealt evenly as well)
+    const int n_kp = EPI == 3 ? p.ksplit : 1;
+    const int64_t n_tiles = (int64_t)p.n_units * p.n_mt * n_kp;
+    const int tile_k = (int)(xcd * n_tiles / 8) + qd;
+    if (tile_k >= (int)((xcd + 1) * n_tiles / 8)) return;
+    const int tile = tile_k / n_kp, kpart = tile_k - tile * n_kp;
     const int unit = tile / p.n_mt, mt = tile - unit * p.n_mt;
     const int m0 = p.m_base + mt * XROWS;
     const int n_slots = p.n_slots;             // EPI 0: Hq query heads, Hkv key heads, Hkv value heads
@@ -181,10 +184,10 @@ __global__ __launch_bounds__((NW + NL) * 64) void k_proj_gemm(GemmArgs p)
     // The loads of a stage are issued in four parts spread over the multiplies of the stage before,
     // because a wave that issues many of them back to back waits for the memory pipeline to take
     // them before it can issue anything else.  part < 0: all of them.
-    // part of the hidden dimension this workgroup covers (EPI 3 only: blockIdx.y of p.ksplit parts)
+    // part of the hidden dimension this workgroup covers (EPI 3 only: part kpart of p.ksplit)
     const int all_stages = p.K / KS;
-    const int st0 = EPI == 3 ? (int)((int64_t)blockIdx.y * all_stages / p.ksplit) : 0;
-    const int n_stages = EPI == 3 ? (int)(((int64_t)blockIdx.y + 1) * all_stages / p.ksplit) - st0 : all_stages;
+    const int st0 = EPI == 3 ? (int)((int64_t)kpart * all_stages / p.ksplit) : 0;
+    const int n_stages = EPI == 3 ? (int)(((int64_t)kpart + 1) * all_stages / p.ksplit) - st0 : all_stages;
     auto issue_stage = [&](int st, int part) {
         unsigned char *dst = smem + (st % SLOTS) * STAGE;
 #ifdef FC_GEMM_TUNE
@@ -383,7 +386,7 @@ __global__ __launch_bounds__((NW + NL) * 64) void k_proj_gemm(GemmArgs p)
                         if (EPI == 2) y[e] = y[e] / (1.0f + expf(-y[e])) * acc[i][t + NSUB / 2][4 * rq + e];
                     }
                     if (EPI == 3) {
-                        *(float4 *)(p.part + (size_t)blockIdx.y * p.M * p.N + at) = make_float4(y[0], y[1], y[2], y[3]);
+                        *(float4 *)(p.part + (size_t)kpart * p.M * p.N + at) = make_float4(y[0], y[1], y[2], y[3]);
                         continue;
                     }
                     if (EPI == 1 && p.res) {
@@ -499,11 +502,10 @@ hipError_t launch_gemm(GemmArgs a, hipStream_t s)
     a.n_mt = (a.m_end - a.m_base + XROWS - 1) / XROWS;
     if (slots < 1 || a.n_mt < 1 || a.slot_base < 0 || a.slot_base + slots > a.n_slots || a.m_base < 0 || a.m_end > a.M)
         return hipErrorInvalidValue;
-    const int64_t n_tiles = (int64_t)a.n_units * a.n_mt;
-    if (n_tiles > (1 << 30)) return hipErrorInvalidValue;
+    const int64_t n_tiles = (int64_t)a.n_units * a.n_mt * (EPI == 3 ? a.ksplit : 1);
+    if (n_tiles > (1 << 30) || (EPI == 3 && a.ksplit < 1)) return hipErrorInvalidValue;
     const unsigned grid = (unsigned)((n_tiles + 7) / 8 * 8);
-    const unsigned gy = EPI == 3 ? (unsigned)a.ksplit : 1u;
-    k_proj_gemm<KS, NW, NSUB, MW, NG, SLOTS, NL, EPI><<<dim3(grid, gy), dim3((NW + NL) * 64), LDS, s>>>(a);
+    k_proj_gemm<KS, NW, NSUB, MW, NG, SLOTS, NL, EPI><<<dim3(grid), dim3((NW + NL) * 64), LDS, s>>>(a);
     return hipGetLastError();
 }
 
@@ -614,14 +616,31 @@ FcWidePlan fc_plan_wide(int dtype, int mode, int M, int K, int N)
     if (units * t256 >= 192) p.shape = 0;
     else if (units * t128 >= 144 || mode == FC_LIN_VOCAB) p.shape = 1;
     else p.shape = 2;
-    // too few slabs even for the smallest tile: also cut the hidden dimension (partial sums in fp32)
+    // Too few slabs even for the smallest tile: also cut the hidden dimension (partial sums in fp32).
+    // Tile and number of parts are chosen together by a two-term estimate that reproduces the measured
+    // order (256 rows, 28 slabs, hidden 18944: 53 us for the 256-row tile in 8 parts, 58 for the 128-row
+    // tile in 4, 68 for the half slab in 2; hidden 3584: 24, 20, 18): a workgroup pulls the rows of
+    // both its operands at about 50 GB/s, and the partial sums are written and read at about 3 TB/s.
     const int64_t wgs = 2 * units * t128;
     if (mode == FC_LIN_RESIDUAL && p.shape == 2 && wgs < 192) {
-        int64_t ks = (256 + wgs / 2) / wgs;
         const int64_t stages = K / KS_MIN;
-        if (ks > stages / 8) ks = stages / 8;
-        if (ks > 16) ks = 16;
-        if (ks > 1) p.ksplit = (int)ks;
+        double best = 1e30;
+        for (int sh = 0; sh < 3; ++sh) {
+            const int64_t rows = sh == 0 ? 256 : 128, wrows = sh == 2 ? 64 : 128;
+            const int64_t tiles = units * (sh == 2 ? 2 : 1) * ((M + rows - 1) / rows);
+            for (int64_t ks = 1; ks <= 16; ++ks) {
+                if (ks > 1 && ks > stages / 8) break;
+                const int64_t wg = tiles * ks;
+                if (wg > 288) break;
+                const double fill_us = (double)((wg + 255) / 256) * (double)(rows + wrows) * (double)(K / ks) * 2.0 / 50e3;
+                const double part_us = ks > 1 ? (double)ks * M * N * 8.0 / 3e6 : 0.0;
+                if (fill_us + part_us < best) {
+                    best = fill_us + part_us;
+                    p.shape = sh;
+                    p.ksplit = (int)ks;
+                }
+            }
+        }
     }
     if (const char *e = getenv("FC_LIN_WIDE_SHAPE")) {  // tuning knobs
         const int v = atoi(e);
