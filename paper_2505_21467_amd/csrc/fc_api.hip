@@ -471,7 +471,7 @@ static fc_status linear_common(int32_t dtype, int mode, const void *x, const voi
     hipError_t e;
     if (wide.kind == 1)
         e = fc_launch_linear_wide(wide, mode, x, w, w2, res, M, K, N, out, workspace, (hipStream_t)stream);
-    else if (plan.kind == 1)
+    else if (plan.kind >= 1)
         e = fc_launch_linear_skinny(plan, mode, x, w, w2, res, M, K, N, out, workspace, (hipStream_t)stream);
     else
         e = fc_launch_linear_generic(dtype, mode, x, w, mode == FC_LIN_GATE_UP ? w2 : res, M, K, N, out,
@@ -603,7 +603,8 @@ LmHeadWs lm_head_ws(int dtype, int M, int K, int V)
     if (w.wide.kind == 1) w.plan.kind = 0;
     w.parts = w.wide.kind == 1 ? V / 128
                                : (w.plan.kind == 1 ? w.plan.slabs
-                                                   : (V + FC_LMHEAD_GENERIC_CHUNK - 1) / FC_LMHEAD_GENERIC_CHUNK);
+                                                   : (w.plan.kind == 2 ? w.plan.G  // one running triple per workgroup
+                                                                       : (V + FC_LMHEAD_GENERIC_CHUNK - 1) / FC_LMHEAD_GENERIC_CHUNK));
     size_t off = 0;
     auto take = [&](size_t bytes) {
         const size_t at = off;
@@ -650,7 +651,7 @@ fc_status fc_lm_head_argmax(int32_t dtype, const void *x, const void *w_vocab, i
     if (w.wide.kind == 1)
         e = fc_launch_linear_wide(w.wide, FC_LIN_VOCAB, x, w_vocab, nullptr, nullptr, M, K, V, nullptr, nullptr,
                                   (hipStream_t)stream, &am);
-    else if (w.plan.kind == 1)
+    else if (w.plan.kind >= 1)
         e = fc_launch_linear_skinny(w.plan, FC_LIN_VOCAB, x, w_vocab, nullptr, nullptr, M, K, V, nullptr, ws + w.tiles,
                                     (hipStream_t)stream, &am);
     else

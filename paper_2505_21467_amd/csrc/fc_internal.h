@@ -111,7 +111,7 @@ hipError_t fc_launch_linear_generic(int dtype, int mode, const void *x, const vo
                                     int M, int K, int N, void *out, hipStream_t s);
 // Launch plan of the weight-streaming linear kernels (host, pure function of the shape).
 struct FcSkinnyPlan {
-    int kind;    // 0 = plain kernel (no workspace), 1 = streaming kernels
+    int kind;    // 0 = plain kernel (no workspace), 1 = streaming kernels, 2 = whole-row kernel (T = half items, G)
     int mt;      // 16-row tiles per pass (1 or 2)
     int chunks;  // passes of up to 32 rows
     int slabs;   // 128-row slabs of the weight matrix (64 gate + 64 up rows in gated mode)

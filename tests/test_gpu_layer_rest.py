@@ -49,6 +49,9 @@ LINEAR_SHAPES = [
     ("bf16", 32, 3584, 3584, True),    # the output projection of the 7B geometry
     ("bf16", 32, 4608, 1536, True),    # long rows: many slices per slab, runs that straddle slabs
     ("bf16", 40, 1024, 384, True),     # two passes of up to 32 rows, ragged second pass
+    ("bf16", 17, 512, 408, True),      # whole-row kernel: 51 half items of 8 rows (the last item is half), ragged rows
+    ("bf16", 32, 4096, 4096 + 24, False),  # whole-row kernel at hidden 4096, more items than workgroups, odd half item
+    ("bf16", 3, 3584, 16 * 300, True),  # whole-row kernel, one 16-row tile of X, uneven runs (300 items over 256 workgroups)
 ]
 
 
@@ -91,6 +94,8 @@ def test_linear_residual_any_number_of_workgroups(wgs, monkeypatch):
 @pytest.mark.parametrize("dtype,M,K,F", [
     ("f32", 6, 40, 70), ("bf16", 5, 136, 72), ("bf16", 32, 1024, 320), ("bf16", 16, 512, 64),
     ("bf16", 32, 3584, 2368), ("bf16", 50, 1024, 192),
+    ("bf16", 9, 512, 100),        # whole-row kernel: 25 half items of 4 features
+    ("bf16", 32, 4096, 2052),     # whole-row kernel at hidden 4096, 513 half items over 256 workgroups
 ])
 def test_ffn_gate_up_matches_oracle(dtype, M, K, F):
     x = inputs.normal(4, "x", (M, K), 1.0, dtype)

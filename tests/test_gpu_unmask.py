@@ -59,6 +59,8 @@ def _check_lm_head(dtype, x, w, what):
     ("bf16", 32, 1024, 2048),
     ("bf16", 40, 1024, 640),      # two passes of rows
     ("bf16", 32, 3584, 8192),     # the 7B hidden width, a slice of the vocabulary
+    ("bf16", 11, 512, 1000),      # whole-row kernel: 125 half items, running triple per workgroup
+    ("bf16", 32, 4096, 4344),     # whole-row kernel at hidden 4096: 543 half items over 256 workgroups
 ])
 def test_lm_head_argmax_matches_oracle(dtype, M, K, V):
     x = inputs.normal(21, "x", (M, K), 1.0, dtype)
