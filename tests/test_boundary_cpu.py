@@ -177,16 +177,18 @@ def test_rest_of_layer_entry_points_reject_bad_arguments_before_any_launch(cache
     _raises(fc.FC_ERR_INVALID_ARG, Lr, BF, FAKE, FAKE, None, 0, 512, 128, FAKE, FAKE, big, S)
     _raises(fc.FC_ERR_UNSUPPORTED, Lr, BF, FAKE, FAKE, None, 32, 100, 128, FAKE, FAKE, big, S)
     _raises(fc.FC_ERR_INVALID_ARG, Lr, BF, FAKE + 2, FAKE, None, 32, 512, 128, FAKE, FAKE, big, S)
-    _raises(fc.FC_ERR_WORKSPACE, Lr, BF, FAKE, FAKE, None, 32, 512, 128, FAKE, None, 0, S)
-    _raises(fc.FC_ERR_WORKSPACE, Lr, BF, FAKE, FAKE, None, 32, 512, 128, FAKE, FAKE, 64, S)
+    _raises(fc.FC_ERR_WORKSPACE, Lr, BF, FAKE, FAKE, None, 32, 1024, 128, FAKE, None, 0, S)
+    _raises(fc.FC_ERR_WORKSPACE, Lr, BF, FAKE, FAKE, None, 32, 1024, 128, FAKE, FAKE, 64, S)
     Gu = fc.fc_ffn_gate_up
     _raises(fc.FC_ERR_INVALID_ARG, Gu, BF, FAKE, FAKE, None, 32, 512, 128, FAKE, FAKE, big, S)
     _raises(fc.FC_ERR_INVALID_ARG, Gu, BF, FAKE, None, FAKE, 32, 512, 128, FAKE, FAKE, big, S)
-    _raises(fc.FC_ERR_WORKSPACE, Gu, BF, FAKE, FAKE, FAKE, 32, 512, 128, FAKE, FAKE, 64, S)
+    _raises(fc.FC_ERR_WORKSPACE, Gu, BF, FAKE, FAKE, FAKE, 32, 1024, 128, FAKE, FAKE, 64, S)
 
-    # workspace sizes: streaming shapes need one, other shapes do not; the gated query is N = 2 F
+    # workspace sizes: the slice-wise streaming kernels need one (partial tiles), the whole-row kernel
+    # (hidden 3584 with at least one item per compute unit) and other shapes do not; the gated query is N = 2 F
     assert fc.fc_linear_workspace_bytes(BF, 32, 3584, 3584) > 0
-    assert fc.fc_linear_workspace_bytes(BF, 32, 3584, 2 * 18944) > 0
+    assert fc.fc_linear_workspace_bytes(BF, 32, 18944, 3584) > 0
+    assert fc.fc_linear_workspace_bytes(BF, 32, 3584, 2 * 18944) == 0
     assert fc.fc_linear_workspace_bytes(BF, 32, 520, 3584) == 0      # K not a multiple of 512
     assert fc.fc_linear_workspace_bytes("f32", 32, 3584, 3584) == 0
     assert fc.fc_linear_workspace_bytes(BF, 0, 3584, 3584) == 0
@@ -232,7 +234,9 @@ def test_unmasking_entry_points_reject_bad_arguments_before_any_launch():
     _raises(fc.FC_ERR_WORKSPACE, H, BF, FAKE, FAKE, 32, 512, 1024, FAKE, FAKE, FAKE, need - 1, S)
     assert fc.fc_lm_head_workspace_bytes(BF, 0, 512, 1024) == 0
     assert fc.fc_lm_head_workspace_bytes("f32", 4, 40, 300) > 0          # the plain kernel keeps per-part state too
-    assert fc.fc_lm_head_workspace_bytes(BF, 32, 3584, 152064) > fc.fc_lm_head_workspace_bytes(BF, 32, 3584, 1024)
+    assert fc.fc_lm_head_workspace_bytes(BF, 32, 1024, 152064) > fc.fc_lm_head_workspace_bytes(BF, 32, 1024, 1024)
+    # hidden 3584: the whole-row kernel keeps one (largest, index, sum) per workgroup and row, nothing else
+    assert fc.fc_lm_head_workspace_bytes(BF, 32, 3584, 152064) == 3 * 256 * 32 * 4
 
     U = fc.fc_unmask_select
     _raises(fc.FC_ERR_INVALID_ARG, U, None, FAKE, FAKE, 0, 2, 32, 4, 9, FAKE, 100, FAKE + 256, FAKE, S)
