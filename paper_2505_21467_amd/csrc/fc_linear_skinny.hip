@@ -3,7 +3,9 @@
 // (paper, Table 1, rows "Output projection", "FFN W_1", "FFN W_2" with the row count L replaced by
 // the window size A).
 //
-// With a few dozen rows the product Y^T = W X^T is bound by reading W once from HBM.  The weight
+// With a few dozen rows the product Y^T = W X^T is bound by reading W once from HBM.  Two kernels:
+// the slice-wise one described here, for any hidden size that is a multiple of 512, and a whole-row
+// one (k_linear_rows, further down) for the hidden sizes whose X block fits in registers.  The weight
 // matrix is cut into work items of 128 rows x KSL hidden elements (every row piece is 1 KB, or 512 B,
 // of contiguous memory); the items, ordered row slab by row slab, are dealt out in equal contiguous
 // runs to one workgroup per compute unit, so the matrix streams once, evenly, whatever its shape.
