@@ -192,6 +192,53 @@ def test_wide_window_projection_tile_shapes(monkeypatch, shape, B, d, Hq, Hkv, L
     g.close()
 
 
+@pytest.mark.parametrize("B,d,Hq,Hkv,L,A", [
+    (1, 512, 28, 4, 300, 32),    # 36 head slots (the 7B head geometry)
+    (2, 512, 3, 1, 77, 10),      # 5 head slots, 20 window rows (two 16-row tiles, the second ragged)
+    (1, 4096, 2, 2, 40, 7),      # hidden 4096, one 16-row tile
+    (3, 3584, 4, 2, 50, 9),      # hidden 3584, 27 rows
+])
+def test_short_window_projection_bias_and_scattered_positions(B, d, Hq, Hkv, L, A):
+    """Windows of at most 32 rows at hidden sizes 512 / 3584 / 4096, with bias and with scattered, padded
+    and out-of-range positions: q, every written K / V row and the freeze rule."""
+    _say("short-window projection B%d d%d Hq%d Hkv%d L%d A%d" % (B, d, Hq, Hkv, L, A))
+    dtype, Dh = "bf16", 128
+    w = inputs.Workload("t", dtype, B, d, Hq, Hkv, Dh, L, A)
+    S = L + A
+    g, o = _pair(dtype, B, d, Hq, Hkv, Dh, S + 7, max_rows=32, fill=0.75)
+    K, V = inputs.kv_fill(w, 19, L)
+    g.write_rows(0, K, V, 0)
+    o.write_rows(K, V, 0)
+    W, b = inputs.weights(w, 19), inputs.bias(w, 19)
+    X = inputs.hidden_states(w, 19, A)
+    # contiguous window
+    Qg, Og = g.step(0, X, W, b, L, S)
+    Qo, Oo = o.step(X, W, b, L, S)
+    assert_close(Qg, Qo, dtype, "Q")
+    assert_close(Og, Oo, dtype, "O")
+    written = np.zeros((B, S + 7), bool)
+    written[:, L:S] = True
+    _compare_cache(g, o, dtype, written=written, what="short-window step")
+    # scattered positions, one padded row and one position beyond the cache per sequence
+    gen = torch.Generator().manual_seed(5)
+    pos = torch.stack([torch.randperm(S + 7, generator=gen)[:A] for _ in range(B)]).to(torch.int32)
+    pos[:, 0] = -1
+    pos_o = pos.clone()
+    if A > 2:
+        pos[:, 2] = S + 100
+        pos_o[:, 2] = -1
+    Qg, Og = g.step(0, X, W, b, 0, S + 7, pos=pos)
+    Qo, Oo = o.step(X, W, b, 0, S + 7, pos=pos_o)
+    assert_close(Qg, Qo, dtype, "Q scattered")
+    assert_close(Og, Oo, dtype, "O scattered")
+    for bb in range(B):
+        for a in range(A):
+            if 0 <= int(pos_o[bb, a]) < S + 7:
+                written[bb, int(pos_o[bb, a])] = True
+    _compare_cache(g, o, dtype, written=written, what="short-window scattered step")
+    g.close()
+
+
 def test_scattered_positions_padding_and_bit_exact_scatter():
     """Arbitrary pos lists, padded rows, and the scatter as a pure bit copy (identity weights)."""
     dtype, B, Dh, Smax, A = "bf16", 2, 128, 210, 24
