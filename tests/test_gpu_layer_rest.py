@@ -110,6 +110,32 @@ def test_ffn_gate_up_matches_oracle(dtype, M, K, F):
     assert_close(inputs.as_oracle(out), ref, dtype, "ffn_gate_up")
 
 
+def test_whole_row_kernel_seeded_shape_sweep():
+    # hidden 512 (the whole-row kernel), 24 seeded shapes: 1..32 rows, 1..600 half items, with and without
+    # residual, both epilogues; every output checked
+    rng = np.random.default_rng(20250527)
+    for case in range(24):
+        M = int(rng.integers(1, 33))
+        gated = case % 2 == 1
+        N = int(rng.integers(1, 601)) * (4 if gated else 8)
+        x = inputs.normal(30 + case, "x", (M, 512), 1.0, "bf16")
+        w = inputs.normal(30 + case, "w", (N, 512), 0.05, "bf16")
+        if gated:
+            wu = inputs.normal(30 + case, "wu", (N, 512), 0.05, "bf16")
+            ref = orc.ffn_gate_up(inputs.as_oracle(x), inputs.as_oracle(w), inputs.as_oracle(wu), "bf16")
+            assert fc.fc_linear_workspace_bytes("bf16", M, 512, 2 * N) == 0
+            out = torch.full((M, N), float("nan"), dtype=torch.bfloat16, device=DEV)
+            fc.fc_ffn_gate_up("bf16", _dev(x), _dev(w), _dev(wu), M, 512, N, out, None, 0)
+        else:
+            r = inputs.normal(30 + case, "r", (M, N), 1.0, "bf16") if case % 4 == 0 else None
+            ref = orc.linear_residual(inputs.as_oracle(x), inputs.as_oracle(w), None if r is None else inputs.as_oracle(r),
+                                      "bf16")
+            out = torch.full((M, N), float("nan"), dtype=torch.bfloat16, device=DEV)
+            fc.fc_linear_residual("bf16", _dev(x), _dev(w), _dev(r), M, 512, N, out, None, 0)
+        torch.cuda.synchronize()
+        assert_close(inputs.as_oracle(out), ref, "bf16", "whole-row sweep case %d (M %d, N %d, gated %s)" % (case, M, N, gated))
+
+
 @pytest.mark.parametrize("shape", ["0", "1", "2"])
 @pytest.mark.parametrize("ksplit", ["1", "3"])
 def test_linear_residual_wide_window_tile_shapes(shape, ksplit, monkeypatch):
