@@ -68,6 +68,16 @@ def test_lm_head_argmax_matches_oracle(dtype, M, K, V):
     _check_lm_head(dtype, x, w, "lm_head %s %dx%dx%d" % (dtype, M, K, V))
 
 
+def test_lm_head_whole_row_kernel_seeded_shape_sweep():
+    # hidden 512 (the whole-row kernel), 12 seeded shapes: 1..32 rows, vocabulary of 1..600 half items of 8
+    rng = np.random.default_rng(20250528)
+    for case in range(12):
+        M, V = int(rng.integers(1, 33)), int(rng.integers(1, 601)) * 8
+        x = inputs.normal(40 + case, "x", (M, 512), 1.0, "bf16")
+        w = inputs.normal(40 + case, "w", (V, 512), 0.03, "bf16")
+        _check_lm_head("bf16", x, w, "lm_head sweep case %d (%d x 512 x %d)" % (case, M, V))
+
+
 @pytest.mark.parametrize("shape", ["0", "1"])
 def test_lm_head_argmax_wide_window(shape, monkeypatch):
     # more than 32 rows: the tiled GEMM keeps arg-max and confidence per slab in its epilogue
