@@ -56,6 +56,10 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0
 # HBM bytes per launch of the attention call (main kernel + merge kernel) on the default workload,
 # from `rocprofv3 --pmc FETCH_SIZE` / `--pmc WRITE_SIZE` runs of this command, scaled by what the same
 # counters read for the plain 256 MiB copy at the end of this file (profiles/ holds the summary).
+# HBM bytes per launch of the gated W_1 at 32 rows and the 7B widths (k_linear_rows), same method
+# (profiles/c4_whole_layer_step.md): 273.8 MB fetched + 3.1 MB written.
+MEASURED_GATE_UP_TRAFFIC_BYTES = {(32, 3584, 18944): 276_900_000}
+
 MEASURED_ATTENTION_TRAFFIC_BYTES = {
     "c4_dream7b_long_L16384_A32": 54_380_000,   # 36.45 + 7.31 MB (main kernel), 10.39 + 0.23 MB (merge)
     "c3_llada8b_B4_L4096_A64": 289_900_000,     # 277.0 + 4.46 MB, 6.35 + 2.10 MB
@@ -392,7 +396,8 @@ def main_layer(args, torch, fc, inputs, dev):
         roof = {"kernel": "fc_ffn_gate_up (%s)" % ("k_linear_stream + k_linear_finish" if M <= 32 else
                                                    "k_proj_gemm, SiLU-gate epilogue"), "bound": "hbm",
                 "achieved": gbs(w_bytes["gate_up"], us_gate), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                "frac": round(w_bytes["gate_up"] / us_gate * 1e-3 / HBM_PEAK_GBS, 4), "traffic": None,
+                "frac": round(w_bytes["gate_up"] / us_gate * 1e-3 / HBM_PEAK_GBS, 4),
+                "traffic": MEASURED_GATE_UP_TRAFFIC_BYTES.get((M, d, F)),
                 "algorithmic_bytes_per_launch": w_bytes["gate_up"] + M * (d + F) * esz,
                 "us_per_launch": round(us_gate, 3), "tflops": round(gate_flops / us_gate * 1e-6, 1)}
     out = {
