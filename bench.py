@@ -60,6 +60,9 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0
 # (profiles/c4_whole_layer_step.md): 273.8 MB fetched + 3.1 MB written.
 MEASURED_GATE_UP_TRAFFIC_BYTES = {(32, 3584, 18944): 276_900_000}
 
+# The vocabulary projection of 32 rows (k_linear_rows, profiles/unmask_step.md): 1091.94 MB fetched, 0.1 MB written.
+MEASURED_LM_HEAD_TRAFFIC_BYTES = {(32, 3584, 152064): 1_092_040_000}
+
 MEASURED_ATTENTION_TRAFFIC_BYTES = {
     "c4_dream7b_long_L16384_A32": 54_380_000,   # 36.45 + 7.31 MB (main kernel), 10.39 + 0.23 MB (merge)
     "c3_llada8b_B4_L4096_A64": 289_900_000,     # 277.0 + 4.46 MB, 6.35 + 2.10 MB
@@ -709,7 +712,8 @@ def main_unmask(args, torch, fc, inputs, dev):
                          "k_linear_stream + k_lmhead_finish" if M <= 32 else "k_proj_gemm with the arg-max epilogue"),
                      "bound": "hbm",
                      "achieved": round(w_bytes / us_head * 1e-3, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": round(w_bytes / us_head * 1e-3 / HBM_PEAK_GBS, 4), "traffic": None,
+                     "frac": round(w_bytes / us_head * 1e-3 / HBM_PEAK_GBS, 4),
+                     "traffic": MEASURED_LM_HEAD_TRAFFIC_BYTES.get((M, d, V)),
                      "algorithmic_bytes_per_launch": w_bytes + M * d * esz + M * 8, "us_per_launch": round(us_head, 3),
                      "tflops": round(2.0 * M * d * V / us_head * 1e-6, 1)},
         "unmask_select_us": round(us_sel, 3),
