@@ -1,5 +1,6 @@
-"""The paper's literal reducing-window decoding loop (section 3.2.1) on a tiny synthetic diffusion LM,
-driven through the C-ABI ops and mirrored on the CPU oracle.
+"""The decoding loop (section 3.2.1) on a tiny synthetic diffusion LM, driven through the C-ABI ops and
+mirrored on the CPU oracle, in two schedules: the paper's literal reducing window, described below, and
+the block window with a refresh of the generation region after every block.
 
 Initial pass: every layer projects and caches all rows of prompt + generation region.  Then, block by
 block, the active window is the current block and all later ones: its rows are re-embedded, run
@@ -24,7 +25,11 @@ pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
 
 
-def test_reducing_window_decoding_loop_on_a_tiny_model():
+@pytest.mark.parametrize("mode", ["reducing", "block"])
+def test_decoding_loop_on_a_tiny_model(mode):
+    """mode "reducing": the paper's literal window (the current block and all later ones).  mode "block":
+    the window is the current block only, and after the last step of a block the whole generation
+    region is refreshed (the schedule of the 28-layer bench configuration)."""
     B, d, Hq, Hkv, Dh, F, V, NL = 2, 512, 4, 2, 128, 1024, 1024, 2
     P, G, Bk, spb = 24, 64, 16, 4          # 4 blocks of 16 tokens, 4 steps per block, 4 tokens per step
     S, MASK, k, eps, dt = P + G, V + 7, Bk // spb, 1e-6, "bf16"
@@ -88,9 +93,14 @@ def test_reducing_window_decoding_loop_on_a_tiny_model():
     close(inputs.as_oracle(x), xo, "initial pass output")
     n_blocks, rows_projected = G // Bk, 0
     for step in range(n_blocks * spb):
-        win_start, rows, _ = fc.fc_window(step, P, G, Bk, spb, 0, 1)        # the reducing window
+        if mode == "reducing":
+            win_start, rows, refresh_after = fc.fc_window(step, P, G, Bk, spb, 0, 1)
+            assert win_start + rows == S
+        else:
+            win_start, rows, refresh_after = fc.fc_window(step, P, G, Bk, spb, spb, 0)
+            assert rows == Bk and refresh_after == (1 if step % spb == spb - 1 else 0)
         blk = step // spb
-        assert win_start == P + blk * Bk and win_start + rows == S
+        assert win_start == P + blk * Bk
         before_k, before_v = g.snapshot()
         x, xo = forward(win_start, rows)
         rows_projected += rows
@@ -129,8 +139,20 @@ def test_reducing_window_decoding_loop_on_a_tiny_model():
         assert np.all(want_count == Bk - k * (step % spb + 1))
         assert np.all(tok_o[:, win_start + Bk:] == MASK)                   # later blocks stay masked
 
+        if mode == "block" and refresh_after:
+            # the block is complete: re-project the whole generation region in every layer; the prompt
+            # rows stay frozen
+            before_k, before_v = g.snapshot()
+            x, xo = forward(P, G)
+            close(inputs.as_oracle(x), xo, "refresh after step %d" % step)
+            after_k, after_v = g.snapshot()
+            assert _frozen_equal(g, before_k, after_k, before_v, after_v, P, NL), "a prompt row changed in a refresh"
+
     assert not np.any(tok_o == MASK)
-    assert rows_projected == spb * Bk * n_blocks * (n_blocks + 1) // 2     # closed form of the reducing window
+    if mode == "reducing":
+        assert rows_projected == spb * Bk * n_blocks * (n_blocks + 1) // 2  # closed form of the reducing window
+    else:
+        assert rows_projected == spb * Bk * n_blocks
     g.close()
 
 
