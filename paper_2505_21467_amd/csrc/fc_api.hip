@@ -122,6 +122,22 @@ FcAttnPlan fc_plan_attention(const fc_config &cfg, int A, int kv_len)
     // One workgroup per compute unit (its LDS ring takes 128 KB), so aim for one wave of them.
     const int r_default = p.row_tiles <= 2 ? 2 : (p.row_tiles <= 7 ? 4 : 8);
     int R = r_default, W = 8, target = 256;
+    {
+        // A short cache cannot give 256 eight-wave workgroups (a split takes at least 128 keys): with
+        // 3..7 row tiles, four-wave workgroups of two tiles, two per compute unit, then fill the chip
+        // better (one sequence, 28/4 heads, 32 rows: 10.7 against 12.7 us at 1056 keys, 11.4 against
+        // 13.9 at 2112; from about 4000 keys on the eight-wave shape is as fast or faster).
+        const int64_t n_rg8 = (p.row_tiles + r_default - 1) / r_default;
+        const int64_t base8 = (int64_t)cfg.batch * cfg.n_kv_heads * n_rg8;
+        const int64_t st = (kv_len + 63) / 64, by_len8 = st / 2 > 1 ? st / 2 : 1;
+        int64_t sp8 = (256 + base8 / 2) / base8;
+        if (sp8 > by_len8) sp8 = by_len8;
+        if (sp8 < 1) sp8 = 1;
+        if (r_default == 4 && base8 * sp8 < 256) {
+            R = 2;
+            W = 4;
+        }
+    }
     attn_env(&R, &W, &target);
     if (R != 2 && R != 4 && R != 8) R = r_default;
     if (W != 4 && W != 8) W = 8;
