@@ -396,7 +396,7 @@ def main_layer(args, torch, fc, inputs, dev):
                 "frac": round(gate_flops / us_gate * 1e-6 / MFMA_BF16_PEAK_TFLOPS, 4), "traffic": None,
                 "algorithmic_flops_per_launch": gate_flops, "us_per_launch": round(us_gate, 3)}
     else:
-        roof = {"kernel": "fc_ffn_gate_up (%s)" % ("k_linear_stream + k_linear_finish" if M <= 32 else
+        roof = {"kernel": "fc_ffn_gate_up (%s)" % ("k_linear_rows" if M <= 32 else
                                                    "k_proj_gemm, SiLU-gate epilogue"), "bound": "hbm",
                 "achieved": gbs(w_bytes["gate_up"], us_gate), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": round(w_bytes["gate_up"] / us_gate * 1e-3 / HBM_PEAK_GBS, 4),
@@ -709,7 +709,7 @@ def main_unmask(args, torch, fc, inputs, dev):
         "config": {"workload": w.name + "/unmask", "batch": B, "block_rows": A, "hidden": d, "vocab": V,
                    "unmasked_per_step": k, "matrices_rotated": n_mats},
         "roofline": {"kernel": "fc_lm_head_argmax (%s + k_lmhead_reduce)" % (
-                         "k_linear_stream + k_lmhead_finish" if M <= 32 else "k_proj_gemm with the arg-max epilogue"),
+                         "k_linear_rows" if M <= 32 else "k_proj_gemm with the arg-max epilogue"),
                      "bound": "hbm",
                      "achieved": round(w_bytes / us_head * 1e-3, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(w_bytes / us_head * 1e-3 / HBM_PEAK_GBS, 4),
