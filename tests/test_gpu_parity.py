@@ -280,22 +280,23 @@ def test_scattered_positions_padding_and_bit_exact_scatter():
     g.close()
 
 
-def test_degenerate_attention_cases():
-    dtype, B, Hq, Hkv, Dh = "bf16", 1, 4, 2, 128
-    w = inputs.Workload("t", dtype, B, 256, Hq, Hkv, Dh, 0, 8)
+@pytest.mark.parametrize("Hq,A", [(4, 8), (8, 24)])   # one row tile; three row tiles (four-wave workgroups)
+def test_degenerate_attention_cases(Hq, A):
+    dtype, B, Hkv, Dh = "bf16", 1, 2, 128
+    w = inputs.Workload("t", dtype, B, 256, Hq, Hkv, Dh, 0, A)
     _say("kv_len = 1 returns the single value row")
     g, o = _pair(dtype, B, 256, Hq, Hkv, Dh, 70, max_rows=64)
     K, V = inputs.kv_fill(w, 9, 70)
     g.write_rows(0, K, V, 0)
-    Q = inputs.normal(9, "q", (B, Hq, 8, Dh), 1.0, dtype)
-    O = inputs.as_oracle(g.attend(0, g.dev_t(Q), 1)).reshape(B, 8, Hq, Dh)
+    Q = inputs.normal(9, "q", (B, Hq, A, Dh), 1.0, dtype)
+    O = inputs.as_oracle(g.attend(0, g.dev_t(Q), 1)).reshape(B, A, Hq, Dh)
     Vf = inputs.as_oracle(V)
     for h in range(Hq):
-        assert np.array_equal(O[0, :, h], np.broadcast_to(Vf[0, h // 2, 0], (8, Dh)))
+        assert np.array_equal(O[0, :, h], np.broadcast_to(Vf[0, h // (Hq // Hkv), 0], (A, Dh)))
     _say("zero queries give the mean of the values")
-    O = inputs.as_oracle(g.attend(0, g.dev_t(torch.zeros_like(Q)), 70)).reshape(B, 8, Hq, Dh)
+    O = inputs.as_oracle(g.attend(0, g.dev_t(torch.zeros_like(Q)), 70)).reshape(B, A, Hq, Dh)
     for h in range(Hq):
-        assert np.max(np.abs(O[0, 0, h] - Vf[0, h // 2].astype(np.float64).mean(0))) < 4e-3
+        assert np.max(np.abs(O[0, 0, h] - Vf[0, h // (Hq // Hkv)].astype(np.float64).mean(0))) < 4e-3
     _say("oracle agreement at kv_len 65 (one key past a 64-row tile) and 70")
     o.write_rows(K, V, 0)
     for S in (65, 70):
@@ -305,11 +306,12 @@ def test_degenerate_attention_cases():
     g.close()
 
 
-def test_split_partials_keep_extreme_value_scales():
+@pytest.mark.parametrize("Hq,A", [(6, 8), (12, 24)])   # one row tile (eight-wave workgroups); three (four-wave ones)
+def test_split_partials_keep_extreme_value_scales(Hq, A):
     """Several key splits with value rows of very large, very small and zero magnitude: the partial
     results exchanged between the splits carry their own scale, so each head keeps its relative
     accuracy."""
-    dtype, B, Hq, Hkv, Dh, S, A = "bf16", 1, 6, 3, 128, 1500, 8
+    dtype, B, Hkv, Dh, S = "bf16", 1, 3, 128, 1500
     _say("split-KV partials with values scaled by 2^100, 2^-100 and 0")
     w = inputs.Workload("t", dtype, B, 256, Hq, Hkv, Dh, 0, A)
     g, o = _pair(dtype, B, 256, Hq, Hkv, Dh, S, max_rows=64)
