@@ -381,7 +381,94 @@ __global__ __launch_bounds__(512) void k_linear_rows(LinArgs p)
     int run_arg = 0x7fffffff;
     int buf = 0;
 
+    // Outputs are collected in LDS and leave as whole row segments (flush): an item gives a row only 16 or
+    // 32 bytes, and written item by item those pieces cost the streaming a tenth of its rate (memory
+    // switching between reading and writing for every piece); a run's segment of a row is one or two
+    // cache lines.  Wave mt stages and flushes its own 16 rows, so no barrier is involved.
+    constexpr int HALF_EL = MODE == FC_LIN_GATE_UP ? 4 : 8;  // output columns of a half item
+    constexpr int STG_ITEMS = 16;                            // items staged between two flushes
+    constexpr int STG_CH = STG_ITEMS * 2 * HALF_EL / 4;      // 8-byte pieces of a staged row (at most 64)
+    __shared__ uint2 stage[MODE == FC_LIN_VOCAB ? 1 : MT * 16][STG_CH + 1];
+    int stage_it0 = it0;  // item in the first staging slot
+    auto flush = [&](int it_end) {  // items stage_it0 .. it_end - 1 are staged
+        const int c0 = max(u0 * HALF_EL, stage_it0 * 2 * HALF_EL), c1 = min(u1 * HALF_EL, it_end * 2 * HALF_EL);
+        const int nch = (c1 - c0) >> 2, ch0 = (c0 - stage_it0 * 2 * HALF_EL) >> 2;
+#pragma unroll 4
+        for (int r = 0; r < 16; ++r) {
+            const int m = 16 * wave + r;
+            if (m < p.M && lane < nch) *(uint2 *)(p.out + (size_t)m * p.N + c0 + 4 * lane) = stage[m][ch0 + lane];
+        }
+    };
+
+    // Sum of the eight partial tiles of item `it` (in red[rb]) and epilogue, by wave mt < MT for tile mt.
+    auto finish_item = [&](int it, int rb) {
+        if (MODE != FC_LIN_VOCAB && it - stage_it0 == STG_ITEMS) {
+            flush(it);
+            stage_it0 = it;
+        }
+        // wave mt sums tile mt: lane (rho, q) = X row 16 mt + rho, item rows 4 q .. 4 q + 3
+        const int mt = wave, m = 16 * mt + rho;
+        float sum[4] = {0.f, 0.f, 0.f, 0.f}, sum2[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int w2 = 0; w2 < 8; ++w2)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                sum[r] += red[rb][w2][mt * 4 + r][lane];
+                if (MODE == FC_LIN_GATE_UP) sum2[r] += red[rb][w2][mt * 4 + r][lane ^ 32];  // up rows: 8 item rows on
+            }
+        if (MODE == FC_LIN_GATE_UP) {
+            const int uu = 2 * it + (q & 1);
+            if (q < 2 && m < p.M && uu >= u0 && uu < u1) {
+                float y[4];
+#pragma unroll
+                for (int r = 0; r < 4; ++r) y[r] = sum[r] / (1.0f + expf(-sum[r])) * sum2[r];
+                uint2 o;
+                o.x = (uint32_t)fc_bf16_bits(y[0]) | ((uint32_t)fc_bf16_bits(y[1]) << 16);
+                o.y = (uint32_t)fc_bf16_bits(y[2]) | ((uint32_t)fc_bf16_bits(y[3]) << 16);
+                stage[m][(it - stage_it0) * 2 + q] = o;
+            }
+        } else if (MODE == FC_LIN_RESIDUAL) {
+            const int uu = 2 * it + (q >> 1);
+            if (m < p.M && uu >= u0 && uu < u1) {
+                const size_t at = (size_t)m * p.N + 16 * it + 4 * q;
+                if (p.res) {
+                    const uint2 rv = *(const uint2 *)(p.res + at);
+                    sum[0] += __uint_as_float(rv.x << 16);
+                    sum[1] += __uint_as_float(rv.x & 0xffff0000u);
+                    sum[2] += __uint_as_float(rv.y << 16);
+                    sum[3] += __uint_as_float(rv.y & 0xffff0000u);
+                }
+                uint2 o;
+                o.x = (uint32_t)fc_bf16_bits(sum[0]) | ((uint32_t)fc_bf16_bits(sum[1]) << 16);
+                o.y = (uint32_t)fc_bf16_bits(sum[2]) | ((uint32_t)fc_bf16_bits(sum[3]) << 16);
+                stage[m][(it - stage_it0) * 4 + q] = o;
+            }
+        } else {
+            // the item's 16 logits of a row: four per lane in ascending order, then the four lanes of the row
+            const int uu = 2 * it + (q >> 1);
+            float mx = -INFINITY, sm = 0.f;
+            int arg = 0x7fffffff;
+            if (uu >= u0 && uu < u1) {
+#pragma unroll
+                for (int r = 0; r < 4; ++r) fc_argmax_merge(mx, arg, sm, sum[r], 16 * it + 4 * q + r, 1.0f);
+            }
+#pragma unroll
+            for (int off = 16; off < 64; off <<= 1) {
+                const float mx2 = __shfl_xor(mx, off, 64), sm2 = __shfl_xor(sm, off, 64);
+                const int arg2 = __shfl_xor(arg, off, 64);
+                fc_argmax_merge(mx, arg, sm, mx2, arg2, sm2);
+            }
+            fc_argmax_merge(run_mx, run_arg, run_sm, mx, arg, sm);
+        }
+    };
+
     for (int it = it0; it < it1; ++it) {
+        // The previous item is finished here, one iteration late: what it loads or stores is then issued
+        // behind the wait for this item's fragments and never part of it.
+        __builtin_amdgcn_s_waitcnt(0 | (7 << 4) | (15 << 8) | (0 << 14));  // vmcnt(0): this item's fragments have landed
+        __builtin_amdgcn_sched_barrier(0);
+        if (it > it0 && wave < MT) finish_item(it - 1, buf ^ 1);
+        __builtin_amdgcn_sched_barrier(0);
         // Fragment s of the next item goes into its register as soon as the multiplies of fragment s are
         // issued.  After the last item every lane re-reads the first 16 bytes of W instead (never used):
         // unconditional loads keep the compiler's wait counts exact.
@@ -405,63 +492,11 @@ __global__ __launch_bounds__(512) void k_linear_rows(LinArgs p)
             }
         __builtin_amdgcn_s_waitcnt(15 | (7 << 4) | (0 << 8) | (3 << 14));  // lgkmcnt(0): the tile is in LDS
         __builtin_amdgcn_s_barrier();
-        if (wave < MT) {
-            // wave mt sums tile mt: lane (rho, q) = X row 16 mt + rho, item rows 4 q .. 4 q + 3
-            const int mt = wave, m = 16 * mt + rho;
-            float sum[4] = {0.f, 0.f, 0.f, 0.f}, sum2[4] = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-            for (int w2 = 0; w2 < 8; ++w2)
-#pragma unroll
-                for (int r = 0; r < 4; ++r) {
-                    sum[r] += red[buf][w2][mt * 4 + r][lane];
-                    if (MODE == FC_LIN_GATE_UP) sum2[r] += red[buf][w2][mt * 4 + r][lane ^ 32];  // up rows: 8 item rows on
-                }
-            if (MODE == FC_LIN_GATE_UP) {
-                const int uu = 2 * it + (q & 1);
-                if (q < 2 && m < p.M && uu >= u0 && uu < u1) {
-                    float y[4];
-#pragma unroll
-                    for (int r = 0; r < 4; ++r) y[r] = sum[r] / (1.0f + expf(-sum[r])) * sum2[r];
-                    uint2 o;
-                    o.x = (uint32_t)fc_bf16_bits(y[0]) | ((uint32_t)fc_bf16_bits(y[1]) << 16);
-                    o.y = (uint32_t)fc_bf16_bits(y[2]) | ((uint32_t)fc_bf16_bits(y[3]) << 16);
-                    *(uint2 *)(p.out + (size_t)m * p.N + 8 * it + 4 * q) = o;
-                }
-            } else if (MODE == FC_LIN_RESIDUAL) {
-                const int uu = 2 * it + (q >> 1);
-                if (m < p.M && uu >= u0 && uu < u1) {
-                    const size_t at = (size_t)m * p.N + 16 * it + 4 * q;
-                    if (p.res) {
-                        const uint2 rv = *(const uint2 *)(p.res + at);
-                        sum[0] += __uint_as_float(rv.x << 16);
-                        sum[1] += __uint_as_float(rv.x & 0xffff0000u);
-                        sum[2] += __uint_as_float(rv.y << 16);
-                        sum[3] += __uint_as_float(rv.y & 0xffff0000u);
-                    }
-                    uint2 o;
-                    o.x = (uint32_t)fc_bf16_bits(sum[0]) | ((uint32_t)fc_bf16_bits(sum[1]) << 16);
-                    o.y = (uint32_t)fc_bf16_bits(sum[2]) | ((uint32_t)fc_bf16_bits(sum[3]) << 16);
-                    *(uint2 *)(p.out + at) = o;
-                }
-            } else {
-                // the item's 16 logits of a row: four per lane in ascending order, then the four lanes of the row
-                const int uu = 2 * it + (q >> 1);
-                float mx = -INFINITY, sm = 0.f;
-                int arg = 0x7fffffff;
-                if (uu >= u0 && uu < u1) {
-#pragma unroll
-                    for (int r = 0; r < 4; ++r) fc_argmax_merge(mx, arg, sm, sum[r], 16 * it + 4 * q + r, 1.0f);
-                }
-#pragma unroll
-                for (int off = 16; off < 64; off <<= 1) {
-                    const float mx2 = __shfl_xor(mx, off, 64), sm2 = __shfl_xor(sm, off, 64);
-                    const int arg2 = __shfl_xor(arg, off, 64);
-                    fc_argmax_merge(mx, arg, sm, mx2, arg2, sm2);
-                }
-                fc_argmax_merge(run_mx, run_arg, run_sm, mx, arg, sm);
-            }
-        }
         buf ^= 1;
+    }
+    if (wave < MT) {
+        finish_item(it1 - 1, buf ^ 1);
+        if (MODE != FC_LIN_VOCAB) flush(it1);
     }
     if (MODE == FC_LIN_VOCAB && wave < MT && q == 0 && 16 * wave + rho < p.M) {
         const size_t at = (size_t)wg * p.M + 16 * wave + rho;
