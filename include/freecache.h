@@ -15,8 +15,11 @@
  *  - Element type of all tensors is fc_config.dtype (float or bfloat16, the latter as raw 16-bit
  *    words), except pos (int32) and the workspace (opaque bytes).
  *  - Compute entry points only enqueue work on `stream` (a hipStream_t passed as void*; NULL is the
- *    default stream).  They never synchronise and never allocate.  Two calls on one stream execute
- *    in order; the attention of a step relies on this to see the step's fresh K/V rows.
+ *    default stream).  They never synchronise, never allocate and clear no memory with a memset
+ *    node, so a caller may record them into a HIP graph on a capturing stream and replay it; what
+ *    a replay reads (x, pos, the cache, tokens) is read anew, the scalar arguments (win_start, A,
+ *    kv_len) are fixed at capture.  Two calls on one stream execute in order; the attention of a
+ *    step relies on this to see the step's fresh K/V rows.
  *  - All argument checks happen on the host before any HIP call.  On failure a nonzero fc_status is
  *    returned, nothing has been enqueued, and fc_last_error() describes the problem.  No entry
  *    point aborts or throws across the ABI.
