@@ -224,8 +224,7 @@ fc_status fc_cache_alloc(const fc_config *cfg, void *k_storage, void *v_storage,
     c->scratch = nullptr;
     {
         void *s = nullptr;
-        hipError_t e = hipMalloc(&s, FC_SCRATCH_BYTES);
-        if (e == hipSuccess) e = hipMemset(s, 0, FC_SCRATCH_COUNTER_BYTES);
+        const hipError_t e = hipMalloc(&s, FC_SCRATCH_BYTES);
         if (e == hipSuccess) {
             c->scratch = s;
         } else {

@@ -17,14 +17,12 @@ struct fc_cache {
     void *v;             // device
     bool owned;
     double inv_freq[64]; // rotary frequencies rope_base^(-2i/Dh), i < Dh/2, computed once on the host
-    // Device scratch owned by the handle (nullptr when no GPU was present at creation): arrival
-    // counters, zero between calls, followed by space for cross-workgroup partial sums.
+    // Device scratch owned by the handle (nullptr when no GPU was present at creation): space for the
+    // partial sums that the short-window projection hands from its first kernel to its second.
     void *scratch;
 };
 
-#define FC_SCRATCH_COUNTER_BYTES (64u * 1024u)
-#define FC_SCRATCH_PARTIAL_BYTES (32u * 1024u * 1024u)
-#define FC_SCRATCH_BYTES (FC_SCRATCH_COUNTER_BYTES + FC_SCRATCH_PARTIAL_BYTES)
+#define FC_SCRATCH_BYTES (32u * 1024u * 1024u)
 
 // Geometry handed to kernels by value.
 struct FcGeom {

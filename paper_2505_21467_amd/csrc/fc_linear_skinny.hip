@@ -544,6 +544,11 @@ FcSkinnyPlan fc_plan_skinny(int dtype, int mode, int M, int K, int N)
 {
     FcSkinnyPlan p;
     memset(&p, 0, sizeof p);
+    int target = 256;  // one workgroup per compute unit
+    if (const char *e = getenv("FC_LIN_WGS")) {  // tuning and test knob: runs of any length
+        const int v = atoi(e);
+        if (v > 0) target = v;
+    }
     {
         // whole-row kernel: at most 32 rows, a hidden size it is built for, whole half items
         static const bool off = getenv("FC_LIN_NO_ROWS") != nullptr;  // tuning knob
@@ -558,7 +563,7 @@ FcSkinnyPlan fc_plan_skinny(int dtype, int mode, int M, int K, int N)
             p.mt = M <= 16 ? 1 : 2;
             p.chunks = 1;
             p.T = N / per_half;               // half items
-            p.G = items < 256 ? items : 256;  // one workgroup per compute unit, at least one item each
+            p.G = items < target ? items : target;  // at least one item each
             return p;
         }
     }
@@ -576,11 +581,6 @@ FcSkinnyPlan fc_plan_skinny(int dtype, int mode, int M, int K, int N)
         return p;
     }
     p.T = (int)T;
-    int target = 256;  // one workgroup per compute unit
-    if (const char *e = getenv("FC_LIN_WGS")) {
-        const int v = atoi(e);
-        if (v > 0) target = v;
-    }
     p.G = p.T < target ? p.T : target;
     // runs are measured in k-steps of 32 hidden elements, so every workgroup streams the same
     // amount to within one k-step; a slab of S * KS k-steps meets at most this many runs

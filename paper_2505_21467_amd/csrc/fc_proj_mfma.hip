@@ -34,7 +34,6 @@ struct ProjArgs {
     FcGeom G;
     int M, A, K, win_start, n_tiles;
     double log2_base_64;   // log2(rope_base) / 64
-    unsigned *counters;    // cache scratch: one arrival counter per head slot, zero between launches
     float *partials;       // cache scratch: partial tiles of the hidden-dimension slices
 #ifdef FC_ATTN_TIMING
     unsigned long long *dbg;  // tuning builds only
@@ -448,12 +447,11 @@ hipError_t fc_launch_project_mfma(const FcGeom &G, const double *inv_freq, const
         a.dbg = env ? (unsigned long long *)strtoull(env, nullptr, 0) : nullptr;
     }
 #endif
-    a.counters = (unsigned *)scratch;
-    a.partials = scratch ? (float *)((char *)scratch + FC_SCRATCH_COUNTER_BYTES) : nullptr;
+    a.partials = (float *)scratch;
     const int slots = G.Hq + 2 * G.Hkv;
     static const bool no_headsplit = getenv("FC_PROJ_NO_HEADSPLIT") != nullptr;  // tuning knob
-    if (!no_headsplit && scratch && a.M <= 32 && a.K % HS_K == 0 && (size_t)slots * sizeof(unsigned) <= FC_SCRATCH_COUNTER_BYTES / 2 &&
-        (size_t)slots * (a.K / HS_K) * 8 * 2 * 256 * sizeof(float) <= FC_SCRATCH_PARTIAL_BYTES) {
+    if (!no_headsplit && scratch && a.M <= 32 && a.K % HS_K == 0 &&
+        (size_t)slots * (a.K / HS_K) * 8 * 2 * 256 * sizeof(float) <= FC_SCRATCH_BYTES) {
         const unsigned grid = (unsigned)(slots * (a.K / HS_K));
         if (a.M <= 16) {
             k_proj_headsplit<1><<<dim3(grid), dim3(512), 0, s>>>(a);

@@ -136,6 +136,27 @@ def test_whole_row_kernel_seeded_shape_sweep():
         assert_close(inputs.as_oracle(out), ref, "bf16", "whole-row sweep case %d (M %d, N %d, gated %s)" % (case, M, N, gated))
 
 
+@pytest.mark.parametrize("wgs", ["2", "7", "300"])
+def test_whole_row_kernel_any_number_of_workgroups(wgs, monkeypatch):
+    # runs of 1, 38 and 131 items: the staged outputs of a run are flushed every 16 items and at its end
+    monkeypatch.setenv("FC_LIN_WGS", wgs)
+    M, K = 27, 512
+    x = inputs.normal(5, "x", (M, K), 1.0, "bf16")
+    for gated, N in ((True, 4 * 523), (False, 8 * 523)):
+        w = inputs.normal(5, "w", (N, K), 0.05, "bf16")
+        out = torch.full((M, N), float("nan"), dtype=torch.bfloat16, device=DEV)
+        if gated:
+            wu = inputs.normal(5, "wu", (N, K), 0.05, "bf16")
+            ref = orc.ffn_gate_up(inputs.as_oracle(x), inputs.as_oracle(w), inputs.as_oracle(wu), "bf16")
+            fc.fc_ffn_gate_up("bf16", _dev(x), _dev(w), _dev(wu), M, K, N, out, None, 0)
+        else:
+            r = inputs.normal(5, "r", (M, N), 1.0, "bf16")
+            ref = orc.linear_residual(inputs.as_oracle(x), inputs.as_oracle(w), inputs.as_oracle(r), "bf16")
+            fc.fc_linear_residual("bf16", _dev(x), _dev(w), _dev(r), M, K, N, out, None, 0)
+        torch.cuda.synchronize()
+        assert_close(inputs.as_oracle(out), ref, "bf16", "whole-row kernel, %s workgroups, gated %s" % (wgs, gated))
+
+
 @pytest.mark.parametrize("shape", ["0", "1", "2"])
 @pytest.mark.parametrize("ksplit", ["1", "3"])
 def test_linear_residual_wide_window_tile_shapes(shape, ksplit, monkeypatch):
