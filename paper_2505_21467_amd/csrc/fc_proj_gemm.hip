@@ -548,6 +548,10 @@ hipError_t launch_wide_shape(int shape, const GemmArgs &a, hipStream_t s)
 // 0: 256 rows x slab, 1: 128 rows x slab, 2: 128 rows x half slab.
 int pick_shape(int64_t slots, int64_t rows, bool allow_half)
 {
+    // Up to 128 rows the 256-row tile is mostly padding; with that many slabs the half slab is the
+    // fastest (gated W_1 of the 7B widths, 296 slabs, 48 / 64 / 128 rows: 67.6 / 71.7 / 83.8 us against
+    // 72.9 / 74.4 / 85.1 with whole slabs and 81.8 / 80.7 / 88.7 with the 256-row tile).
+    if (rows <= 128 && slots >= 192) return allow_half ? 2 : 1;
     if (slots * ((rows + 255) / 256) >= 192) return 0;
     if (slots * ((rows + 127) / 128) >= 144 || !allow_half) return 1;
     return 2;
@@ -612,8 +616,11 @@ FcWidePlan fc_plan_wide(int dtype, int mode, int M, int K, int N)
     if ((int64_t)N * K * 2 >= ((int64_t)1 << 32) || (int64_t)M * K * 2 >= ((int64_t)1 << 32)) return p;
     p.kind = 1;
     const int64_t units = N / per_slab, t256 = (M + 255) / 256, t128 = (M + 127) / 128;
-    // the largest tile that still gives the chip about one workgroup per compute unit
-    if (units * t256 >= 192) p.shape = 0;
+    // the largest tile that still gives the chip about one workgroup per compute unit; up to 128 rows
+    // the 256-row tile is mostly padding (vocabulary projection of the 7B widths at 48 / 64 / 128 rows:
+    // 263 / 253 / 271 us with the 128-row tile against 345 / 329 / 323)
+    if (M <= 128 && units >= 192) p.shape = mode == FC_LIN_VOCAB ? 1 : 2;
+    else if (units * t256 >= 192) p.shape = 0;
     else if (units * t128 >= 144 || mode == FC_LIN_VOCAB) p.shape = 1;
     else p.shape = 2;
     // Too few slabs even for the smallest tile: also cut the hidden dimension (partial sums in fp32).

@@ -96,6 +96,7 @@ def test_linear_residual_any_number_of_workgroups(wgs, monkeypatch):
     ("bf16", 32, 3584, 2368), ("bf16", 50, 1024, 192),
     ("bf16", 9, 512, 100),        # whole-row kernel: 25 half items of 4 features
     ("bf16", 32, 4096, 2052),     # whole-row kernel at hidden 4096, 513 half items over 256 workgroups
+    ("bf16", 64, 1024, 12800),    # tiled GEMM, 200 slabs and at most 128 rows: 128-row tiles of half slabs
 ])
 def test_ffn_gate_up_matches_oracle(dtype, M, K, F):
     x = inputs.normal(4, "x", (M, K), 1.0, dtype)
