@@ -134,6 +134,40 @@ def test_cached_step_matches_oracle(dtype, B, d, Hq, Hkv, Dh, L, A):
     g.close()
 
 
+def test_cached_step_seeded_shape_sweep():
+    """20 seeded shapes of the bf16 / head_dim 128 path: 1..3 sequences, 1..4 KV heads, 1..7 query heads
+    per KV head, windows of 1..80 rows, 1..2500 cached rows, hidden 128..512.  Between them they take
+    every branch of the attention planner (eight- and four-wave workgroups, one or several row groups,
+    one or many key splits, ragged last stage) and both projection paths (up to 32 rows, more)."""
+    rng = np.random.default_rng(20250529)
+    for case in range(20):
+        B = int(rng.integers(1, 4))
+        Hkv = int(rng.choice([1, 2, 4]))
+        Hq = Hkv * int(rng.choice([1, 2, 4, 7]))
+        A = int(rng.integers(1, 81))
+        L = int(rng.integers(1, 2501))
+        d = int(rng.choice([128, 256, 512]))
+        dtype, Dh = "bf16", 128
+        _say("sweep case %d: B%d d%d Hq%d Hkv%d L%d A%d" % (case, B, d, Hq, Hkv, L, A))
+        w = inputs.Workload("sweep", dtype, B, d, Hq, Hkv, Dh, L, A)
+        S = L + A
+        g, o = _pair(dtype, B, d, Hq, Hkv, Dh, S + 5, max_rows=max(A, 64), fill=1.5)
+        K, V = inputs.kv_fill(w, 100 + case, L)
+        g.write_rows(0, K, V, 0)
+        o.write_rows(K, V, 0)
+        W, b = inputs.weights(w, 100 + case), (inputs.bias(w, 100 + case) if case % 2 else None)
+        X = inputs.hidden_states(w, 100 + case, A)
+        Qg, Og = g.step(0, X, W, b, L, S)
+        Qo, Oo = o.step(X, W, b, L, S)
+        what = "sweep case %d (B%d d%d Hq%d Hkv%d L%d A%d)" % (case, B, d, Hq, Hkv, L, A)
+        assert_close(Qg, Qo, dtype, what + " Q")
+        assert_close(Og, Oo, dtype, what + " O")
+        written = np.zeros((B, S + 5), bool)
+        written[:, L:S] = True
+        _compare_cache(g, o, dtype, written=written, what=what)
+        g.close()
+
+
 @pytest.mark.parametrize("B,d,Hq,Hkv,L,A", [
     (1, 1024, 4, 1, 50, 33),    # 33 window rows: one ragged row tile
     (3, 768, 6, 3, 90, 37),     # 111 rows
