@@ -168,6 +168,39 @@ def test_cached_step_seeded_shape_sweep():
         g.close()
 
 
+def test_refresh_seeded_shape_sweep():
+    """10 seeded refreshes of a region in the middle of a filled cache (section 3.2.1: re-projection of a
+    region): 33..500 rows from a random start, keys before and behind the region, one call."""
+    rng = np.random.default_rng(20250530)
+    for case in range(10):
+        B = int(rng.integers(1, 3))
+        Hkv = int(rng.choice([1, 2, 4]))
+        Hq = Hkv * int(rng.choice([1, 2, 7]))
+        R = int(rng.integers(33, 501))
+        start = int(rng.integers(0, 300))
+        tail = int(rng.integers(0, 200))
+        d = int(rng.choice([256, 512, 768]))
+        dtype, Dh = "bf16", 128
+        S = start + R + tail
+        _say("refresh sweep case %d: B%d d%d Hq%d Hkv%d start%d R%d kv_len%d" % (case, B, d, Hq, Hkv, start, R, S))
+        w = inputs.Workload("rsweep", dtype, B, d, Hq, Hkv, Dh, S, R)
+        g, o = _pair(dtype, B, d, Hq, Hkv, Dh, S + 3, max_rows=R, fill=0.5)
+        K, V = inputs.kv_fill(w, 200 + case, S)
+        g.write_rows(0, K, V, 0)
+        o.write_rows(K, V, 0)
+        W, b = inputs.weights(w, 200 + case), (inputs.bias(w, 200 + case) if case % 2 else None)
+        X = inputs.hidden_states(w, 200 + case, R)
+        Qg, Og = g.refresh(0, X, W, b, start, S)
+        Qo, Oo = o.step(X, W, b, start, S)
+        what = "refresh sweep case %d (B%d d%d Hq%d Hkv%d start%d R%d kv_len%d)" % (case, B, d, Hq, Hkv, start, R, S)
+        assert_close(Qg, Qo, dtype, what + " Q")
+        assert_close(Og, Oo, dtype, what + " O")
+        written = np.zeros((B, S + 3), bool)
+        written[:, start:start + R] = True
+        _compare_cache(g, o, dtype, written=written, what=what)
+        g.close()
+
+
 @pytest.mark.parametrize("B,d,Hq,Hkv,L,A", [
     (1, 1024, 4, 1, 50, 33),    # 33 window rows: one ragged row tile
     (3, 768, 6, 3, 90, 37),     # 111 rows
