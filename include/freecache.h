@@ -160,6 +160,19 @@ fc_status fc_active_attention(fc_cache *cache, int32_t layer, const void *q, int
                               int32_t kv_len, const int32_t *pos, void *out, void *workspace,
                               size_t workspace_bytes, void *stream);
 
+/* fc_active_attention for callers that cannot allocate or bring a workspace: code recorded under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, result
+ * and errors as fc_active_attention, except that the split-KV partial results go to a static device
+ * array inside the library (16 MiB per GPU, held until the process ends; its address on the current
+ * device is looked up on the first call there, with that device current).  The call allocates
+ * nothing.  A shape whose partial results exceed fc_active_attention_static_max_bytes() (compare
+ * fc_workspace_bytes) is rejected with FC_ERR_WORKSPACE.  All calls on one GPU share the one array:
+ * calls that overlap in time on the same GPU (two streams, two threads) race; calls on one stream
+ * are ordered and safe.  Nothing in the array has to be cleared between calls. */
+size_t fc_active_attention_static_max_bytes(void);
+fc_status fc_active_attention_static(fc_cache *cache, int32_t layer, const void *q, int32_t A,
+                                     int32_t kv_len, const int32_t *pos, void *out, void *stream);
+
 /* Full refresh of rows [start, start+R) (section 3.2.1: the initial pass that fills the cache for
  * prompt + all blocks, and any later re-projection of a region): fc_qkv_project_scatter with
  * pos = start + r followed, if out != NULL, by fc_active_attention over [0, kv_len).

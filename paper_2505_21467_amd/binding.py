@@ -21,6 +21,7 @@ EXPORTS = (
     "fc_last_error", "fc_cache_storage_bytes", "fc_cache_alloc", "fc_cache_free", "fc_cache_ptrs",
     "fc_cache_write_rows", "fc_cache_read_rows", "fc_window", "fc_qkv_project_scatter",
     "fc_workspace_bytes", "fc_active_attention", "fc_refresh",
+    "fc_active_attention_static_max_bytes", "fc_active_attention_static",
     "fc_rmsnorm", "fc_linear_workspace_bytes", "fc_linear_residual", "fc_ffn_gate_up",
     "fc_full_layer_workspace_bytes", "fc_full_layer_step",
     "fc_lm_head_workspace_bytes", "fc_lm_head_argmax", "fc_unmask_select", "fc_gather_rows",
@@ -83,6 +84,10 @@ def lib():
         L.fc_workspace_bytes.argtypes = [cfgp, i32]
         L.fc_active_attention.restype = ctypes.c_int
         L.fc_active_attention.argtypes = [vp, i32, vp, i32, i32, vp, vp, vp, sz, vp]
+        L.fc_active_attention_static_max_bytes.restype = sz
+        L.fc_active_attention_static_max_bytes.argtypes = []
+        L.fc_active_attention_static.restype = ctypes.c_int
+        L.fc_active_attention_static.argtypes = [vp, i32, vp, i32, i32, vp, vp, vp]
         L.fc_refresh.restype = ctypes.c_int
         L.fc_refresh.argtypes = [vp, i32, vp, vp, vp, i32, i32, i32, vp, vp, vp, sz, vp]
         L.fc_rmsnorm.restype = ctypes.c_int
@@ -200,6 +205,15 @@ def fc_active_attention(cache, layer, q, A, kv_len, pos, out, workspace, workspa
         workspace_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
     _check(lib().fc_active_attention(cache, layer, _ptr(q), A, kv_len, _ptr(pos), _ptr(out),
                                      _ptr(workspace), workspace_bytes, _stream(stream)))
+
+
+def fc_active_attention_static_max_bytes() -> int:
+    return int(lib().fc_active_attention_static_max_bytes())
+
+
+def fc_active_attention_static(cache, layer, q, A, kv_len, pos, out, stream=None) -> None:
+    _check(lib().fc_active_attention_static(cache, layer, _ptr(q), A, kv_len, _ptr(pos), _ptr(out),
+                                            _stream(stream)))
 
 
 def fc_refresh(cache, layer, x, w_qkv, b_qkv, start, R, kv_len, q_scratch, out, workspace,

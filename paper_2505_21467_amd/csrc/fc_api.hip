@@ -388,6 +388,72 @@ fc_status fc_active_attention(fc_cache *cache, int32_t layer, const void *q, int
     return e == hipSuccess ? FC_OK : hip_fail(e, "attention launch");
 }
 
+// ---------------------------------------------------------------------------------------------
+// Attention for callers that cannot allocate: the split-KV partial results live in a static device
+// array instead of a caller-provided workspace.  The array's name is only a host-side stand-in for
+// the symbol; its device address is looked up once per device and kept.
+}  // extern "C"
+
+#define FC_STATIC_SCRATCH_BYTES (16u * 1024u * 1024u)
+#define FC_MAX_DEVICES 64
+static __device__ __align__(256) unsigned char fc_static_scratch[FC_STATIC_SCRATCH_BYTES];
+
+namespace {
+
+// Device address of fc_static_scratch on the current device (each GPU holds its own copy of the
+// array at its own address).  On failure *out stays nullptr and the status (error text set) is returned.
+fc_status static_scratch_ptr(void **out)
+{
+    *out = nullptr;
+    static void *ptrs[FC_MAX_DEVICES];  // zero-initialised; a slot is written once and then only read
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return hip_fail(e, "hipGetDevice");
+    if (dev < 0 || dev >= FC_MAX_DEVICES)
+        return fail(FC_ERR_UNSUPPORTED, "device ordinal %d outside [0, %d)", dev, FC_MAX_DEVICES);
+    void *p = __atomic_load_n(&ptrs[dev], __ATOMIC_ACQUIRE);
+    if (!p) {
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(fc_static_scratch));
+        if (e != hipSuccess) return hip_fail(e, "hipGetSymbolAddress(fc_static_scratch)");
+        if (!p) return fail(FC_ERR_HIP, "hipGetSymbolAddress(fc_static_scratch) returned a null address");
+        __atomic_store_n(&ptrs[dev], p, __ATOMIC_RELEASE);
+    }
+    *out = p;
+    return FC_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t fc_active_attention_static_max_bytes(void) { return FC_STATIC_SCRATCH_BYTES; }
+
+fc_status fc_active_attention_static(fc_cache *cache, int32_t layer, const void *q, int32_t A, int32_t kv_len,
+                                     const int32_t *pos, void *out, void *stream)
+{
+    fc_status st = check_cache_layer(cache, layer);
+    if (st != FC_OK) return st;
+    if (!q || !out) return fail(FC_ERR_INVALID_ARG, "q or out is NULL");
+    if (A < 1) return fail(FC_ERR_INVALID_ARG, "A %d must be >= 1", A);
+    if ((int64_t)A * cache->cfg.batch > (1 << 24))
+        return fail(FC_ERR_UNSUPPORTED, "batch * A exceeds 2^24 rows");
+    if (kv_len < 1 || kv_len > cache->cfg.max_seq)
+        return fail(FC_ERR_BOUNDS, "kv_len %d outside [1, %d]", kv_len, cache->cfg.max_seq);
+    const FcAttnPlan plan = fc_plan_attention(cache->cfg, A, kv_len);
+    const size_t need = fc_plan_workspace(cache->cfg, plan, A);
+    if (need > FC_STATIC_SCRATCH_BYTES)
+        return fail(FC_ERR_WORKSPACE, "this shape needs %zu bytes of partial results, the static scratch holds %u",
+                    need, FC_STATIC_SCRATCH_BYTES);
+    void *scratch = nullptr;
+    if (need > 0) {
+        st = static_scratch_ptr(&scratch);
+        if (st != FC_OK) return st;
+    }
+    // Nothing in the scratch has to start at zero: every (row tile, split) slot the merge kernel
+    // reads is written by the first kernel of the same call.
+    return fc_active_attention(cache, layer, q, A, kv_len, pos, out, scratch, need, stream);
+}
+
 fc_status fc_refresh(fc_cache *cache, int32_t layer, const void *x, const void *w_qkv, const void *b_qkv,
                      int32_t start, int32_t R, int32_t kv_len, void *q_scratch, void *out,
                      void *workspace, size_t workspace_bytes, void *stream)

@@ -140,6 +140,28 @@ def test_workspace_is_demanded_when_the_plan_splits_keys():
         fc.fc_cache_free(h)
 
 
+def test_static_scratch_attention_validates_on_the_host():
+    """The entry point that allocates nothing checks its arguments like fc_active_attention and
+    refuses, before any HIP call, a shape whose partial results exceed its static array."""
+    St = fc.fc_active_attention_static
+    cap = fc.fc_active_attention_static_max_bytes()
+    assert cap == 16 * 1024 * 1024
+    c = fc.make_config(1, 1, 256, 32, 4, 128, 8192, "bf16")
+    assert fc.fc_workspace_bytes(c, 64) > cap
+    assert fc.fc_workspace_bytes(fc.make_config(1, 1, 3584, 28, 4, 128, 16800, "bf16"), 32) <= cap
+    h = fc.fc_cache_alloc(c, FAKE, FAKE)
+    try:
+        _raises(fc.FC_ERR_WORKSPACE, St, h, 0, FAKE, 64, 8192, None, FAKE, 0)
+        _raises(fc.FC_ERR_INVALID_ARG, St, None, 0, FAKE, 64, 8192, None, FAKE, 0)
+        _raises(fc.FC_ERR_INVALID_ARG, St, h, 0, None, 64, 8192, None, FAKE, 0)
+        _raises(fc.FC_ERR_INVALID_ARG, St, h, 0, FAKE, 64, 8192, None, None, 0)
+        _raises(fc.FC_ERR_INVALID_ARG, St, h, 0, FAKE, 0, 8192, None, FAKE, 0)
+        _raises(fc.FC_ERR_BOUNDS, St, h, 1, FAKE, 64, 8192, None, FAKE, 0)
+        _raises(fc.FC_ERR_BOUNDS, St, h, 0, FAKE, 64, 8193, None, FAKE, 0)
+    finally:
+        fc.fc_cache_free(h)
+
+
 @pytest.mark.parametrize("mode", [0, 1])
 def test_window_schedule_equals_oracle(mode):
     cases = [(16384, 416, 32, 8, 0), (2048, 256, 32, 8, 8), (0, 70, 32, 1, 3), (5, 64, 64, 4, 2), (9, 1, 1, 1, 1)]
