@@ -9,6 +9,12 @@ active window, then attention of the window's queries over the cache.  The defau
 long-context Dream-7B-shaped configuration (prompt 16384, window of 32 rows sliding by 32 every 8
 steps, 28/4 GQA heads, head_dim 128, bf16), on which the metric's bandwidth target is quoted.
 
+`value` is the time of exactly `--steps` steps recorded once into a HIP graph and replayed (the library's
+calls allocate nothing, issue no memset node and never synchronise, so they are captured as they
+are); the same steps launched one by one from the host are reported beside it (`eager_us_per_step`).
+The default run also carries the other configurations in compact form (`others`: C2, C3, the cached
+step and the refresh of C5, and the 28-layer block schedule of C5 in decoded tokens/s).
+
 So that the key/value stream really comes from HBM and not from the 256 MB memory-side cache, the
 timed loop rotates over `--layers` distinct layer caches and weight matrices (default: enough for
 more than 1.5 GB of working set), as a 28-layer model does between two visits of one layer.  The
@@ -63,9 +69,22 @@ MEASURED_GATE_UP_TRAFFIC_BYTES = {(32, 3584, 18944): 274_990_000}
 # The vocabulary projection of 32 rows (k_linear_rows, profiles/unmask_step.md): 1091.94 MB fetched, 0.1 MB written.
 MEASURED_LM_HEAD_TRAFFIC_BYTES = {(32, 3584, 152064): 1_092_040_000}
 
-MEASURED_ATTENTION_TRAFFIC_BYTES = {
-    "c4_dream7b_long_L16384_A32": 54_380_000,   # 36.45 + 7.31 MB (main kernel), 10.39 + 0.23 MB (merge)
-    "c3_llada8b_B4_L4096_A64": 289_900_000,     # 277.0 + 4.46 MB, 6.35 + 2.10 MB
+# HBM bytes per launch of the attention call (main kernel + merge kernel), from `rocprofv3 --pmc
+# FETCH_SIZE` / `--pmc WRITE_SIZE` runs of this command, scaled by what the same counters read for the
+# plain 256 MiB copy at the end of the run.  Each figure is tied to the launch plan it was measured
+# with (fc_attention_plan) and to the summary under profiles/ that holds the counter values; a run
+# whose planner picks another plan reports null instead.
+MEASURED_ATTENTION_TRAFFIC = {
+    "c4_dream7b_long_L16384_A32": {
+        "bytes": 54_380_000,   # 36.45 MB read + 7.31 MB written (main kernel), 10.39 + 0.23 MB (merge)
+        "plan": {"kind": 1, "splits": 30, "keys_per_split": 576, "tiles_per_wg": 4, "waves": 8},
+        "kernels": "k_attn_mfma<1,8,2> + k_attn_combine<8,4>",
+        "profile": "profiles/c4_long_context_layer_step.md"},
+    "c3_llada8b_B4_L4096_A64": {
+        "bytes": 289_900_000,  # 277.0 + 4.46 MB, 6.35 + 2.10 MB
+        "plan": {"kind": 1, "splits": 2, "keys_per_split": 2112, "tiles_per_wg": 2, "waves": 8},
+        "kernels": "k_attn_mfma<1,8,4> + k_attn_combine<2,1>",
+        "profile": "profiles/other_workloads_layer_step.md"},
 }
 
 
@@ -82,45 +101,58 @@ def _parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-single", action="store_true",
                     help="skip the single-cache loops (for counter runs: every dispatch then streams from HBM)")
+    ap.add_argument("--no-others", action="store_true",
+                    help="default workload only: skip the compact figures of the other configurations")
     ap.add_argument("--repeats", type=int, default=5, help="timed repetitions; the median is reported")
     return ap.parse_args()
 
 
-def main():
-    args = _parse()
-    if args.gpus != 1:
-        print("bench.py: this build runs on one GPU only (no sharding, no collectives); "
-              "--gpus %d is not supported" % args.gpus, file=sys.stderr)
-        sys.exit(2)
+def _graph_of(torch, n, fn):
+    """Record n calls of fn(s) into one HIP graph (the library issues no memset node and never
+    synchronises, so its calls can be captured as they are).  Returns the graph."""
+    g = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        for s in range(min(n, 3)):
+            fn(s)
+        torch.cuda.synchronize()
+        with torch.cuda.graph(g, stream=side):
+            for s in range(n):
+                fn(s)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    return g
 
-    import torch
-    from paper_2505_21467_amd import binding as fc
-    from paper_2505_21467_amd import inputs
 
-    assert torch.cuda.is_available(), "bench.py needs a GPU"
-    fc.lib()
-    dev = torch.device("cuda:0")
-    if args.workload.startswith("c5_decode"):
-        args.steps = 64 if args.steps is None else args.steps
-        return main_decode(args, torch, fc, inputs, dev)
-    args.steps = 100 if args.steps is None else args.steps
-    if args.workload.endswith("_layer"):
-        return main_layer(args, torch, fc, inputs, dev)
-    if args.workload.endswith("_unmask"):
-        return main_unmask(args, torch, fc, inputs, dev)
-    if args.workload.endswith("_accept"):
-        return main_accept(args, torch, fc, inputs, dev)
-    if args.workload.endswith("_drift"):
-        return main_drift(args, torch, fc, inputs, dev)
-    refresh = args.workload == "c5_refresh"
-    w = {"c2": inputs.C2, "c3": inputs.C3, "c4": inputs.C4, "c5": inputs.C5, "c5_refresh": inputs.C5}[args.workload]
+def _time_replays(torch, g, n, repeats):
+    """Median over repeats of the per-step time (us) of one replay of a graph of n steps, between two
+    events on the stream the graph is launched on."""
+    res = []
+    for _ in range(repeats):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        e0.record()
+        g.replay()
+        e1.record()
+        torch.cuda.synchronize()
+        res.append(e0.elapsed_time(e1) * 1000.0 / n)
+    res.sort()
+    return res[len(res) // 2]
+
+
+def hot_path(torch, fc, inputs, dev, wname, steps, warmup, repeats, layers=0, no_single=False):
+    """The hot path (projection + RoPE + scatter, then attention) of one configuration, rotating over
+    distinct layers.  Returns the measured figures as a dict."""
+    refresh = wname == "c5_refresh"
+    w = {"c2": inputs.C2, "c3": inputs.C3, "c4": inputs.C4, "c5": inputs.C5, "c5_refresh": inputs.C5}[wname]
     B, Dh, Hq, Hkv = w.batch, w.head_dim, w.n_q_heads, w.n_kv_heads
     A = w.gen_len if refresh else w.active  # a refresh re-projects the whole generation region
     S = w.kv_len
     esz = 2
     kv_bytes_layer = 2 * B * S * Hkv * Dh * esz
     w_bytes_layer = w.qkv_width * w.hidden * esz
-    n_layers = args.layers or max(4, math.ceil(1.6e9 / (kv_bytes_layer + w_bytes_layer)))
+    n_layers = layers or max(4, math.ceil(1.6e9 / (kv_bytes_layer + w_bytes_layer)))
     tdt = inputs.TORCH_DTYPE[w.dtype]
 
     cfg = fc.make_config(n_layers, B, w.hidden, Hq, Hkv, Dh, S, w.dtype, w.rope_base)
@@ -160,10 +192,9 @@ def main():
         if do_attn:
             fc.fc_active_attention(cache, layer, Q, A, S, None, O, ws, ws_bytes)
 
-    def timed(n, **kw):
-        """Median over repeats of the per-step time (us) of n back-to-back steps on the current stream."""
+    def timed_eager(n, **kw):
         res = []
-        for _ in range(args.repeats):
+        for _ in range(repeats):
             e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
             torch.cuda.synchronize()
             e0.record()
@@ -175,44 +206,87 @@ def main():
         res.sort()
         return res[len(res) // 2]
 
-    for s in range(args.warmup):
+    for s in range(warmup):
         step(s)
     torch.cuda.synchronize()
 
-    # the headline: exactly --steps steps between two events, barrier (sync) on both sides
+    # Eager: exactly `steps` steps launched one by one from the host (four kernels per step).
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     torch.cuda.synchronize()
     t_host0 = time.perf_counter()
     e0.record()
-    for s in range(args.steps):
+    for s in range(steps):
         step(s)
     e1.record()
     torch.cuda.synchronize()
     t_host = time.perf_counter() - t_host0
-    us_step = e0.elapsed_time(e1) * 1000.0 / args.steps
+    us_step_eager = e0.elapsed_time(e1) * 1000.0 / steps
 
-    # per-kernel figures, same launch configuration, each its own back-to-back loop
-    us_attn = timed(args.steps, do_proj=False)
-    us_proj = timed(args.steps, do_attn=False)
+    # The headline: the same `steps` steps (rotating layers, the window moving as scheduled) recorded
+    # once into a HIP graph and replayed, so the host's launch rate is out of the figure; one replay =
+    # exactly `steps` steps between two events, synchronised on both sides.
+    g_all = _graph_of(torch, steps, step)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    e0.record()
+    g_all.replay()
+    e1.record()
+    torch.cuda.synchronize()
+    us_step = e0.elapsed_time(e1) * 1000.0 / steps
+    us_step_med = _time_replays(torch, g_all, steps, repeats)
+
+    # per-call figures, same launch configuration, each its own replayed loop
+    g_attn = _graph_of(torch, steps, lambda s: step(s, do_proj=False))
+    us_attn = _time_replays(torch, g_attn, steps, repeats)
+    g_proj = _graph_of(torch, steps, lambda s: step(s, do_attn=False))
+    us_proj = _time_replays(torch, g_proj, steps, repeats)
+    us_attn_eager = timed_eager(steps, do_proj=False)
     us_single = us_attn_single = float("nan")
-    if not args.no_single:
-        us_single = timed(args.steps, rotate=False)
-        us_attn_single = timed(args.steps, rotate=False, do_proj=False)
+    if not no_single:
+        us_single = timed_eager(steps, rotate=False)
+        us_attn_single = timed_eager(steps, rotate=False, do_proj=False)
+    del g_all, g_attn, g_proj
 
-    attn_bytes = kv_bytes_layer + 2 * B * A * Hq * Dh * esz
-    proj_bytes = w_bytes_layer + B * A * (w.hidden + w.qkv_width) * esz
-    attn_gbs = attn_bytes / us_attn * 1e-3
-    proj_flops = 2.0 * B * A * w.hidden * w.qkv_width
-    attn_flops = 4.0 * B * A * Hq * S * Dh
-    flops = proj_flops + attn_flops
+    plan = fc.fc_attention_plan(cfg, A, S)
+    res = dict(w=w, refresh=refresh, B=B, A=A, S=S, Hq=Hq, Hkv=Hkv, Dh=Dh, n_layers=n_layers, steps=steps, warmup=warmup,
+               us_step=us_step, us_step_med=us_step_med, us_step_eager=us_step_eager, us_attn=us_attn, us_proj=us_proj,
+               us_attn_eager=us_attn_eager, us_single=us_single, us_attn_single=us_attn_single,
+               host_us=t_host * 1e6 / steps, plan=plan,
+               attn_bytes=kv_bytes_layer + 2 * B * A * Hq * Dh * esz,
+               proj_bytes=w_bytes_layer + B * A * (w.hidden + w.qkv_width) * esz,
+               proj_flops=2.0 * B * A * w.hidden * w.qkv_width, attn_flops=4.0 * B * A * Hq * S * Dh)
+    torch.cuda.synchronize()
+    fc.fc_cache_free(cache)
+    del k_store, v_store, Ws, W0, K0d, V0d, Xs, Q, O, ws
+    torch.cuda.empty_cache()
+    return res
 
+
+def _traffic(r):
+    """HBM bytes of the attention call, if a counter run of this workload with this launch plan is on
+    file (profiles/): otherwise null rather than a figure of another kernel or plan."""
+    rec = MEASURED_ATTENTION_TRAFFIC.get(r["w"].name)
+    if rec is None or r["refresh"]:
+        return None, None
+    same = all(r["plan"][k] == v for k, v in rec["plan"].items())
+    if not same:
+        return None, "no counter run on file for plan %s" % r["plan"]
+    return rec["bytes"], {"profile": rec["profile"], "plan": rec["plan"], "kernels": rec["kernels"]}
+
+
+def hot_path_json(r, args_layers_note=""):
+    w, refresh = r["w"], r["refresh"]
+    us_step, us_attn, us_proj = r["us_step"], r["us_attn"], r["us_proj"]
+    attn_gbs = r["attn_bytes"] / us_attn * 1e-3
+    traffic, traffic_src = _traffic(r)
+    nan_none = lambda v, nd=3: None if v != v else round(v, nd)
     out = {
         "metric": "us per cached denoising layer-step + achieved KV-read HBM GB/s (fraction of peak)",
         "value": round(us_step, 3),
         "unit": "us",
         "n_gpus": 1,
-        "steps": args.steps,
-        "warmup": args.warmup,
+        "steps": r["steps"],
+        "warmup": r["warmup"],
         "ms_per_step": round(us_step / 1000.0, 6),
         "higher_is_better": False,
         "scaling": "weak",
@@ -220,10 +294,12 @@ def main():
         "dtype": w.dtype,
         "data": "synthetic",
         "config": {
-            "workload": w.name + ("/refresh" if refresh else ""), "batch": B, "hidden": w.hidden, "n_q_heads": Hq, "n_kv_heads": Hkv,
-            "head_dim": Dh, "kv_len": S, "active_rows": A, "layers_rotated": n_layers,
+            "workload": w.name + ("/refresh" if refresh else ""), "batch": r["B"], "hidden": w.hidden,
+            "n_q_heads": r["Hq"], "n_kv_heads": r["Hkv"], "head_dim": r["Dh"], "kv_len": r["S"], "active_rows": r["A"],
+            "layers_rotated": r["n_layers"],
             "window_schedule": "start %d, +%d every %d steps" % (w.cached_len, w.block, w.steps_per_block)
             if w.gen_len else "fixed at %d" % w.cached_len,
+            "launch": "the timed steps are recorded into one HIP graph and replayed once",
         },
         "roofline": {
             "kernel": "fc_active_attention (k_attn_mfma + k_attn_combine)",
@@ -232,25 +308,104 @@ def main():
             "peak": HBM_PEAK_GBS,
             "unit": "GB/s",
             "frac": round(attn_gbs / HBM_PEAK_GBS, 4),
-            "traffic": MEASURED_ATTENTION_TRAFFIC_BYTES.get(w.name) if not refresh else None,
-            "algorithmic_bytes_per_launch": attn_bytes,
+            "traffic": traffic,
+            "traffic_source": traffic_src,
+            "algorithmic_bytes_per_launch": r["attn_bytes"],
             "us_per_launch": round(us_attn, 3),
+            "us_per_launch_eager": round(r["us_attn_eager"], 3),
+            "launch_plan": r["plan"],
         },
         "projection": {
             "kernel": "fc_qkv_project_scatter",
             "us_per_launch": round(us_proj, 3),
-            "weight_stream_gbs": round(proj_bytes / us_proj * 1e-3, 1),
-            "frac_of_hbm_peak": round(proj_bytes / us_proj * 1e-3 / HBM_PEAK_GBS, 4),
-            "tflops": round(proj_flops / us_proj * 1e-6, 1),
-            "frac_of_mfma_peak": round(proj_flops / us_proj * 1e-6 / MFMA_BF16_PEAK_TFLOPS, 4),
+            "weight_stream_gbs": round(r["proj_bytes"] / us_proj * 1e-3, 1),
+            "frac_of_hbm_peak": round(r["proj_bytes"] / us_proj * 1e-3 / HBM_PEAK_GBS, 4),
+            "tflops": round(r["proj_flops"] / us_proj * 1e-6, 1),
+            "frac_of_mfma_peak": round(r["proj_flops"] / us_proj * 1e-6 / MFMA_BF16_PEAK_TFLOPS, 4),
         },
-        "active_rows_per_s": round(B * A / (us_step * 1e-6), 1),
-        "tflops": round(flops / us_step * 1e-6, 2),
-        "single_cache_us": None if args.no_single else round(us_single, 3),
-        "single_cache_attention_us": None if args.no_single else round(us_attn_single, 3),
-        "single_cache_attention_gbs": None if args.no_single else round(attn_bytes / us_attn_single * 1e-3, 1),
-        "host_wall_us_per_step": round(t_host * 1e6 / args.steps, 2),
+        "active_rows_per_s": round(r["B"] * r["A"] / (us_step * 1e-6), 1),
+        "tflops": round((r["proj_flops"] + r["attn_flops"]) / us_step * 1e-6, 2),
+        "graph_us_per_step_median": round(r["us_step_med"], 3),
+        "eager_us_per_step": round(r["us_step_eager"], 3),
+        "host_wall_us_per_step": round(r["host_us"], 2),
+        "single_cache_us": nan_none(r["us_single"]),
+        "single_cache_attention_us": nan_none(r["us_attn_single"]),
+        "single_cache_attention_gbs": None if r["us_attn_single"] != r["us_attn_single"]
+        else round(r["attn_bytes"] / r["us_attn_single"] * 1e-3, 1),
     }
+    if refresh:
+        # the refresh is a dense pass: both calls are bound by the matrix cores, the projection GEMM
+        # being the longer one
+        out["roofline"] = {
+            "kernel": "fc_qkv_project_scatter (k_proj_gemm)",
+            "bound": "mfma",
+            "achieved": round(r["proj_flops"] / us_proj * 1e-6, 1),
+            "peak": MFMA_BF16_PEAK_TFLOPS,
+            "unit": "TFLOP/s",
+            "frac": round(r["proj_flops"] / us_proj * 1e-6 / MFMA_BF16_PEAK_TFLOPS, 4),
+            "traffic": None,
+            "algorithmic_flops_per_launch": r["proj_flops"],
+            "us_per_launch": round(us_proj, 3),
+        }
+        out["attention"] = {
+            "kernel": "fc_active_attention",
+            "us_per_launch": round(us_attn, 3),
+            "tflops": round(r["attn_flops"] / us_attn * 1e-6, 1),
+            "frac_of_mfma_peak": round(r["attn_flops"] / us_attn * 1e-6 / MFMA_BF16_PEAK_TFLOPS, 4),
+        }
+    return out
+
+
+def others_summary(args, torch, fc, inputs, dev):
+    """The other configurations in the same run, compact: value and roofline fraction each."""
+    res = {}
+    for name in ("c2", "c3", "c5", "c5_refresh"):
+        r = hot_path(torch, fc, inputs, dev, name, steps=20 if name == "c5_refresh" else 40, warmup=8, repeats=3,
+                     no_single=True)
+        j = hot_path_json(r)
+        res[name] = {"workload": j["config"]["workload"], "us_per_step": j["value"],
+                     "attention_us": round(r["us_attn"], 3), "projection_us": round(r["us_proj"], 3),
+                     "roofline_bound": j["roofline"]["bound"], "roofline_kernel": j["roofline"]["kernel"],
+                     "roofline_frac": j["roofline"]["frac"],
+                     "attention_kv_gbs": round(r["attn_bytes"] / r["us_attn"] * 1e-3, 1)}
+    sub = argparse.Namespace(**vars(args))
+    sub.workload, sub.steps, sub.warmup, sub.repeats, sub.no_cpu_baseline = "c5_decode", 64, 8, 3, True
+    d = main_decode(sub, torch, fc, inputs, dev)
+    res["c5_decode"] = {"workload": d["config"]["workload"], "tokens_per_s": d["value"], "ms_per_28_layer_step": d["ms_per_step"],
+                        "roofline_frac": d["roofline"]["frac"], "initial_pass_ms": d["initial_pass_ms"]}
+    return res
+
+
+def main():
+    args = _parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no sharding, no collectives); "
+              "--gpus %d is not supported" % args.gpus, file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2505_21467_amd import binding as fc
+    from paper_2505_21467_amd import inputs
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    fc.lib()
+    dev = torch.device("cuda:0")
+    if args.workload.startswith("c5_decode"):
+        args.steps = 64 if args.steps is None else args.steps
+        print(json.dumps(main_decode(args, torch, fc, inputs, dev)))
+        return
+    args.steps = 100 if args.steps is None else args.steps
+    if args.workload.endswith("_layer"):
+        return main_layer(args, torch, fc, inputs, dev)
+    if args.workload.endswith("_unmask"):
+        return main_unmask(args, torch, fc, inputs, dev)
+    if args.workload.endswith("_accept"):
+        return main_accept(args, torch, fc, inputs, dev)
+    if args.workload.endswith("_drift"):
+        return main_drift(args, torch, fc, inputs, dev)
+
+    r = hot_path(torch, fc, inputs, dev, args.workload, args.steps, args.warmup, args.repeats, args.layers, args.no_single)
+    out = hot_path_json(r)
 
     # A plain elementwise copy kernel of known size, so that a counter run of this same command
     # (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE) can be scaled: 256 MiB read and 256 MiB written.
@@ -260,33 +415,12 @@ def main():
         torch.add(cal_src, 1.0, out=cal_dst)  # an elementwise kernel: reads 256 MiB, writes 256 MiB
     torch.cuda.synchronize()
     out["calibration_copy_bytes"] = cal_src.numel() * 4
+    del cal_src, cal_dst
 
-    if refresh:
-        # the refresh is a dense pass: both calls are bound by the matrix cores, the projection GEMM
-        # being the longer one
-        out["roofline"] = {
-            "kernel": "fc_qkv_project_scatter (k_proj_gemm)",
-            "bound": "mfma",
-            "achieved": round(proj_flops / us_proj * 1e-6, 1),
-            "peak": MFMA_BF16_PEAK_TFLOPS,
-            "unit": "TFLOP/s",
-            "frac": round(proj_flops / us_proj * 1e-6 / MFMA_BF16_PEAK_TFLOPS, 4),
-            "traffic": None,
-            "algorithmic_flops_per_launch": proj_flops,
-            "us_per_launch": round(us_proj, 3),
-        }
-        out["attention"] = {
-            "kernel": "fc_active_attention",
-            "us_per_launch": round(us_attn, 3),
-            "tflops": round(attn_flops / us_attn * 1e-6, 1),
-            "frac_of_mfma_peak": round(attn_flops / us_attn * 1e-6 / MFMA_BF16_PEAK_TFLOPS, 4),
-        }
-
+    if args.workload == "c4" and not args.no_others:
+        out["others"] = others_summary(args, torch, fc, inputs, dev)
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(w, inputs, A, refresh)
-
-    torch.cuda.synchronize()
-    fc.fc_cache_free(cache)
+        out["cpu_baseline"] = cpu_baseline(r["w"], inputs, r["A"], r["refresh"])
     print(json.dumps(out))
 
 
@@ -644,7 +778,7 @@ def main_decode(args, torch, fc, inputs, dev):
                                "sample": cb["sample"] + "; scaled to 28 layers per step, refreshes not included"}
     torch.cuda.synchronize()
     fc.fc_cache_free(cache)
-    print(json.dumps(out))
+    return out
 
 
 def main_unmask(args, torch, fc, inputs, dev):
@@ -889,7 +1023,7 @@ def cpu_baseline(w, inputs, A, refresh):
     import numpy as np
     from oracle import fc_oracle as orc
 
-    max_samples, budget_s = 100, 12.0  # stop after about 12 s of oracle work
+    max_samples, budget_s = 100, 10.0  # stop after about 10 s of oracle work
     S = w.kv_len
     cfg = orc.OracleConfig(w.batch, w.hidden, w.n_q_heads, w.n_kv_heads, w.head_dim, S, w.dtype, w.rope_base)
     K0, V0 = inputs.kv_fill(w, 0, S)

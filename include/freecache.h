@@ -69,6 +69,18 @@ typedef struct fc_cache fc_cache; /* opaque */
 /* Thread-local description of the last failure on the calling thread ("" if none). */
 const char *fc_last_error(void);
 
+/* Tuning knobs, for A/B measurements and for tests that force a code path; the defaults are the
+ * measured best and no caller needs this.  Each knob starts from the environment variable of the same
+ * name (read once, at the library's first planning call) and is changed afterwards only here:
+ * value NULL restores the default.  Names: FC_ATTN_TILES ("R,W": row tiles and waves per attention
+ * workgroup), FC_ATTN_WGS, FC_LIN_WGS, FC_ACCEPT_WGS (target workgroup counts), FC_LIN_NO_ROWS,
+ * FC_GEMM_NO_SPLIT, FC_PROJ_NO_HEADSPLIT (any value switches the named path off), FC_LIN_WIDE_SHAPE,
+ * FC_PROJ_GEMM_SHAPE (one GEMM tile shape for everything), FC_LIN_KSPLIT (parts of the hidden
+ * dimension).  Host only; not thread-safe against concurrent calls into the library; workspace sizes
+ * depend on the knobs, so query them after setting.
+ * Errors: INVALID_ARG (NULL or unknown name). */
+fc_status fc_tuning_set(const char *name, const char *value);
+
 /* ---------------------------------------------------------------------------------------------
  * Persistent per-layer KV cache (section 3.2.1, "Initialization and Partitioning": the K/V
  * projections of prompt + all blocks are saved once and then reused).
@@ -146,6 +158,15 @@ fc_status fc_qkv_project_scatter(fc_cache *cache, int32_t layer, const void *x, 
 /* Workspace bytes fc_active_attention / fc_refresh need for windows of up to max_rows rows
  * (split-KV partial results).  0 on bad arguments. */
 size_t fc_workspace_bytes(const fc_config *cfg, int32_t max_rows);
+
+/* The launch plan fc_active_attention would use for a window of A rows over kv_len cached rows
+ * (host, pure function of the shape and the tuning knobs; for reports and for tying a measured HBM
+ * traffic figure to the plan it was measured with):
+ *   plan[0] kind (0 plain kernel, 1 matrix-core split-KV kernel)   plan[1] key ranges (splits)
+ *   plan[2] keys per split   plan[3] 32-row tiles per (sequence, kv head)
+ *   plan[4] row tiles per workgroup   plan[5] waves per workgroup
+ * Errors: INVALID_ARG, UNSUPPORTED (config), BOUNDS (kv_len). */
+fc_status fc_attention_plan(const fc_config *cfg, int32_t A, int32_t kv_len, int32_t plan[6]);
 
 /* Bidirectional attention of the window's queries over cache rows [0, kv_len) (Table 1, rows
  * "QK^T" and "score x V", L x L -> A x L): out[b][a][h*Dh + i] = sum_t softmax_t(scale q.k_t) v_t[i]

@@ -18,7 +18,7 @@ DTYPE_CODE = {"f32": FC_F32, "bf16": FC_BF16, torch.float32: FC_F32, torch.bfloa
 TORCH_DTYPE = {FC_F32: torch.float32, FC_BF16: torch.bfloat16}
 
 EXPORTS = (
-    "fc_last_error", "fc_cache_storage_bytes", "fc_cache_alloc", "fc_cache_free", "fc_cache_ptrs",
+    "fc_last_error", "fc_tuning_set", "fc_attention_plan", "fc_cache_storage_bytes", "fc_cache_alloc", "fc_cache_free", "fc_cache_ptrs",
     "fc_cache_write_rows", "fc_cache_read_rows", "fc_window", "fc_qkv_project_scatter",
     "fc_workspace_bytes", "fc_active_attention", "fc_refresh",
     "fc_active_attention_static_max_bytes", "fc_active_attention_static",
@@ -65,6 +65,10 @@ def lib():
         cfgp = ctypes.POINTER(fc_config)
         L.fc_last_error.restype = ctypes.c_char_p
         L.fc_last_error.argtypes = []
+        L.fc_tuning_set.restype = ctypes.c_int
+        L.fc_tuning_set.argtypes = [ctypes.c_char_p, ctypes.c_char_p]
+        L.fc_attention_plan.restype = ctypes.c_int
+        L.fc_attention_plan.argtypes = [cfgp, i32, i32, ctypes.POINTER(i32)]
         L.fc_cache_storage_bytes.restype = sz
         L.fc_cache_storage_bytes.argtypes = [cfgp]
         L.fc_cache_alloc.restype = ctypes.c_int
@@ -152,6 +156,17 @@ def make_config(n_layers, batch, hidden, n_q_heads, n_kv_heads, head_dim, max_se
                 rope_base=10000.0, softmax_scale=0.0) -> fc_config:
     return fc_config(n_layers, batch, hidden, n_q_heads, n_kv_heads, head_dim, max_seq,
                      DTYPE_CODE[dtype], rope_base, softmax_scale)
+
+
+def fc_tuning_set(name: str, value=None) -> None:
+    """Set a tuning knob (value None restores the default)."""
+    _check(lib().fc_tuning_set(name.encode(), None if value is None else str(value).encode()))
+
+
+def fc_attention_plan(cfg: fc_config, A: int, kv_len: int) -> dict:
+    out = (ctypes.c_int32 * 6)()
+    _check(lib().fc_attention_plan(ctypes.byref(cfg), A, kv_len, out))
+    return dict(zip(("kind", "splits", "keys_per_split", "row_tiles", "tiles_per_wg", "waves"), list(out)))
 
 
 def fc_cache_storage_bytes(cfg: fc_config) -> int:

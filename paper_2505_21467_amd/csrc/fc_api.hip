@@ -92,22 +92,59 @@ fc_status hip_fail(hipError_t e, const char *what)
 // ---------------------------------------------------------------------------------------------
 // Launch planning (pure host functions).
 
-// Tuning knobs for experiments: FC_ATTN_TILES=R,W forces the workgroup shape, FC_ATTN_WGS the
-// number of workgroups the split heuristic aims for.  Read once.
-static void attn_env(int *r, int *w, int *target)
+// Tuning knobs (see FcKnobs): read from the environment once, then changed only by fc_tuning_set.
+namespace {
+
+FcKnobs g_knobs;
+bool g_knobs_init = false;
+
+void knobs_defaults(FcKnobs &k)
 {
-    static int er = 0, ew = 0, et = 0, init = 0;
-    if (!init) {
-        if (const char *e = getenv("FC_ATTN_TILES")) sscanf(e, "%d,%d", &er, &ew);
-        if (const char *e = getenv("FC_ATTN_WGS")) et = atoi(e);
-        init = 1;
-    }
-    if (er > 0 && ew > 0) {
-        *r = er;
-        *w = ew;
-    }
-    if (et > 0) *target = et;
+    memset(&k, 0, sizeof k);
+    k.lin_wide_shape = -1;
+    k.proj_gemm_shape = -1;
 }
+
+// Apply one "NAME", "value" pair (value NULL = back to the default).  False for an unknown name.
+bool knob_apply(FcKnobs &k, const char *name, const char *value)
+{
+    FcKnobs d;
+    knobs_defaults(d);
+    const int v = value ? atoi(value) : 0;
+    if (!strcmp(name, "FC_ATTN_TILES")) {
+        k.attn_r = k.attn_w = 0;
+        if (value) sscanf(value, "%d,%d", &k.attn_r, &k.attn_w);
+    } else if (!strcmp(name, "FC_ATTN_WGS")) k.attn_wgs = value ? v : d.attn_wgs;
+    else if (!strcmp(name, "FC_LIN_WGS")) k.lin_wgs = value ? v : d.lin_wgs;
+    else if (!strcmp(name, "FC_LIN_NO_ROWS")) k.lin_no_rows = value ? 1 : 0;
+    else if (!strcmp(name, "FC_LIN_WIDE_SHAPE")) k.lin_wide_shape = value ? v : d.lin_wide_shape;
+    else if (!strcmp(name, "FC_LIN_KSPLIT")) k.lin_ksplit = value ? v : d.lin_ksplit;
+    else if (!strcmp(name, "FC_GEMM_NO_SPLIT")) k.gemm_no_split = value ? 1 : 0;
+    else if (!strcmp(name, "FC_PROJ_GEMM_SHAPE")) k.proj_gemm_shape = value ? v : d.proj_gemm_shape;
+    else if (!strcmp(name, "FC_PROJ_NO_HEADSPLIT")) k.proj_no_headsplit = value ? 1 : 0;
+    else if (!strcmp(name, "FC_ACCEPT_WGS")) k.accept_wgs = value ? v : d.accept_wgs;
+    else return false;
+    return true;
+}
+
+const char *const KNOB_NAMES[] = {"FC_ATTN_TILES", "FC_ATTN_WGS", "FC_LIN_WGS", "FC_LIN_NO_ROWS", "FC_LIN_WIDE_SHAPE",
+                                  "FC_LIN_KSPLIT", "FC_GEMM_NO_SPLIT", "FC_PROJ_GEMM_SHAPE", "FC_PROJ_NO_HEADSPLIT",
+                                  "FC_ACCEPT_WGS"};
+
+FcKnobs &knobs_mut()
+{
+    if (!g_knobs_init) {
+        knobs_defaults(g_knobs);
+        for (const char *n : KNOB_NAMES)
+            if (const char *e = getenv(n)) knob_apply(g_knobs, n, e);
+        g_knobs_init = true;
+    }
+    return g_knobs;
+}
+
+}  // namespace
+
+const FcKnobs &fc_knobs() { return knobs_mut(); }
 
 FcAttnPlan fc_plan_attention(const fc_config &cfg, int A, int kv_len)
 {
@@ -138,7 +175,14 @@ FcAttnPlan fc_plan_attention(const fc_config &cfg, int A, int kv_len)
             W = 4;
         }
     }
-    attn_env(&R, &W, &target);
+    {
+        const FcKnobs &kn = fc_knobs();
+        if (kn.attn_r > 0 && kn.attn_w > 0) {
+            R = kn.attn_r;
+            W = kn.attn_w;
+        }
+        if (kn.attn_wgs > 0) target = kn.attn_wgs;
+    }
     if (R != 2 && R != 4 && R != 8) R = r_default;
     if (W != 4 && W != 8) W = 8;
     if (W == 4) {  // four-wave workgroups: two or four tiles, two workgroups per compute unit
@@ -176,6 +220,30 @@ extern "C" {
 
 const char *fc_last_error(void) { return g_err; }
 
+fc_status fc_tuning_set(const char *name, const char *value)
+{
+    if (!name) return fail(FC_ERR_INVALID_ARG, "name is NULL");
+    if (!knob_apply(knobs_mut(), name, value)) return fail(FC_ERR_INVALID_ARG, "unknown tuning knob %s", name);
+    return FC_OK;
+}
+
+fc_status fc_attention_plan(const fc_config *cfg, int32_t A, int32_t kv_len, int32_t *plan)
+{
+    fc_status st = check_config(cfg);
+    if (st != FC_OK) return st;
+    if (!plan) return fail(FC_ERR_INVALID_ARG, "plan is NULL");
+    if (A < 1) return fail(FC_ERR_INVALID_ARG, "A %d must be >= 1", A);
+    if (kv_len < 1 || kv_len > cfg->max_seq) return fail(FC_ERR_BOUNDS, "kv_len %d outside [1, %d]", kv_len, cfg->max_seq);
+    const FcAttnPlan p = fc_plan_attention(*cfg, A, kv_len);
+    plan[0] = p.kind;
+    plan[1] = p.splits;
+    plan[2] = p.keys_per_split;
+    plan[3] = p.row_tiles;
+    plan[4] = p.tiles_per_wg;
+    plan[5] = p.waves;
+    return FC_OK;
+}
+
 size_t fc_cache_storage_bytes(const fc_config *cfg)
 {
     if (check_config(cfg) != FC_OK) return 0;
@@ -202,6 +270,7 @@ fc_status fc_cache_alloc(const fc_config *cfg, void *k_storage, void *v_storage,
     c->k = k_storage;
     c->v = v_storage;
     c->owned = false;
+    c->ws_A = c->ws_d_ff = 0;
     for (int i = 0; i < 64; ++i)
         c->inv_freq[i] = i < cfg->head_dim / 2 ? pow((double)cfg->rope_base, -2.0 * i / cfg->head_dim) : 0.0;
     if (!k_storage) {
@@ -642,7 +711,16 @@ fc_status fc_full_layer_step(fc_cache *cache, int32_t layer, const fc_layer_weig
         return fail(FC_ERR_BOUNDS, "window [%d, %d+%d) outside the cache of %d rows", win_start, win_start, A,
                     c.max_seq);
     if (kv_len < 1 || kv_len > c.max_seq) return fail(FC_ERR_BOUNDS, "kv_len %d outside [1, %d]", kv_len, c.max_seq);
-    const LayerWs w = layer_ws(c, wt->d_ff, A);
+    LayerWs w;
+    static_assert(sizeof(LayerWs) == sizeof(cache->ws_part), "cached carve-up");
+    if (cache->ws_A == A && cache->ws_d_ff == wt->d_ff) {
+        memcpy(&w, cache->ws_part, sizeof w);
+    } else {
+        w = layer_ws(c, wt->d_ff, A);
+        memcpy(cache->ws_part, &w, sizeof w);
+        cache->ws_A = A;
+        cache->ws_d_ff = wt->d_ff;
+    }
     if (!workspace || workspace_bytes < w.total)
         return fail(FC_ERR_WORKSPACE, "workspace of %zu bytes needed, %zu given", w.total,
                     workspace ? workspace_bytes : (size_t)0);

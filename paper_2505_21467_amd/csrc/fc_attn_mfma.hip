@@ -57,17 +57,8 @@ struct AttnArgs {
     int B, Hq, Hkv, g, A, kv_len, spad, max_seq;
     int row_tiles, n_rg, splits, keys_per_split, n_units;
     float c;              // softmax scale * log2(e)
-#ifdef FC_ATTN_TIMING
-    unsigned long long *dbg;  // tuning builds only: 8 cycle-counter stamps per workgroup
-    int dbg_flags;            // tuning builds only: 1 = skip the compute, 2 = skip the loads
-#endif
 };
 
-#ifdef FC_ATTN_TIMING
-#define FC_STAMP(k) do { if (p.dbg && threadIdx.x == 0) p.dbg[(size_t)blockIdx.x * 8 + (k)] = __builtin_amdgcn_s_memrealtime(); } while (0)
-#else
-#define FC_STAMP(k) do { } while (0)
-#endif
 
 __device__ __forceinline__ int kappa(int x) { return (x & 0x13) | ((x & 4) << 1) | ((x & 8) >> 1); }
 
@@ -166,7 +157,6 @@ __global__ __launch_bounds__(W * 64) __attribute__((amdgpu_waves_per_eu(2, 2))) 
     static_assert(W % KW == 0 && (KW == 1 || KW == 2 || KW == 4) && (W == 4 || W == 8), "shape");
     extern __shared__ __align__(1024) unsigned char smem[];
 
-    FC_STAMP(0);
     // Workgroup -> (unit, row group).  Workgroup ids that are equal modulo 8 land on the same XCD; the
     // (unit, row group) pairs, ordered unit by unit, are dealt to the eight XCDs in equal contiguous
     // runs, so the workgroups that stream the same keys share an L2 and every XCD gets the same number
@@ -251,9 +241,6 @@ __global__ __launch_bounds__(W * 64) __attribute__((amdgpu_waves_per_eu(2, 2))) 
     auto issue_stage = [&](int st) {
         const unsigned char *src = gsrc + (size_t)st * (STAGE_BYTES / 2);  // 64 keys * 256 B for K and for V
         unsigned char *dst = smem + (st % SLOTS) * STAGE_BYTES + lds_dst;
-#ifdef FC_ATTN_TIMING
-        if (p.dbg_flags & 2) return;
-#endif
 #pragma unroll
         for (int i = 0; i < LB; ++i) load_lds16(src + goff[i], dst + i * 1024);
     };
@@ -271,7 +258,6 @@ __global__ __launch_bounds__(W * 64) __attribute__((amdgpu_waves_per_eu(2, 2))) 
 
     if (n_stages > 0) issue_stage(0);
     if (AHEAD > 1 && n_stages > 1) issue_stage(1);
-    FC_STAMP(1);
 
     for (int it = 0; it < n_stages; ++it) {
         const int ks = k0 + it * KT;
@@ -305,9 +291,6 @@ __global__ __launch_bounds__(W * 64) __attribute__((amdgpu_waves_per_eu(2, 2))) 
             }
             __syncthreads();
         }
-#ifdef FC_ATTN_TIMING
-        if (p.dbg_flags & 1) continue;
-#endif
         if (KW == 4 && (it & 1) != (kw >> 1)) continue;
 #pragma unroll
         for (int hh = 0; hh < (KW == 1 ? 2 : 1); ++hh) {
@@ -350,7 +333,6 @@ __global__ __launch_bounds__(W * 64) __attribute__((amdgpu_waves_per_eu(2, 2))) 
         }
     }
     __syncthreads();  // every wave is done with the ring; LDS is reused below
-    FC_STAMP(2);
 
     float *xch = (float *)smem;
 #pragma unroll
@@ -374,7 +356,6 @@ __global__ __launch_bounds__(W * 64) __attribute__((amdgpu_waves_per_eu(2, 2))) 
             }
         }
         __syncthreads();
-        FC_STAMP(3);
         if (kw == 0) {
 #pragma unroll
             for (int u = 0; u < T; ++u) {
@@ -400,7 +381,6 @@ __global__ __launch_bounds__(W * 64) __attribute__((amdgpu_waves_per_eu(2, 2))) 
             }
         }
         __syncthreads();  // the exchange area is reused as output staging
-        FC_STAMP(4);
     }
     if (kw != 0) return;
 
@@ -417,9 +397,6 @@ __global__ __launch_bounds__(W * 64) __attribute__((amdgpu_waves_per_eu(2, 2))) 
             if (!tile_valid[u]) continue;
             const size_t ts = ((size_t)bj * p.row_tiles + rt0 + u) * p.splits + split;
             uint4 *po = (uint4 *)p.part_o + ts * (8 * 64) + lane;
-#ifdef FC_ATTN_TIMING
-            if (p.dbg_flags & 4) continue;
-#endif
             float amax = 0.f;
 #pragma unroll
             for (int dt = 0; dt < 4; ++dt)
@@ -438,7 +415,6 @@ __global__ __launch_bounds__(W * 64) __attribute__((amdgpu_waves_per_eu(2, 2))) 
             }
             if (hi == 0) ((float4 *)p.part_ml)[ts * 32 + col] = make_float4(t[u].m * p.c, t[u].l, (float)k, 0.f);
         }
-        FC_STAMP(5);
         return;
     }
 
@@ -482,7 +458,6 @@ __global__ __launch_bounds__(W * 64) __attribute__((amdgpu_waves_per_eu(2, 2))) 
         __builtin_amdgcn_wave_barrier();
         __builtin_amdgcn_s_waitcnt(0xc07f);  // reads of the staging area are done before the next tile reuses it
     }
-    FC_STAMP(5);
 }
 
 // Merge the per-split partials: one workgroup of NWV waves per (row tile, pair of 16-byte accumulator
@@ -494,7 +469,6 @@ __global__ __launch_bounds__(W * 64) __attribute__((amdgpu_waves_per_eu(2, 2))) 
 template <int CB, int NWV>
 __global__ __launch_bounds__(64 * NWV) void k_attn_combine(AttnArgs p)
 {
-    FC_STAMP(6);
     __shared__ float xw[NWV > 1 ? NWV : 1][10][64];
     const int lane = threadIdx.x & 63, col = lane & 31, hi = lane >> 5;
     const int wv = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -580,7 +554,6 @@ __global__ __launch_bounds__(64 * NWV) void k_attn_combine(AttnArgs p)
         const int dh = 32 * (q2 >> 1) + 8 * (2 * (q2 & 1) + g2) + 4 * hi;
         *(uint2 *)(orow + dh) = w;
     }
-    FC_STAMP(7);
 }
 
 template <int T, int W, int KW>
@@ -625,14 +598,6 @@ hipError_t fc_launch_attention_mfma(const FcGeom &G, const FcAttnPlan &pl, const
     a.keys_per_split = pl.keys_per_split;
     a.n_units = G.B * G.Hkv * pl.splits;
     a.c = G.scale * 1.4426950408889634f;
-#ifdef FC_ATTN_TIMING
-    {
-        const char *env = getenv("FC_ATTN_DBG_PTR");
-        a.dbg = env ? (unsigned long long *)strtoull(env, nullptr, 0) : nullptr;
-        const char *fl = getenv("FC_ATTN_DBG_FLAGS");
-        a.dbg_flags = fl ? atoi(fl) : 0;
-    }
-#endif
     hipError_t e;
     const int R = pl.tiles_per_wg;
     if (pl.waves == 8) {  // one tile per wave
@@ -646,9 +611,6 @@ hipError_t fc_launch_attention_mfma(const FcGeom &G, const FcAttnPlan &pl, const
         else return hipErrorInvalidValue;
     }
     if (e != hipSuccess || pl.splits == 1) return e;
-#ifdef FC_ATTN_TIMING
-    if (a.dbg_flags & 8) return e;
-#endif
     const dim3 cgrid((unsigned)(tiles * 8));
     if (pl.splits <= 2) k_attn_combine<2, 1><<<cgrid, dim3(64), 0, s>>>(a);
     else if (pl.splits <= 8) k_attn_combine<8, 1><<<cgrid, dim3(64), 0, s>>>(a);

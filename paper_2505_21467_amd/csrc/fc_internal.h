@@ -20,9 +20,30 @@ struct fc_cache {
     // Device scratch owned by the handle (nullptr when no GPU was present at creation): space for the
     // partial sums that the short-window projection hands from its first kernel to its second.
     void *scratch;
+    // Carve-up of the whole-layer workspace for the last (d_ff, A) seen: fc_full_layer_step is called
+    // with the same shape step after step, and planning it anew walks every window size up to A.
+    int32_t ws_d_ff, ws_A;
+    size_t ws_part[10];
 };
 
 #define FC_SCRATCH_BYTES (32u * 1024u * 1024u)
+
+// Tuning knobs: defaults (0 / -1 = the planner decides), overridden once from the environment
+// variables of the same names at first use and afterwards only through fc_tuning_set.  Planners and
+// launchers read this struct; nothing on a launch path calls getenv.
+struct FcKnobs {
+    int attn_r, attn_w;     // FC_ATTN_TILES=R,W      row tiles and waves per attention workgroup
+    int attn_wgs;           // FC_ATTN_WGS=n          workgroups the split heuristic aims for
+    int lin_wgs;            // FC_LIN_WGS=n           workgroups of the weight-streaming linear kernels
+    int lin_no_rows;        // FC_LIN_NO_ROWS         slice-wise instead of whole-row weight streaming
+    int lin_wide_shape;     // FC_LIN_WIDE_SHAPE=0..2 one tile shape for the tiled linear GEMM (-1 = planned)
+    int lin_ksplit;         // FC_LIN_KSPLIT=n        parts of the hidden dimension
+    int gemm_no_split;      // FC_GEMM_NO_SPLIT       never cut a GEMM into two launches
+    int proj_gemm_shape;    // FC_PROJ_GEMM_SHAPE=0..3 one tile shape for the projection GEMM (-1 = planned)
+    int proj_no_headsplit;  // FC_PROJ_NO_HEADSPLIT   short-window projection without the head-split kernels
+    int accept_wgs;         // FC_ACCEPT_WGS=n        workgroups of the acceptance scan
+};
+const FcKnobs &fc_knobs();
 
 // Geometry handed to kernels by value.
 struct FcGeom {

@@ -40,16 +40,8 @@ struct LinArgs {
     float *partials;      // [m chunk][slab][maxseg][wave][mt][4][64]
     int M, K, N;          // N = output columns
     int S, T, G, maxseg, slabs;
-#ifdef FC_LIN_TIMING
-    unsigned long long *dbg;  // tuning builds only: 16 stamps of the 100 MHz clock per workgroup
-#endif
 };
 
-#ifdef FC_LIN_TIMING
-#define FC_LSTAMP(k) do { if (p.dbg && threadIdx.x == 0 && (k) < 16) p.dbg[(size_t)blockIdx.x * 16 + (k)] = __builtin_amdgcn_s_memrealtime(); } while (0)
-#else
-#define FC_LSTAMP(k) do { } while (0)
-#endif
 
 __device__ __forceinline__ bf16x8 ld8(const uint16_t *p)
 {
@@ -157,25 +149,21 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(KSL >= 512 
     };
 
     if (ulo >= uhi) return;
-    FC_LSTAMP(0);
     bf16x8 wa[KS], wb[KS];
     issue(lo, wa, xs[0]);
     int item = lo;
     for (;;) {
         __syncthreads();  // the loads of `item` have landed; every wave is done with the other buffers
-        FC_LSTAMP(1 + item - lo);
         if (item + 1 < hi) issue(item + 1, wb, xs[1]);
         compute(wa, xs[0]);
         tail(item);
         if (++item >= hi) break;
         __syncthreads();
-        FC_LSTAMP(1 + item - lo);
         if (item + 1 < hi) issue(item + 1, wa, xs[0]);
         compute(wb, xs[1]);
         tail(item);
         if (++item >= hi) break;
     }
-    FC_LSTAMP(15);
 }
 
 // Sum of a slab's partial tiles + epilogue; one wave per (slab, 16-row tile of W), grid.y = m chunk.
@@ -545,13 +533,10 @@ FcSkinnyPlan fc_plan_skinny(int dtype, int mode, int M, int K, int N)
     FcSkinnyPlan p;
     memset(&p, 0, sizeof p);
     int target = 256;  // one workgroup per compute unit
-    if (const char *e = getenv("FC_LIN_WGS")) {  // tuning and test knob: runs of any length
-        const int v = atoi(e);
-        if (v > 0) target = v;
-    }
+    if (fc_knobs().lin_wgs > 0) target = fc_knobs().lin_wgs;  // tuning and test knob: runs of any length
     {
         // whole-row kernel: at most 32 rows, a hidden size it is built for, whole half items
-        static const bool off = getenv("FC_LIN_NO_ROWS") != nullptr;  // tuning knob
+        const bool off = fc_knobs().lin_no_rows != 0;  // tuning knob
         const int per_half = mode == FC_LIN_GATE_UP ? 4 : 8;
         // With less than one item per compute unit at a long hidden size (W_out of the 7B geometry: 224
         // items) the X block, K x 64 bytes per workgroup, is a third of what a workgroup reads, and the
@@ -651,12 +636,6 @@ hipError_t fc_launch_linear_skinny(const FcSkinnyPlan &pl, int mode, const void 
     a.G = pl.G;
     a.maxseg = pl.maxseg;
     a.slabs = pl.slabs;
-#ifdef FC_LIN_TIMING
-    {
-        const char *env = getenv("FC_LIN_DBG_PTR");
-        a.dbg = env ? (unsigned long long *)strtoull(env, nullptr, 0) : nullptr;
-    }
-#endif
     if (mode == FC_LIN_VOCAB) {
         if (!am) return hipErrorInvalidValue;
         a.am = *am;

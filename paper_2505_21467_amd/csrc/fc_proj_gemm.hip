@@ -59,17 +59,8 @@ struct GemmArgs {
     int N;                 // output columns
     int ksplit;            // EPI 3: parts the hidden dimension is cut into
     FcArgmaxPart am;       // EPI 4: per (slab, row) largest logit, its index, sum of exponentials
-#ifdef FC_GEMM_TUNE
-    int flags;             // tuning builds only: 1 skip the multiplies, 2 skip the LDS reads, 4 skip the global loads
-    unsigned long long *dbg;  // tuning builds only: time stamps (100 MHz), 8 per workgroup
-#endif
 };
 
-#ifdef FC_GEMM_TUNE
-#define FC_GSTAMP(k) do { if (p.dbg && threadIdx.x == 0) p.dbg[(size_t)blockIdx.x * 8 + (k)] = __builtin_amdgcn_s_memrealtime(); } while (0)
-#else
-#define FC_GSTAMP(k) do { } while (0)
-#endif
 
 __device__ __forceinline__ void load_lds16g(const void *g, void *l)
 {
@@ -127,7 +118,6 @@ __global__ __launch_bounds__((NW + NL) * 64) void k_proj_gemm(GemmArgs p)
     static_assert(EPI == 0 || NG == 1, "the plain linear layers use one slab per workgroup");
     extern __shared__ __align__(1024) unsigned char smem[];
     const FcGeom &G = p.G;
-    FC_GSTAMP(0);
 
     // Workgroup -> (unit, row tile).  Workgroup ids that are equal modulo 8 land on the same XCD; the
     // tiles, ordered unit by unit, are dealt to the eight XCDs in equal contiguous runs, so the
@@ -190,9 +180,6 @@ __global__ __launch_bounds__((NW + NL) * 64) void k_proj_gemm(GemmArgs p)
     const int n_stages = EPI == 3 ? (int)(((int64_t)kpart + 1) * all_stages / p.ksplit) - st0 : all_stages;
     auto issue_stage = [&](int st, int part) {
         unsigned char *dst = smem + (st % SLOTS) * STAGE;
-#ifdef FC_GEMM_TUNE
-        if (FC_GEMM_TUNE & 4) return;
-#endif
 #pragma unroll
         for (int i = 0; i < LBW; ++i) {
             if (part >= 0 && (i & 3) != part) continue;
@@ -227,23 +214,14 @@ __global__ __launch_bounds__((NW + NL) * 64) void k_proj_gemm(GemmArgs p)
     // multiplies of k-step kk, and the first reads of the next stage go out (behind that stage's
     // barrier) before the last multiplies of this one, so the matrix core never waits for LDS.
     bf16x8 xf[2][MW], wf[2][NSUB];
-#ifdef FC_GEMM_TUNE
-    for (int i = 0; i < 2; ++i) { for (int e = 0; e < 8; ++e) wf[i][0][e] = (__bf16)(float)lane; for (int t = 0; t < NSUB; ++t) wf[i][t] = wf[i][0]; for (int t = 0; t < MW; ++t) xf[i][t] = wf[i][0]; }
-#endif
     auto read_frags = [&](int slot, int kk, int buf) {
         const unsigned char *st = smem + slot * STAGE;
-#ifdef FC_GEMM_TUNE
-        if (FC_GEMM_TUNE & 2) return;
-#endif
 #pragma unroll
         for (int i = 0; i < MW; ++i) xf[buf][i] = *(const bf16x8 *)(st + x_base + i * (32 * ROWB) + foff[kk]);
 #pragma unroll
         for (int t = 0; t < NSUB; ++t) wf[buf][t] = *(const bf16x8 *)(st + w_base + t * (32 * ROWB) + foff[kk]);
     };
     auto multiply = [&](int buf) {
-#ifdef FC_GEMM_TUNE
-        if (FC_GEMM_TUNE & 1) { acc[0][0][0] += (float)xf[buf][0][0] + (float)wf[buf][0][0] + (float)wf[buf][NSUB - 1][1]; return; }
-#endif
 #pragma unroll
         for (int i = 0; i < MW; ++i)
 #pragma unroll
@@ -251,7 +229,6 @@ __global__ __launch_bounds__((NW + NL) * 64) void k_proj_gemm(GemmArgs p)
                 acc[i][t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[buf][t], xf[buf][i], acc[i][t], 0, 0, 0);
     };
 
-    FC_GSTAMP(1);
     const int n_pro = min(SLOTS, n_stages);
     if (NL > 0) {
         // ---- loading waves: one barrier per stage, shared with the multiplying waves.  Barrier `it`
@@ -326,7 +303,6 @@ __global__ __launch_bounds__((NW + NL) * 64) void k_proj_gemm(GemmArgs p)
     }
     }
 
-    FC_GSTAMP(2);
     // ---- epilogue, in registers.  Lane (col, hi) of sub-tile i holds window row m0 + 32 (wm MW + i) + col;
     // register r of sub-tile t is feature 32 t' + 8 (r >> 2) + 4 hi + (r & 3) of the head, with t' = t
     // for a whole head and {half, half + 2} for a half head.
@@ -485,7 +461,6 @@ __global__ __launch_bounds__((NW + NL) * 64) void k_proj_gemm(GemmArgs p)
             }
         }
     }
-    FC_GSTAMP(4);
 }
 
 template <int KS, int NW, int NSUB, int MW, int NG, int SLOTS, int NL, int EPI = 0>
@@ -569,7 +544,7 @@ struct GemmPiece {
 int plan_pieces(int slots, int M, bool allow_half, GemmPiece out[2])
 {
     out[0] = GemmPiece{pick_shape(slots, M, allow_half), 0, slots, 0, M};
-    static const bool no_split = getenv("FC_GEMM_NO_SPLIT") != nullptr;  // tuning knob
+    const bool no_split = fc_knobs().gemm_no_split != 0;  // tuning knob
     if (out[0].shape != 0 || no_split) return 1;
     const int64_t mt = (M + 255) / 256, tiles = (int64_t)slots * mt, rounds = tiles / 256, rem = tiles % 256;
     if (rounds != 1 || rem == 0 || rem > 160) return 1;
@@ -649,13 +624,11 @@ FcWidePlan fc_plan_wide(int dtype, int mode, int M, int K, int N)
             }
         }
     }
-    if (const char *e = getenv("FC_LIN_WIDE_SHAPE")) {  // tuning knobs
-        const int v = atoi(e);
+    {  // tuning knobs
+        const int v = fc_knobs().lin_wide_shape;
         if (v >= 0 && v <= (mode == FC_LIN_VOCAB ? 1 : 2)) p.shape = v;
-    }
-    if (const char *e = getenv("FC_LIN_KSPLIT")) {
-        const int v = atoi(e);
-        if (v >= 1 && v <= 16 && v <= K / KS_MIN / 4 && mode == FC_LIN_RESIDUAL) p.ksplit = v;
+        const int ks = fc_knobs().lin_ksplit;
+        if (ks >= 1 && ks <= 16 && ks <= K / KS_MIN / 4 && mode == FC_LIN_RESIDUAL) p.ksplit = ks;
     }
     return p;
 }
@@ -688,7 +661,7 @@ hipError_t fc_launch_linear_wide(const FcWidePlan &pl, int mode, const void *x, 
     a.slots_here = a.n_slots;
     a.m_base = 0;
     a.m_end = M;
-    const bool forced = getenv("FC_LIN_WIDE_SHAPE") != nullptr;  // a forced shape is used for the whole problem
+    const bool forced = fc_knobs().lin_wide_shape >= 0;  // a forced shape is used for the whole problem
     if (mode == FC_LIN_VOCAB) {
         if (!am || pl.shape > 1) return hipErrorInvalidValue;
         a.am = *am;
@@ -737,10 +710,6 @@ hipError_t fc_launch_project_gemm(const FcGeom &G, const void *x, const void *w,
     a.N = 0;
     a.ksplit = 1;
     a.log2_base_64 = G.log_base * 1.4426950408889634074 / 64.0;
-#ifdef FC_GEMM_TUNE
-    a.flags = getenv("FC_GEMM_FLAGS") ? atoi(getenv("FC_GEMM_FLAGS")) : 0;
-    a.dbg = getenv("FC_GEMM_DBG_PTR") ? (unsigned long long *)strtoull(getenv("FC_GEMM_DBG_PTR"), nullptr, 0) : nullptr;
-#endif
     // The two 128-row shapes get four extra waves that only issue the loads (their four multiplying
     // waves are alone on their SIMDs); the half-head shape also takes 128 hidden elements per stage.
     auto launch_shape = [&](int shape, const GemmArgs &g) -> hipError_t {
@@ -754,7 +723,7 @@ hipError_t fc_launch_project_gemm(const FcGeom &G, const void *x, const void *w,
     a.slots_here = a.n_slots;
     a.m_base = 0;
     a.m_end = a.M;
-    if (const char *e = getenv("FC_PROJ_GEMM_SHAPE")) return launch_shape(atoi(e), a);  // tuning knob: one shape for all
+    if (fc_knobs().proj_gemm_shape >= 0) return launch_shape(fc_knobs().proj_gemm_shape, a);  // tuning knob: one shape for all
     GemmPiece pc[2];
     const int n = plan_pieces(a.n_slots, a.M, true, pc);
     for (int i = 0; i < n; ++i) {

@@ -35,16 +35,8 @@ struct ProjArgs {
     int M, A, K, win_start, n_tiles;
     double log2_base_64;   // log2(rope_base) / 64
     float *partials;       // cache scratch: partial tiles of the hidden-dimension slices
-#ifdef FC_ATTN_TIMING
-    unsigned long long *dbg;  // tuning builds only
-#endif
 };
 
-#ifdef FC_ATTN_TIMING
-#define FC_PSTAMP(k) do { if (p.dbg && threadIdx.x == 0) p.dbg[(size_t)blockIdx.x * 8 + (k)] = __builtin_readcyclecounter(); } while (0)
-#else
-#define FC_PSTAMP(k) do { } while (0)
-#endif
 
 #ifndef FC_PROJ_VARIANT
 #define FC_PROJ_VARIANT 0  // tuning builds: 1 = no activation loads, 2 = no weight loads
@@ -71,7 +63,6 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(4, 4)))
 {
     __shared__ float red[NW - 1][MT][4][64];
     __shared__ float2 cs[16 * MT][8];  // (cos, sin) for (window row of this chunk, rotary index i0 + e)
-    FC_PSTAMP(0);
     const FcGeom &G = p.G;
     // workgroup id -> (m chunk, n tile): chunks of one n tile have ids equal modulo 8 (same XCD)
     const int tiles8 = (p.n_tiles + 7) & ~7;
@@ -129,10 +120,8 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(4, 4)))
 #pragma unroll
             for (int mt = 0; mt < MT; ++mt) xf[mt][s] = (FC_PROJ_VARIANT == 1) ? wf[s] : ld8(xrow[mt] + 32 * s);
         __builtin_amdgcn_sched_barrier(0);
-        FC_PSTAMP(1);
         rope_table();
         __builtin_amdgcn_sched_barrier(0);
-        FC_PSTAMP(2);
 #pragma unroll
         for (int s = 0; s < H; ++s)
 #pragma unroll
@@ -167,10 +156,8 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(4, 4)))
 #pragma unroll
             for (int r = 0; r < 4; ++r) red[wave - 1][mt][r][lane] = acc[mt][r];
     }
-    FC_PSTAMP(3);
     __syncthreads();
     if (wave > 0) return;
-    FC_PSTAMP(4);
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
@@ -225,7 +212,6 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(4, 4)))
             }
         }
     }
-    FC_PSTAMP(5);
 }
 
 // -------------------------------------------------------------------------------------------------
@@ -441,15 +427,9 @@ hipError_t fc_launch_project_mfma(const FcGeom &G, const double *inv_freq, const
     a.n_tiles = (G.Hq + 2 * G.Hkv) * 8;
     (void)inv_freq;
     a.log2_base_64 = G.log_base * 1.4426950408889634074 / 64.0;
-#ifdef FC_ATTN_TIMING
-    {
-        const char *env = getenv("FC_PROJ_DBG_PTR");
-        a.dbg = env ? (unsigned long long *)strtoull(env, nullptr, 0) : nullptr;
-    }
-#endif
     a.partials = (float *)scratch;
     const int slots = G.Hq + 2 * G.Hkv;
-    static const bool no_headsplit = getenv("FC_PROJ_NO_HEADSPLIT") != nullptr;  // tuning knob
+    const bool no_headsplit = fc_knobs().proj_no_headsplit != 0;  // tuning knob
     if (!no_headsplit && scratch && a.M <= 32 && a.K % HS_K == 0 &&
         (size_t)slots * (a.K / HS_K) * 8 * 2 * 256 * sizeof(float) <= FC_SCRATCH_BYTES) {
         const unsigned grid = (unsigned)(slots * (a.K / HS_K));

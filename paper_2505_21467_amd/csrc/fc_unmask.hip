@@ -457,7 +457,7 @@ __global__ __launch_bounds__(256) void k_gather_rows(const uint4 *__restrict__ t
 // workgroups, 26.6 with 512, 37.5 with 256 for a 32-row block at vocabulary 152064), chunks of whole float4s.
 int fc_accept_parts(int B, int A, int V)
 {
-    static const int target = getenv("FC_ACCEPT_WGS") ? atoi(getenv("FC_ACCEPT_WGS")) : 2048;  // tuning knob
+    const int target = fc_knobs().accept_wgs > 0 ? fc_knobs().accept_wgs : 2048;  // tuning knob
     int64_t parts = (target > 0 ? target : 2048) / ((int64_t)B * A);
     if (parts > 64) parts = 64;
     if (parts > (V + 2047) / 2048) parts = (V + 2047) / 2048;  // at least 2048 entries per part

@@ -27,3 +27,18 @@ def pytest_collection_modifyitems(config, items):
     for item in items:
         if "gpu" in item.keywords:
             item.add_marker(skip)
+
+
+@pytest.fixture()
+def knob():
+    """Set library tuning knobs for one test (fc_tuning_set); every knob set is restored afterwards."""
+    from paper_2505_21467_amd import binding as fc
+    used = []
+
+    def set_knob(name, value):
+        fc.fc_tuning_set(name, value)
+        used.append(name)
+
+    yield set_knob
+    for name in used:
+        fc.fc_tuning_set(name, None)

@@ -140,6 +140,26 @@ def test_workspace_is_demanded_when_the_plan_splits_keys():
         fc.fc_cache_free(h)
 
 
+def test_tuning_knobs_change_the_attention_plan_and_are_restored():
+    c = fc.make_config(1, 1, 3584, 28, 4, 128, 16800, "bf16")
+    base = fc.fc_attention_plan(c, 32, 16800)
+    assert base["kind"] == 1 and base["row_tiles"] == 7 and base["splits"] * base["keys_per_split"] >= 16800
+    assert base["keys_per_split"] % 64 == 0 and (base["splits"] - 1) * base["keys_per_split"] < 16800
+    try:
+        fc.fc_tuning_set("FC_ATTN_TILES", "8,8")
+        fc.fc_tuning_set("FC_ATTN_WGS", 64)
+        forced = fc.fc_attention_plan(c, 32, 16800)
+        assert forced["tiles_per_wg"] == 8 and forced["waves"] == 8 and forced["splits"] < base["splits"]
+        _raises(fc.FC_ERR_INVALID_ARG, fc.fc_tuning_set, "FC_NO_SUCH_KNOB", 1)
+    finally:
+        fc.fc_tuning_set("FC_ATTN_TILES", None)
+        fc.fc_tuning_set("FC_ATTN_WGS", None)
+    assert fc.fc_attention_plan(c, 32, 16800) == base
+    assert fc.fc_attention_plan(fc.make_config(1, 1, 256, 4, 4, 64, 288, "f32"), 32, 288)["kind"] == 0
+    with pytest.raises(fc.FreeCacheError):
+        fc.fc_attention_plan(c, 32, 16801)
+
+
 def test_static_scratch_attention_validates_on_the_host():
     """The entry point that allocates nothing checks its arguments like fc_active_attention and
     refuses, before any HIP call, a shape whose partial results exceed its static array."""

@@ -76,9 +76,9 @@ def test_linear_residual_matches_oracle(dtype, M, K, N, with_res):
 
 
 @pytest.mark.parametrize("wgs", ["3", "100", "1000"])
-def test_linear_residual_any_number_of_workgroups(wgs, monkeypatch):
+def test_linear_residual_any_number_of_workgroups(wgs, knob):
     # the work items are dealt to however many workgroups the plan asks for; runs of every length
-    monkeypatch.setenv("FC_LIN_WGS", wgs)
+    knob("FC_LIN_WGS", wgs)
     M, K, N = 32, 2560, 640
     x = inputs.normal(3, "x", (M, K), 1.0, "bf16")
     w = inputs.normal(3, "w", (N, K), 0.05, "bf16")
@@ -138,9 +138,9 @@ def test_whole_row_kernel_seeded_shape_sweep():
 
 
 @pytest.mark.parametrize("wgs", ["2", "7", "300"])
-def test_whole_row_kernel_any_number_of_workgroups(wgs, monkeypatch):
+def test_whole_row_kernel_any_number_of_workgroups(wgs, knob):
     # runs of 1, 38 and 131 items: the staged outputs of a run are flushed every 16 items and at its end
-    monkeypatch.setenv("FC_LIN_WGS", wgs)
+    knob("FC_LIN_WGS", wgs)
     M, K = 27, 512
     x = inputs.normal(5, "x", (M, K), 1.0, "bf16")
     for gated, N in ((True, 4 * 523), (False, 8 * 523)):
@@ -160,11 +160,11 @@ def test_whole_row_kernel_any_number_of_workgroups(wgs, monkeypatch):
 
 @pytest.mark.parametrize("shape", ["0", "1", "2"])
 @pytest.mark.parametrize("ksplit", ["1", "3"])
-def test_linear_residual_wide_window_tile_shapes(shape, ksplit, monkeypatch):
+def test_linear_residual_wide_window_tile_shapes(shape, ksplit, knob):
     # more than 32 rows: tiled GEMM, every tile shape, with and without a split of the hidden dimension;
     # ragged row count, an odd number of 128-row slabs
-    monkeypatch.setenv("FC_LIN_WIDE_SHAPE", shape)
-    monkeypatch.setenv("FC_LIN_KSPLIT", ksplit)
+    knob("FC_LIN_WIDE_SHAPE", shape)
+    knob("FC_LIN_KSPLIT", ksplit)
     M, K, N = 200, 1024, 384
     x = inputs.normal(12, "x", (M, K), 1.0, "bf16")
     w = inputs.normal(12, "w", (N, K), 0.05, "bf16")
@@ -184,8 +184,8 @@ def test_linear_residual_wide_window_tile_shapes(shape, ksplit, monkeypatch):
 
 
 @pytest.mark.parametrize("shape", ["0", "1", "2"])
-def test_ffn_gate_up_wide_window_tile_shapes(shape, monkeypatch):
-    monkeypatch.setenv("FC_LIN_WIDE_SHAPE", shape)
+def test_ffn_gate_up_wide_window_tile_shapes(shape, knob):
+    knob("FC_LIN_WIDE_SHAPE", shape)
     M, K, F = 100, 1024, 320
     x = inputs.normal(13, "x", (M, K), 1.0, "bf16")
     wg = inputs.normal(13, "wg", (F, K), 0.05, "bf16")

@@ -79,9 +79,9 @@ def test_lm_head_whole_row_kernel_seeded_shape_sweep():
 
 
 @pytest.mark.parametrize("shape", ["0", "1"])
-def test_lm_head_argmax_wide_window(shape, monkeypatch):
+def test_lm_head_argmax_wide_window(shape, knob):
     # more than 32 rows: the tiled GEMM keeps arg-max and confidence per slab in its epilogue
-    monkeypatch.setenv("FC_LIN_WIDE_SHAPE", shape)
+    knob("FC_LIN_WIDE_SHAPE", shape)
     for M, K, V in ((100, 1024, 640), (256, 3584, 2048), (64, 1024, 25600)):  # the last: 200 slabs, 128-row tiles
         x = inputs.normal(23, "x", (M, K), 1.0, "bf16")
         w = inputs.normal(23, "w", (V, K), 0.03, "bf16")
