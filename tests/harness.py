@@ -5,7 +5,8 @@ Tolerances (stated by the benchmark spec for this path): fp32 storage: max-abs 1e-5 and me
 bf16 storage: max-abs 2e-2 and mean-rel 5e-3, where mean-rel = mean|gpu-ref| / mean|ref| over one
 output tensor.  For bf16 values of magnitude >= 4 one unit in the last place is 2^-5 or more, i.e.
 larger than 2e-2, so a rounding decided the other way (fp32 vs fp64 accumulation) cannot meet a
-2e-2 bound; such elements must agree to one bf16 ulp instead.
+2e-2 bound; such elements must agree to one bf16 ulp instead, and at most 2 in 1000 elements of a
+tensor may exceed the plain 2e-2 bound at all (assert_close returns the strict largest error).
 """
 import numpy as np
 import torch
@@ -38,8 +39,33 @@ def assert_close(gpu, ref, dtype, what):
             assert err[~big].max() <= 2e-2, "%s: max-abs %.3e > 2e-2" % (what, err[~big].max())
         if np.any(big):
             assert np.all(err[big] <= bf16_ulp(ref[big])), "%s: large element off by more than 1 ulp" % what
+            # the one-ulp rule is for the rare large element whose rounding fell the other way; it must
+            # not carry a tensor: at most 2 in 1000 elements may be beyond the plain 2e-2 bound
+            over = float(np.mean(err > 2e-2))
+            assert over <= 2e-3, "%s: %.2e of the elements beyond 2e-2 (strict max-abs %.3e)" % (what, over, err.max())
         assert mean_rel <= 5e-3, "%s: mean-rel %.3e > 5e-3" % (what, mean_rel)
     return float(err.max()), mean_rel
+
+
+def assert_chain_close(y, ref, dtype, what):
+    """End-to-end check of the chained modules against the oracle's chain.  Both sides round every
+    tensor that passes from module to module to the storage dtype, so from the attention output on the
+    two chains no longer see identical inputs: roundings decided the other way in o and in the residual
+    stream x2 (about one element in eight at the 7B widths) spread through the feed-forward network as
+    noise of a fraction of a bf16 ulp per output.  The single-module bound therefore holds module by
+    module on identical inputs (checked separately) but not end to end; here the mean relative
+    error keeps its bound, 5e-3, and the largest error gets four times the single-module bound (four
+    roundings to storage lie between the attention output and y), or two ulps for large elements.
+    fp32 keeps the single-module bound."""
+    if dtype == "f32":
+        return assert_close(y, ref, dtype, what)
+    y = np.asarray(y, np.float64)
+    err = np.abs(y - ref)
+    lim = np.maximum(8e-2, 2.0 * bf16_ulp(ref))
+    assert np.all(np.isfinite(y)), what + ": non-finite values"
+    assert np.all(err <= lim), "%s: max-abs %.3e beyond the chained bound" % (what, err.max())
+    mean_rel = float(np.mean(err)) / max(float(np.mean(np.abs(ref))), 1e-30)
+    assert mean_rel <= 5e-3, "%s: mean-rel %.3e > 5e-3" % (what, mean_rel)
 
 
 class GpuLayerCache:

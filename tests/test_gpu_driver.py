@@ -19,7 +19,7 @@ import torch
 from oracle import fc_oracle as orc
 from paper_2505_21467_amd import binding as fc
 from paper_2505_21467_amd import inputs
-from tests.harness import GpuLayerCache
+from tests.harness import GpuLayerCache, assert_chain_close
 
 pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
@@ -66,8 +66,11 @@ def test_decoding_loop_on_a_tiny_model(mode):
     lm_bytes = fc.fc_lm_head_workspace_bytes(dt, B * Bk, d, V)
     lm_ws = torch.empty(lm_bytes, dtype=torch.uint8, device=DEV)
 
-    def forward(win_start, rows):
-        """Embed the window rows and run them through every layer, on both sides; returns (x_gpu, x_oracle)."""
+    def forward(win_start, rows, first_layer_bound=None):
+        """Embed the window rows and run them through every layer, on both sides; returns (x_gpu, x_oracle).
+        first_layer_bound: name of the pass whose first layer sees the same input rows on both sides; its
+        output is then held to the per-tensor bound of a whole layer (largest error and mean relative
+        error), not only to the loose mean used further down the chain."""
         idx = (torch.arange(B, device=DEV)[:, None] * S + win_start + torch.arange(rows, device=DEV)[None, :])
         ids = tok_d.view(-1)[idx.reshape(-1)].contiguous()
         x = torch.empty((B, rows, d), dtype=tdt, device=DEV)
@@ -79,9 +82,17 @@ def test_decoding_loop_on_a_tiny_model(mode):
             fc.fc_full_layer_step(g.handle, layer, handles[layer], x, win_start, rows, None, S, y, ws, ws_bytes)
             x = y
             xo = orc.full_layer_step(ocfg, xo, orc_layers[layer], pos, S, Kc[layer], Vc[layer], eps)
+            if layer == 0 and first_layer_bound:
+                torch.cuda.synchronize()
+                assert_chain_close(inputs.as_oracle(x), xo, dt, first_layer_bound + ", first layer")
         torch.cuda.synchronize()
         return x, xo
 
+    # Past the first layer of a pass the two sides no longer see the same inputs: each feeds its own
+    # rounded hidden states to the next layer and attends over its own cache rows, so differences of
+    # one storage ulp are amplified layer by layer and step by step.  There only a mean bound (four
+    # times the single-tensor one) is applied; the per-tensor bounds are applied where the inputs are
+    # the same (first layer of the initial pass and of step 0) and, op by op, in the other test files.
     def close(gpu, ref, what, mean_rel=2e-2):
         gpu, ref = np.asarray(gpu, np.float64), np.asarray(ref, np.float64)
         assert np.all(np.isfinite(gpu)), what
@@ -89,7 +100,7 @@ def test_decoding_loop_on_a_tiny_model(mode):
         assert err <= mean_rel, "%s: mean-rel %.3e" % (what, err)
 
     # initial pass over prompt + all blocks
-    x, xo = forward(0, S)
+    x, xo = forward(0, S, first_layer_bound="initial pass")
     close(inputs.as_oracle(x), xo, "initial pass output")
     n_blocks, rows_projected = G // Bk, 0
     for step in range(n_blocks * spb):
@@ -102,7 +113,7 @@ def test_decoding_loop_on_a_tiny_model(mode):
         blk = step // spb
         assert win_start == P + blk * Bk
         before_k, before_v = g.snapshot()
-        x, xo = forward(win_start, rows)
+        x, xo = forward(win_start, rows, first_layer_bound="step 0" if step == 0 else None)
         rows_projected += rows
         close(inputs.as_oracle(x), xo, "step %d window output" % step)
         # freeze rule: cache rows before the window are bit-identical, in every layer

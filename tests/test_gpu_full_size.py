@@ -117,42 +117,51 @@ def test_config4_long_context_hundred_steps():
 
 
 def test_config5_one_layer_of_28_cached_step_and_block_refresh():
-    """Layer 27 of a 28-layer, batch-8 cache: one cached step (all sequences against the oracle on a
-    sampled sequence) and the periodic refresh of the generation region."""
+    """Layer 27 of a 28-layer, batch-8 cache: one cached step and the periodic refresh of the
+    generation region, all eight sequences against the oracle (queries, outputs and every written
+    K/V row)."""
     w = inputs.C5
     B, P, G, A = w.batch, w.cached_len, w.gen_len, w.active
     S = P + G
-    layer, b_s = 27, 5  # sampled sequence
-    _say("config5 bf16 B8 28 layers P2048 G256: layer %d, oracle on sequence %d" % (layer, b_s))
+    layer = 27
+    _say("config5 bf16 B8 28 layers P2048 G256: layer %d, oracle on all %d sequences" % (layer, B))
     g = GpuLayerCache(w.dtype, B, w.hidden, w.n_q_heads, w.n_kv_heads, w.head_dim, S, n_layers=w.n_layers,
                       max_rows=G)
-    o = OracleLayerCache(w.dtype, 1, w.hidden, w.n_q_heads, w.n_kv_heads, w.head_dim, S)
+    o = OracleLayerCache(w.dtype, B, w.hidden, w.n_q_heads, w.n_kv_heads, w.head_dim, S)
     K, V = inputs.kv_fill(w, 0, S)  # stands in for the initial full pass
     g.write_rows(layer, K, V, 0)
-    o.write_rows(K[b_s:b_s + 1], V[b_s:b_s + 1], 0)
+    o.write_rows(K, V, 0)
+    Kf, Vf = inputs.as_oracle(K), inputs.as_oracle(V)
     W = inputs.weights(w, 0, layer=layer)
     s = 27  # block 3
     ws, rows, ra = fc.fc_window(s, P, G, w.block, w.steps_per_block, w.refresh_every)
     assert (ws, rows, ra) == (P + 96, 32, 0)
     X = inputs.hidden_states(w, 0, A, tag="x.%d" % s)
     Qg, Og = g.step(layer, X, W, None, ws, S)
-    Qo, Oo = o.step(X[b_s:b_s + 1], W, None, ws, S)
-    assert_close(Qg[b_s:b_s + 1], Qo, w.dtype, "cached Q")
-    assert_close(Og[b_s:b_s + 1], Oo, w.dtype, "cached O")
-    assert np.all(np.isfinite(Og))
+    Qo, Oo = o.step(X, W, None, ws, S)
+    for b in range(B):  # per sequence, so that one bad sequence cannot hide in the mean of eight
+        assert_close(Qg[b], Qo[b], w.dtype, "cached Q, sequence %d" % b)
+        assert_close(Og[b], Oo[b], w.dtype, "cached O, sequence %d" % b)
+    Kg, Vg = g.read_rows(layer, 0, S)
+    outside = np.ones(S, bool)
+    outside[ws:ws + A] = False
+    assert np.array_equal(Kg[:, :, outside], Kf[:, :, outside]) and np.array_equal(Vg[:, :, outside], Vf[:, :, outside])
+    assert_close(Kg[:, :, ws:ws + A], o.Kc[:, :, ws:ws + A], w.dtype, "cached-step K rows")
+    assert_close(Vg[:, :, ws:ws + A], o.Vc[:, :, ws:ws + A], w.dtype, "cached-step V rows")
 
-    _say("  refresh of the generation region [2048, 2304) after step 31")
+    _say("  refresh of the generation region [2048, 2304) after step 31, all sequences")
     assert fc.fc_window(31, P, G, w.block, w.steps_per_block, w.refresh_every)[2] == 1
     Xr = inputs.hidden_states(w, 0, G, tag="x.refresh")
     Qg, Og = g.refresh(layer, Xr, W, None, P, S)
-    Qo, Oo = o.step(Xr[b_s:b_s + 1], W, None, P, S)
-    assert_close(Qg[b_s:b_s + 1], Qo, w.dtype, "refresh Q")
-    assert_close(Og[b_s:b_s + 1], Oo, w.dtype, "refresh O")
+    Qo, Oo = o.step(Xr, W, None, P, S)
+    for b in range(B):
+        assert_close(Qg[b], Qo[b], w.dtype, "refresh Q, sequence %d" % b)
+        assert_close(Og[b], Oo[b], w.dtype, "refresh O, sequence %d" % b)
     Kg, Vg = g.read_rows(layer, 0, S)
-    Kf, Vf = inputs.as_oracle(K), inputs.as_oracle(V)
     assert np.array_equal(Kg[:, :, :P], Kf[:, :, :P]) and np.array_equal(Vg[:, :, :P], Vf[:, :, :P])
-    assert_close(Kg[b_s:b_s + 1, :, P:], o.Kc[:, :, P:], w.dtype, "refresh K rows")
-    assert_close(Vg[b_s:b_s + 1, :, P:], o.Vc[:, :, P:], w.dtype, "refresh V rows")
+    for b in range(B):
+        assert_close(Kg[b, :, P:], o.Kc[b, :, P:], w.dtype, "refresh K rows, sequence %d" % b)
+        assert_close(Vg[b, :, P:], o.Vc[b, :, P:], w.dtype, "refresh V rows, sequence %d" % b)
     K0, V0 = g.read_rows(0, 0, 64)  # other layers untouched
     assert np.all(K0 == 0) and np.all(V0 == 0)
     g.close()

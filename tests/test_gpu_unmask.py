@@ -227,6 +227,26 @@ def test_guided_accept_is_bit_exact(B, A, V, L):
         assert np.array_equal(pn, want[1]) and np.array_equal(cn, want[2])
 
 
+def test_guided_accept_on_probabilities_is_bit_exact():
+    """The same call fed softmax outputs instead of raw logits (what Algorithm 1 calls "logits"):
+    comparisons of given floats, bit-exact against the oracle, threshold on and off."""
+    rng = np.random.default_rng(77)
+    B, A, V, L, MASK = 3, 24, 3000, 40, 200000
+    dlm = rng.normal(0, 3, (B, A, V)).astype(np.float32)
+    ar = (dlm + rng.normal(0, 1.0, (B, A, V))).astype(np.float32)
+    sm = lambda z: torch.softmax(torch.from_numpy(z), dim=-1).numpy()
+    p_dlm, p_ar = sm(dlm), sm(ar)
+    pos = np.stack([np.sort(rng.choice(L, A, replace=False)) for _ in range(B)]).astype(np.int32)
+    tokens = rng.integers(0, V, (B, L)).astype(np.int32)
+    tokens[rng.random((B, L)) < 0.8] = MASK
+    for topk, tau in ((1, 0.0), (2, 0.5), (5, 0.9)):
+        want_t = tokens.copy()
+        want = orc.guided_accept(p_dlm, p_ar, pos, topk, tau, MASK, want_t)
+        got_t, n, pn, cn = _gpu_accept(p_dlm, p_ar, pos, 0, topk, tau, MASK, tokens)
+        assert np.array_equal(got_t, want_t) and np.array_equal(n, want[0])
+        assert np.array_equal(pn, want[1]) and np.array_equal(cn, want[2])
+
+
 def test_guided_accept_until_everything_is_unmasked():
     # Algorithm 1's loop: proposals and guide logits are redrawn each round; every round makes progress
     rng = np.random.default_rng(3)

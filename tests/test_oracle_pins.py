@@ -780,6 +780,39 @@ def test_guided_accept_brute_force():
         assert np.all((n >= 1) | (cnt + n == 0))          # progress whenever something is masked
 
 
+def test_guided_accept_is_agnostic_to_logits_or_probabilities():
+    """Algorithm 1 calls the models' softmax outputs "logits"; the acceptance rule only compares the
+    given floats, so feeding probabilities must work too.  Softmax is monotone within a row, hence
+    arg-max and Top-K membership are the same on either input (threshold off); with the threshold on,
+    the comparison is between probabilities, worked by hand here."""
+    rng = np.random.default_rng(5)
+    MASK, B, A, V, L = 99, 2, 9, 12, 20
+    softmax = lambda z: (np.exp(z - z.max(-1, keepdims=True)) / np.exp(z - z.max(-1, keepdims=True)).sum(-1, keepdims=True))
+    for trial in range(10):
+        # distinct, well separated values per row: no ties appear or vanish under the fp32 softmax
+        dlm = np.stack([[rng.permutation(V) * 0.75 for _ in range(A)] for _ in range(B)]).astype(np.float32)
+        ar = np.stack([[rng.permutation(V) * 0.5 for _ in range(A)] for _ in range(B)]).astype(np.float32)
+        ar[:, ::2] = dlm[:, ::2] * 0.5  # every other row: the guide ranks like the proposal
+        pos = np.tile(np.arange(4, 4 + A, dtype=np.int32), (B, 1))
+        tokens = np.full((B, L), MASK, np.int32)
+        tokens[:, :4] = 1
+        for topk in (1, 2, 3):
+            t1, t2 = tokens.copy(), tokens.copy()
+            r1 = orc.guided_accept(dlm, ar, pos, topk, 0.0, MASK, t1)
+            r2 = orc.guided_accept(softmax(dlm).astype(np.float32), softmax(ar).astype(np.float32), pos, topk, 0.0, MASK, t2)
+            assert np.array_equal(t1, t2) and all(np.array_equal(a, b) for a, b in zip(r1, r2))
+    # threshold on probabilities: both models put their mass on token 2; p_dlm(2) = 0.6, p_ar(2) = 0.9
+    tokens = np.array([[1, MASK, MASK]], np.int32)
+    pos = np.array([[1, 2]], np.int32)
+    p_dlm = np.array([[[0.1, 0.3, 0.6], [0.1, 0.3, 0.6]]], np.float32)
+    p_ar = np.array([[[0.04, 0.06, 0.9], [0.04, 0.06, 0.9]]], np.float32)
+    t = tokens.copy()
+    assert orc.guided_accept(p_dlm, p_ar, pos, 1, 0.5, MASK, t)[0][0] == 2     # 0.6 > 0.45: both rows accepted
+    t = tokens.copy()
+    n, _, _ = orc.guided_accept(p_dlm, p_ar, pos, 1, 0.7, MASK, t)             # 0.6 < 0.63: fallback, first row only
+    assert n[0] == 1 and list(t[0]) == [1, 2, MASK]
+
+
 # --------------------------------------------------------------------------- KV drift diagnostic
 
 def test_kv_similarity_closed_forms_and_library_formula():
