@@ -76,12 +76,12 @@ MEASURED_LM_HEAD_TRAFFIC_BYTES = {(32, 3584, 152064): 1_092_040_000}
 # whose planner picks another plan reports null instead.
 MEASURED_ATTENTION_TRAFFIC = {
     "c4_dream7b_long_L16384_A32": {
-        "bytes": 54_380_000,   # 36.45 MB read + 7.31 MB written (main kernel), 10.39 + 0.23 MB (merge)
+        "bytes": 53_010_000,   # 35.08 MB read + 7.31 MB written (main kernel), 10.39 + 0.23 MB (merge)
         "plan": {"kind": 1, "splits": 30, "keys_per_split": 576, "tiles_per_wg": 4, "waves": 8},
         "kernels": "k_attn_mfma<1,8,2> + k_attn_combine<8,4>",
         "profile": "profiles/c4_long_context_layer_step.md"},
     "c3_llada8b_B4_L4096_A64": {
-        "bytes": 289_900_000,  # 277.0 + 4.46 MB, 6.35 + 2.10 MB
+        "bytes": 287_800_000,  # 274.9 + 4.46 MB, 6.34 + 2.10 MB
         "plan": {"kind": 1, "splits": 2, "keys_per_split": 2112, "tiles_per_wg": 2, "waves": 8},
         "kernels": "k_attn_mfma<1,8,4> + k_attn_combine<2,1>",
         "profile": "profiles/other_workloads_layer_step.md"},
