@@ -110,10 +110,19 @@ __global__ __launch_bounds__((NW + NL) * 64) void k_proj_gemm(GemmArgs p)
     constexpr int WROWS = 32 * NSUB * NG, XROWS = 32 * MW * WM;
     constexpr int WBYTES = WROWS * ROWB, STAGE = (WROWS + XROWS) * ROWB;
     constexpr int NBLK = (WROWS + XROWS) / RPB;  // 1 KB blocks per stage
-    constexpr int LBW = NBLK / NLW;            // blocks per loading wave and stage
-    constexpr int WBW = (WROWS / RPB) / NLW;   // of which weight blocks (the first ones)
+    // NSUB = 5 ("dealt pairs", EPI 0 and 2 only): the workgroup takes 80 consecutive PAIRS of weight rows
+    // -- rotary pairs (i, i + 64) of the head slots laid end to end, or (gate row, up row) pairs -- 16
+    // pairs per sub-tile: the low rows in rows 0..15 of the sub-tile, the high rows in rows 16..31, so
+    // that the two members of a pair sit in one lane, registers r and r + 8.  The 52 blocks of a stage
+    // do not divide by the eight waves: waves 0..3 issue seven loads per stage, waves 4..7 six.
+    constexpr bool DEALT = NSUB == 5;
+    constexpr int WBLK = WROWS / RPB;          // weight blocks of a stage (the first ones)
+    constexpr int LBW = (NBLK + NLW - 1) / NLW;  // blocks per loading wave and stage (DEALT: at most)
+    constexpr int WBW = WBLK / NLW;            // of which weight blocks (not DEALT)
     static_assert(KS == 64 || KS == 128, "stage depth");
-    static_assert(NW % NG == 0 && NBLK % NLW == 0 && (WROWS / RPB) % NLW == 0 && (NSUB == 4 || NG == 1), "tile shape");
+    static_assert(NW % NG == 0 && (DEALT || (NBLK % NLW == 0 && WBLK % NLW == 0)) && (NSUB >= 4 || NG == 1), "tile shape");
+    static_assert(!DEALT || ((EPI == 0 || EPI == 2) && NG == 1 && NL == 0 && KS == 64 && NBLK - (LBW - 1) * NLW == NLW / 2),
+                  "dealt pairs: QKV or gated epilogue, every wave loads");
     static_assert((SLOTS - 1) * LBW < 64 && SLOTS >= 2 && SLOTS <= 4, "vmcnt range");
     static_assert(EPI == 0 || NG == 1, "the plain linear layers use one slab per workgroup");
     extern __shared__ __align__(1024) unsigned char smem[];
@@ -142,22 +151,29 @@ __global__ __launch_bounds__((NW + NL) * 64) void k_proj_gemm(GemmArgs p)
     const bool is_loader = NL > 0 && wave >= NW;  // wave-uniform
     const int lw = NL > 0 ? wave - NW : wave;     // index among the loading waves
     const int wn = (wave % NW) / WM, wm = wave % WM;  // this wave's head group and row group
-    const int hs = p.slot_base + (NSUB == 4 ? unit * NG + wn : unit >> 1);
-    const int half = NSUB == 4 ? 0 : unit & 1;  // which rotary-paired half of the head
-    const bool head_valid = hs < n_slots;       // an odd number of heads leaves the last pair half empty
+    const int hs = p.slot_base + (NSUB >= 4 ? unit * NG + wn : unit >> 1);  // (DEALT: not used)
+    const int half = NSUB >= 4 ? 0 : unit & 1;  // which rotary-paired half of the head
+    const bool head_valid = DEALT || hs < n_slots;  // an odd number of heads leaves the last pair half empty
+    const int n_pairs = n_slots * 64;           // DEALT: pairs of the whole problem
+    const int my_blocks = DEALT && lw >= NLW / 2 ? LBW - 1 : LBW;  // wave-uniform
 
     // ---- loader: per-lane source offsets (bytes from W / X, hidden offset 0) of this wave's blocks
     uint32_t goff[LBW];
 #pragma unroll
     for (int i = 0; i < LBW; ++i) {
         const int bid = lw + NLW * i;               // block of the stage: weight blocks first (junk for lw < 0)
-        const int rl = RPB * (i < WBW ? bid : bid - WROWS / RPB) + lane / CPR;  // row of the W / X tile
+        const bool is_w = DEALT ? bid < WBLK : i < WBW;
+        const int rl = RPB * (is_w ? bid : bid - WBLK) + lane / CPR;  // row of the W / X tile
         // logical 16-byte chunk that lands at position lane % CPR of the row piece: 128-byte pieces are
         // swizzled with bits 1..3 of the row, 256-byte pieces with bits 0..3
         const int c = (lane % CPR) ^ (KS == 64 ? (rl >> 1) & 7 : rl & 15);
-        if (i < WBW) {
+        if (is_w) {
             int n;
-            if (EPI == 2) {  // row of the gate or of the up matrix (which of the two: see issue_stage)
+            if (DEALT) {
+                const int pr = min(80 * unit + 16 * (rl >> 5) + (rl & 15), n_pairs - 1);  // pairs past the end are never stored
+                if (EPI == 2) n = pr;  // row pr of the gate matrix (low) or of the up matrix (high)
+                else n = (pr >> 6) * 128 + (pr & 63) + ((rl & 16) ? 64 : 0);
+            } else if (EPI == 2) {  // row of the gate or of the up matrix (which of the two: see issue_stage)
                 const int u = min(hs, n_slots - 1);  // NG = 1 here: hs is the slab of the whole workgroup
                 n = u * 64 + (NSUB == 4 ? rl & 63 : 32 * half + (rl & 31));
             } else if (NSUB == 4) {
@@ -183,8 +199,13 @@ __global__ __launch_bounds__((NW + NL) * 64) void k_proj_gemm(GemmArgs p)
 #pragma unroll
         for (int i = 0; i < LBW; ++i) {
             if (part >= 0 && (i & 3) != part) continue;
+            if (DEALT && i >= my_blocks) continue;
             const uint16_t *mat = p.X;
-            if (i < WBW) {
+            if (DEALT) {
+                // rows 16..31 of a sub-tile (blocks 2, 3 of every four) are the high rows: EPI 2 takes them from the up matrix
+                const int bid = lw + NLW * i;
+                if (bid < WBLK) mat = (EPI == 2 && (bid & 2)) ? p.W2 : p.W;
+            } else if (i < WBW) {
                 // EPI 2: the second half of the tile rows (a whole number of 1 KB blocks) is the up matrix
                 const bool up = EPI == 2 && RPB * (lw + NLW * i) >= (NSUB == 4 ? 64 : 32);
                 mat = up ? p.W2 : p.W;
@@ -270,7 +291,8 @@ __global__ __launch_bounds__((NW + NL) * 64) void k_proj_gemm(GemmArgs p)
         }
     } else {
     for (int st = 0; st < n_pro; ++st) issue_stage(st, -1);
-    wait_stages<LBW, false>(n_pro - 1);
+    if (my_blocks == LBW) wait_stages<LBW, false>(n_pro - 1);
+    else wait_stages<LBW - 1, false>(n_pro - 1);
     __builtin_amdgcn_s_barrier();  // stage 0 is complete for every wave
     read_frags(0, 0, 0);
     int slot = 0;
@@ -291,7 +313,8 @@ __global__ __launch_bounds__((NW + NL) * 64) void k_proj_gemm(GemmArgs p)
         if (it + 1 < n_stages) {
             // This wave's reads of stage `it` have all returned (lgkmcnt 0); behind the barrier that
             // holds for every wave, and stage it+1 is complete (later stages may still be in flight).
-            wait_stages<LBW, true>(min(n_stages, it + SLOTS) - (it + 2));
+            if (my_blocks == LBW) wait_stages<LBW, true>(min(n_stages, it + SLOTS) - (it + 2));
+            else wait_stages<LBW - 1, true>(min(n_stages, it + SLOTS) - (it + 2));
             __builtin_amdgcn_s_barrier();
             if (it + SLOTS < n_stages) issue_stage(it + SLOTS, 0);
             read_frags(nslot, 0, 0);
@@ -342,6 +365,34 @@ __global__ __launch_bounds__((NW + NL) * 64) void k_proj_gemm(GemmArgs p)
         }
         return;
     }
+    if (DEALT && EPI == 2) {
+        // Gated layer, dealt pairs: registers 4 rq + e (gate) and 8 + 4 rq + e (up), rq < 2, of sub-tile t
+        // are output column 80 unit + 16 t + 8 rq + 4 hi + e.
+#pragma unroll
+        for (int i = 0; i < MW; ++i) {
+            const int m = m0 + 32 * (wm * MW + i) + col;
+            if (m >= p.m_end) continue;
+#pragma unroll
+            for (int t = 0; t < NSUB; ++t) {
+                const int base = 80 * unit + 16 * t;
+                if (base >= n_pairs) continue;
+#pragma unroll
+                for (int rq = 0; rq < 2; ++rq) {
+                    float y[4];
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        const float g = acc[i][t][4 * rq + e];
+                        y[e] = g / (1.0f + expf(-g)) * acc[i][t][8 + 4 * rq + e];
+                    }
+                    uint2 w;
+                    w.x = (uint32_t)fc_bf16_bits(y[0]) | ((uint32_t)fc_bf16_bits(y[1]) << 16);
+                    w.y = (uint32_t)fc_bf16_bits(y[2]) | ((uint32_t)fc_bf16_bits(y[3]) << 16);
+                    *(uint2 *)(p.out + (size_t)m * p.N + base + 8 * rq + 4 * hi) = w;
+                }
+            }
+        }
+        return;
+    }
     if (EPI != 0) {
         // Plain linear layers.  Register r of sub-tile t of lane (col, hi) is output column
         // 32 t' + 8 (r >> 2) + 4 hi + (r & 3) of the slab (of its 64 outputs for EPI 2, t' < 2).
@@ -381,11 +432,81 @@ __global__ __launch_bounds__((NW + NL) * 64) void k_proj_gemm(GemmArgs p)
         }
         return;
     }
-    const bool rotate = hs < G.Hq + G.Hkv;
-    constexpr int NP = NSUB / 2;  // rotary pairs of sub-tiles: (t, t + NP)
     // base^(-1/64) and its powers; base^(-i/64) / (2 pi) = turns per position of pair i
     const double r1 = exp2(-p.log2_base_64);
     const double r2 = r1 * r1, r4 = r2 * r2, r8 = r4 * r4, r16 = r8 * r8, r32 = r16 * r16;
+    if (DEALT) {
+        // Dealt pairs: sub-tile t holds the 16 rotary pairs ib .. ib + 15 of head slot hs_t; registers
+        // 4 rq + e (feature ib + 8 rq + 4 hi + e) and 8 + 4 rq + e (the same + 64), rq < 2.
+#pragma unroll
+        for (int i = 0; i < MW; ++i) {
+            const int m = m0 + 32 * (wm * MW + i) + col;
+            const bool mvalid = m < p.m_end;
+            const int mm = mvalid ? m : 0;
+            const int b = mm / p.A, a = mm - b * p.A;
+            const int pp = p.pos ? p.pos[mm] : p.win_start + a;
+            const bool valid = mvalid && pp >= 0 && pp < G.max_seq;
+#pragma unroll
+            for (int t = 0; t < NSUB; ++t) {
+                const int base = 80 * unit + 16 * t;
+                if (base >= n_pairs) continue;  // workgroup-uniform
+                const int hs_t = base >> 6, ib = base & 63;
+                if (p.bias) {
+#pragma unroll
+                    for (int r = 0; r < 16; ++r)
+                        acc[i][t][r] += fc_to_float(
+                            bf16_t{p.bias[hs_t * 128 + ib + 8 * ((r >> 2) & 1) + 4 * hi + (r & 3) + 64 * (r >> 3)]});
+                }
+                if (hs_t < G.Hq + G.Hkv) {
+                    double f = 0.15915494309189533576888;
+                    if (ib & 16) f *= r16;
+                    if (ib & 32) f *= r32;
+                    if (hi) f *= r4;
+#pragma unroll
+                    for (int rq = 0; rq < 2; ++rq) {
+                        double fr = f;
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) {
+                            const int r = 4 * rq + e;
+                            const double turns = (double)pp * fr;
+                            const float ph = (float)(turns - rint(turns));
+                            const float c = __builtin_amdgcn_cosf(ph), sn = __builtin_amdgcn_sinf(ph);
+                            const float lo = acc[i][t][r], hi2 = acc[i][t][r + 8];
+                            acc[i][t][r] = lo * c - hi2 * sn;
+                            acc[i][t][r + 8] = hi2 * c + lo * sn;
+                            fr *= r1;
+                        }
+                        f *= r8;
+                    }
+                }
+                if (!mvalid) continue;
+#pragma unroll
+                for (int rq4 = 0; rq4 < 4; ++rq4) {
+                    const int d0 = ib + 8 * (rq4 & 1) + 4 * hi + 64 * (rq4 >> 1);
+                    uint2 w;
+                    w.x = (uint32_t)fc_bf16_bits(acc[i][t][4 * rq4]) | ((uint32_t)fc_bf16_bits(acc[i][t][4 * rq4 + 1]) << 16);
+                    w.y = (uint32_t)fc_bf16_bits(acc[i][t][4 * rq4 + 2]) | ((uint32_t)fc_bf16_bits(acc[i][t][4 * rq4 + 3]) << 16);
+                    if (hs_t < G.Hq) {
+                        if (!valid) w = make_uint2(0, 0);
+                        *(uint2 *)(p.Q + (((size_t)b * G.Hq + hs_t) * p.A + a) * 128 + d0) = w;
+                    } else if (valid) {
+                        if (hs_t < G.Hq + G.Hkv) {
+                            *(uint2 *)(p.Kc + fc_k_index(G, b, hs_t - G.Hq, pp, d0)) = w;
+                        } else {
+                            uint16_t *v = p.Vc + fc_v_index(G, b, hs_t - G.Hq - G.Hkv, pp, d0);
+                            v[0] = (uint16_t)(w.x & 0xffff);
+                            v[FC_VTILE] = (uint16_t)(w.x >> 16);
+                            v[2 * FC_VTILE] = (uint16_t)(w.y & 0xffff);
+                            v[3 * FC_VTILE] = (uint16_t)(w.y >> 16);
+                        }
+                    }
+                }
+            }
+        }
+        return;
+    }
+    const bool rotate = hs < G.Hq + G.Hkv;
+    constexpr int NP = NSUB / 2;  // rotary pairs of sub-tiles: (t, t + NP)
 
 #pragma unroll
     for (int i = 0; i < MW; ++i) {
@@ -473,7 +594,8 @@ hipError_t launch_gemm(GemmArgs a, hipStream_t s)
                                                  hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
     if (attr != hipSuccess) return attr;
     const int slots = a.slots_here;
-    a.n_units = NSUB == 4 ? (slots + NG - 1) / NG : 2 * slots;
+    a.n_units = NSUB == 5 ? (a.n_slots * 64 + 79) / 80 : NSUB == 4 ? (slots + NG - 1) / NG : 2 * slots;
+    if (NSUB == 5 && (a.slot_base != 0 || slots != a.n_slots)) return hipErrorInvalidValue;  // dealt pairs cover every slab
     a.n_mt = (a.m_end - a.m_base + XROWS - 1) / XROWS;
     if (slots < 1 || a.n_mt < 1 || a.slot_base < 0 || a.slot_base + slots > a.n_slots || a.m_base < 0 || a.m_end > a.M)
         return hipErrorInvalidValue;
@@ -514,6 +636,10 @@ __global__ __launch_bounds__(256) void k_splitk_finish(const float *__restrict__
 template <int EPI>
 hipError_t launch_wide_shape(int shape, const GemmArgs &a, hipStream_t s)
 {
+    if (shape == 4) {  // 256 rows x 80 dealt pairs (gated layer only)
+        if constexpr (EPI == 2) return launch_gemm<64, 8, 5, 1, 1, 3, 0, EPI>(a, s);
+        else return hipErrorInvalidValue;
+    }
     if (shape == 0) return launch_gemm<64, 8, 4, 1, 1, 3, 0, EPI>(a, s);  // 256 rows x slab
     if (shape == 1) return launch_gemm<64, 4, 4, 1, 1, 4, 4, EPI>(a, s);  // 128 rows x slab
     return launch_gemm<64, 4, 2, 1, 1, 4, 4, EPI>(a, s);                  // 128 rows x half slab
@@ -541,13 +667,21 @@ int pick_shape(int64_t slots, int64_t rows, bool allow_half)
 struct GemmPiece {
     int shape, slot_base, slots, m_base, m_end;
 };
-int plan_pieces(int slots, int M, bool allow_half, GemmPiece out[2])
+int plan_pieces(int slots, int M, bool allow_half, bool allow_dealt, GemmPiece out[2])
 {
     out[0] = GemmPiece{pick_shape(slots, M, allow_half), 0, slots, 0, M};
     const bool no_split = fc_knobs().gemm_no_split != 0;  // tuning knob
     if (out[0].shape != 0 || no_split) return 1;
     const int64_t mt = (M + 255) / 256, tiles = (int64_t)slots * mt, rounds = tiles / 256, rem = tiles % 256;
     if (rounds != 1 || rem == 0 || rem > 160) return 1;
+    // Layers whose weight rows come in pairs (rotary pairs, gate and up rows) have a fifth shape, 256
+    // rows x 80 dealt pairs: a quarter more work per workgroup, so up to 320 tiles of the 256-row shape
+    // still make one round, in one launch (36 head slots x 8 row tiles: 89.5 -> 82.5 us; 296 gated slabs
+    // x 256 rows: 98.5 -> 88.5 us).
+    if (allow_dealt && (((int64_t)slots * 64 + 79) / 80) * mt <= 256) {
+        out[0].shape = 4;
+        return 1;
+    }
     if (mt == 1) {
         out[0].slots = 256;
         out[1] = GemmPiece{pick_shape(slots - 256, M, allow_half), 256, slots - 256, 0, M};
@@ -564,7 +698,7 @@ template <int EPI>
 hipError_t launch_pieces(GemmArgs a, bool allow_half, hipStream_t s)
 {
     GemmPiece pc[2];
-    const int n = plan_pieces(a.n_slots, a.M, allow_half, pc);
+    const int n = plan_pieces(a.n_slots, a.M, allow_half, EPI == 2, pc);
     for (int i = 0; i < n; ++i) {
         a.slot_base = pc[i].slot_base;
         a.slots_here = pc[i].slots;
@@ -626,7 +760,7 @@ FcWidePlan fc_plan_wide(int dtype, int mode, int M, int K, int N)
     }
     {  // tuning knobs
         const int v = fc_knobs().lin_wide_shape;
-        if (v >= 0 && v <= (mode == FC_LIN_VOCAB ? 1 : 2)) p.shape = v;
+        if ((v >= 0 && v <= (mode == FC_LIN_VOCAB ? 1 : 2)) || (v == 4 && mode == FC_LIN_GATE_UP)) p.shape = v;
         const int ks = fc_knobs().lin_ksplit;
         if (ks >= 1 && ks <= 16 && ks <= K / KS_MIN / 4 && mode == FC_LIN_RESIDUAL) p.ksplit = ks;
     }
@@ -713,6 +847,7 @@ hipError_t fc_launch_project_gemm(const FcGeom &G, const void *x, const void *w,
     // The two 128-row shapes get four extra waves that only issue the loads (their four multiplying
     // waves are alone on their SIMDs); the half-head shape also takes 128 hidden elements per stage.
     auto launch_shape = [&](int shape, const GemmArgs &g) -> hipError_t {
+        if (shape == 4) return launch_gemm<64, 8, 5, 1, 1, 3, 0>(g, s);   // 256 rows x 80 dealt rotary pairs
         if (shape == 3) return launch_gemm<64, 8, 4, 2, 2, 2, 0>(g, s);   // 256 rows x two heads
         if (shape == 0) return launch_gemm<64, 8, 4, 1, 1, 3, 0>(g, s);   // 256 rows x head
         if (shape == 1) return launch_gemm<64, 4, 4, 1, 1, 4, 4>(g, s);   // 128 rows x head
@@ -725,7 +860,7 @@ hipError_t fc_launch_project_gemm(const FcGeom &G, const void *x, const void *w,
     a.m_end = a.M;
     if (fc_knobs().proj_gemm_shape >= 0) return launch_shape(fc_knobs().proj_gemm_shape, a);  // tuning knob: one shape for all
     GemmPiece pc[2];
-    const int n = plan_pieces(a.n_slots, a.M, true, pc);
+    const int n = plan_pieces(a.n_slots, a.M, true, true, pc);
     for (int i = 0; i < n; ++i) {
         a.slot_base = pc[i].slot_base;
         a.slots_here = pc[i].slots;

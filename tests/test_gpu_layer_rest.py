@@ -183,7 +183,7 @@ def test_linear_residual_wide_window_tile_shapes(shape, ksplit, knob):
     assert torch.equal(rd, out)
 
 
-@pytest.mark.parametrize("shape", ["0", "1", "2"])
+@pytest.mark.parametrize("shape", ["0", "1", "2", "4"])
 def test_ffn_gate_up_wide_window_tile_shapes(shape, knob):
     knob("FC_LIN_WIDE_SHAPE", shape)
     M, K, F = 100, 1024, 320
@@ -199,10 +199,12 @@ def test_ffn_gate_up_wide_window_tile_shapes(shape, knob):
     assert_close(inputs.as_oracle(out), ref, "bf16", "wide ffn_gate_up shape " + shape)
 
 
-def test_wide_linear_layers_cut_into_two_launches():
-    # 260 slabs x one row tile of the 256-row shape are 260 workgroups: 256 slabs run in that shape, the
-    # last 4 in a second launch with a smaller tile; both modes, every output checked
-    M, K = 100, 256
+def test_wide_linear_layers_of_a_little_more_than_one_round():
+    # 260 slabs x one row tile of the 256-row shape are 260 workgroups, a little more than one per compute
+    # unit.  The plain layer is cut in two launches (256 slabs in that shape, the last 4 with a smaller
+    # tile); the gated layer takes the shape of 80 dealt (gate, up) pairs in one launch, and with 330 slabs,
+    # too many for that, two launches again.  Every output checked.
+    M, K = 200, 256
     x = inputs.normal(15, "x", (M, K), 1.0, "bf16")
     N = 128 * 260
     w = inputs.normal(15, "w", (N, K), 0.05, "bf16")
@@ -213,14 +215,15 @@ def test_wide_linear_layers_cut_into_two_launches():
     torch.cuda.synchronize()
     assert_close(inputs.as_oracle(out), orc.linear_residual(inputs.as_oracle(x), inputs.as_oracle(w), inputs.as_oracle(r),
                                                             "bf16"), "bf16", "two-launch linear_residual")
-    F = 64 * 260
-    wg = inputs.normal(15, "wg", (F, K), 0.05, "bf16")
-    wu = inputs.normal(15, "wu", (F, K), 0.05, "bf16")
-    act = torch.full((M, F), float("nan"), dtype=torch.bfloat16, device=DEV)
-    fc.fc_ffn_gate_up("bf16", _dev(x), _dev(wg), _dev(wu), M, K, F, act, None, 0)
-    torch.cuda.synchronize()
-    assert_close(inputs.as_oracle(act), orc.ffn_gate_up(inputs.as_oracle(x), inputs.as_oracle(wg), inputs.as_oracle(wu),
-                                                        "bf16"), "bf16", "two-launch ffn_gate_up")
+    for slabs in (260, 330):
+        F = 64 * slabs
+        wg = inputs.normal(15, "wg%d" % slabs, (F, K), 0.05, "bf16")
+        wu = inputs.normal(15, "wu%d" % slabs, (F, K), 0.05, "bf16")
+        act = torch.full((M, F), float("nan"), dtype=torch.bfloat16, device=DEV)
+        fc.fc_ffn_gate_up("bf16", _dev(x), _dev(wg), _dev(wu), M, K, F, act, None, 0)
+        torch.cuda.synchronize()
+        assert_close(inputs.as_oracle(act), orc.ffn_gate_up(inputs.as_oracle(x), inputs.as_oracle(wg), inputs.as_oracle(wu),
+                                                            "bf16"), "bf16", "ffn_gate_up, %d slabs" % slabs)
 
 
 def test_linear_calls_default_plan_at_block_widths():
