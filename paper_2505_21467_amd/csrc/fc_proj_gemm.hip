@@ -9,6 +9,9 @@
 // register), with NSUB = 2 it covers the rotary-paired half head {32 h .. 32 h + 31} u {64 + 32 h ..}
 // (more, smaller workgroups when the window is too short to fill the chip).  The rotation, the bias and
 // the stores to q_out / the K rows / the transposed V tiles therefore need no exchange between lanes.
+// A fifth shape (NSUB = 5) deals the rotary pairs of all head slots, laid end to end, 80 to a workgroup
+// (16 per sub-tile, low rows then high rows: the partner of register r is register r + 8): a quarter more
+// work per workgroup than a head, for grids that would otherwise be a little more than one round.
 //
 // Both operands are contiguous along the hidden dimension.  64 (or 128) hidden elements of every row
 // of the tile (128- or 256-byte row pieces) stream HBM/L2 -> LDS with direct-to-LDS 16-byte loads into
@@ -107,7 +110,8 @@ __global__ __launch_bounds__((NW + NL) * 64) void k_proj_gemm(GemmArgs p)
     constexpr int NKK = KS / 16;               // k-steps per stage
     constexpr int WM = NW / NG;
     constexpr int NLW = NL > 0 ? NL : NW;      // waves that issue loads
-    constexpr int WROWS = 32 * NSUB * NG, XROWS = 32 * MW * WM;
+    constexpr bool DEALT = NSUB == 5;
+    constexpr int WROWS = DEALT ? 160 : 32 * NSUB * NG, XROWS = 32 * MW * WM;
     constexpr int WBYTES = WROWS * ROWB, STAGE = (WROWS + XROWS) * ROWB;
     constexpr int NBLK = (WROWS + XROWS) / RPB;  // 1 KB blocks per stage
     // NSUB = 5 ("dealt pairs", EPI 0 and 2 only): the workgroup takes 80 consecutive PAIRS of weight rows
@@ -115,16 +119,21 @@ __global__ __launch_bounds__((NW + NL) * 64) void k_proj_gemm(GemmArgs p)
     // pairs per sub-tile: the low rows in rows 0..15 of the sub-tile, the high rows in rows 16..31, so
     // that the two members of a pair sit in one lane, registers r and r + 8.  The 52 blocks of a stage
     // do not divide by the eight waves: waves 0..3 issue seven loads per stage, waves 4..7 six.
-    constexpr bool DEALT = NSUB == 5;
+    // With NG = 2 the five sub-tiles are split between the two waves of a SIMD (sub-tiles 0..2 and 3..4),
+    // each wave taking MW = 2 row sub-tiles: the pair of waves reads 5 + 4 fragments for its 6 + 4
+    // multiplies of a k-step instead of 2 x 6 for 2 x 5 with 32-row waves (same time measured, less LDS
+    // traffic).
+    constexpr int NT = DEALT ? (NG == 2 ? 3 : 5) : NSUB;  // sub-tiles a wave owns (at most)
     constexpr int WBLK = WROWS / RPB;          // weight blocks of a stage (the first ones)
     constexpr int LBW = (NBLK + NLW - 1) / NLW;  // blocks per loading wave and stage (DEALT: at most)
     constexpr int WBW = WBLK / NLW;            // of which weight blocks (not DEALT)
     static_assert(KS == 64 || KS == 128, "stage depth");
     static_assert(NW % NG == 0 && (DEALT || (NBLK % NLW == 0 && WBLK % NLW == 0)) && (NSUB >= 4 || NG == 1), "tile shape");
-    static_assert(!DEALT || ((EPI == 0 || EPI == 2) && NG == 1 && NL == 0 && KS == 64 && NBLK - (LBW - 1) * NLW == NLW / 2),
-                  "dealt pairs: QKV or gated epilogue, every wave loads");
+    static_assert(!DEALT || ((EPI == 0 || EPI == 2) && (NG == 1 || NG == 2) && KS == 64 &&
+                             (NL == 0 ? NBLK - (LBW - 1) * NLW == NLW / 2 : NBLK % NLW == 0)),
+                  "dealt pairs: QKV or gated epilogue");
     static_assert((SLOTS - 1) * LBW < 64 && SLOTS >= 2 && SLOTS <= 4, "vmcnt range");
-    static_assert(EPI == 0 || NG == 1, "the plain linear layers use one slab per workgroup");
+    static_assert(EPI == 0 || NG == 1 || DEALT, "the plain linear layers use one slab per workgroup");
     extern __shared__ __align__(1024) unsigned char smem[];
     const FcGeom &G = p.G;
 
@@ -155,7 +164,9 @@ __global__ __launch_bounds__((NW + NL) * 64) void k_proj_gemm(GemmArgs p)
     const int half = NSUB >= 4 ? 0 : unit & 1;  // which rotary-paired half of the head
     const bool head_valid = DEALT || hs < n_slots;  // an odd number of heads leaves the last pair half empty
     const int n_pairs = n_slots * 64;           // DEALT: pairs of the whole problem
-    const int my_blocks = DEALT && lw >= NLW / 2 ? LBW - 1 : LBW;  // wave-uniform
+    const int my_blocks = DEALT && NL == 0 && lw >= NLW / 2 ? LBW - 1 : LBW;  // wave-uniform
+    const int t0 = DEALT && NG == 2 && wn ? 3 : 0;        // DEALT: first sub-tile of this wave
+    const int nt_mine = DEALT && NG == 2 && wn ? 2 : NT;  // and how many it owns (wave-uniform)
 
     // ---- loader: per-lane source offsets (bytes from W / X, hidden offset 0) of this wave's blocks
     uint32_t goff[LBW];
@@ -220,34 +231,36 @@ __global__ __launch_bounds__((NW + NL) * 64) void k_proj_gemm(GemmArgs p)
 #pragma unroll
     for (int kk = 0; kk < NKK; ++kk)
         foff[kk] = (uint32_t)(col * ROWB + (((2 * kk + hi) ^ (KS == 64 ? (col >> 1) & 7 : col & 15)) << 4));
-    const uint32_t w_base = (uint32_t)(wn * NSUB * 32 * ROWB);
+    const uint32_t w_base = (uint32_t)((DEALT ? t0 : wn * NSUB) * 32 * ROWB);
     const uint32_t x_base = (uint32_t)(WBYTES + wm * MW * 32 * ROWB);
 
-    f32x16 acc[MW][NSUB];
+    f32x16 acc[MW][NT];
 #pragma unroll
     for (int i = 0; i < MW; ++i)
 #pragma unroll
-        for (int t = 0; t < NSUB; ++t)
+        for (int t = 0; t < NT; ++t)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][t][r] = 0.f;
 
     // Fragments are double-buffered in registers: the LDS reads of k-step kk+1 are issued before the
     // multiplies of k-step kk, and the first reads of the next stage go out (behind that stage's
     // barrier) before the last multiplies of this one, so the matrix core never waits for LDS.
-    bf16x8 xf[2][MW], wf[2][NSUB];
+    bf16x8 xf[2][MW], wf[2][NT];
     auto read_frags = [&](int slot, int kk, int buf) {
         const unsigned char *st = smem + slot * STAGE;
 #pragma unroll
         for (int i = 0; i < MW; ++i) xf[buf][i] = *(const bf16x8 *)(st + x_base + i * (32 * ROWB) + foff[kk]);
 #pragma unroll
-        for (int t = 0; t < NSUB; ++t) wf[buf][t] = *(const bf16x8 *)(st + w_base + t * (32 * ROWB) + foff[kk]);
+        for (int t = 0; t < NT; ++t)
+            if (t < nt_mine) wf[buf][t] = *(const bf16x8 *)(st + w_base + t * (32 * ROWB) + foff[kk]);
     };
     auto multiply = [&](int buf) {
 #pragma unroll
         for (int i = 0; i < MW; ++i)
 #pragma unroll
-            for (int t = 0; t < NSUB; ++t)
-                acc[i][t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[buf][t], xf[buf][i], acc[i][t], 0, 0, 0);
+            for (int t = 0; t < NT; ++t)
+                if (t < nt_mine)
+                    acc[i][t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[buf][t], xf[buf][i], acc[i][t], 0, 0, 0);
     };
 
     const int n_pro = min(SLOTS, n_stages);
@@ -330,7 +343,7 @@ __global__ __launch_bounds__((NW + NL) * 64) void k_proj_gemm(GemmArgs p)
     // register r of sub-tile t is feature 32 t' + 8 (r >> 2) + 4 hi + (r & 3) of the head, with t' = t
     // for a whole head and {half, half + 2} for a half head.
     if (!head_valid) return;
-    if (EPI == 4) {
+    if constexpr (EPI == 4) {
         // Lane (col, hi) holds, for window row col, the logits 32 t + 8 (r >> 2) + 4 hi + (r & 3) of the
         // slab: ascending in (t, r), so ties keep the smaller index; the other half is in lane ^ 32.
         static_assert(EPI != 4 || NSUB == 4, "vocabulary mode uses whole slabs");
@@ -373,9 +386,9 @@ __global__ __launch_bounds__((NW + NL) * 64) void k_proj_gemm(GemmArgs p)
             const int m = m0 + 32 * (wm * MW + i) + col;
             if (m >= p.m_end) continue;
 #pragma unroll
-            for (int t = 0; t < NSUB; ++t) {
-                const int base = 80 * unit + 16 * t;
-                if (base >= n_pairs) continue;
+            for (int t = 0; t < NT; ++t) {
+                const int base = 80 * unit + 16 * (t0 + t);
+                if (t >= nt_mine || base >= n_pairs) continue;
 #pragma unroll
                 for (int rq = 0; rq < 2; ++rq) {
                     float y[4];
@@ -393,7 +406,7 @@ __global__ __launch_bounds__((NW + NL) * 64) void k_proj_gemm(GemmArgs p)
         }
         return;
     }
-    if (EPI != 0) {
+    if constexpr (EPI != 0 && !DEALT) {
         // Plain linear layers.  Register r of sub-tile t of lane (col, hi) is output column
         // 32 t' + 8 (r >> 2) + 4 hi + (r & 3) of the slab (of its 64 outputs for EPI 2, t' < 2).
 #pragma unroll
@@ -435,7 +448,7 @@ __global__ __launch_bounds__((NW + NL) * 64) void k_proj_gemm(GemmArgs p)
     // base^(-1/64) and its powers; base^(-i/64) / (2 pi) = turns per position of pair i
     const double r1 = exp2(-p.log2_base_64);
     const double r2 = r1 * r1, r4 = r2 * r2, r8 = r4 * r4, r16 = r8 * r8, r32 = r16 * r16;
-    if (DEALT) {
+    if constexpr (DEALT) {
         // Dealt pairs: sub-tile t holds the 16 rotary pairs ib .. ib + 15 of head slot hs_t; registers
         // 4 rq + e (feature ib + 8 rq + 4 hi + e) and 8 + 4 rq + e (the same + 64), rq < 2.
 #pragma unroll
@@ -447,9 +460,9 @@ __global__ __launch_bounds__((NW + NL) * 64) void k_proj_gemm(GemmArgs p)
             const int pp = p.pos ? p.pos[mm] : p.win_start + a;
             const bool valid = mvalid && pp >= 0 && pp < G.max_seq;
 #pragma unroll
-            for (int t = 0; t < NSUB; ++t) {
-                const int base = 80 * unit + 16 * t;
-                if (base >= n_pairs) continue;  // workgroup-uniform
+            for (int t = 0; t < NT; ++t) {
+                const int base = 80 * unit + 16 * (t0 + t);
+                if (t >= nt_mine || base >= n_pairs) continue;  // wave-uniform
                 const int hs_t = base >> 6, ib = base & 63;
                 if (p.bias) {
 #pragma unroll
@@ -505,6 +518,7 @@ __global__ __launch_bounds__((NW + NL) * 64) void k_proj_gemm(GemmArgs p)
         }
         return;
     }
+    if constexpr (!DEALT) {
     const bool rotate = hs < G.Hq + G.Hkv;
     constexpr int NP = NSUB / 2;  // rotary pairs of sub-tiles: (t, t + NP)
 
@@ -582,13 +596,14 @@ __global__ __launch_bounds__((NW + NL) * 64) void k_proj_gemm(GemmArgs p)
             }
         }
     }
+    }
 }
 
 template <int KS, int NW, int NSUB, int MW, int NG, int SLOTS, int NL, int EPI = 0>
 hipError_t launch_gemm(GemmArgs a, hipStream_t s)
 {
     constexpr int XROWS = 32 * MW * (NW / NG);
-    constexpr int LDS = SLOTS * (32 * NSUB * NG + XROWS) * KS * 2;
+    constexpr int LDS = SLOTS * ((NSUB == 5 ? 160 : 32 * NSUB * NG) + XROWS) * KS * 2;
     static_assert(LDS <= 160 * 1024, "LDS ring too large");
     static hipError_t attr = hipFuncSetAttribute((const void *)k_proj_gemm<KS, NW, NSUB, MW, NG, SLOTS, NL, EPI>,
                                                  hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
@@ -637,7 +652,7 @@ template <int EPI>
 hipError_t launch_wide_shape(int shape, const GemmArgs &a, hipStream_t s)
 {
     if (shape == 4) {  // 256 rows x 80 dealt pairs (gated layer only)
-        if constexpr (EPI == 2) return launch_gemm<64, 8, 5, 1, 1, 3, 0, EPI>(a, s);
+        if constexpr (EPI == 2) return launch_gemm<64, 8, 5, 2, 2, 3, 0, EPI>(a, s);
         else return hipErrorInvalidValue;
     }
     if (shape == 0) return launch_gemm<64, 8, 4, 1, 1, 3, 0, EPI>(a, s);  // 256 rows x slab
@@ -847,7 +862,7 @@ hipError_t fc_launch_project_gemm(const FcGeom &G, const void *x, const void *w,
     // The two 128-row shapes get four extra waves that only issue the loads (their four multiplying
     // waves are alone on their SIMDs); the half-head shape also takes 128 hidden elements per stage.
     auto launch_shape = [&](int shape, const GemmArgs &g) -> hipError_t {
-        if (shape == 4) return launch_gemm<64, 8, 5, 1, 1, 3, 0>(g, s);   // 256 rows x 80 dealt rotary pairs
+        if (shape == 4) return launch_gemm<64, 8, 5, 2, 2, 3, 0>(g, s);   // 256 rows x 80 dealt rotary pairs
         if (shape == 3) return launch_gemm<64, 8, 4, 2, 2, 2, 0>(g, s);   // 256 rows x two heads
         if (shape == 0) return launch_gemm<64, 8, 4, 1, 1, 3, 0>(g, s);   // 256 rows x head
         if (shape == 1) return launch_gemm<64, 4, 4, 1, 1, 4, 4>(g, s);   // 128 rows x head
