@@ -39,7 +39,7 @@ struct FcKnobs {
     int lin_wide_shape;     // FC_LIN_WIDE_SHAPE=0..2 (4: gated layer only) one tile shape for the tiled linear GEMM (-1 = planned)
     int lin_ksplit;         // FC_LIN_KSPLIT=n        parts of the hidden dimension
     int gemm_no_split;      // FC_GEMM_NO_SPLIT       never cut a GEMM into two launches
-    int proj_gemm_shape;    // FC_PROJ_GEMM_SHAPE=0..4 one tile shape for the projection GEMM (-1 = planned)
+    int proj_gemm_shape;    // FC_PROJ_GEMM_SHAPE=0..5 one tile shape for the projection GEMM (-1 = planned)
     int proj_no_headsplit;  // FC_PROJ_NO_HEADSPLIT   short-window projection without the head-split kernels
     int accept_wgs;         // FC_ACCEPT_WGS=n        workgroups of the acceptance scan
 };

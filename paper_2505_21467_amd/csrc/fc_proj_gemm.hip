@@ -9,9 +9,10 @@
 // register), with NSUB = 2 it covers the rotary-paired half head {32 h .. 32 h + 31} u {64 + 32 h ..}
 // (more, smaller workgroups when the window is too short to fill the chip).  The rotation, the bias and
 // the stores to q_out / the K rows / the transposed V tiles therefore need no exchange between lanes.
-// A fifth shape (NSUB = 5) deals the rotary pairs of all head slots, laid end to end, 80 to a workgroup
-// (16 per sub-tile, low rows then high rows: the partner of register r is register r + 8): a quarter more
-// work per workgroup than a head, for grids that would otherwise be a little more than one round.
+// Two more shapes (NSUB = 5, 3) deal the rotary pairs of all head slots, laid end to end, 80 or 48 to a
+// workgroup (16 per sub-tile, low rows then high rows: the partner of register r is register r + 8): a
+// quarter more work per workgroup than a head for grids that would otherwise be a little more than one
+// round, a quarter less for grids well short of one.
 //
 // Both operands are contiguous along the hidden dimension.  64 (or 128) hidden elements of every row
 // of the tile (128- or 256-byte row pieces) stream HBM/L2 -> LDS with direct-to-LDS 16-byte loads into
@@ -110,27 +111,29 @@ __global__ __launch_bounds__((NW + NL) * 64) void k_proj_gemm(GemmArgs p)
     constexpr int NKK = KS / 16;               // k-steps per stage
     constexpr int WM = NW / NG;
     constexpr int NLW = NL > 0 ? NL : NW;      // waves that issue loads
-    constexpr bool DEALT = NSUB == 5;
-    constexpr int WROWS = DEALT ? 160 : 32 * NSUB * NG, XROWS = 32 * MW * WM;
+    constexpr bool DEALT = NSUB == 5 || NSUB == 3;
+    constexpr int PPU = 16 * NSUB;             // DEALT: pairs per workgroup
+    constexpr int WROWS = DEALT ? 32 * NSUB : 32 * NSUB * NG, XROWS = 32 * MW * WM;
     constexpr int WBYTES = WROWS * ROWB, STAGE = (WROWS + XROWS) * ROWB;
     constexpr int NBLK = (WROWS + XROWS) / RPB;  // 1 KB blocks per stage
-    // NSUB = 5 ("dealt pairs", EPI 0 and 2 only): the workgroup takes 80 consecutive PAIRS of weight rows
+    // NSUB = 5 or 3 ("dealt pairs", EPI 0 and 2 only): the workgroup takes 16 NSUB consecutive PAIRS of weight rows
     // -- rotary pairs (i, i + 64) of the head slots laid end to end, or (gate row, up row) pairs -- 16
     // pairs per sub-tile: the low rows in rows 0..15 of the sub-tile, the high rows in rows 16..31, so
     // that the two members of a pair sit in one lane, registers r and r + 8.  The 52 blocks of a stage
-    // do not divide by the eight waves: waves 0..3 issue seven loads per stage, waves 4..7 six.
+    // of the 80-pair shape do not divide by its eight waves: waves 0..3 issue seven loads per stage, waves
+    // 4..7 six (the 48-pair shape has four loading waves of seven blocks each).
     // With NG = 2 the five sub-tiles are split between the two waves of a SIMD (sub-tiles 0..2 and 3..4),
     // each wave taking MW = 2 row sub-tiles: the pair of waves reads 5 + 4 fragments for its 6 + 4
     // multiplies of a k-step instead of 2 x 6 for 2 x 5 with 32-row waves (same time measured, less LDS
     // traffic).
-    constexpr int NT = DEALT ? (NG == 2 ? 3 : 5) : NSUB;  // sub-tiles a wave owns (at most)
+    constexpr int NT = DEALT && NG == 2 ? (NSUB + 1) / 2 : NSUB;  // sub-tiles a wave owns (at most)
     constexpr int WBLK = WROWS / RPB;          // weight blocks of a stage (the first ones)
     constexpr int LBW = (NBLK + NLW - 1) / NLW;  // blocks per loading wave and stage (DEALT: at most)
     constexpr int WBW = WBLK / NLW;            // of which weight blocks (not DEALT)
     static_assert(KS == 64 || KS == 128, "stage depth");
     static_assert(NW % NG == 0 && (DEALT || (NBLK % NLW == 0 && WBLK % NLW == 0)) && (NSUB >= 4 || NG == 1), "tile shape");
-    static_assert(!DEALT || ((EPI == 0 || EPI == 2) && (NG == 1 || NG == 2) && KS == 64 &&
-                             (NL == 0 ? NBLK - (LBW - 1) * NLW == NLW / 2 : NBLK % NLW == 0)),
+    static_assert(!DEALT || ((EPI == 0 || EPI == 2) && (NG == 1 || NG == 2) &&
+                             (NL == 0 ? NBLK - (LBW - 1) * NLW == NLW / 2 : (NBLK % NLW == 0 && WBLK % NLW == 0))),
                   "dealt pairs: QKV or gated epilogue");
     static_assert((SLOTS - 1) * LBW < 64 && SLOTS >= 2 && SLOTS <= 4, "vmcnt range");
     static_assert(EPI == 0 || NG == 1 || DEALT, "the plain linear layers use one slab per workgroup");
@@ -165,8 +168,8 @@ __global__ __launch_bounds__((NW + NL) * 64) void k_proj_gemm(GemmArgs p)
     const bool head_valid = DEALT || hs < n_slots;  // an odd number of heads leaves the last pair half empty
     const int n_pairs = n_slots * 64;           // DEALT: pairs of the whole problem
     const int my_blocks = DEALT && NL == 0 && lw >= NLW / 2 ? LBW - 1 : LBW;  // wave-uniform
-    const int t0 = DEALT && NG == 2 && wn ? 3 : 0;        // DEALT: first sub-tile of this wave
-    const int nt_mine = DEALT && NG == 2 && wn ? 2 : NT;  // and how many it owns (wave-uniform)
+    const int t0 = DEALT && NG == 2 && wn ? NT : 0;              // DEALT: first sub-tile of this wave
+    const int nt_mine = DEALT && NG == 2 && wn ? NSUB - NT : NT;  // and how many it owns (wave-uniform)
 
     // ---- loader: per-lane source offsets (bytes from W / X, hidden offset 0) of this wave's blocks
     uint32_t goff[LBW];
@@ -181,7 +184,7 @@ __global__ __launch_bounds__((NW + NL) * 64) void k_proj_gemm(GemmArgs p)
         if (is_w) {
             int n;
             if (DEALT) {
-                const int pr = min(80 * unit + 16 * (rl >> 5) + (rl & 15), n_pairs - 1);  // pairs past the end are never stored
+                const int pr = min(PPU * unit + 16 * (rl >> 5) + (rl & 15), n_pairs - 1);  // pairs past the end are never stored
                 if (EPI == 2) n = pr;  // row pr of the gate matrix (low) or of the up matrix (high)
                 else n = (pr >> 6) * 128 + (pr & 63) + ((rl & 16) ? 64 : 0);
             } else if (EPI == 2) {  // row of the gate or of the up matrix (which of the two: see issue_stage)
@@ -213,9 +216,9 @@ __global__ __launch_bounds__((NW + NL) * 64) void k_proj_gemm(GemmArgs p)
             if (DEALT && i >= my_blocks) continue;
             const uint16_t *mat = p.X;
             if (DEALT) {
-                // rows 16..31 of a sub-tile (blocks 2, 3 of every four) are the high rows: EPI 2 takes them from the up matrix
+                // rows 16..31 of a sub-tile are the high rows: EPI 2 takes them from the up matrix
                 const int bid = lw + NLW * i;
-                if (bid < WBLK) mat = (EPI == 2 && (bid & 2)) ? p.W2 : p.W;
+                if (bid < WBLK) mat = (EPI == 2 && ((RPB * bid) & 16)) ? p.W2 : p.W;
             } else if (i < WBW) {
                 // EPI 2: the second half of the tile rows (a whole number of 1 KB blocks) is the up matrix
                 const bool up = EPI == 2 && RPB * (lw + NLW * i) >= (NSUB == 4 ? 64 : 32);
@@ -387,7 +390,7 @@ __global__ __launch_bounds__((NW + NL) * 64) void k_proj_gemm(GemmArgs p)
             if (m >= p.m_end) continue;
 #pragma unroll
             for (int t = 0; t < NT; ++t) {
-                const int base = 80 * unit + 16 * (t0 + t);
+                const int base = PPU * unit + 16 * (t0 + t);
                 if (t >= nt_mine || base >= n_pairs) continue;
 #pragma unroll
                 for (int rq = 0; rq < 2; ++rq) {
@@ -461,7 +464,7 @@ __global__ __launch_bounds__((NW + NL) * 64) void k_proj_gemm(GemmArgs p)
             const bool valid = mvalid && pp >= 0 && pp < G.max_seq;
 #pragma unroll
             for (int t = 0; t < NT; ++t) {
-                const int base = 80 * unit + 16 * (t0 + t);
+                const int base = PPU * unit + 16 * (t0 + t);
                 if (t >= nt_mine || base >= n_pairs) continue;  // wave-uniform
                 const int hs_t = base >> 6, ib = base & 63;
                 if (p.bias) {
@@ -603,14 +606,15 @@ template <int KS, int NW, int NSUB, int MW, int NG, int SLOTS, int NL, int EPI =
 hipError_t launch_gemm(GemmArgs a, hipStream_t s)
 {
     constexpr int XROWS = 32 * MW * (NW / NG);
-    constexpr int LDS = SLOTS * ((NSUB == 5 ? 160 : 32 * NSUB * NG) + XROWS) * KS * 2;
+    constexpr bool DEALT = NSUB == 5 || NSUB == 3;
+    constexpr int LDS = SLOTS * ((DEALT ? 32 * NSUB : 32 * NSUB * NG) + XROWS) * KS * 2;
     static_assert(LDS <= 160 * 1024, "LDS ring too large");
     static hipError_t attr = hipFuncSetAttribute((const void *)k_proj_gemm<KS, NW, NSUB, MW, NG, SLOTS, NL, EPI>,
                                                  hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
     if (attr != hipSuccess) return attr;
     const int slots = a.slots_here;
-    a.n_units = NSUB == 5 ? (a.n_slots * 64 + 79) / 80 : NSUB == 4 ? (slots + NG - 1) / NG : 2 * slots;
-    if (NSUB == 5 && (a.slot_base != 0 || slots != a.n_slots)) return hipErrorInvalidValue;  // dealt pairs cover every slab
+    a.n_units = DEALT ? (a.n_slots * 64 + 16 * NSUB - 1) / (16 * NSUB) : NSUB == 4 ? (slots + NG - 1) / NG : 2 * slots;
+    if (DEALT && (a.slot_base != 0 || slots != a.n_slots)) return hipErrorInvalidValue;  // dealt pairs cover every slab
     a.n_mt = (a.m_end - a.m_base + XROWS - 1) / XROWS;
     if (slots < 1 || a.n_mt < 1 || a.slot_base < 0 || a.slot_base + slots > a.n_slots || a.m_base < 0 || a.m_end > a.M)
         return hipErrorInvalidValue;
@@ -863,6 +867,7 @@ hipError_t fc_launch_project_gemm(const FcGeom &G, const void *x, const void *w,
     // waves are alone on their SIMDs); the half-head shape also takes 128 hidden elements per stage.
     auto launch_shape = [&](int shape, const GemmArgs &g) -> hipError_t {
         if (shape == 4) return launch_gemm<64, 8, 5, 2, 2, 3, 0>(g, s);   // 256 rows x 80 dealt rotary pairs
+        if (shape == 5) return launch_gemm<64, 4, 3, 1, 1, 4, 4>(g, s);   // 128 rows x 48 dealt rotary pairs, 4 + 4 waves
         if (shape == 3) return launch_gemm<64, 8, 4, 2, 2, 2, 0>(g, s);   // 256 rows x two heads
         if (shape == 0) return launch_gemm<64, 8, 4, 1, 1, 3, 0>(g, s);   // 256 rows x head
         if (shape == 1) return launch_gemm<64, 4, 4, 1, 1, 4, 4>(g, s);   // 128 rows x head
@@ -876,6 +881,16 @@ hipError_t fc_launch_project_gemm(const FcGeom &G, const void *x, const void *w,
     if (fc_knobs().proj_gemm_shape >= 0) return launch_shape(fc_knobs().proj_gemm_shape, a);  // tuning knob: one shape for all
     GemmPiece pc[2];
     const int n = plan_pieces(a.n_slots, a.M, true, true, pc);
+    if (n == 1 && pc[0].shape == 1) {
+        // 128 rows x head leaves compute units idle when the grid is well short of a round (96 head slots
+        // x 2 row tiles = 192 workgroups); dealt in units of 48 rotary pairs the same rows make more,
+        // smaller workgroups (256 there).  A workgroup's time goes with the rows of both operands it
+        // pulls (128 + 128 against 128 + 96): 44.3 -> 40.8 us at 256 rows, 96 slots, hidden 4096.  (64
+        // rows x 48 pairs for the 36-slot geometry measured the same as the half-head shape: not used.)
+        const int64_t t128 = (a.M + 127) / 128;
+        const int64_t wg1 = (int64_t)a.n_slots * t128, wg5 = (((int64_t)a.n_slots * 64 + 47) / 48) * t128;
+        if (((wg5 + 255) / 256) * 224 < ((wg1 + 255) / 256) * 256) pc[0].shape = 5;
+    }
     for (int i = 0; i < n; ++i) {
         a.slot_base = pc[i].slot_base;
         a.slots_here = pc[i].slots;

@@ -230,14 +230,14 @@ def test_mid_window_projection(B, d, Hq, Hkv, L, A):
     g.close()
 
 
-@pytest.mark.parametrize("shape", [0, 1, 2, 3, 4])
+@pytest.mark.parametrize("shape", [0, 1, 2, 3, 4, 5])
 @pytest.mark.parametrize("B,d,Hq,Hkv,L,A", [
     (3, 192, 8, 2, 100, 23),   # 69 window rows: one ragged row tile, three hidden stages
     (2, 320, 4, 4, 70, 160),   # 320 window rows: several row tiles, the last one ragged
     (2, 64, 3, 1, 50, 40),     # an odd number of head slots (5), a single hidden stage
 ])
 def test_wide_window_projection_tile_shapes(knob, shape, B, d, Hq, Hkv, L, A):
-    """The tiled projection (more than 32 window rows) in each of its five tile shapes."""
+    """The tiled projection (more than 32 window rows) in each of its six tile shapes."""
     _say("wide-window projection, tile shape %d, B%d d%d Hq%d Hkv%d L%d A%d" % (shape, B, d, Hq, Hkv, L, A))
     knob("FC_PROJ_GEMM_SHAPE", str(shape))
     dtype, Dh = "bf16", 128
